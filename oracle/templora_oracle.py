@@ -1,0 +1,326 @@
+"""CPU oracle for the Temp-Lora chunk update (TEST INFRASTRUCTURE, not a product path).
+
+A plain, slow, fp64 numpy statement of what one "Train Theta_k: In X_T -> Out
+Chunk_k" step of Algorithm 1 computes for a Llama2-style decoder (Section 3,
+"Baselines") whose projections carry a LoRA module (Section 2; rank and alpha
+from Section 3 "Setup"): forward, next-token loss on the chunk, backward to the
+LoRA factors only, one AdamW step at the paper's learning rate.
+
+Rules this file keeps:
+  * every function takes the algorithm's steps in order, in fp64, with a numpy
+    matmul / exp / sum as the only primitives; no blocking, fusion or reuse
+    tricks, so that it can be checked against the paper by eye;
+  * it imports nothing from the HIP package and shares no code with it;
+  * only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may
+    import it.
+
+Pins (tests/test_oracle_pins.py): B = 0 gives the base model exactly; merged
+weight W + s*B*A gives the same forward; central finite differences and an
+independent autograd graph agree with every gradient; the loss is a valid NLL
+(ln V on uniform logits, agreement with a library log-softmax); AdamW agrees
+with its step-1 closed form and with a library optimizer over several steps;
+RoPE and RMSNorm invariants; causality.  Absolute loss / gradient values at the
+workload shapes are printed nowhere in the paper: they are pinned only through
+these properties.
+
+Layouts: activations [T, width]; W [d_out, d_in]; A [r, d_in]; B [d_out, r].
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PROJ = ("q", "k", "v", "o", "gate", "up", "down")
+F64 = np.float64
+
+
+def _f(x):
+    return np.asarray(x, dtype=F64)
+
+
+# --------------------------------------------------------------------------
+# Labels and loss mask (Section 2: the preceding L_T tokens are the input, the
+# chunk is the output; Algorithm 1, the "Train" line).
+# --------------------------------------------------------------------------
+def labels_and_mask(tokens, n_ctx: int):
+    """label[t] = tokens[t+1]; position t carries loss iff its label is a chunk token.
+
+    tokens = n_ctx conditioning tokens followed by the chunk.  Position t
+    predicts token t+1, so it is a target iff t+1 >= max(n_ctx, 1) and t+1 < T.
+    Returns (labels int64[T] with labels[T-1] = -1, mask bool[T], N targets).
+    """
+    tok = np.asarray(tokens, dtype=np.int64)
+    T = tok.shape[0]
+    labels = np.full(T, -1, dtype=np.int64)
+    labels[: T - 1] = tok[1:]
+    t = np.arange(T)
+    mask = (t + 1 >= max(int(n_ctx), 1)) & (t + 1 < T)
+    return labels, mask, int(mask.sum())
+
+
+# --------------------------------------------------------------------------
+# LoRA-adapted linear layer (Section 2: a temporary LoRA module on a frozen LM).
+# --------------------------------------------------------------------------
+def lora_linear_fwd(X, W, A, B, s: float):
+    """Y = X W^T + s (X A^T) B^T.  Returns (Y, H) with H = X A^T."""
+    X, W, A, B = _f(X), _f(W), _f(A), _f(B)
+    H = X @ A.T
+    Y = X @ W.T + s * (H @ B.T)
+    return Y, H
+
+
+def lora_linear_bwd(dY, X, W, A, B, s: float):
+    """Gradients of <dY, Y> w.r.t. X, A, B; W is frozen so no dW exists.
+
+    dH = s dY B;  dX = dY W + dH A;  dA = dH^T X;  dB = s dY^T (X A^T).
+    """
+    dY, X, W, A, B = _f(dY), _f(X), _f(W), _f(A), _f(B)
+    dH = s * (dY @ B)
+    dX = dY @ W + dH @ A
+    dA = dH.T @ X
+    dB = s * (dY.T @ (X @ A.T))
+    return dX, dA, dB
+
+
+# --------------------------------------------------------------------------
+# RMSNorm, RoPE, SwiGLU (Llama2 decoder blocks, Section 3 "Baselines").
+# --------------------------------------------------------------------------
+def rmsnorm_fwd(h, g, eps: float):
+    h, g = _f(h), _f(g)
+    rho = 1.0 / np.sqrt(np.mean(h * h, axis=-1, keepdims=True) + eps)
+    return h * rho * g
+
+
+def rmsnorm_bwd(dy, h, g, eps: float):
+    """dh = rho (g*dy) - h rho^3 mean_j(h_j g_j dy_j); the gain is frozen (no dg)."""
+    dy, h, g = _f(dy), _f(h), _f(g)
+    rho = 1.0 / np.sqrt(np.mean(h * h, axis=-1, keepdims=True) + eps)
+    gd = g * dy
+    return rho * gd - h * rho ** 3 * np.mean(h * gd, axis=-1, keepdims=True)
+
+
+def _rope_angles(T: int, d_head: int, base: float, pos0: int = 0):
+    i = np.arange(d_head // 2, dtype=F64)
+    theta = base ** (-2.0 * i / d_head)
+    p = np.arange(pos0, pos0 + T, dtype=F64)
+    return np.outer(p, theta)  # [T, d_head/2]
+
+
+def rope_fwd(x, base: float, pos0: int = 0, sign: float = 1.0):
+    """x [T, n_heads, d_head]; pair (i, i + d_head/2) rotated by angle p*theta_i."""
+    x = _f(x)
+    T, _, dh = x.shape
+    ang = sign * _rope_angles(T, dh, base, pos0)
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., : dh // 2], x[..., dh // 2:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def rope_bwd(dy, base: float, pos0: int = 0):
+    """The rotation is orthogonal: its transpose is the rotation by the negated angle."""
+    return rope_fwd(dy, base, pos0, sign=-1.0)
+
+
+def swiglu_fwd(g, u):
+    g, u = _f(g), _f(u)
+    return g / (1.0 + np.exp(-g)) * u
+
+
+def swiglu_bwd(da, g, u):
+    da, g, u = _f(da), _f(g), _f(u)
+    sig = 1.0 / (1.0 + np.exp(-g))
+    dg = da * u * sig * (1.0 + g * (1.0 - sig))
+    du = da * g * sig
+    return dg, du
+
+
+# --------------------------------------------------------------------------
+# Causal self-attention within the call's tokens.
+# --------------------------------------------------------------------------
+def attention_fwd(q, k, v):
+    """q, k, v [T, n_heads, d_head] -> (o [T, n_heads, d_head], P [n_heads, T, T])."""
+    q, k, v = _f(q), _f(k), _f(v)
+    T, nh, dh = q.shape
+    S = np.einsum("thd,uhd->htu", q, k) / np.sqrt(dh)
+    future = np.triu(np.ones((T, T), dtype=bool), k=1)
+    S = np.where(future[None], -np.inf, S)
+    S = S - S.max(axis=-1, keepdims=True)
+    P = np.exp(S)
+    P /= P.sum(axis=-1, keepdims=True)
+    o = np.einsum("htu,uhd->thd", P, v)
+    return o, P
+
+
+def attention_bwd(do, q, k, v, P):
+    do, q, k, v = _f(do), _f(q), _f(k), _f(v)
+    dh = q.shape[-1]
+    dv = np.einsum("htu,thd->uhd", P, do)
+    dP = np.einsum("thd,uhd->htu", do, v)
+    dS = P * (dP - np.sum(dP * P, axis=-1, keepdims=True))
+    dq = np.einsum("htu,uhd->thd", dS, k) / np.sqrt(dh)
+    dk = np.einsum("htu,thd->uhd", dS, q) / np.sqrt(dh)
+    return dq, dk, dv
+
+
+# --------------------------------------------------------------------------
+# Next-token cross-entropy on the chunk positions (perplexity = exp(loss),
+# Section 3 "Evaluation Metric").
+# --------------------------------------------------------------------------
+def cross_entropy(logits, labels, mask):
+    """loss = mean over masked positions of (logsumexp(logits_t) - logits_t[label_t]).
+
+    Returns (loss, nll [T] (0 where unmasked), dlogits [T, V] = d loss / d logits).
+    """
+    z = _f(logits)
+    T, V = z.shape
+    N = int(np.sum(mask))
+    zmax = z.max(axis=-1, keepdims=True)
+    lse = np.log(np.exp(z - zmax).sum(axis=-1)) + zmax[:, 0]
+    nll = np.zeros(T, dtype=F64)
+    dlogits = np.zeros_like(z)
+    for t in range(T):
+        if mask[t]:
+            nll[t] = lse[t] - z[t, labels[t]]
+            p = np.exp(z[t] - lse[t])
+            p[labels[t]] -= 1.0
+            dlogits[t] = p / N
+    loss = nll.sum() / N
+    return loss, nll, dlogits
+
+
+# --------------------------------------------------------------------------
+# AdamW on the LoRA factors (Section 3 "Setup": learning rate 5e-5).
+# --------------------------------------------------------------------------
+def adamw_step(p, g, m, v, tau: int, lr: float, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0):
+    """One decoupled-weight-decay Adam step with bias correction; tau is 1-based."""
+    p, g, m, v = _f(p), _f(g), _f(m), _f(v)
+    p = p * (1.0 - lr * wd)
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** tau)
+    vhat = v / (1.0 - beta2 ** tau)
+    p = p - lr * mhat / (np.sqrt(vhat) + eps)
+    return p, m, v
+
+
+# --------------------------------------------------------------------------
+# One decoder layer with LoRA on q, k, v, o, gate, up, down.
+# --------------------------------------------------------------------------
+def layer_fwd(h, W: dict, L: dict, shape, pos0: int = 0):
+    """h [T, d] -> (h_out, cache).  W[p] frozen [d_out, d_in], W['g1'|'g2'] gains; L[p] = (A, B)."""
+    h = _f(h)
+    T = h.shape[0]
+    nh, dh, s = shape.n_heads, shape.d_head, shape.scale
+    c = {"h0": h}
+    c["x1"] = rmsnorm_fwd(h, W["g1"], shape.rms_eps)
+    q, _ = lora_linear_fwd(c["x1"], W["q"], *L["q"], s)
+    k, _ = lora_linear_fwd(c["x1"], W["k"], *L["k"], s)
+    v, _ = lora_linear_fwd(c["x1"], W["v"], *L["v"], s)
+    c["q"] = rope_fwd(q.reshape(T, nh, dh), shape.rope_base, pos0)
+    c["k"] = rope_fwd(k.reshape(T, nh, dh), shape.rope_base, pos0)
+    c["v"] = v.reshape(T, nh, dh)
+    o, c["P"] = attention_fwd(c["q"], c["k"], c["v"])
+    c["o"] = o.reshape(T, nh * dh)
+    yo, _ = lora_linear_fwd(c["o"], W["o"], *L["o"], s)
+    c["h1"] = h + yo
+    c["x2"] = rmsnorm_fwd(c["h1"], W["g2"], shape.rms_eps)
+    c["g"], _ = lora_linear_fwd(c["x2"], W["gate"], *L["gate"], s)
+    c["u"], _ = lora_linear_fwd(c["x2"], W["up"], *L["up"], s)
+    c["a"] = swiglu_fwd(c["g"], c["u"])
+    yd, _ = lora_linear_fwd(c["a"], W["down"], *L["down"], s)
+    return c["h1"] + yd, c
+
+
+def layer_bwd(dh_out, c: dict, W: dict, L: dict, shape, pos0: int = 0):
+    """Upstream d loss / d h_out -> (d loss / d h_in, {p: (dA, dB)})."""
+    dh_out = _f(dh_out)
+    T = dh_out.shape[0]
+    nh, dh, s = shape.n_heads, shape.d_head, shape.scale
+    G = {}
+    da, *G["down"] = lora_linear_bwd(dh_out, c["a"], W["down"], *L["down"], s)
+    dg, du = swiglu_bwd(da, c["g"], c["u"])
+    dx2_g, *G["gate"] = lora_linear_bwd(dg, c["x2"], W["gate"], *L["gate"], s)
+    dx2_u, *G["up"] = lora_linear_bwd(du, c["x2"], W["up"], *L["up"], s)
+    dh1 = dh_out + rmsnorm_bwd(dx2_g + dx2_u, c["h1"], W["g2"], shape.rms_eps)
+    do, *G["o"] = lora_linear_bwd(dh1, c["o"], W["o"], *L["o"], s)
+    dq, dk, dv = attention_bwd(do.reshape(T, nh, dh), c["q"], c["k"], c["v"], c["P"])
+    dq = rope_bwd(dq, shape.rope_base, pos0).reshape(T, nh * dh)
+    dk = rope_bwd(dk, shape.rope_base, pos0).reshape(T, nh * dh)
+    dv = dv.reshape(T, nh * dh)
+    dx1_q, *G["q"] = lora_linear_bwd(dq, c["x1"], W["q"], *L["q"], s)
+    dx1_k, *G["k"] = lora_linear_bwd(dk, c["x1"], W["k"], *L["k"], s)
+    dx1_v, *G["v"] = lora_linear_bwd(dv, c["x1"], W["v"], *L["v"], s)
+    dh0 = dh1 + rmsnorm_bwd(dx1_q + dx1_k + dx1_v, c["h0"], W["g1"], shape.rms_eps)
+    return dh0, {p: tuple(G[p]) for p in PROJ}
+
+
+# --------------------------------------------------------------------------
+# The whole chunk update.
+# --------------------------------------------------------------------------
+def model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, keep=()):
+    """Forward + backward of one call's tokens.
+
+    get_layer(l) returns layer l's frozen dict (so a 7B-shape caller can build
+    layers on demand); lora[l][p] = (A, B).  Returns a dict with loss, nll,
+    n_targets, grads[l][p] = (dA, dB), and dh at the layer inputs listed in
+    `keep` (plus 'final' = gradient at the last layer's output).
+    """
+    tok = np.asarray(tokens, dtype=np.int64)
+    if tok.min() < 0 or tok.max() >= shape.vocab:
+        raise ValueError("token id out of range")
+    labels, mask, N = labels_and_mask(tok, n_ctx)
+    if N < 1:
+        raise ValueError("no target positions")
+    h = _f(emb)[tok]
+    caches = []
+    for l in range(shape.n_layers):
+        h, c = layer_fwd(h, get_layer(l), lora[l], shape)
+        caches.append(c)
+    hf = rmsnorm_fwd(h, g_final, shape.rms_eps)
+    logits = hf @ _f(head).T
+    loss, nll, dlogits = cross_entropy(logits, labels, mask)
+    dhf = dlogits @ _f(head)
+    dh = rmsnorm_bwd(dhf, h, g_final, shape.rms_eps)
+    out = {"loss": loss, "nll": nll, "n_targets": N, "labels": labels, "mask": mask,
+           "logits": logits, "dh": {"final": dh}, "grads": [None] * shape.n_layers}
+    for l in reversed(range(shape.n_layers)):
+        dh, out["grads"][l] = layer_bwd(dh, caches[l], get_layer(l), lora[l], shape)
+        caches[l] = None
+        if l in keep:
+            out["dh"][l] = dh
+    return out
+
+
+def new_opt_state(lora):
+    """Zero first/second moments for every factor; step counter 0."""
+    return {"tau": 0,
+            "m": [{p: (np.zeros_like(_f(a)), np.zeros_like(_f(b))) for p, (a, b) in L.items()} for L in lora],
+            "v": [{p: (np.zeros_like(_f(a)), np.zeros_like(_f(b))) for p, (a, b) in L.items()} for L in lora]}
+
+
+def chunk_update(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, opt, lr,
+                 beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0, keep=()):
+    """One optimizer step on one chunk: returns (result dict, new lora, new opt)."""
+    res = model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, keep)
+    tau = opt["tau"] + 1
+    new_lora, new_m, new_v = [], [], []
+    for l in range(shape.n_layers):
+        Ll, Ml, Vl = {}, {}, {}
+        for p in PROJ:
+            facs, ms, vs = [], [], []
+            for i in range(2):  # 0: A, 1: B
+                pn, mn, vn = adamw_step(lora[l][p][i], res["grads"][l][p][i], opt["m"][l][p][i],
+                                        opt["v"][l][p][i], tau, lr, beta1, beta2, eps, wd)
+                facs.append(pn), ms.append(mn), vs.append(vn)
+            Ll[p], Ml[p], Vl[p] = tuple(facs), tuple(ms), tuple(vs)
+        new_lora.append(Ll), new_m.append(Ml), new_v.append(Vl)
+    return res, new_lora, {"tau": tau, "m": new_m, "v": new_v}
+
+
+def linear_step(X, W, A, B, dY, s, lr, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0):
+    """Single LoRA-adapted linear layer: forward, backward, first AdamW step on A and B."""
+    Y, _ = lora_linear_fwd(X, W, A, B, s)
+    dX, dA, dB = lora_linear_bwd(dY, X, W, A, B, s)
+    z = np.zeros_like
+    A1, _, _ = adamw_step(A, dA, z(_f(A)), z(_f(A)), 1, lr, beta1, beta2, eps, wd)
+    B1, _, _ = adamw_step(B, dB, z(_f(B)), z(_f(B)), 1, lr, beta1, beta2, eps, wd)
+    return {"Y": Y, "dX": dX, "dA": dA, "dB": dB, "A1": A1, "B1": B1}

@@ -1,0 +1,509 @@
+"""Pins for the CPU oracle: each test checks it against something other than itself.
+
+The paper prints no worked numeric example of one update, so the oracle is pinned
+by what the method and the mathematics fix: special cases (B = 0), identities
+(merged weight), brute force (finite differences), library routines (an
+independent autograd graph, a library AdamW, a library log-softmax) and closed
+forms.  A dropped term, wrong sign, wrong index or transposed operand in the
+oracle fails at least one test below.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import templora_oracle as O
+from paper_2401_11504_amd import synth
+
+PROJ = synth.PROJ
+TINY = synth.SHAPES["tiny"]
+
+
+def _rel(a, b):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300)
+
+
+def _tiny_model(seed=7, b_std=0.05, shape=TINY, n_tokens=10):
+    Ws = [synth.layer_weights(seed, shape, l, bf16=False) for l in range(shape.n_layers)]
+    # larger weights than the workload's 0.02 so that every path carries signal at d = 32
+    for W in Ws:
+        for p in PROJ:
+            W[p] = W[p] * 10.0
+        W["g1"] = 1.0 + 0.1 * synth.normal(seed, (90, 1), W["g1"].shape, 1.0, False)
+        W["g2"] = 1.0 + 0.1 * synth.normal(seed, (90, 2), W["g2"].shape, 1.0, False)
+    lora = [synth.lora_factors(seed, shape, l, b_std=b_std, a_std=0.2) for l in range(shape.n_layers)]
+    emb = synth.embedding(seed, shape, bf16=False) * 30.0
+    head = synth.lm_head(seed, shape, bf16=False) * 10.0
+    gf = 1.0 + 0.1 * synth.normal(seed, (90, 3), (shape.d_model,), 1.0, False)
+    tok = synth.uniform_tokens(seed, n_tokens, shape.vocab)
+    return Ws, lora, emb, head, gf, tok
+
+
+def _run(Ws, lora, emb, head, gf, tok, n_ctx=0, shape=TINY, keep=()):
+    return O.model_fwd_bwd(tok, n_ctx, shape, emb, head, gf, lambda l: Ws[l], lora, keep=keep)
+
+
+# ---------------------------------------------------------------- labels / mask
+def test_labels_and_mask_bare_chunk():
+    tok = np.array([5, 9, 2, 7])
+    lab, mask, n = O.labels_and_mask(tok, 0)
+    assert lab.tolist() == [9, 2, 7, -1]
+    assert mask.tolist() == [True, True, True, False] and n == 3
+
+
+def test_labels_and_mask_with_context_counts_chunk_tokens():
+    # 3 conditioning tokens + 4 chunk tokens: exactly the 4 chunk tokens are predicted
+    tok = np.arange(7)
+    lab, mask, n = O.labels_and_mask(tok, 3)
+    assert n == 4
+    assert mask.tolist() == [False, False, True, True, True, True, False]
+    assert lab[mask].tolist() == [3, 4, 5, 6]
+
+
+# ---------------------------------------------------------------- LoRA linear
+def _lin(seed=3, T=6, din=5, dout=7, r=3):
+    g = np.random.default_rng(seed)
+    return (g.standard_normal((T, din)), g.standard_normal((dout, din)), g.standard_normal((r, din)),
+            g.standard_normal((dout, r)), g.standard_normal((T, dout)))
+
+
+def test_lora_b_zero_is_base_exactly():
+    X, W, A, B, _ = _lin()
+    Y, _ = O.lora_linear_fwd(X, W, A, np.zeros_like(B), 2.0)
+    assert np.array_equal(Y, X @ W.T)
+
+
+def test_lora_merged_weight_same_forward():
+    X, W, A, B, _ = _lin()
+    s = 1.7
+    Y, _ = O.lora_linear_fwd(X, W, A, B, s)
+    Ym, _ = O.lora_linear_fwd(X, W + s * B @ A, A, np.zeros_like(B), s)
+    assert _rel(Y, Ym) < 1e-14
+
+
+def test_lora_brute_force_elementwise():
+    # the definition written out index by index in pure Python
+    X, W, A, B, dY = _lin(T=3, din=4, dout=2, r=2)
+    s = 0.5
+    Y, _ = O.lora_linear_fwd(X, W, A, B, s)
+    for t in range(3):
+        for o in range(2):
+            acc = sum(X[t, i] * W[o, i] for i in range(4))
+            acc += s * sum(B[o, j] * sum(A[j, i] * X[t, i] for i in range(4)) for j in range(2))
+            assert abs(Y[t, o] - acc) < 1e-12
+
+
+def test_lora_backward_finite_differences():
+    X, W, A, B, dY = _lin()
+    s = 2.0
+    dX, dA, dB = O.lora_linear_bwd(dY, X, W, A, B, s)
+
+    def f(X_, A_, B_):
+        return float(np.sum(O.lora_linear_fwd(X_, W, A_, B_, s)[0] * dY))
+
+    eps = 1e-6
+    for arr, grad, which in ((X, dX, 0), (A, dA, 1), (B, dB, 2)):
+        num = np.zeros_like(arr)
+        for idx in np.ndindex(arr.shape):
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += eps
+            am[idx] -= eps
+            args_p = [X, A, B]
+            args_m = [X, A, B]
+            args_p[which], args_m[which] = ap, am
+            num[idx] = (f(*args_p) - f(*args_m)) / (2 * eps)
+        assert _rel(grad, num) < 1e-8
+
+
+def test_lora_b_zero_gives_zero_dA_and_base_dX():
+    X, W, A, B, dY = _lin()
+    dX, dA, dB = O.lora_linear_bwd(dY, X, W, A, np.zeros_like(B), 2.0)
+    assert np.all(dA == 0.0)
+    assert np.array_equal(dX, dY @ W)
+    assert np.linalg.norm(dB) > 0
+
+
+def test_lora_backward_linear_in_dY():
+    X, W, A, B, dY = _lin()
+    g1 = O.lora_linear_bwd(dY, X, W, A, B, 2.0)
+    g3 = O.lora_linear_bwd(3.0 * dY, X, W, A, B, 2.0)
+    for a, b in zip(g1, g3):
+        assert _rel(b, 3.0 * a) < 1e-14
+
+
+def test_linear_step_matches_autograd_and_library_adamw():
+    c = synth.linear_case(11, n_tokens=16, d_in=12, d_out=10, rank=4)
+    s, lr = 2.0, 5e-5
+    out = O.linear_step(c["X"], c["W"], c["A"], c["B"], c["dY"], s, lr)
+    X = torch.tensor(c["X"], dtype=torch.float64, requires_grad=True)
+    W = torch.tensor(c["W"], dtype=torch.float64)
+    A = torch.tensor(c["A"], dtype=torch.float64, requires_grad=True)
+    B = torch.tensor(c["B"], dtype=torch.float64, requires_grad=True)
+    Y = F.linear(X, W) + s * F.linear(F.linear(X, A), B)
+    opt = torch.optim.AdamW([A, B], lr=lr, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.0)
+    Y.backward(torch.tensor(c["dY"], dtype=torch.float64))
+    assert _rel(out["Y"], Y.detach().numpy()) < 1e-13
+    assert _rel(out["dX"], X.grad.numpy()) < 1e-13
+    assert _rel(out["dA"], A.grad.numpy()) < 1e-13
+    assert _rel(out["dB"], B.grad.numpy()) < 1e-13
+    opt.step()
+    assert _rel(out["A1"] - c["A"], A.detach().numpy() - c["A"]) < 1e-9
+    assert _rel(out["B1"] - c["B"], B.detach().numpy() - c["B"]) < 1e-9
+
+
+# ---------------------------------------------------------------- AdamW
+def test_adamw_first_step_closed_form():
+    g = np.array([0.3, -2.0, 1e-3, 0.0, -1e-6])
+    p0 = np.array([1.0, -1.0, 0.5, 0.25, 2.0])
+    lr, eps = 5e-5, 1e-8
+    p, m, v = O.adamw_step(p0, g, np.zeros(5), np.zeros(5), 1, lr, eps=eps)
+    # step 1, wd = 0: bias-corrected m = g, v = g^2  =>  dp = -lr g / (|g| + eps)
+    assert np.allclose(p - p0, -lr * g / (np.abs(g) + eps), rtol=1e-9, atol=0)
+    assert (p - p0)[3] == 0.0
+    assert np.allclose(m, 0.1 * g) and np.allclose(v, 0.001 * g * g)
+
+
+def test_adamw_matches_library_over_steps_with_decay():
+    rng = np.random.default_rng(0)
+    p0 = rng.standard_normal(50)
+    tp = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([tp], lr=1e-2, betas=(0.8, 0.95), eps=1e-6, weight_decay=0.1)
+    p, m, v = p0.copy(), np.zeros(50), np.zeros(50)
+    for tau in range(1, 6):
+        g = rng.standard_normal(50)
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        p, m, v = O.adamw_step(p, g, m, v, tau, 1e-2, 0.8, 0.95, 1e-6, 0.1)
+    assert _rel(p, tp.detach().numpy()) < 1e-12
+
+
+# ---------------------------------------------------------------- cross entropy
+def test_ce_uniform_logits_is_log_vocab():
+    V, T = 37, 5
+    labels = np.array([1, 2, 3, 4, -1])
+    mask = np.array([True, True, True, True, False])
+    loss, nll, dl = O.cross_entropy(np.full((T, V), 0.123), labels, mask)
+    assert abs(loss - math.log(V)) < 1e-13
+
+
+def test_ce_valid_nll_and_matches_library():
+    rng = np.random.default_rng(5)
+    T, V = 9, 23
+    z = rng.standard_normal((T, V)) * 3
+    tok = rng.integers(0, V, T)
+    labels, mask, N = O.labels_and_mask(tok, 3)
+    loss, nll, dl = O.cross_entropy(z, labels, mask)
+    assert np.all(nll >= 0) and np.all(nll[~mask] == 0)
+    assert abs(loss - nll.sum() / N) < 1e-14
+    assert np.allclose(dl.sum(axis=1), 0, atol=1e-15)          # softmax - onehot sums to 0
+    assert np.all(dl[~mask] == 0)
+    zt = torch.tensor(z, requires_grad=True)
+    lab = torch.tensor(np.where(mask, labels, -100))
+    lt = F.cross_entropy(zt, lab, ignore_index=-100, reduction="mean")
+    lt.backward()
+    assert abs(loss - lt.item()) < 1e-13
+    assert _rel(dl, zt.grad.numpy()) < 1e-13
+
+
+# ---------------------------------------------------------------- RoPE
+def test_rope_two_dim_head_is_plane_rotation_by_position():
+    # d_head = 2: theta_0 = 1, so position p rotates (x0, x1) by p radians
+    x = np.array([[[1.0, 0.0]], [[1.0, 0.0]], [[0.0, 2.0]]])
+    y = O.rope_fwd(x, 10000.0)
+    assert np.allclose(y[0, 0], [1, 0])
+    assert np.allclose(y[1, 0], [math.cos(1), math.sin(1)])
+    assert np.allclose(y[2, 0], [-2 * math.sin(2), 2 * math.cos(2)])
+
+
+def test_rope_frequencies_and_pairing():
+    # unit vector on coordinate i: after p steps it has rotated by p * base^(-2i/d) in plane (i, i + d/2)
+    d, base, p = 8, 10000.0, 3
+    for i in range(d // 2):
+        x = np.zeros((p + 1, 1, d))
+        x[:, 0, i] = 1.0
+        y = O.rope_fwd(x, base)[p, 0]
+        ang = p * base ** (-2 * i / d)
+        exp = np.zeros(d)
+        exp[i], exp[i + d // 2] = math.cos(ang), math.sin(ang)
+        assert np.allclose(y, exp, atol=1e-14)
+
+
+def test_rope_norm_relative_position_and_inverse():
+    rng = np.random.default_rng(2)
+    T, nh, dh = 12, 2, 16
+    q, k = rng.standard_normal((T, nh, dh)), rng.standard_normal((T, nh, dh))
+    rq = O.rope_fwd(q, 10000.0)
+    assert np.allclose(np.linalg.norm(rq, axis=-1), np.linalg.norm(q, axis=-1))
+    # same vectors placed at two position pairs with equal offset give equal scores
+    qq = np.repeat(q[:1], T, 0)
+    kk = np.repeat(k[:1], T, 0)
+    rq, rk = O.rope_fwd(qq, 10000.0), O.rope_fwd(kk, 10000.0)
+    s_a = np.einsum("hd,hd->h", rq[7], rk[3])
+    s_b = np.einsum("hd,hd->h", rq[10], rk[6])
+    assert np.allclose(s_a, s_b)
+    assert np.allclose(O.rope_bwd(O.rope_fwd(q, 10000.0), 10000.0), q)
+    # pos0 shifts positions
+    assert np.allclose(O.rope_fwd(q, 10000.0, pos0=4)[0], O.rope_fwd(np.repeat(q[:1], 5, 0), 10000.0)[4])
+
+
+def test_rope_backward_is_adjoint():
+    rng = np.random.default_rng(3)
+    x, dy = rng.standard_normal((5, 2, 8)), rng.standard_normal((5, 2, 8))
+    assert abs(np.sum(O.rope_fwd(x, 100.0) * dy) - np.sum(x * O.rope_bwd(dy, 100.0))) < 1e-12
+
+
+# ---------------------------------------------------------------- RMSNorm / SwiGLU
+def test_rmsnorm_unit_rms_scale_invariance_and_library():
+    rng = np.random.default_rng(4)
+    h, g, dy = rng.standard_normal((6, 10)) * 3, rng.standard_normal(10), rng.standard_normal((6, 10))
+    y = O.rmsnorm_fwd(h, np.ones(10), 0.0)
+    assert np.allclose(np.sqrt(np.mean(y * y, -1)), 1.0)
+    assert np.allclose(O.rmsnorm_fwd(5.0 * h, g, 0.0), O.rmsnorm_fwd(h, g, 0.0))
+    dh = O.rmsnorm_bwd(dy, h, g, 0.0)
+    assert np.allclose(np.sum(h * dh, -1), 0.0, atol=1e-12)   # scale invariance => h . dh = 0
+    ht = torch.tensor(h, requires_grad=True)
+    yt = F.rms_norm(ht, (10,), torch.tensor(g), eps=1e-5)
+    yt.backward(torch.tensor(dy))
+    assert _rel(O.rmsnorm_fwd(h, g, 1e-5), yt.detach().numpy()) < 1e-14
+    assert _rel(O.rmsnorm_bwd(dy, h, g, 1e-5), ht.grad.numpy()) < 1e-13
+
+
+def test_swiglu_matches_library_and_autograd():
+    rng = np.random.default_rng(6)
+    g, u, da = (rng.standard_normal((4, 9)) * 2 for _ in range(3))
+    gt, ut = torch.tensor(g, requires_grad=True), torch.tensor(u, requires_grad=True)
+    a = F.silu(gt) * ut
+    a.backward(torch.tensor(da))
+    assert _rel(O.swiglu_fwd(g, u), a.detach().numpy()) < 1e-14
+    dg, du = O.swiglu_bwd(da, g, u)
+    assert _rel(dg, gt.grad.numpy()) < 1e-13 and _rel(du, ut.grad.numpy()) < 1e-13
+
+
+# ---------------------------------------------------------------- attention
+def test_attention_zero_queries_give_running_mean_of_values():
+    rng = np.random.default_rng(8)
+    T, nh, dh = 7, 2, 4
+    k, v = rng.standard_normal((T, nh, dh)), rng.standard_normal((T, nh, dh))
+    o, P = O.attention_fwd(np.zeros((T, nh, dh)), k, v)
+    exp = np.cumsum(v, axis=0) / np.arange(1, T + 1)[:, None, None]
+    assert np.allclose(o, exp)
+    assert np.allclose(P.sum(-1), 1.0)
+    assert np.all(P[:, np.triu_indices(T, 1)[0], np.triu_indices(T, 1)[1]] == 0)
+
+
+def test_attention_matches_library_sdpa_and_autograd():
+    rng = np.random.default_rng(9)
+    T, nh, dh = 11, 3, 8
+    q, k, v, do = (rng.standard_normal((T, nh, dh)) for _ in range(4))
+    o, P = O.attention_fwd(q, k, v)
+    dq, dk, dv = O.attention_bwd(do, q, k, v, P)
+    tq, tk, tv = (torch.tensor(x.transpose(1, 0, 2).copy(), requires_grad=True) for x in (q, k, v))
+    to = F.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    to.backward(torch.tensor(do.transpose(1, 0, 2).copy()))
+    assert _rel(o, to.detach().numpy().transpose(1, 0, 2)) < 1e-13
+    for a, b in ((dq, tq), (dk, tk), (dv, tv)):
+        assert _rel(a, b.grad.numpy().transpose(1, 0, 2)) < 1e-12
+
+
+def test_attention_is_causal():
+    rng = np.random.default_rng(10)
+    q, k, v = (rng.standard_normal((6, 1, 4)) for _ in range(3))
+    o1, _ = O.attention_fwd(q, k, v)
+    k2, v2 = k.copy(), v.copy()
+    k2[4:] += 1.0
+    v2[4:] -= 2.0
+    o2, _ = O.attention_fwd(q, k2, v2)
+    assert np.array_equal(o1[:4], o2[:4]) and not np.allclose(o1[4:], o2[4:])
+
+
+# ---------------------------------------------------------------- whole model
+def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape):
+    """The same network written as an independent autograd graph with library ops.
+
+    RoPE is formed as a complex multiplication by exp(i p theta) (a different
+    formulation from the oracle's cos/sin pair update).
+    """
+    t64 = lambda x: torch.tensor(np.asarray(x, np.float64))
+    T = len(tok)
+    nh, dh, s = shape.n_heads, shape.d_head, shape.scale
+    params = []
+    h = t64(emb)[torch.tensor(np.asarray(tok, np.int64))]
+    theta = shape.rope_base ** (-torch.arange(0, dh, 2, dtype=torch.float64) / dh)
+    rot = torch.polar(torch.ones(T, dh // 2, dtype=torch.float64),
+                      torch.arange(T, dtype=torch.float64)[:, None] * theta[None])
+
+    def rope(x):
+        x = x.view(T, nh, dh)
+        z = torch.complex(x[..., : dh // 2], x[..., dh // 2:]) * rot[:, None, :]
+        return torch.cat([z.real, z.imag], -1)
+
+    def lin(x, W, AB):
+        A = t64(AB[0]).requires_grad_()
+        B = t64(AB[1]).requires_grad_()
+        params.append((A, B))
+        return F.linear(x, t64(W)) + s * F.linear(F.linear(x, A), B)
+
+    for l in range(shape.n_layers):
+        W, L = Ws[l], lora[l]
+        x1 = F.rms_norm(h, (shape.d_model,), t64(W["g1"]), eps=shape.rms_eps)
+        q, k, v = lin(x1, W["q"], L["q"]), lin(x1, W["k"], L["k"]), lin(x1, W["v"], L["v"])
+        q, k, v = rope(q), rope(k), v.view(T, nh, dh)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1), k.transpose(0, 1), v.transpose(0, 1),
+                                           is_causal=True).transpose(0, 1).reshape(T, nh * dh)
+        h = h + lin(o, W["o"], L["o"])
+        x2 = F.rms_norm(h, (shape.d_model,), t64(W["g2"]), eps=shape.rms_eps)
+        a = F.silu(lin(x2, W["gate"], L["gate"])) * lin(x2, W["up"], L["up"])
+        h = h + lin(a, W["down"], L["down"])
+    hf = F.rms_norm(h, (shape.d_model,), t64(gf), eps=shape.rms_eps)
+    logits = F.linear(hf, t64(head))
+    lab = torch.full((T,), -100, dtype=torch.int64)
+    first = max(n_ctx, 1) - 1
+    lab[first: T - 1] = torch.tensor(np.asarray(tok[first + 1:], np.int64))
+    loss = F.cross_entropy(logits, lab, ignore_index=-100)
+    return loss, params
+
+
+@pytest.mark.parametrize("n_ctx", [0, 4])
+def test_model_matches_independent_autograd_graph(n_ctx):
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    res = _run(Ws, lora, emb, head, gf, tok, n_ctx)
+    loss, params = _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, TINY)
+    loss.backward()
+    assert abs(res["loss"] - loss.item()) < 1e-12 * max(1, abs(loss.item()))
+    it = iter(params)
+    for l in range(TINY.n_layers):
+        for p in PROJ:
+            A, B = next(it)
+            assert _rel(res["grads"][l][p][0], A.grad.numpy()) < 1e-10, (l, p, "dA")
+            assert _rel(res["grads"][l][p][1], B.grad.numpy()) < 1e-10, (l, p, "dB")
+
+
+def test_model_finite_differences_on_factors():
+    Ws, lora, emb, head, gf, tok = _tiny_model(n_tokens=8)
+    res = _run(Ws, lora, emb, head, gf, tok)
+    rng = np.random.default_rng(0)
+    eps = 1e-5
+    for l in range(TINY.n_layers):
+        for p in PROJ:
+            for which in (0, 1):
+                arr = lora[l][p][which]
+                for _ in range(2):
+                    idx = tuple(rng.integers(0, n) for n in arr.shape)
+                    vals = []
+                    for sgn in (+1, -1):
+                        pert = arr.astype(np.float64).copy()
+                        pert[idx] += sgn * eps
+                        lora2 = [dict(L) for L in lora]
+                        ab = list(lora2[l][p])
+                        ab[which] = pert
+                        lora2[l][p] = tuple(ab)
+                        vals.append(_run(Ws, lora2, emb, head, gf, tok)["loss"])
+                    num = (vals[0] - vals[1]) / (2 * eps)
+                    ana = res["grads"][l][p][which][idx]
+                    assert abs(num - ana) < 1e-7 * max(1.0, abs(ana) * 100), (l, p, which, num, ana)
+
+
+def test_model_b_zero_equals_base_and_zero_dA():
+    Ws, lora, emb, head, gf, tok = _tiny_model(b_std=0.0)
+    res = _run(Ws, lora, emb, head, gf, tok)
+    # base model: rank-1 all-zero factors
+    zero = [{p: (np.zeros((1, TINY.proj_dims(p)[1])), np.zeros((TINY.proj_dims(p)[0], 1))) for p in PROJ}
+            for _ in range(TINY.n_layers)]
+    base = _run(Ws, zero, emb, head, gf, tok)
+    assert res["loss"] == base["loss"] and np.array_equal(res["logits"], base["logits"])
+    for l in range(TINY.n_layers):
+        for p in PROJ:
+            assert np.all(res["grads"][l][p][0] == 0.0)
+            assert np.linalg.norm(res["grads"][l][p][1]) > 0
+
+
+def test_model_merged_weights_same_logits():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    res = _run(Ws, lora, emb, head, gf, tok)
+    Wm = []
+    for l in range(TINY.n_layers):
+        W = dict(Ws[l])
+        for p in PROJ:
+            A, B = lora[l][p]
+            W[p] = W[p].astype(np.float64) + TINY.scale * B.astype(np.float64) @ A.astype(np.float64)
+        Wm.append(W)
+    zero = [{p: (lora[l][p][0], np.zeros_like(lora[l][p][1])) for p in PROJ} for l in range(TINY.n_layers)]
+    merged = _run(Wm, zero, emb, head, gf, tok)
+    assert _rel(res["logits"], merged["logits"]) < 1e-13
+    assert abs(res["loss"] - merged["loss"]) < 1e-13
+
+
+def test_model_causality_of_per_token_nll():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    a = _run(Ws, lora, emb, head, gf, tok)["nll"]
+    tok2 = tok.copy()
+    u = 6
+    tok2[u] = (tok2[u] + 1) % TINY.vocab
+    b = _run(Ws, lora, emb, head, gf, tok2)["nll"]
+    assert np.array_equal(a[: u - 1], b[: u - 1])      # nll_t for t < u-1 untouched
+    assert a[u - 1] != b[u - 1]                        # label of position u-1 changed
+
+
+def test_model_random_init_loss_band():
+    # logits of a random-init net are roughly N(0, sigma^2): loss ~ ln V + sigma^2 / 2
+    shape = synth.SHAPES["small"]
+    Ws = [synth.layer_weights(1, shape, l) for l in range(shape.n_layers)]
+    lora = [synth.lora_factors(1, shape, l) for l in range(shape.n_layers)]
+    emb, head = synth.embedding(1, shape), synth.lm_head(1, shape)
+    tok = synth.uniform_tokens(1, 48, shape.vocab)
+    res = O.model_fwd_bwd(tok, 0, shape, emb, head, np.ones(shape.d_model), lambda l: Ws[l], lora)
+    sig2 = shape.d_model * 0.02 ** 2
+    assert abs(res["loss"] - (math.log(shape.vocab) + sig2 / 2)) < 0.15
+    assert res["n_targets"] == 47
+
+
+def test_chunk_update_state_and_descent():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    opt = O.new_opt_state(lora)
+    get = lambda l: Ws[l]
+    r0, l0, o0 = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, opt, lr=0.0)
+    r1, _, o1 = O.chunk_update(tok, 0, TINY, emb, head, gf, get, l0, o0, lr=0.0)
+    assert r0["loss"] == r1["loss"] and o1["tau"] == 2
+    rA, lA, oA = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, opt, lr=1e-3)
+    rB, _, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lA, oA, lr=1e-3)
+    assert rB["loss"] < rA["loss"]                     # second epoch on the same chunk descends
+    # first step moves every factor entry with a non-zero gradient by ~lr
+    for l in range(TINY.n_layers):
+        for p in PROJ:
+            for i in (0, 1):
+                g = rA["grads"][l][p][i]
+                d = lA[l][p][i] - lora[l][p][i]
+                big = np.abs(g) > 1e-4
+                assert np.allclose(d[big], -1e-3 * np.sign(g[big]), rtol=1e-3)
+
+
+def test_chunk_update_rejects_bad_tokens():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    bad = tok.copy()
+    bad[3] = TINY.vocab
+    with pytest.raises(ValueError):
+        _run(Ws, lora, emb, head, gf, bad)
+
+
+def test_layer_dh_matches_autograd():
+    # gradient w.r.t. the hidden state entering a layer (the dX the GPU path is compared on)
+    shape = TINY.with_layers(1)
+    Ws, lora, emb, head, gf, tok = _tiny_model(shape=shape)
+    T = 9
+    h = synth.hidden(3, T, shape.d_model)
+    dy = synth.upstream_grad(3, T, shape.d_model)
+    out, c = O.layer_fwd(h, Ws[0], lora[0], shape)
+    dh, G = O.layer_bwd(dy, c, Ws[0], lora[0], shape)
+    eps = 1e-6
+    rng = np.random.default_rng(1)
+    for _ in range(6):
+        idx = (rng.integers(0, T), rng.integers(0, shape.d_model))
+        hp, hm = h.astype(np.float64).copy(), h.astype(np.float64).copy()
+        hp[idx] += eps
+        hm[idx] -= eps
+        num = (np.sum(O.layer_fwd(hp, Ws[0], lora[0], shape)[0] * dy)
+               - np.sum(O.layer_fwd(hm, Ws[0], lora[0], shape)[0] * dy)) / (2 * eps)
+        assert abs(num - dh[idx]) < 1e-6 * max(1.0, abs(dh[idx]))
