@@ -137,27 +137,36 @@ def swiglu_bwd(da, g, u):
 # Causal self-attention within the call's tokens.
 # --------------------------------------------------------------------------
 def attention_fwd(q, k, v):
-    """q, k, v [T, n_heads, d_head] -> (o [T, n_heads, d_head], P [n_heads, T, T])."""
+    """q, k, v [T, n_heads, d_head] -> (o [T, n_heads, d_head], P [n_heads, T, T]).
+
+    Per head: S = q k^T / sqrt(d_head), S_tu = -inf for u > t, P = softmax over u, o = P v.
+    """
     q, k, v = _f(q), _f(k), _f(v)
     T, nh, dh = q.shape
-    S = np.einsum("thd,uhd->htu", q, k) / np.sqrt(dh)
     future = np.triu(np.ones((T, T), dtype=bool), k=1)
-    S = np.where(future[None], -np.inf, S)
-    S = S - S.max(axis=-1, keepdims=True)
-    P = np.exp(S)
-    P /= P.sum(axis=-1, keepdims=True)
-    o = np.einsum("htu,uhd->thd", P, v)
+    P = np.empty((nh, T, T), dtype=F64)
+    o = np.empty((T, nh, dh), dtype=F64)
+    for h in range(nh):
+        S = (q[:, h, :] @ k[:, h, :].T) / np.sqrt(dh)
+        S[future] = -np.inf
+        S -= S.max(axis=-1, keepdims=True)
+        E = np.exp(S)
+        P[h] = E / E.sum(axis=-1, keepdims=True)
+        o[:, h, :] = P[h] @ v[:, h, :]
     return o, P
 
 
 def attention_bwd(do, q, k, v, P):
+    """dv = P^T do; dP = do v^T; dS = P * (dP - rowsum(dP * P)); dq = dS k / sqrt(d); dk = dS^T q / sqrt(d)."""
     do, q, k, v = _f(do), _f(q), _f(k), _f(v)
-    dh = q.shape[-1]
-    dv = np.einsum("htu,thd->uhd", P, do)
-    dP = np.einsum("thd,uhd->htu", do, v)
-    dS = P * (dP - np.sum(dP * P, axis=-1, keepdims=True))
-    dq = np.einsum("htu,uhd->thd", dS, k) / np.sqrt(dh)
-    dk = np.einsum("htu,thd->uhd", dS, q) / np.sqrt(dh)
+    T, nh, dh = q.shape
+    dq, dk, dv = np.empty_like(q), np.empty_like(k), np.empty_like(v)
+    for h in range(nh):
+        dv[:, h, :] = P[h].T @ do[:, h, :]
+        dP = do[:, h, :] @ v[:, h, :].T
+        dS = P[h] * (dP - np.sum(dP * P[h], axis=-1, keepdims=True))
+        dq[:, h, :] = (dS @ k[:, h, :]) / np.sqrt(dh)
+        dk[:, h, :] = (dS.T @ q[:, h, :]) / np.sqrt(dh)
     return dq, dk, dv
 
 

@@ -1,0 +1,423 @@
+// Causal self-attention within one chunk, forward and backward, on bf16 MFMA (gfx950).
+//
+// All three kernels work on the TRANSPOSED score tile where that keeps the softmax row in one lane:
+//   forward / dQ :  S^T[u][t] = K[u] . Q[t]   -> a lane owns one query t (and its partner lane t too),
+//                   so the running max, the row sum, lse[t] and delta[t] are per-lane scalars;
+//                   O^T[d][t] += V^T[d][u] P^T[u][t]   and   dQ^T[d][t] += K^T[d][u] dS^T[u][t]
+//                   reuse the score fragment directly as the B operand (see tiles.h).
+//   dK / dV      :  S[t][u] = Q[t] . K[u]     -> a lane owns one key u;
+//                   dV^T[d][u] += dO^T[d][t] P[t][u],  dK^T[d][u] += Q^T[d][t] dS[t][u].
+// P is never stored: the backward kernels rebuild it from the saved log-sum-exp.
+// The two backward kernels write disjoint outputs, so no atomics are needed and results are
+// bit-reproducible.
+#include "kernels.h"
+#include "tiles.h"
+
+#define NEG_BIG (-1.0e30f)
+
+template <int DH>
+struct AttnCfg {
+    static constexpr int LSK = DH + 8;  // row stride of a [row][d] tile
+    static constexpr int NKS = DH / 16; // MFMA steps over d
+    static constexpr int ND = DH / 32;  // 32-wide d tiles
+};
+
+// load a [64 rows][DH] tile (rows r0.., zero beyond T) into a padded LDS tile
+template <int DH>
+__device__ __forceinline__ void load_tile_regs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs) {
+    constexpr int CH = DH / 8;  // chunks per row
+#pragma unroll
+    for (int i = 0; i < DH / 32; ++i) {
+        const int c = threadIdx.x + 256 * i, row = c / CH, ch = c % CH;
+        regs[i] = (r0 + row < T) ? *(const uint4*)(base + (long)(r0 + row) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
+    }
+}
+template <int DH>
+__device__ __forceinline__ void store_tile_normal(bf16_t* tile, const uint4* regs) {
+    constexpr int CH = DH / 8;
+#pragma unroll
+    for (int i = 0; i < DH / 32; ++i) {
+        const int c = threadIdx.x + 256 * i, row = c / CH, ch = c % CH;
+        *(uint4*)(tile + row * AttnCfg<DH>::LSK + ch * 8) = regs[i];
+    }
+}
+// the same tile as row pairs for the transposing store: unit = (row pair, 8-column chunk)
+template <int DH>
+__device__ __forceinline__ void load_tile_pairs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs) {
+    constexpr int CH = DH / 8;
+#pragma unroll
+    for (int i = 0; i < DH / 64; ++i) {
+        const int c = threadIdx.x + 256 * i, rp = c / CH, ch = c % CH;
+        const int r = r0 + 2 * rp;
+        regs[2 * i] = (r < T) ? *(const uint4*)(base + (long)r * ld + ch * 8) : make_uint4(0, 0, 0, 0);
+        regs[2 * i + 1] = (r + 1 < T) ? *(const uint4*)(base + (long)(r + 1) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
+    }
+}
+template <int DH>
+__device__ __forceinline__ void store_tile_transposed(bf16_t* tile, const uint4* regs) {
+    constexpr int CH = DH / 8;
+#pragma unroll
+    for (int i = 0; i < DH / 64; ++i) {
+        const int c = threadIdx.x + 256 * i, rp = c / CH, ch = c % CH;
+        store_transposed_pair(tile, ch * 8, 2 * rp, regs[2 * i], regs[2 * i + 1]);
+    }
+}
+
+// write a D fragment set holding X^T[d][row] (lane = row) as bf16 rows of X
+template <int DH>
+__device__ __forceinline__ void write_rows_from_dT(bf16_t* __restrict__ dst, const f32x16_t* acc, float mul, int g) {
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+            uint2 w;
+            w.x = pack_bf16x2(acc[dt][4 * vq] * mul, acc[dt][4 * vq + 1] * mul);
+            w.y = pack_bf16x2(acc[dt][4 * vq + 2] * mul, acc[dt][4 * vq + 3] * mul);
+            *(uint2*)(dst + dt * 32 + 8 * vq + 4 * g) = w;
+        }
+}
+
+// ======================================================================== forward
+template <int DH>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                       const bf16_t* __restrict__ v, long ldq, int T,
+                                                       bf16_t* __restrict__ o, long ldo, float* __restrict__ lse,
+                                                       float scale_log2e) {
+    using C = AttnCfg<DH>;
+    __shared__ __align__(16) bf16_t sK[64 * C::LSK];
+    __shared__ __align__(16) bf16_t sVt[DH * LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int qb = gridDim.x - 1 - blockIdx.x;  // heaviest (latest) query blocks first
+    const int head = blockIdx.y;
+    const int q0 = qb * 128, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
+    const bf16_t* qh = q + (long)head * DH;
+    const bf16_t* kh = k + (long)head * DH;
+    const bf16_t* vh = v + (long)head * DH;
+
+    bf16x8_t qf[C::NKS];
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks) {
+        uint4 r = (t_abs < T) ? *(const uint4*)(qh + (long)t_abs * ldq + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
+        qf[ks] = *(bf16x8_t*)&r;
+    }
+    f32x16_t oacc[C::ND];
+#pragma unroll
+    for (int dt = 0; dt < C::ND; ++dt) oacc[dt] = zero16();
+    float m = NEG_BIG, lpart = 0.f;
+
+    const int kend = min(q0 + 128, T);
+    const int n_tiles = (kend + 63) / 64;
+    uint4 rk[DH / 32], rv[DH / 32];
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int u0 = tile * 64;
+        load_tile_regs<DH>(kh, ldq, u0, T, rk);
+        load_tile_pairs<DH>(vh, ldq, u0, T, rv);
+        __syncthreads();
+        store_tile_normal<DH>(sK, rk);
+        store_tile_transposed<DH>(sVt, rv);
+        __syncthreads();
+        if (u0 > tq0 + 31) continue;  // wave-uniform: every key of this tile is in the future
+#pragma unroll
+        for (int us = 0; us < 2; ++us) {
+            const int usub0 = u0 + us * 32;
+            if (usub0 > tq0 + 31) continue;
+            f32x16_t sacc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < C::NKS; ++ks) {
+                bf16x8_t a = *(const bf16x8_t*)(sK + (us * 32 + l32) * C::LSK + ks * 16 + g * 8);
+                sacc = mfma32(a, qf[ks], sacc);
+            }
+            float x[16];
+            float mloc = NEG_BIG;
+#pragma unroll
+            for (int vv = 0; vv < 16; ++vv) {
+                const int u = usub0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
+                x[vv] = (u > t_abs) ? NEG_BIG : sacc[vv] * scale_log2e;
+                mloc = fmaxf(mloc, x[vv]);
+            }
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            const float m_new = fmaxf(m, mloc);
+            const float alpha = exp2f(m - m_new);
+            float psum = 0.f;
+#pragma unroll
+            for (int vv = 0; vv < 16; ++vv) {
+                x[vv] = exp2f(x[vv] - m_new);
+                psum += x[vv];
+            }
+            lpart = lpart * alpha + psum;
+            m = m_new;
+#pragma unroll
+            for (int dt = 0; dt < C::ND; ++dt)
+#pragma unroll
+                for (int vv = 0; vv < 16; ++vv) oacc[dt][vv] *= alpha;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const bf16x8_t b = pack_b_from_d(x, h);
+#pragma unroll
+                for (int dt = 0; dt < C::ND; ++dt) {
+                    const bf16x8_t a = load_a_permuted(sVt, dt * 32 + l32, us * 32 + 16 * h, g);
+                    oacc[dt] = mfma32(a, b, oacc[dt]);
+                }
+            }
+        }
+    }
+    const float ltot = lpart + __shfl_xor(lpart, 32, 64);
+    if (t_abs < T) {
+        write_rows_from_dT<DH>(o + (long)t_abs * ldo + (long)head * DH, oacc, 1.f / ltot, g);
+        if (g == 0) lse[(long)head * T + t_abs] = (m + log2f(ltot)) * 0.6931471805599453f;
+    }
+}
+
+// ======================================================================== delta = rowsum(dO * O)
+__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
+                                                         long ldo, int T, int n_heads, int d_head,
+                                                         float* __restrict__ delta) {
+    const int t = blockIdx.x;
+    const int sub = d_head >> 3;  // lanes per head
+    const int chunks = n_heads * sub;
+    for (int c = threadIdx.x; c < ((chunks + 63) & ~63); c += blockDim.x) {
+        float s = 0.f;
+        if (c < chunks) {
+            uint4 a = *(const uint4*)(o + (long)t * ldo + c * 8);
+            uint4 b = *(const uint4*)(d_o + (long)t * ldo + c * 8);
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                s += bf16_to_f32(aw[e] & 0xffff) * bf16_to_f32(bw[e] & 0xffff) +
+                     bf16_to_f32(aw[e] >> 16) * bf16_to_f32(bw[e] >> 16);
+        }
+        for (int off = sub >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (c < chunks && (c % sub) == 0) delta[(long)(c / sub) * T + t] = s;
+    }
+}
+
+// ======================================================================== backward: dQ
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                          const bf16_t* __restrict__ v,
+                                                          const bf16_t* __restrict__ d_o,
+                                                          const float* __restrict__ lse,
+                                                          const float* __restrict__ delta, long ldq, long ldo, int T,
+                                                          bf16_t* __restrict__ dq, float scale) {
+    using C = AttnCfg<DH>;
+    __shared__ __align__(16) bf16_t sK[64 * C::LSK];
+    __shared__ __align__(16) bf16_t sV[64 * C::LSK];
+    __shared__ __align__(16) bf16_t sKt[DH * LS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int qb = gridDim.x - 1 - blockIdx.x;
+    const int head = blockIdx.y;
+    const int q0 = qb * 128, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const bf16_t* qh = q + (long)head * DH;
+    const bf16_t* kh = k + (long)head * DH;
+    const bf16_t* vh = v + (long)head * DH;
+    const bf16_t* doh = d_o + (long)head * DH;
+
+    bf16x8_t qf[C::NKS], dof[C::NKS];
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks) {
+        uint4 r = (t_abs < T) ? *(const uint4*)(qh + (long)t_abs * ldq + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
+        qf[ks] = *(bf16x8_t*)&r;
+        uint4 r2 = (t_abs < T) ? *(const uint4*)(doh + (long)t_abs * ldo + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
+        dof[ks] = *(bf16x8_t*)&r2;
+    }
+    const float lse2 = (t_abs < T) ? lse[(long)head * T + t_abs] * 1.4426950408889634f : 1.0e30f;
+    const float dlt = (t_abs < T) ? delta[(long)head * T + t_abs] : 0.f;
+    f32x16_t acc[C::ND];
+#pragma unroll
+    for (int dt = 0; dt < C::ND; ++dt) acc[dt] = zero16();
+
+    const int kend = min(q0 + 128, T);
+    const int n_tiles = (kend + 63) / 64;
+    uint4 rk[DH / 32], rv[DH / 32], rkp[DH / 32];
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int u0 = tile * 64;
+        load_tile_regs<DH>(kh, ldq, u0, T, rk);
+        load_tile_regs<DH>(vh, ldq, u0, T, rv);
+        load_tile_pairs<DH>(kh, ldq, u0, T, rkp);
+        __syncthreads();
+        store_tile_normal<DH>(sK, rk);
+        store_tile_normal<DH>(sV, rv);
+        store_tile_transposed<DH>(sKt, rkp);
+        __syncthreads();
+        if (u0 > tq0 + 31) continue;
+#pragma unroll
+        for (int us = 0; us < 2; ++us) {
+            const int usub0 = u0 + us * 32;
+            if (usub0 > tq0 + 31) continue;
+            f32x16_t sacc = zero16(), dpacc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < C::NKS; ++ks) {
+                bf16x8_t a = *(const bf16x8_t*)(sK + (us * 32 + l32) * C::LSK + ks * 16 + g * 8);
+                sacc = mfma32(a, qf[ks], sacc);
+                bf16x8_t b = *(const bf16x8_t*)(sV + (us * 32 + l32) * C::LSK + ks * 16 + g * 8);
+                dpacc = mfma32(b, dof[ks], dpacc);
+            }
+            float ds[16];
+#pragma unroll
+            for (int vv = 0; vv < 16; ++vv) {
+                const int u = usub0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
+                const float p = (u > t_abs) ? 0.f : exp2f(sacc[vv] * scale_log2e - lse2);
+                ds[vv] = p * (dpacc[vv] - dlt);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const bf16x8_t b = pack_b_from_d(ds, h);
+#pragma unroll
+                for (int dt = 0; dt < C::ND; ++dt) {
+                    const bf16x8_t a = load_a_permuted(sKt, dt * 32 + l32, us * 32 + 16 * h, g);
+                    acc[dt] = mfma32(a, b, acc[dt]);
+                }
+            }
+        }
+    }
+    if (t_abs < T) write_rows_from_dT<DH>(dq + (long)t_abs * ldq + (long)head * DH, acc, scale, g);
+}
+
+// ======================================================================== backward: dK, dV
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                           const bf16_t* __restrict__ v,
+                                                           const bf16_t* __restrict__ d_o,
+                                                           const float* __restrict__ lse,
+                                                           const float* __restrict__ delta, long ldq, long ldo, int T,
+                                                           bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
+                                                           float scale) {
+    using C = AttnCfg<DH>;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* sQ = (bf16_t*)smem;             // [64][LSK]
+    bf16_t* sdO = sQ + 64 * C::LSK;         // [64][LSK]
+    bf16_t* sQt = sdO + 64 * C::LSK;        // [DH][LS]
+    bf16_t* sdOt = sQt + DH * LS;           // [DH][LS]
+    float* sLse = (float*)(sdOt + DH * LS); // [64]
+    float* sDelta = sLse + 64;              // [64]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int kb = blockIdx.x;  // early key blocks see the most queries and are scheduled first
+    const int head = blockIdx.y;
+    const int u0 = kb * 128, uw0 = u0 + 32 * wave, u_abs = uw0 + l32;
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const bf16_t* qh = q + (long)head * DH;
+    const bf16_t* kh = k + (long)head * DH;
+    const bf16_t* vh = v + (long)head * DH;
+    const bf16_t* doh = d_o + (long)head * DH;
+
+    bf16x8_t kf[C::NKS], vf[C::NKS];
+#pragma unroll
+    for (int ks = 0; ks < C::NKS; ++ks) {
+        uint4 r = (u_abs < T) ? *(const uint4*)(kh + (long)u_abs * ldq + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
+        kf[ks] = *(bf16x8_t*)&r;
+        uint4 r2 = (u_abs < T) ? *(const uint4*)(vh + (long)u_abs * ldq + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
+        vf[ks] = *(bf16x8_t*)&r2;
+    }
+    f32x16_t dkacc[C::ND], dvacc[C::ND];
+#pragma unroll
+    for (int dt = 0; dt < C::ND; ++dt) { dkacc[dt] = zero16(); dvacc[dt] = zero16(); }
+
+    const int n_tiles = (T + 63) / 64;
+    uint4 rq[DH / 32], rdo[DH / 32], rqp[DH / 32], rdop[DH / 32];
+    for (int tile = u0 / 64; tile < n_tiles; ++tile) {
+        const int t0 = tile * 64;
+        load_tile_regs<DH>(qh, ldq, t0, T, rq);
+        load_tile_regs<DH>(doh, ldo, t0, T, rdo);
+        load_tile_pairs<DH>(qh, ldq, t0, T, rqp);
+        load_tile_pairs<DH>(doh, ldo, t0, T, rdop);
+        float lse_v = 0.f, dl_v = 0.f;
+        if (tid < 64) {
+            const int t = t0 + tid;
+            lse_v = (t < T) ? lse[(long)head * T + t] * 1.4426950408889634f : 1.0e30f;
+            dl_v = (t < T) ? delta[(long)head * T + t] : 0.f;
+        }
+        __syncthreads();
+        store_tile_normal<DH>(sQ, rq);
+        store_tile_normal<DH>(sdO, rdo);
+        store_tile_transposed<DH>(sQt, rqp);
+        store_tile_transposed<DH>(sdOt, rdop);
+        if (tid < 64) { sLse[tid] = lse_v; sDelta[tid] = dl_v; }
+        __syncthreads();
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) {
+            const int tsub0 = t0 + ts * 32;
+            if (tsub0 + 31 < uw0) continue;  // wave-uniform: every query of this sub-tile precedes every key
+            f32x16_t sacc = zero16(), dpacc = zero16();
+#pragma unroll
+            for (int ks = 0; ks < C::NKS; ++ks) {
+                bf16x8_t a = *(const bf16x8_t*)(sQ + (ts * 32 + l32) * C::LSK + ks * 16 + g * 8);
+                sacc = mfma32(a, kf[ks], sacc);
+                bf16x8_t b = *(const bf16x8_t*)(sdO + (ts * 32 + l32) * C::LSK + ks * 16 + g * 8);
+                dpacc = mfma32(b, vf[ks], dpacc);
+            }
+            float p[16], ds[16];
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int tl = ts * 32 + 8 * vq + 4 * g;
+                const float4 l4 = *(const float4*)(sLse + tl);
+                const float4 d4 = *(const float4*)(sDelta + tl);
+                const float ll[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int vv = 4 * vq + e;
+                    const int t = t0 + tl + e;
+                    const float pv = (u_abs > t) ? 0.f : exp2f(sacc[vv] * scale_log2e - ll[e]);
+                    p[vv] = pv;
+                    ds[vv] = pv * (dpacc[vv] - dd[e]);
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const bf16x8_t bp = pack_b_from_d(p, h);
+                const bf16x8_t bs = pack_b_from_d(ds, h);
+#pragma unroll
+                for (int dt = 0; dt < C::ND; ++dt) {
+                    const bf16x8_t a1 = load_a_permuted(sdOt, dt * 32 + l32, ts * 32 + 16 * h, g);
+                    dvacc[dt] = mfma32(a1, bp, dvacc[dt]);
+                    const bf16x8_t a2 = load_a_permuted(sQt, dt * 32 + l32, ts * 32 + 16 * h, g);
+                    dkacc[dt] = mfma32(a2, bs, dkacc[dt]);
+                }
+            }
+        }
+    }
+    if (u_abs < T) {
+        write_rows_from_dT<DH>(dk + (long)u_abs * ldq + (long)head * DH, dkacc, scale, g);
+        write_rows_from_dT<DH>(dv + (long)u_abs * ldq + (long)head * DH, dvacc, 1.f, g);
+    }
+}
+
+// ======================================================================== launchers
+hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ldq, int T, int n_heads,
+                                int d_head, bf16_t* o, long ldo, float* lse, hipStream_t s) {
+    if (T <= 0 || n_heads <= 0) return hipSuccess;
+    if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
+    const float sl2 = (1.f / sqrtf((float)d_head)) * 1.4426950408889634f;
+    dim3 grid(cdiv(T, 128), n_heads);
+    if (d_head == 128) attn_fwd_kernel<128><<<grid, 256, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
+    else if (d_head == 64) attn_fwd_kernel<64><<<grid, 256, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+template <int DH>
+static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* d_o, const float* lse,
+                          const float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
+                          bf16_t* dv, hipStream_t s) {
+    using C = AttnCfg<DH>;
+    const float scale = 1.f / sqrtf((float)DH);
+    dim3 grid(cdiv(T, 128), n_heads);
+    attn_bwd_dq_kernel<DH><<<grid, 256, 0, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, scale);
+    const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LS) * sizeof(bf16_t) + 128 * sizeof(float);
+    auto kern = attn_bwd_dkv_kernel<DH>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, 256, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
+                                const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
+                                bf16_t* dk, bf16_t* dv, float* delta, hipStream_t s) {
+    if (T <= 0 || n_heads <= 0) return hipSuccess;
+    if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
+    attn_delta_kernel<<<T, 256, 0, s>>>(o, d_o, ldo, T, n_heads, d_head, delta);
+    if (d_head == 128) return run_bwd<128>(q, k, v, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, s);
+    if (d_head == 64) return run_bwd<64>(q, k, v, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, s);
+    return hipErrorInvalidValue;
+}

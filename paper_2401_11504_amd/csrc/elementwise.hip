@@ -1,0 +1,475 @@
+// Bandwidth-bound kernels of the Temp-Lora chunk update: RMSNorm, RoPE, SwiGLU,
+// embedding gather, fused softmax cross-entropy, fused AdamW, and layout helpers.
+// Every kernel streams its operands once with 16-byte accesses where the layout allows.
+#include "kernels.h"
+
+// ---------------------------------------------------------------- RMSNorm
+// One block per token row.  y = h * rsqrt(mean(h^2) + eps) * g   (Llama2 decoder norm).
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ h, const float* __restrict__ g,
+                                                          int d, float eps, bf16_t* __restrict__ y) {
+    __shared__ float red[16];
+    const long row = blockIdx.x;
+    const float4* hp = (const float4*)(h + row * d);
+    const float4* gp = (const float4*)g;
+    const int n4 = d >> 2;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+        float4 x = hp[i];
+        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    }
+    ss = block_sum(ss, red);
+    const float rho = rsqrtf(ss / (float)d + eps);
+    uint2* yp = (uint2*)(y + row * d);
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+        float4 x = hp[i];
+        float4 w = gp[i];
+        uint2 o;
+        o.x = pack_bf16x2(x.x * rho * w.x, x.y * rho * w.y);
+        o.y = pack_bf16x2(x.z * rho * w.z, x.w * rho * w.w);
+        yp[i] = o;
+    }
+}
+
+// dh_out = dres + rho (g*dy) - h rho^3 mean(h g dy); gain is frozen, so no gain gradient.
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restrict__ dy, const float* __restrict__ h,
+                                                          const float* __restrict__ g, const float* __restrict__ dres,
+                                                          int d, float eps, float* __restrict__ dh_out,
+                                                          bf16_t* __restrict__ dh_bf) {
+    __shared__ float red[16];
+    const long row = blockIdx.x;
+    const float4* hp = (const float4*)(h + row * d);
+    const float4* gp = (const float4*)g;
+    const uint2* dp = (const uint2*)(dy + row * d);
+    const int n4 = d >> 2;
+    float ss = 0.f, dot = 0.f;
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+        float4 x = hp[i];
+        float4 w = gp[i];
+        uint2 r = dp[i];
+        float d0 = bf16_to_f32(r.x & 0xffff), d1 = bf16_to_f32(r.x >> 16);
+        float d2 = bf16_to_f32(r.y & 0xffff), d3 = bf16_to_f32(r.y >> 16);
+        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        dot += x.x * w.x * d0 + x.y * w.y * d1 + x.z * w.z * d2 + x.w * w.w * d3;
+    }
+    ss = block_sum(ss, red);
+    dot = block_sum(dot, red);
+    const float rho = rsqrtf(ss / (float)d + eps);
+    const float c = rho * rho * rho * (dot / (float)d);
+    const float4* rp = dres ? (const float4*)(dres + row * d) : nullptr;
+    float4* op = (float4*)(dh_out + row * d);
+    uint2* bp = dh_bf ? (uint2*)(dh_bf + row * d) : nullptr;
+    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+        float4 x = hp[i];
+        float4 w = gp[i];
+        uint2 r = dp[i];
+        float d0 = bf16_to_f32(r.x & 0xffff), d1 = bf16_to_f32(r.x >> 16);
+        float d2 = bf16_to_f32(r.y & 0xffff), d3 = bf16_to_f32(r.y >> 16);
+        float4 o;
+        o.x = rho * w.x * d0 - x.x * c;
+        o.y = rho * w.y * d1 - x.y * c;
+        o.z = rho * w.z * d2 - x.z * c;
+        o.w = rho * w.w * d3 - x.w * c;
+        if (rp) {
+            float4 q = rp[i];
+            o.x += q.x; o.y += q.y; o.z += q.z; o.w += q.w;
+        }
+        op[i] = o;
+        if (bp) {
+            uint2 b;
+            b.x = pack_bf16x2(o.x, o.y);
+            b.y = pack_bf16x2(o.z, o.w);
+            bp[i] = b;
+        }
+    }
+}
+
+hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    rmsnorm_fwd_kernel<<<T, 256, 0, s>>>(h, g, d, eps, y);
+    return hipGetLastError();
+}
+hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
+                              float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    rmsnorm_bwd_kernel<<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- RoPE
+// Pair (i, i + d_head/2) of every head rotated by pos * base^(-2i/d_head) (half-split pairing).
+// table[pos * d_head/2 + i] = (cos, sin) in fp32, built in fp64; without a table the angle is formed in fp64 here.
+__global__ void rope_table_kernel(float2* table, int n_pos, int half, double base) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)n_pos * half) return;
+    const int i = (int)(idx % half), p = (int)(idx / half);
+    const double theta = pow(base, -2.0 * (double)i / (double)(2 * half));
+    double sn, cs;
+    sincos((double)p * theta, &sn, &cs);
+    table[idx] = make_float2((float)cs, (float)sn);
+}
+
+__global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ x, long ld, int T, int n_heads, int d_head,
+                                                   double base, int pos0, float sign,
+                                                   const float2* __restrict__ table) {
+    const int half = d_head >> 1;
+    const int per_row = n_heads * (half >> 1);  // two pairs per thread
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)T * per_row) return;
+    const int t = (int)(idx / per_row);
+    const int rem = (int)(idx % per_row);
+    const int hd = rem / (half >> 1);
+    const int i = (rem % (half >> 1)) * 2;
+    bf16_t* p = x + (long)t * ld + (long)hd * d_head + i;
+    uint32_t lo = *(uint32_t*)p, hi = *(uint32_t*)(p + half);
+    float c[2], sn[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        if (table) {
+            float2 cs = table[(long)(pos0 + t) * half + i + e];
+            c[e] = cs.x; sn[e] = cs.y;
+        } else {
+            double theta = pow(base, -2.0 * (double)(i + e) / (double)d_head);
+            double sd, cd;
+            sincos((double)(pos0 + t) * theta, &sd, &cd);
+            c[e] = (float)cd; sn[e] = (float)sd;
+        }
+        sn[e] *= sign;
+    }
+    float a0 = bf16_to_f32(lo & 0xffff), a1 = bf16_to_f32(lo >> 16);
+    float b0 = bf16_to_f32(hi & 0xffff), b1 = bf16_to_f32(hi >> 16);
+    *(uint32_t*)p = pack_bf16x2(a0 * c[0] - b0 * sn[0], a1 * c[1] - b1 * sn[1]);
+    *(uint32_t*)(p + half) = pack_bf16x2(b0 * c[0] + a0 * sn[0], b1 * c[1] + a1 * sn[1]);
+}
+
+hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, hipStream_t s) {
+    const long n = (long)n_pos * (d_head / 2);
+    if (n <= 0) return hipSuccess;
+    rope_table_kernel<<<cdiv(n, 256), 256, 0, s>>>(table, n_pos, d_head / 2, (double)base);
+    return hipGetLastError();
+}
+hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float base, int pos0, int sign,
+                       const float2* table, hipStream_t s) {
+    const long n = (long)T * n_heads * (d_head / 4);
+    if (n <= 0) return hipSuccess;
+    rope_kernel<<<cdiv(n, 256), 256, 0, s>>>(x, ld, T, n_heads, d_head, (double)base, pos0, sign >= 0 ? 1.f : -1.f,
+                                             table);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- SwiGLU
+__device__ __forceinline__ void unpack8(uint4 r, float* f) {
+    f[0] = bf16_to_f32(r.x & 0xffff); f[1] = bf16_to_f32(r.x >> 16);
+    f[2] = bf16_to_f32(r.y & 0xffff); f[3] = bf16_to_f32(r.y >> 16);
+    f[4] = bf16_to_f32(r.z & 0xffff); f[5] = bf16_to_f32(r.z >> 16);
+    f[6] = bf16_to_f32(r.w & 0xffff); f[7] = bf16_to_f32(r.w >> 16);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+    uint4 r;
+    r.x = pack_bf16x2(f[0], f[1]); r.y = pack_bf16x2(f[2], f[3]);
+    r.z = pack_bf16x2(f[4], f[5]); r.w = pack_bf16x2(f[6], f[7]);
+    return r;
+}
+
+// gu [T, 2f] = [gate | up];  a = gate * sigmoid(gate) * up
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const bf16_t* __restrict__ gu, int T, int f,
+                                                         bf16_t* __restrict__ a) {
+    const int f8 = f >> 3;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)T * f8) return;
+    const long t = idx / f8;
+    const int c = (int)(idx % f8) * 8;
+    float g[8], u[8], o[8];
+    unpack8(*(const uint4*)(gu + t * 2 * f + c), g);
+    unpack8(*(const uint4*)(gu + t * 2 * f + f + c), u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.f + __expf(-g[e])) * u[e];
+    *(uint4*)(a + t * f + c) = pack8(o);
+}
+
+// dgate = da * up * sig * (1 + gate (1 - sig));  dup = da * gate * sig
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t* __restrict__ da, const bf16_t* __restrict__ gu,
+                                                         int T, int f, bf16_t* __restrict__ dgu) {
+    const int f8 = f >> 3;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)T * f8) return;
+    const long t = idx / f8;
+    const int c = (int)(idx % f8) * 8;
+    float g[8], u[8], d[8], dg[8], du[8];
+    unpack8(*(const uint4*)(gu + t * 2 * f + c), g);
+    unpack8(*(const uint4*)(gu + t * 2 * f + f + c), u);
+    unpack8(*(const uint4*)(da + t * f + c), d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float sg = 1.f / (1.f + __expf(-g[e]));
+        dg[e] = d[e] * u[e] * sg * (1.f + g[e] * (1.f - sg));
+        du[e] = d[e] * g[e] * sg;
+    }
+    *(uint4*)(dgu + t * 2 * f + c) = pack8(dg);
+    *(uint4*)(dgu + t * 2 * f + f + c) = pack8(du);
+}
+
+hipError_t launch_swiglu_fwd(const bf16_t* gu, int T, int f, bf16_t* a, hipStream_t s) {
+    const long n = (long)T * (f / 8);
+    if (n <= 0) return hipSuccess;
+    swiglu_fwd_kernel<<<cdiv(n, 256), 256, 0, s>>>(gu, T, f, a);
+    return hipGetLastError();
+}
+hipError_t launch_swiglu_bwd(const bf16_t* da, const bf16_t* gu, int T, int f, bf16_t* dgu, hipStream_t s) {
+    const long n = (long)T * (f / 8);
+    if (n <= 0) return hipSuccess;
+    swiglu_bwd_kernel<<<cdiv(n, 256), 256, 0, s>>>(da, gu, T, f, dgu);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- embedding / labels
+__global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ E, const int* __restrict__ tok, int d,
+                                                    float* __restrict__ h) {
+    const long t = blockIdx.x;
+    const bf16_t* src = E + (long)tok[t] * d;
+    float* dst = h + t * d;
+    for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
+        float f[8];
+        unpack8(*(const uint4*)(src + i), f);
+        *(float4*)(dst + i) = make_float4(f[0], f[1], f[2], f[3]);
+        *(float4*)(dst + i + 4) = make_float4(f[4], f[5], f[6], f[7]);
+    }
+}
+hipError_t launch_embed(const bf16_t* E, const int* tokens, int T, int d, float* h, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    embed_kernel<<<T, 256, 0, s>>>(E, tokens, d, h);
+    return hipGetLastError();
+}
+
+// label[t] = tok[t + 1]; the last position has no label (-1)
+__global__ void labels_kernel(const int* __restrict__ tok, int T, int* __restrict__ labels) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < T) labels[t] = (t + 1 < T) ? tok[t + 1] : -1;
+}
+hipError_t launch_labels(const int* tokens, int T, int* labels, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    labels_kernel<<<cdiv(T, 256), 256, 0, s>>>(tokens, T, labels);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- fused softmax cross-entropy
+// One block per position.  Pass 1: online max / sum-exp over the vocabulary; pass 2 (targets only):
+// dlogits = (softmax - onehot) / n_targets.  Non-target rows get nll = 0 and zero gradient.
+__global__ __launch_bounds__(512) void cross_entropy_kernel(const float* __restrict__ logits,
+                                                            const int* __restrict__ labels, int T, int V,
+                                                            int first_target, float inv_n, float* __restrict__ nll,
+                                                            bf16_t* __restrict__ dlogits) {
+    __shared__ float red[16];
+    const int t = blockIdx.x;
+    const float* z = logits + (long)t * V;
+    bf16_t* dz = dlogits ? dlogits + (long)t * V : nullptr;
+    const bool target = (t >= first_target) && (t < T - 1);
+    if (!target) {
+        if (threadIdx.x == 0) nll[t] = 0.f;
+        if (dz) for (int i = threadIdx.x; i < V; i += blockDim.x) dz[i] = 0;
+        return;
+    }
+    float m = -INFINITY, ssum = 0.f;
+    for (int i = threadIdx.x; i < V; i += blockDim.x) {
+        float x = z[i];
+        if (x > m) { ssum *= __expf(m - x); m = x; }
+        ssum += __expf(x - m);
+    }
+    const float M = block_max(m, red);
+    ssum = block_sum(ssum * __expf(m - M), red);
+    const float lse = M + logf(ssum);
+    const int lab = labels[t];
+    if (threadIdx.x == 0) nll[t] = lse - z[lab];
+    if (dz) {
+        for (int i = threadIdx.x; i < V; i += blockDim.x) {
+            float p = __expf(z[i] - lse);
+            if (i == lab) p -= 1.f;
+            dz[i] = f32_to_bf16(p * inv_n);
+        }
+    }
+}
+// deterministic sum of nll over the call's positions (one block)
+__global__ __launch_bounds__(256) void nll_sum_kernel(const float* __restrict__ nll, int T, float* __restrict__ out) {
+    __shared__ float red[16];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < T; i += blockDim.x) s += nll[i];
+    s = block_sum(s, red);
+    if (threadIdx.x == 0) out[0] = s;
+}
+hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, int V, int first_target,
+                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    cross_entropy_kernel<<<T, 512, 0, s>>>(logits, labels, T, V, first_target, 1.f / (float)n_targets, nll, dlogits);
+    if (loss_sum) nll_sum_kernel<<<1, 256, 0, s>>>(nll, T, loss_sum);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- fused AdamW
+// Decoupled weight decay, bias correction, epsilon added after the corrected square root.
+__global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ p, const float* __restrict__ g,
+                                                    float* __restrict__ m, float* __restrict__ v,
+                                                    bf16_t* __restrict__ shadow, size_t n4, size_t n, float lr,
+                                                    float b1, float b2, float eps, float decay, float inv_bc1,
+                                                    float inv_bc2) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 P = ((float4*)p)[i], G = ((const float4*)g)[i], Mm = ((float4*)m)[i], Vv = ((float4*)v)[i];
+        float pp[4] = {P.x, P.y, P.z, P.w}, gg[4] = {G.x, G.y, G.z, G.w};
+        float mm[4] = {Mm.x, Mm.y, Mm.z, Mm.w}, vv[4] = {Vv.x, Vv.y, Vv.z, Vv.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            pp[e] *= decay;
+            mm[e] = b1 * mm[e] + (1.f - b1) * gg[e];
+            vv[e] = b2 * vv[e] + (1.f - b2) * gg[e] * gg[e];
+            pp[e] -= lr * (mm[e] * inv_bc1) / (sqrtf(vv[e] * inv_bc2) + eps);
+        }
+        ((float4*)p)[i] = make_float4(pp[0], pp[1], pp[2], pp[3]);
+        ((float4*)m)[i] = make_float4(mm[0], mm[1], mm[2], mm[3]);
+        ((float4*)v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        if (shadow) {
+            uint2 b;
+            b.x = pack_bf16x2(pp[0], pp[1]);
+            b.y = pack_bf16x2(pp[2], pp[3]);
+            ((uint2*)shadow)[i] = b;
+        }
+    }
+    // tail (n not a multiple of 4)
+    if (blockIdx.x == 0) {
+        for (size_t i = n4 * 4 + threadIdx.x; i < n; i += blockDim.x) {
+            float pp = p[i] * decay, gg = g[i];
+            float mm = b1 * m[i] + (1.f - b1) * gg;
+            float vv = b2 * v[i] + (1.f - b2) * gg * gg;
+            pp -= lr * (mm * inv_bc1) / (sqrtf(vv * inv_bc2) + eps);
+            p[i] = pp; m[i] = mm; v[i] = vv;
+            if (shadow) shadow[i] = f32_to_bf16(pp);
+        }
+    }
+}
+hipError_t launch_adamw(float* p, const float* g, float* m, float* v, bf16_t* shadow, size_t n, long step, float lr,
+                        float beta1, float beta2, float eps, float wd, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    const double bc1 = 1.0 - pow((double)beta1, (double)step);
+    const double bc2 = 1.0 - pow((double)beta2, (double)step);
+    const size_t n4 = n / 4;
+    size_t blocks = (n4 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks < 1) blocks = 1;
+    adamw_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, g, m, v, shadow, n4, n, lr, beta1, beta2, eps, 1.f - lr * wd,
+                                                  (float)(1.0 / bc1), (float)(1.0 / bc2));
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- conversions / fills / init
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f32_to_bf16(src[i]);
+}
+hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    f32_to_bf16_kernel<<<(unsigned)blocks, 256, 0, s>>>(src, dst, n);
+    return hipGetLastError();
+}
+__global__ void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+hipError_t launch_fill_f32(float* p, size_t n, float value, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    fill_f32_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, n, value);
+    return hipGetLastError();
+}
+
+// Counter-based normal draws for the initial A factors: a 64-bit mix of (seed, stream, index)
+// gives two uniforms, Box-Muller gives the value.  Element i depends only on (seed, stream, i).
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+__global__ void init_normal_kernel(float* __restrict__ p, size_t n, float std, uint64_t seed, uint64_t stream_id) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint64_t r = mix64(mix64(seed ^ mix64(stream_id)) + i);
+        float u1 = ((float)(uint32_t)(r >> 40) + 1.0f) * (1.0f / 16777217.0f);  // (0, 1)
+        float u2 = (float)(uint32_t)((r >> 8) & 0xffffffu) * (1.0f / 16777216.0f);
+        p[i] = std * sqrtf(-2.f * logf(u1)) * cosf(6.283185307179586f * u2);
+    }
+}
+hipError_t launch_init_normal(float* p, size_t n, float std, uint64_t seed, uint64_t stream_id, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    init_normal_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, n, std, seed, stream_id);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- transposes / copies
+// 64x64 bf16 tiles through LDS (row stride 66 elements keeps both phases spread over the banks)
+__device__ __forceinline__ void transpose_tile(const bf16_t* __restrict__ src, long lds, int rows, int cols,
+                                               bf16_t* __restrict__ dst, long ldd, int tr, int tc, bf16_t* tile) {
+    const int r0 = tr * 64, c0 = tc * 64;
+    for (int i = threadIdx.x; i < 64 * 64; i += blockDim.x) {
+        const int r = i >> 6, c = i & 63;
+        bf16_t v = 0;
+        if (r0 + r < rows && c0 + c < cols) v = src[(long)(r0 + r) * lds + c0 + c];
+        tile[r * 66 + c] = v;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += blockDim.x) {
+        const int c = i >> 6, r = i & 63;
+        if (r0 + r < rows && c0 + c < cols) dst[(long)(c0 + c) * ldd + r0 + r] = tile[r * 66 + c];
+    }
+}
+__global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ src, long lds, int rows, int cols,
+                                                        bf16_t* __restrict__ dst, long ldd) {
+    __shared__ bf16_t tile[64 * 66];
+    transpose_tile(src, lds, rows, cols, dst, ldd, blockIdx.y, blockIdx.x, tile);
+}
+hipError_t launch_transpose_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd,
+                                 hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    dim3 grid(cdiv(cols, 64), cdiv(rows, 64));
+    transpose_kernel<<<grid, 256, 0, s>>>(src, lds, rows, cols, dst, ldd);
+    return hipGetLastError();
+}
+__global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __restrict__ src_base,
+                                                              bf16_t* __restrict__ dst_base,
+                                                              const TransposeDesc* __restrict__ tab, int n_desc) {
+    __shared__ bf16_t tile[64 * 66];
+    // binary search for the descriptor whose tile range holds this block
+    int lo = 0, hi = n_desc - 1;
+    const int b = blockIdx.x;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (tab[mid].tile0 <= b) lo = mid; else hi = mid - 1;
+    }
+    const TransposeDesc d = tab[lo];
+    const int local = b - d.tile0;
+    const int tiles_c = (d.cols + 63) >> 6;
+    transpose_tile(src_base + d.src_off, d.lds, d.rows, d.cols, dst_base + d.dst_off, d.ldd, local / tiles_c,
+                   local % tiles_c, tile);
+}
+hipError_t launch_transpose_table(const bf16_t* src_base, bf16_t* dst_base, const TransposeDesc* table_dev,
+                                  int n_desc, int total_tiles, hipStream_t s) {
+    if (n_desc <= 0 || total_tiles <= 0) return hipSuccess;
+    transpose_table_kernel<<<total_tiles, 256, 0, s>>>(src_base, dst_base, table_dev, n_desc);
+    return hipGetLastError();
+}
+__global__ void copy2d_kernel(const bf16_t* __restrict__ src, long lds, int rows, int cols8, bf16_t* __restrict__ dst,
+                              long ldd) {
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)rows * cols8) return;
+    const long r = idx / cols8;
+    const int c = (int)(idx % cols8) * 8;
+    *(uint4*)(dst + r * ldd + c) = *(const uint4*)(src + r * lds + c);
+}
+hipError_t launch_copy2d_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd, hipStream_t s) {
+    const long n = (long)rows * (cols / 8);
+    if (n <= 0) return hipSuccess;
+    copy2d_kernel<<<cdiv(n, 256), 256, 0, s>>>(src, lds, rows, cols / 8, dst, ldd);
+    return hipGetLastError();
+}

@@ -1,0 +1,76 @@
+// Internal launch interface between the host orchestration and the gfx950 kernels.
+#pragma once
+#include "common.h"
+
+// ---------------------------------------------------------------- GEMM (gemm_bf16.hip)
+// C = alpha * (A B^T + A2 B2^T) (+ R), bf16 operands, fp32 accumulate (MFMA 32x32x16).
+struct GemmNT {
+    const bf16_t* A = nullptr;  long lda = 0;   // [M, K]
+    const bf16_t* B = nullptr;  long ldb = 0;   // [N, K]
+    int M = 0, N = 0, K = 0;
+    const bf16_t* A2 = nullptr; long lda2 = 0;  // [M, K2]  (low-rank K-extension; may be null)
+    const bf16_t* B2 = nullptr; long ldb2 = 0;  // [N, K2]
+    int K2 = 0;
+    float alpha = 1.f;
+    const float* R = nullptr;                   // fp32 [M, N] residual (c_f32 only), row stride ldc
+    void* C = nullptr;          long ldc = 0;   // bf16 or fp32 [M, N]
+    int c_f32 = 0;
+    int batch = 1;                              // grid.z; element offsets applied per batch index:
+    long bA = 0, bB = 0, bA2 = 0, bB2 = 0, bC = 0;
+    int split_k = 0;                            // 0 = choose; >1 needs `partial`
+    float* partial = nullptr;                   // fp32 scratch, >= batch*split*M*N elements
+    size_t partial_elems = 0;
+};
+hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s);
+
+// C[Mo, No] (fp32) = alpha * P[T, Mo]^T Q[T, No]
+struct GemmTN {
+    const bf16_t* P = nullptr; long ldp = 0;
+    const bf16_t* Q = nullptr; long ldq = 0;
+    int T = 0, Mo = 0, No = 0;
+    float alpha = 1.f;
+    float* C = nullptr; long ldc = 0;
+    int batch = 1;
+    long bP = 0, bQ = 0, bC = 0;
+};
+hipError_t launch_gemm_tn(const GemmTN& g, hipStream_t s);
+
+// fp32 reference-precision GEMM for the single-layer fp32 step: C = alpha * op(A) op(B) + beta * C
+// ta/tb: 0 = as stored [rows, cols] row-major, 1 = transposed use.  (gemm_f32.hip)
+hipError_t launch_sgemm(int ta, int tb, int M, int N, int K, float alpha, const float* A, int lda, const float* B,
+                        int ldb, float beta, float* C, int ldc, hipStream_t s);
+
+// ---------------------------------------------------------------- attention (attention.hip)
+hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ldq, int T, int n_heads,
+                                int d_head, bf16_t* o, long ldo, float* lse, hipStream_t s);
+hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
+                                const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
+                                bf16_t* dk, bf16_t* dv, float* delta, hipStream_t s);
+
+// ---------------------------------------------------------------- elementwise / reductions (elementwise.hip)
+hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s);
+hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
+                              float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s);
+hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float base, int pos0, int sign,
+                       const float2* table, hipStream_t s);
+hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, hipStream_t s);
+hipError_t launch_swiglu_fwd(const bf16_t* gu, int T, int f, bf16_t* a, hipStream_t s);
+hipError_t launch_swiglu_bwd(const bf16_t* da, const bf16_t* gu, int T, int f, bf16_t* dgu, hipStream_t s);
+hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, int V, int first_target,
+                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s);
+hipError_t launch_adamw(float* p, const float* g, float* m, float* v, bf16_t* shadow, size_t n, long step, float lr,
+                        float beta1, float beta2, float eps, float wd, hipStream_t s);
+hipError_t launch_embed(const bf16_t* E, const int* tokens, int T, int d, float* h, hipStream_t s);
+hipError_t launch_labels(const int* tokens, int T, int* labels, hipStream_t s);
+hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t s);
+hipError_t launch_fill_f32(float* p, size_t n, float value, hipStream_t s);
+hipError_t launch_init_normal(float* p, size_t n, float std, uint64_t seed, uint64_t stream_id, hipStream_t s);
+// dst[c, r] = src[r, c] for a [rows, cols] bf16 matrix with row strides lds / ldd
+hipError_t launch_transpose_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd,
+                                 hipStream_t s);
+// many transposes in one launch: descriptors live in device memory
+struct TransposeDesc { long src_off, dst_off; int rows, cols, lds, ldd, tile0, pad; };
+hipError_t launch_transpose_table(const bf16_t* src_base, bf16_t* dst_base, const TransposeDesc* table_dev,
+                                  int n_desc, int total_tiles, hipStream_t s);
+// copy rows [rows, cols] bf16 from src (stride lds) to dst (stride ldd)
+hipError_t launch_copy2d_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd, hipStream_t s);

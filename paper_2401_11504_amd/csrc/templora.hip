@@ -1,0 +1,806 @@
+// Host side of the Temp-Lora chunk-update library: C ABI, memory ownership and the
+// order in which the gfx950 kernels run.  See include/templora.h for the contract.
+#include "../../include/templora.h"
+#include "kernels.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+// ---------------------------------------------------------------- errors
+static thread_local char g_err[512] = "";
+static tl_status fail(tl_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+#define HIPCHK(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e__ = (expr);                                                                  \
+        if (e__ != hipSuccess)                                                                    \
+            return fail(e__ == hipErrorOutOfMemory ? TL_ERR_OOM : TL_ERR_DEVICE, "%s: %s (%s:%d)", #expr, \
+                        hipGetErrorString(e__), __FILE__, __LINE__);                              \
+    } while (0)
+#define TLCHK(expr)                      \
+    do {                                 \
+        tl_status s__ = (expr);          \
+        if (s__ != TL_OK) return s__;    \
+    } while (0)
+
+extern "C" const char* tl_last_error(void) { return g_err; }
+extern "C" const char* tl_version(void) { return "templora-gfx950 0.1"; }
+
+static tl_status require_gfx950() {
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return fail(TL_ERR_DEVICE, "no HIP device: this library has no CPU fallback");
+    }
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIPCHK(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(TL_ERR_DEVICE, "device %d is %s; kernels are built for gfx950 only", dev, prop.gcnArchName);
+    return TL_OK;
+}
+
+// ---------------------------------------------------------------- device memory bookkeeping
+struct Pool {
+    std::vector<void*> ptrs;
+    template <typename T>
+    tl_status alloc(T** out, size_t n_elems) {
+        void* p = nullptr;
+        size_t bytes = n_elems * sizeof(T);
+        if (bytes == 0) bytes = 16;
+        hipError_t e = hipMalloc(&p, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(TL_ERR_OOM, "hipMalloc of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+        }
+        ptrs.push_back(p);
+        *out = (T*)p;
+        return TL_OK;
+    }
+    void release() {
+        for (void* p : ptrs) (void)hipFree(p);
+        ptrs.clear();
+    }
+};
+
+// projection groups that share an input: q|k|v, o, gate|up, down
+enum { G_QKV = 0, G_O = 1, G_GU = 2, G_DOWN = 3, N_GROUPS = 4 };
+static const int kGroupCount[N_GROUPS] = {3, 1, 2, 1};
+static const int kProjGroup[7] = {G_QKV, G_QKV, G_QKV, G_O, G_GU, G_GU, G_DOWN};
+static const int kProjIndex[7] = {0, 1, 2, 0, 0, 1, 0};
+
+struct LayerW {
+    bf16_t* w[N_GROUPS];   // packed [G*d_out, d_in]
+    bf16_t* wt[N_GROUPS];  // transposed [d_in, G*d_out]
+    float *g1, *g2;
+};
+
+struct tl_model {
+    tl_model_cfg cfg;
+    hipStream_t stream;
+    int device;
+    Pool pool;
+    std::vector<LayerW> layers;
+    bf16_t *emb = nullptr, *head = nullptr, *head_t = nullptr;
+    float* gf = nullptr;
+    float2* rope = nullptr;
+    int d_in(int g) const { return g == G_DOWN ? cfg.d_ffn : cfg.d_model; }
+    int d_out(int g) const { return g == G_GU ? cfg.d_ffn : cfg.d_model; }
+};
+
+struct LayerOff {           // element offsets into the LoRA arenas
+    size_t A[N_GROUPS], B[N_GROUPS];    // fp32 arenas and same-layout bf16 shadow
+    size_t AT[N_GROUPS], BT[N_GROUPS];  // transposed bf16 shadows
+};
+
+struct LayerSave {          // activations kept from forward to backward
+    bf16_t *x1, *qkv, *o, *x2, *gu, *act, *hs[N_GROUPS];
+    float *lse, *hmid;
+};
+
+struct tl_lora {
+    tl_model* model = nullptr;
+    tl_lora_cfg cfg;
+    bool discarded = false;
+    int64_t step = 0;
+    int last_tokens = 0;
+    bool have_grads = false;
+    float s = 1.f;
+    Pool pool;
+    size_t n_params = 0, n_t = 0;
+    float *P = nullptr, *G = nullptr, *M = nullptr, *V = nullptr;
+    bf16_t *S = nullptr, *ST = nullptr;
+    std::vector<LayerOff> off;
+    TransposeDesc* ttable = nullptr;
+    int n_desc = 0, total_tiles = 0;
+    std::vector<LayerSave> save;
+    std::vector<float*> hs, dhs;   // residual stream / its gradient at the L+1 layer boundaries
+    // shared temporaries
+    bf16_t *hf = nullptr, *dlogits = nullptr, *dhf = nullptr, *dh_bf = nullptr, *d_act = nullptr, *dgu = nullptr,
+           *dx = nullptr, *dhmid_bf = nullptr, *d_o = nullptr, *dqkv = nullptr, *dH = nullptr;
+    float *logits = nullptr, *nll = nullptr, *loss_sum = nullptr, *dhmid = nullptr, *delta = nullptr,
+          *partial = nullptr;
+    size_t partial_elems = 0;
+    int *tok = nullptr, *labels = nullptr;
+    int* tok_host = nullptr;      // pinned
+    float* loss_host = nullptr;   // pinned
+};
+
+// ---------------------------------------------------------------- model
+extern "C" tl_status tl_model_create(const tl_model_cfg* cfg, const void* const* wp, void* hip_stream,
+                                     tl_model** out) {
+    if (!cfg || !wp || !out) return fail(TL_ERR_ARG, "tl_model_create: null argument");
+    const tl_model_cfg c = *cfg;
+    if (c.n_layers < 1 || c.d_model < 8 || c.n_heads < 1 || c.d_ffn < 8 || c.vocab < 0 || c.max_tokens < 2)
+        return fail(TL_ERR_SHAPE, "tl_model_create: non-positive dimension");
+    if (c.d_head != 64 && c.d_head != 128) return fail(TL_ERR_SHAPE, "d_head must be 64 or 128 (got %d)", c.d_head);
+    if (c.d_model != c.n_heads * c.d_head) return fail(TL_ERR_SHAPE, "d_model != n_heads * d_head");
+    if ((c.d_model & 7) || (c.d_ffn & 7) || (c.vocab & 7))
+        return fail(TL_ERR_SHAPE, "d_model, d_ffn and vocab must be multiples of 8");
+    if (!(c.rms_eps >= 0.f) || !(c.rope_base > 1.f)) return fail(TL_ERR_ARG, "bad rms_eps / rope_base");
+    const int nptr = TL_N_WEIGHT_PTRS(c.n_layers);
+    for (int i = 0; i < nptr; ++i) {
+        const bool tail = i >= TL_PTRS_PER_LAYER * c.n_layers;
+        if (!wp[i] && !(tail && c.vocab == 0)) return fail(TL_ERR_ARG, "weight pointer %d is null", i);
+    }
+    TLCHK(require_gfx950());
+    tl_model* m = new (std::nothrow) tl_model();
+    if (!m) return fail(TL_ERR_OOM, "host allocation failed");
+    m->cfg = c;
+    m->stream = (hipStream_t)hip_stream;
+    hipStream_t s = m->stream;
+    tl_status st = TL_OK;
+    auto body = [&]() -> tl_status {
+        HIPCHK(hipGetDevice(&m->device));
+        const int d = c.d_model, f = c.d_ffn;
+        m->layers.resize(c.n_layers);
+        for (int l = 0; l < c.n_layers; ++l) {
+            LayerW& L = m->layers[l];
+            const void* const* p = wp + TL_PTRS_PER_LAYER * l;
+            for (int g = 0; g < N_GROUPS; ++g) {
+                const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g);
+                TLCHK(m->pool.alloc(&L.w[g], (size_t)G * dout * din));
+                TLCHK(m->pool.alloc(&L.wt[g], (size_t)G * dout * din));
+            }
+            for (int pj = 0; pj < 7; ++pj) {
+                const int g = kProjGroup[pj], i = kProjIndex[pj], din = m->d_in(g), dout = m->d_out(g);
+                HIPCHK(hipMemcpyAsync(L.w[g] + (size_t)i * dout * din, p[pj], (size_t)dout * din * sizeof(bf16_t),
+                                      hipMemcpyDeviceToDevice, s));
+            }
+            for (int g = 0; g < N_GROUPS; ++g) {
+                const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g);
+                HIPCHK(launch_transpose_bf16(L.w[g], din, G * dout, din, L.wt[g], (long)G * dout, s));
+            }
+            TLCHK(m->pool.alloc(&L.g1, (size_t)d));
+            TLCHK(m->pool.alloc(&L.g2, (size_t)d));
+            HIPCHK(hipMemcpyAsync(L.g1, p[7], d * sizeof(float), hipMemcpyDeviceToDevice, s));
+            HIPCHK(hipMemcpyAsync(L.g2, p[8], d * sizeof(float), hipMemcpyDeviceToDevice, s));
+            (void)f;
+        }
+        if (c.vocab > 0) {
+            const void* const* p = wp + TL_PTRS_PER_LAYER * c.n_layers;
+            const size_t n = (size_t)c.vocab * d;
+            TLCHK(m->pool.alloc(&m->emb, n));
+            TLCHK(m->pool.alloc(&m->head, n));
+            TLCHK(m->pool.alloc(&m->head_t, n));
+            TLCHK(m->pool.alloc(&m->gf, (size_t)d));
+            HIPCHK(hipMemcpyAsync(m->emb, p[0], n * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
+            HIPCHK(hipMemcpyAsync(m->gf, p[1], d * sizeof(float), hipMemcpyDeviceToDevice, s));
+            HIPCHK(hipMemcpyAsync(m->head, p[2], n * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
+            HIPCHK(launch_transpose_bf16(m->head, d, c.vocab, d, m->head_t, c.vocab, s));
+        }
+        TLCHK(m->pool.alloc(&m->rope, (size_t)c.max_tokens * (c.d_head / 2)));
+        HIPCHK(launch_rope_table(m->rope, c.max_tokens, c.d_head, c.rope_base, s));
+        HIPCHK(hipStreamSynchronize(s));
+        return TL_OK;
+    };
+    st = body();
+    if (st != TL_OK) {
+        m->pool.release();
+        delete m;
+        return st;
+    }
+    *out = m;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_model_destroy(tl_model* m) {
+    if (!m) return TL_OK;
+    (void)hipStreamSynchronize(m->stream);
+    m->pool.release();
+    delete m;
+    return TL_OK;
+}
+
+// ---------------------------------------------------------------- module life cycle
+static void lora_release(tl_lora* L) {
+    L->pool.release();
+    if (L->tok_host) (void)hipHostFree(L->tok_host);
+    if (L->loss_host) (void)hipHostFree(L->loss_host);
+    L->tok_host = nullptr;
+    L->loss_host = nullptr;
+    L->P = L->G = L->M = L->V = nullptr;
+}
+
+static tl_status refresh_transposed(tl_lora* L) {
+    HIPCHK(launch_transpose_table(L->S, L->ST, L->ttable, L->n_desc, L->total_tiles, L->model->stream));
+    return TL_OK;
+}
+
+extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora** out) {
+    if (!m || !cfg || !out) return fail(TL_ERR_ARG, "tl_lora_init: null argument");
+    const tl_lora_cfg c = *cfg;
+    if (c.rank < 8 || (c.rank & 7) || c.rank > 256) return fail(TL_ERR_SHAPE, "rank must be a multiple of 8 in [8, 256]");
+    if (!(c.alpha > 0.f) || !(c.beta1 >= 0.f && c.beta1 < 1.f) || !(c.beta2 >= 0.f && c.beta2 < 1.f) ||
+        !(c.eps >= 0.f) || !(c.weight_decay >= 0.f) || !(c.a_init_std >= 0.f))
+        return fail(TL_ERR_ARG, "tl_lora_init: bad hyper-parameter");
+    TLCHK(require_gfx950());
+    tl_lora* L = new (std::nothrow) tl_lora();
+    if (!L) return fail(TL_ERR_OOM, "host allocation failed");
+    L->model = m;
+    L->cfg = c;
+    L->s = c.alpha / (float)c.rank;
+    const tl_model_cfg& mc = m->cfg;
+    const int r = c.rank, d = mc.d_model, f = mc.d_ffn, nl = mc.n_layers, Tm = mc.max_tokens, V = mc.vocab;
+    hipStream_t s = m->stream;
+    auto body = [&]() -> tl_status {
+        // arena layout: per layer, per group: A_pack [G r, d_in] then B_pack [G d_out, r]
+        L->off.resize(nl);
+        size_t n = 0, nt = 0;
+        std::vector<TransposeDesc> desc;
+        int tiles = 0;
+        for (int l = 0; l < nl; ++l)
+            for (int g = 0; g < N_GROUPS; ++g) {
+                const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g);
+                L->off[l].A[g] = n;  n += (size_t)G * r * din;
+                L->off[l].B[g] = n;  n += (size_t)G * dout * r;
+                L->off[l].AT[g] = nt; nt += (size_t)G * r * din;
+                L->off[l].BT[g] = nt; nt += (size_t)G * dout * r;
+                // A_pack [G r, d_in] -> AT [d_in, G r]
+                TransposeDesc da = {(long)L->off[l].A[g], (long)L->off[l].AT[g], G * r, din, din, G * r, tiles, 0};
+                desc.push_back(da);
+                tiles += cdiv(G * r, 64) * cdiv(din, 64);
+                // each B_p [d_out, r] -> BT_p [r, d_out]
+                for (int i = 0; i < G; ++i) {
+                    TransposeDesc db = {(long)(L->off[l].B[g] + (size_t)i * dout * r),
+                                        (long)(L->off[l].BT[g] + (size_t)i * dout * r), dout, r, r, dout, tiles, 0};
+                    desc.push_back(db);
+                    tiles += cdiv(dout, 64) * cdiv(r, 64);
+                }
+            }
+        L->n_params = n;
+        L->n_t = nt;
+        L->n_desc = (int)desc.size();
+        L->total_tiles = tiles;
+        TLCHK(L->pool.alloc(&L->P, n));
+        TLCHK(L->pool.alloc(&L->G, n));
+        TLCHK(L->pool.alloc(&L->M, n));
+        TLCHK(L->pool.alloc(&L->V, n));
+        TLCHK(L->pool.alloc(&L->S, n));
+        TLCHK(L->pool.alloc(&L->ST, nt));
+        TLCHK(L->pool.alloc(&L->ttable, desc.size()));
+        HIPCHK(hipMemcpyAsync(L->ttable, desc.data(), desc.size() * sizeof(TransposeDesc), hipMemcpyHostToDevice, s));
+        HIPCHK(hipStreamSynchronize(s));  // desc is a host temporary
+        HIPCHK(launch_fill_f32(L->P, n, 0.f, s));
+        HIPCHK(launch_fill_f32(L->G, n, 0.f, s));
+        HIPCHK(launch_fill_f32(L->M, n, 0.f, s));
+        HIPCHK(launch_fill_f32(L->V, n, 0.f, s));
+        for (int l = 0; l < nl; ++l)
+            for (int g = 0; g < N_GROUPS; ++g)
+                HIPCHK(launch_init_normal(L->P + L->off[l].A[g], (size_t)kGroupCount[g] * r * m->d_in(g),
+                                          c.a_init_std, c.seed, (uint64_t)(l * N_GROUPS + g), s));
+        HIPCHK(launch_f32_to_bf16(L->P, L->S, n, s));
+        TLCHK(refresh_transposed(L));
+
+        // activations
+        const size_t Td = (size_t)Tm * d;
+        L->save.resize(nl);
+        L->hs.resize(nl + 1);
+        L->dhs.resize(nl + 1);
+        for (int l = 0; l <= nl; ++l) {
+            TLCHK(L->pool.alloc(&L->hs[l], Td));
+            TLCHK(L->pool.alloc(&L->dhs[l], Td));
+        }
+        for (int l = 0; l < nl; ++l) {
+            LayerSave& sv = L->save[l];
+            TLCHK(L->pool.alloc(&sv.x1, Td));
+            TLCHK(L->pool.alloc(&sv.qkv, 3 * Td));
+            TLCHK(L->pool.alloc(&sv.o, Td));
+            TLCHK(L->pool.alloc(&sv.x2, Td));
+            TLCHK(L->pool.alloc(&sv.gu, (size_t)Tm * 2 * f));
+            TLCHK(L->pool.alloc(&sv.act, (size_t)Tm * f));
+            for (int g = 0; g < N_GROUPS; ++g) TLCHK(L->pool.alloc(&sv.hs[g], (size_t)Tm * kGroupCount[g] * r));
+            TLCHK(L->pool.alloc(&sv.lse, (size_t)mc.n_heads * Tm));
+            TLCHK(L->pool.alloc(&sv.hmid, Td));
+        }
+        TLCHK(L->pool.alloc(&L->dh_bf, Td));
+        TLCHK(L->pool.alloc(&L->d_act, (size_t)Tm * f));
+        TLCHK(L->pool.alloc(&L->dgu, (size_t)Tm * 2 * f));
+        TLCHK(L->pool.alloc(&L->dx, Td));
+        TLCHK(L->pool.alloc(&L->dhmid, Td));
+        TLCHK(L->pool.alloc(&L->dhmid_bf, Td));
+        TLCHK(L->pool.alloc(&L->d_o, Td));
+        TLCHK(L->pool.alloc(&L->dqkv, 3 * Td));
+        TLCHK(L->pool.alloc(&L->dH, (size_t)Tm * 3 * r));
+        TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
+        L->partial_elems = (size_t)Tm * 3 * r * 16;
+        TLCHK(L->pool.alloc(&L->partial, L->partial_elems));
+        TLCHK(L->pool.alloc(&L->tok, (size_t)Tm));
+        TLCHK(L->pool.alloc(&L->labels, (size_t)Tm));
+        TLCHK(L->pool.alloc(&L->nll, (size_t)Tm));
+        TLCHK(L->pool.alloc(&L->loss_sum, (size_t)4));
+        if (V > 0) {
+            TLCHK(L->pool.alloc(&L->hf, Td));
+            TLCHK(L->pool.alloc(&L->dhf, Td));
+            TLCHK(L->pool.alloc(&L->logits, (size_t)Tm * V));
+            TLCHK(L->pool.alloc(&L->dlogits, (size_t)Tm * V));
+        }
+        HIPCHK(hipHostMalloc((void**)&L->tok_host, (size_t)Tm * sizeof(int), hipHostMallocDefault));
+        HIPCHK(hipHostMalloc((void**)&L->loss_host, 4 * sizeof(float), hipHostMallocDefault));
+        HIPCHK(hipStreamSynchronize(s));
+        return TL_OK;
+    };
+    tl_status st = body();
+    if (st != TL_OK) {
+        lora_release(L);
+        delete L;
+        return st;
+    }
+    *out = L;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_discard(tl_lora* L) {
+    if (!L) return fail(TL_ERR_ARG, "tl_discard: null handle");
+    if (L->discarded) return fail(TL_ERR_DISCARDED, "module already discarded");
+    (void)hipStreamSynchronize(L->model->stream);
+    lora_release(L);
+    L->discarded = true;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_lora_free(tl_lora* L) {
+    if (!L) return TL_OK;
+    if (!L->discarded) {
+        (void)hipStreamSynchronize(L->model->stream);
+        lora_release(L);
+    }
+    delete L;
+    return TL_OK;
+}
+
+#define LIVE(L, name)                                                        \
+    do {                                                                     \
+        if (!(L)) return fail(TL_ERR_ARG, name ": null handle");             \
+        if ((L)->discarded) return fail(TL_ERR_DISCARDED, name ": module was discarded"); \
+    } while (0)
+
+// ---------------------------------------------------------------- one LoRA-adapted projection group
+// forward:  Hs = s X A^T  (kept),  Y = X W^T + Hs B^T (+ residual)
+static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf16_t* Y_bf, float* Y_f32,
+                           const float* resid) {
+    tl_model* m = L->model;
+    hipStream_t s = m->stream;
+    const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
+    const LayerOff& o = L->off[l];
+    bf16_t* Hs = L->save[l].hs[g];
+    GemmNT h;
+    h.A = X; h.lda = din; h.B = L->S + o.A[g]; h.ldb = din; h.M = T; h.N = G * r; h.K = din;
+    h.alpha = L->s; h.C = Hs; h.ldc = G * r;
+    h.partial = L->partial; h.partial_elems = L->partial_elems;
+    HIPCHK(launch_gemm_nt(h, s));
+    GemmNT y;
+    y.A = X; y.lda = din; y.B = m->layers[l].w[g]; y.ldb = din; y.M = T; y.N = dout; y.K = din;
+    y.A2 = Hs; y.lda2 = G * r; y.B2 = L->S + o.B[g]; y.ldb2 = r; y.K2 = r;
+    y.batch = G; y.bB = (long)dout * din; y.bA2 = r; y.bB2 = (long)dout * r; y.bC = dout;
+    y.ldc = (long)G * dout;
+    if (Y_f32) { y.C = Y_f32; y.c_f32 = 1; y.R = resid; } else { y.C = Y_bf; }
+    HIPCHK(launch_gemm_nt(y, s));
+    return TL_OK;
+}
+
+// backward: dH = s dY B;  dX = dY W + dH A;  dA = dH^T X;  dB = dY^T Hs.   dX may be null (not needed).
+static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf16_t* X, int T, bf16_t* dX) {
+    tl_model* m = L->model;
+    hipStream_t s = m->stream;
+    const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
+    const LayerOff& o = L->off[l];
+    const bf16_t* Hs = L->save[l].hs[g];
+    GemmNT h;
+    h.A = dY; h.lda = (long)G * dout; h.B = L->ST + o.BT[g]; h.ldb = dout; h.M = T; h.N = r; h.K = dout;
+    h.alpha = L->s; h.C = L->dH; h.ldc = G * r;
+    h.batch = G; h.bA = dout; h.bB = (long)r * dout; h.bC = r;
+    h.partial = L->partial; h.partial_elems = L->partial_elems;
+    HIPCHK(launch_gemm_nt(h, s));
+    if (dX) {
+        GemmNT x;
+        x.A = dY; x.lda = (long)G * dout; x.B = m->layers[l].wt[g]; x.ldb = (long)G * dout; x.M = T; x.N = din;
+        x.K = G * dout;
+        x.A2 = L->dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r;
+        x.C = dX; x.ldc = din;
+        HIPCHK(launch_gemm_nt(x, s));
+    }
+    GemmTN a;
+    a.P = L->dH; a.ldp = G * r; a.Q = X; a.ldq = din; a.T = T; a.Mo = G * r; a.No = din;
+    a.C = L->G + o.A[g]; a.ldc = din;
+    HIPCHK(launch_gemm_tn(a, s));
+    GemmTN b;
+    b.P = dY; b.ldp = (long)G * dout; b.Q = Hs; b.ldq = G * r; b.T = T; b.Mo = dout; b.No = r;
+    b.C = L->G + o.B[g]; b.ldc = r;
+    b.batch = G; b.bP = dout; b.bQ = r; b.bC = (long)dout * r;
+    HIPCHK(launch_gemm_tn(b, s));
+    return TL_OK;
+}
+
+// ---------------------------------------------------------------- one decoder layer
+static tl_status layer_forward(tl_lora* L, int l, const float* h_in, float* h_out, int T) {
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    hipStream_t s = m->stream;
+    const int d = c.d_model, f = c.d_ffn;
+    LayerSave& sv = L->save[l];
+    const LayerW& W = m->layers[l];
+    HIPCHK(launch_rmsnorm_fwd(h_in, W.g1, T, d, c.rms_eps, sv.x1, s));
+    TLCHK(group_fwd(L, l, G_QKV, sv.x1, T, sv.qkv, nullptr, nullptr));
+    HIPCHK(launch_rope(sv.qkv, 3L * d, T, 2 * c.n_heads, c.d_head, c.rope_base, 0, +1, m->rope, s));  // q and k
+    HIPCHK(launch_attention_fwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, 3L * d, T, c.n_heads, c.d_head, sv.o, d, sv.lse, s));
+    TLCHK(group_fwd(L, l, G_O, sv.o, T, nullptr, sv.hmid, h_in));
+    HIPCHK(launch_rmsnorm_fwd(sv.hmid, W.g2, T, d, c.rms_eps, sv.x2, s));
+    TLCHK(group_fwd(L, l, G_GU, sv.x2, T, sv.gu, nullptr, nullptr));
+    HIPCHK(launch_swiglu_fwd(sv.gu, T, f, sv.act, s));
+    TLCHK(group_fwd(L, l, G_DOWN, sv.act, T, nullptr, h_out, sv.hmid));
+    return TL_OK;
+}
+
+// dh_out (fp32) and its bf16 copy dh_out_bf -> dh_in (fp32) and, if dh_in_bf != null, its bf16 copy
+static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const float* dh_out, const bf16_t* dh_out_bf,
+                                float* dh_in, bf16_t* dh_in_bf, int T) {
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    hipStream_t s = m->stream;
+    const int d = c.d_model, f = c.d_ffn;
+    LayerSave& sv = L->save[l];
+    const LayerW& W = m->layers[l];
+    TLCHK(group_bwd(L, l, G_DOWN, dh_out_bf, sv.act, T, L->d_act));
+    HIPCHK(launch_swiglu_bwd(L->d_act, sv.gu, T, f, L->dgu, s));
+    TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx));
+    HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s));
+    TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o));
+    HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
+                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, s));
+    HIPCHK(launch_rope(L->dqkv, 3L * d, T, 2 * c.n_heads, c.d_head, c.rope_base, 0, -1, m->rope, s));
+    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx));
+    HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s));
+    return TL_OK;
+}
+
+static tl_status optimizer_step(tl_lora* L, float lr, size_t off, size_t n) {
+    hipStream_t s = L->model->stream;
+    HIPCHK(launch_adamw(L->P + off, L->G + off, L->M + off, L->V + off, L->S + off, n, (long)(L->step + 1), lr,
+                        L->cfg.beta1, L->cfg.beta2, L->cfg.eps, L->cfg.weight_decay, s));
+    TLCHK(refresh_transposed(L));
+    return TL_OK;
+}
+
+// ---------------------------------------------------------------- chunk update
+static tl_status check_tokens(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx) {
+    const tl_model_cfg& c = L->model->cfg;
+    if (!tokens) return fail(TL_ERR_ARG, "tokens is null");
+    if (c.vocab <= 0) return fail(TL_ERR_SHAPE, "model was created without embedding / lm_head (vocab = 0)");
+    if (n_tokens < 2 || n_tokens > c.max_tokens)
+        return fail(TL_ERR_WINDOW, "n_tokens = %d outside [2, max_tokens = %d]", n_tokens, c.max_tokens);
+    if (n_ctx < 0 || n_ctx >= n_tokens) return fail(TL_ERR_WINDOW, "n_ctx = %d must be in [0, n_tokens)", n_ctx);
+    for (int i = 0; i < n_tokens; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab)
+            return fail(TL_ERR_TOKEN_RANGE, "tokens[%d] = %d outside [0, %d)", i, tokens[i], c.vocab);
+    return TL_OK;
+}
+
+static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ctx, bool want_grad, int* n_targets) {
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    hipStream_t s = m->stream;
+    const int d = c.d_model, V = c.vocab;
+    // position t predicts token t+1: a target iff t+1 >= max(n_ctx, 1) and t+1 < T
+    const int first = (n_ctx > 1 ? n_ctx : 1) - 1;
+    const int N = (T - 1) - first;
+    *n_targets = N;
+    memcpy(L->tok_host, tokens, (size_t)T * sizeof(int));
+    HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
+    HIPCHK(launch_labels(L->tok, T, L->labels, s));
+    HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
+    for (int l = 0; l < c.n_layers; ++l) TLCHK(layer_forward(L, l, L->hs[l], L->hs[l + 1], T));
+    HIPCHK(launch_rmsnorm_fwd(L->hs[c.n_layers], m->gf, T, d, c.rms_eps, L->hf, s));
+    GemmNT lg;
+    lg.A = L->hf; lg.lda = d; lg.B = m->head; lg.ldb = d; lg.M = T; lg.N = V; lg.K = d;
+    lg.C = L->logits; lg.ldc = V; lg.c_f32 = 1;
+    HIPCHK(launch_gemm_nt(lg, s));
+    HIPCHK(launch_cross_entropy(L->logits, L->labels, T, V, first, N, L->nll, want_grad ? L->dlogits : nullptr,
+                                L->loss_sum, s));
+    HIPCHK(hipMemcpyAsync(L->loss_host, L->loss_sum, sizeof(float), hipMemcpyDeviceToHost, s));
+    L->last_tokens = T;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_chunk_loss(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx,
+                                   float* loss_out, int32_t* n_targets_out) {
+    LIVE(L, "tl_chunk_loss");
+    if (!loss_out) return fail(TL_ERR_ARG, "loss_out is null");
+    TLCHK(check_tokens(L, tokens, n_tokens, n_ctx));
+    int N = 0;
+    TLCHK(forward_loss(L, tokens, n_tokens, n_ctx, false, &N));
+    HIPCHK(hipStreamSynchronize(L->model->stream));
+    const float loss = L->loss_host[0] / (float)N;
+    if (!std::isfinite(loss)) return fail(TL_ERR_NONFINITE, "loss is not finite");
+    *loss_out = loss;
+    if (n_targets_out) *n_targets_out = N;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float lr,
+                                     float* loss_out, int32_t* n_targets_out) {
+    LIVE(L, "tl_chunk_update");
+    if (!loss_out) return fail(TL_ERR_ARG, "loss_out is null");
+    if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
+    TLCHK(check_tokens(L, tokens, n_tokens, n_ctx));
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    hipStream_t s = m->stream;
+    const int T = n_tokens, d = c.d_model, V = c.vocab, nl = c.n_layers;
+    int N = 0;
+    TLCHK(forward_loss(L, tokens, T, n_ctx, true, &N));
+    // the loss decides whether anything is updated: read it before touching the module
+    HIPCHK(hipStreamSynchronize(s));
+    const float loss = L->loss_host[0] / (float)N;
+    if (!std::isfinite(loss)) return fail(TL_ERR_NONFINITE, "loss is not finite; optimizer step skipped");
+    // backward: lm_head, final norm, layers
+    GemmNT dh;
+    dh.A = L->dlogits; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T; dh.N = d; dh.K = V;
+    dh.C = L->dhf; dh.ldc = d;
+    HIPCHK(launch_gemm_nt(dh, s));
+    HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf, s));
+    for (int l = nl - 1; l >= 0; --l)
+        TLCHK(layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf, L->dhs[l], L->dh_bf, T));
+    L->have_grads = true;
+    TLCHK(optimizer_step(L, lr, 0, L->n_params));
+    HIPCHK(hipStreamSynchronize(s));
+    L->step += 1;
+    *loss_out = loss;
+    if (n_targets_out) *n_targets_out = N;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in, const float* dh_out, int32_t n_tokens,
+                                   float* h_out, float* dh_in, float lr, int32_t apply_adamw) {
+    LIVE(L, "tl_layer_step");
+    if (!h_in || !dh_out || !h_out || !dh_in) return fail(TL_ERR_ARG, "tl_layer_step: null pointer");
+    const tl_model_cfg& c = L->model->cfg;
+    if (layer < 0 || layer >= c.n_layers) return fail(TL_ERR_ARG, "layer %d out of range", layer);
+    if (n_tokens < 1 || n_tokens > c.max_tokens) return fail(TL_ERR_WINDOW, "n_tokens outside [1, max_tokens]");
+    if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
+    hipStream_t s = L->model->stream;
+    TLCHK(layer_forward(L, layer, h_in, h_out, n_tokens));
+    HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf, (size_t)n_tokens * c.d_model, s));
+    TLCHK(layer_backward(L, layer, h_in, dh_out, L->dh_bf, dh_in, nullptr, n_tokens));
+    L->have_grads = true;
+    L->last_tokens = n_tokens;
+    if (apply_adamw) {
+        const size_t off = L->off[layer].A[0];
+        const size_t end = (layer + 1 < c.n_layers) ? L->off[layer + 1].A[0] : L->n_params;
+        TLCHK(optimizer_step(L, lr, off, end - off));
+    }
+    HIPCHK(hipStreamSynchronize(s));
+    if (apply_adamw) L->step += 1;
+    return TL_OK;
+}
+
+// ---------------------------------------------------------------- inspection
+static tl_status factor_span(tl_lora* L, int layer, int proj, int which, size_t n, size_t* off) {
+    const tl_model* m = L->model;
+    if (layer < 0 || layer >= m->cfg.n_layers || proj < 0 || proj > 6 || which < 0 || which > 7)
+        return fail(TL_ERR_ARG, "bad (layer, proj, which) = (%d, %d, %d)", layer, proj, which);
+    const int g = kProjGroup[proj], i = kProjIndex[proj], r = L->cfg.rank;
+    const size_t na = (size_t)r * m->d_in(g), nb = (size_t)m->d_out(g) * r;
+    const bool isB = which & 1;
+    if (n != (isB ? nb : na)) return fail(TL_ERR_ARG, "size mismatch: expected %zu elements", isB ? nb : na);
+    *off = isB ? L->off[layer].B[g] + i * nb : L->off[layer].A[g] + i * na;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_get_factor(tl_lora* L, int32_t layer, int32_t proj, int32_t which, float* host_out, size_t n) {
+    LIVE(L, "tl_get_factor");
+    if (!host_out) return fail(TL_ERR_ARG, "host_out is null");
+    size_t off = 0;
+    TLCHK(factor_span(L, layer, proj, which, n, &off));
+    const float* base = which < 2 ? L->P : which < 4 ? L->G : which < 6 ? L->M : L->V;
+    HIPCHK(hipStreamSynchronize(L->model->stream));
+    HIPCHK(hipMemcpy(host_out, base + off, n * sizeof(float), hipMemcpyDeviceToHost));
+    return TL_OK;
+}
+
+extern "C" tl_status tl_set_factor(tl_lora* L, int32_t layer, int32_t proj, int32_t which, const float* host_in,
+                                   size_t n) {
+    LIVE(L, "tl_set_factor");
+    if (!host_in) return fail(TL_ERR_ARG, "host_in is null");
+    if (which != TL_FACTOR_A && which != TL_FACTOR_B) return fail(TL_ERR_ARG, "only A or B can be set");
+    size_t off = 0;
+    TLCHK(factor_span(L, layer, proj, which, n, &off));
+    hipStream_t s = L->model->stream;
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipMemcpy(L->P + off, host_in, n * sizeof(float), hipMemcpyHostToDevice));
+    HIPCHK(launch_f32_to_bf16(L->P + off, L->S + off, n, s));
+    TLCHK(refresh_transposed(L));
+    HIPCHK(hipStreamSynchronize(s));
+    return TL_OK;
+}
+
+extern "C" tl_status tl_get_step(tl_lora* L, int64_t* step_out) {
+    LIVE(L, "tl_get_step");
+    if (!step_out) return fail(TL_ERR_ARG, "step_out is null");
+    *step_out = L->step;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_get_nll(tl_lora* L, float* host_out, size_t n) {
+    LIVE(L, "tl_get_nll");
+    if (!host_out) return fail(TL_ERR_ARG, "host_out is null");
+    if (L->last_tokens <= 0 || n != (size_t)L->last_tokens) return fail(TL_ERR_ARG, "n must equal the last call's n_tokens");
+    HIPCHK(hipStreamSynchronize(L->model->stream));
+    HIPCHK(hipMemcpy(host_out, L->nll, n * sizeof(float), hipMemcpyDeviceToHost));
+    return TL_OK;
+}
+
+extern "C" tl_status tl_get_dh(tl_lora* L, int32_t boundary, float* host_out, size_t n) {
+    LIVE(L, "tl_get_dh");
+    if (!host_out) return fail(TL_ERR_ARG, "host_out is null");
+    const tl_model_cfg& c = L->model->cfg;
+    if (boundary < 0 || boundary > c.n_layers) return fail(TL_ERR_ARG, "boundary out of range");
+    if (!L->have_grads || n != (size_t)L->last_tokens * c.d_model) return fail(TL_ERR_ARG, "n must be n_tokens * d_model of the last update");
+    HIPCHK(hipStreamSynchronize(L->model->stream));
+    HIPCHK(hipMemcpy(host_out, L->dhs[boundary], n * sizeof(float), hipMemcpyDeviceToHost));
+    return TL_OK;
+}
+
+// ---------------------------------------------------------------- single fp32 LoRA-adapted linear layer
+extern "C" tl_status tl_linear_step(const float* X, const float* W, const float* A, const float* B, const float* dY,
+                                    int32_t T, int32_t d_in, int32_t d_out, int32_t r, float s, float lr, float beta1,
+                                    float beta2, float eps, float wd, int32_t apply_adamw, float* Y, float* dX,
+                                    float* dA, float* dB, float* A_new, float* B_new, void* hip_stream) {
+    if (!X || !W || !A || !B || !dY || !Y || !dX || !dA || !dB) return fail(TL_ERR_ARG, "tl_linear_step: null pointer");
+    if (apply_adamw && (!A_new || !B_new)) return fail(TL_ERR_ARG, "tl_linear_step: A_new/B_new required");
+    if (T < 1 || d_in < 1 || d_out < 1 || r < 1) return fail(TL_ERR_SHAPE, "tl_linear_step: non-positive dimension");
+    TLCHK(require_gfx950());
+    hipStream_t st = (hipStream_t)hip_stream;
+    Pool pool;
+    float *H = nullptr, *dH = nullptr, *mom = nullptr;
+    auto body = [&]() -> tl_status {
+        TLCHK(pool.alloc(&H, (size_t)T * r));
+        TLCHK(pool.alloc(&dH, (size_t)T * r));
+        // H = X A^T;  Y = X W^T + s H B^T
+        HIPCHK(launch_sgemm(0, 1, T, r, d_in, 1.f, X, d_in, A, d_in, 0.f, H, r, st));
+        HIPCHK(launch_sgemm(0, 1, T, d_out, d_in, 1.f, X, d_in, W, d_in, 0.f, Y, d_out, st));
+        HIPCHK(launch_sgemm(0, 1, T, d_out, r, s, H, r, B, r, 1.f, Y, d_out, st));
+        // dH = s dY B;  dX = dY W + dH A;  dA = dH^T X;  dB = s dY^T H
+        HIPCHK(launch_sgemm(0, 0, T, r, d_out, s, dY, d_out, B, r, 0.f, dH, r, st));
+        HIPCHK(launch_sgemm(0, 0, T, d_in, d_out, 1.f, dY, d_out, W, d_in, 0.f, dX, d_in, st));
+        HIPCHK(launch_sgemm(0, 0, T, d_in, r, 1.f, dH, r, A, d_in, 1.f, dX, d_in, st));
+        HIPCHK(launch_sgemm(1, 0, r, d_in, T, 1.f, dH, r, X, d_in, 0.f, dA, d_in, st));
+        HIPCHK(launch_sgemm(1, 0, d_out, r, T, s, dY, d_out, H, r, 0.f, dB, r, st));
+        if (apply_adamw) {
+            const size_t na = (size_t)r * d_in, nb = (size_t)d_out * r;
+            TLCHK(pool.alloc(&mom, 2 * (na + nb)));
+            HIPCHK(launch_fill_f32(mom, 2 * (na + nb), 0.f, st));
+            HIPCHK(hipMemcpyAsync(A_new, A, na * sizeof(float), hipMemcpyDeviceToDevice, st));
+            HIPCHK(hipMemcpyAsync(B_new, B, nb * sizeof(float), hipMemcpyDeviceToDevice, st));
+            HIPCHK(launch_adamw(A_new, dA, mom, mom + na, nullptr, na, 1, lr, beta1, beta2, eps, wd, st));
+            HIPCHK(launch_adamw(B_new, dB, mom + 2 * na, mom + 2 * na + nb, nullptr, nb, 1, lr, beta1, beta2, eps, wd, st));
+        }
+        HIPCHK(hipStreamSynchronize(st));
+        return TL_OK;
+    };
+    tl_status rc = body();
+    if (rc != TL_OK) (void)hipStreamSynchronize(st);
+    pool.release();
+    return rc;
+}
+
+// ---------------------------------------------------------------- single kernels
+#define KARGS_OK(cond, name) \
+    do { if (!(cond)) return fail(TL_ERR_ARG, name ": bad argument"); } while (0)
+
+extern "C" tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t* B, int32_t ldb, int32_t M, int32_t N,
+                                  int32_t K, const uint16_t* A2, int32_t lda2, const uint16_t* B2, int32_t ldb2,
+                                  int32_t K2, float alpha, const float* R, void* C, int32_t ldc, int32_t c_f32,
+                                  void* hip_stream) {
+    KARGS_OK(A && B && C && M >= 0 && N >= 0 && K >= 0 && K2 >= 0 && (K2 == 0 || (A2 && B2)), "tl_k_gemm_nt");
+    GemmNT g;
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.M = M; g.N = N; g.K = K;
+    g.A2 = K2 ? A2 : nullptr; g.lda2 = lda2; g.B2 = K2 ? B2 : nullptr; g.ldb2 = ldb2; g.K2 = K2;
+    g.alpha = alpha; g.R = R; g.C = C; g.ldc = ldc; g.c_f32 = c_f32;
+    HIPCHK(launch_gemm_nt(g, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_gemm_tn(const uint16_t* P, int32_t ldp, const uint16_t* Q, int32_t ldq, int32_t T, int32_t Mo,
+                                  int32_t No, float alpha, float* C, int32_t ldc, void* hip_stream) {
+    KARGS_OK(P && Q && C && T >= 0 && Mo >= 0 && No >= 0, "tl_k_gemm_tn");
+    GemmTN g;
+    g.P = P; g.ldp = ldp; g.Q = Q; g.ldq = ldq; g.T = T; g.Mo = Mo; g.No = No; g.alpha = alpha; g.C = C; g.ldc = ldc;
+    HIPCHK(launch_gemm_tn(g, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_rmsnorm_fwd(const float* h, const float* g, int32_t T, int32_t d, float eps, uint16_t* y,
+                                      void* hip_stream) {
+    KARGS_OK(h && g && y && T >= 0 && d > 0 && (d & 7) == 0, "tl_k_rmsnorm_fwd");
+    HIPCHK(launch_rmsnorm_fwd(h, g, T, d, eps, y, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_rmsnorm_bwd(const uint16_t* dy, const float* h, const float* g, const float* dres, int32_t T,
+                                      int32_t d, float eps, float* dh_out, uint16_t* dh_out_bf16, void* hip_stream) {
+    KARGS_OK(dy && h && g && dh_out && T >= 0 && d > 0 && (d & 7) == 0, "tl_k_rmsnorm_bwd");
+    HIPCHK(launch_rmsnorm_bwd(dy, h, g, dres, T, d, eps, dh_out, dh_out_bf16, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_heads, int32_t d_head, float base,
+                               int32_t pos0, int32_t sign, void* hip_stream) {
+    KARGS_OK(x && T >= 0 && n_heads > 0 && d_head >= 4 && (d_head & 3) == 0 && (ld & 1) == 0 && pos0 >= 0, "tl_k_rope");
+    HIPCHK(launch_rope(x, ld, T, n_heads, d_head, base, pos0, sign, nullptr, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a, void* hip_stream) {
+    KARGS_OK(gu && a && T >= 0 && f > 0 && (f & 7) == 0, "tl_k_swiglu_fwd");
+    HIPCHK(launch_swiglu_fwd(gu, T, f, a, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_swiglu_bwd(const uint16_t* da, const uint16_t* gu, int32_t T, int32_t f, uint16_t* dgu,
+                                     void* hip_stream) {
+    KARGS_OK(da && gu && dgu && T >= 0 && f > 0 && (f & 7) == 0, "tl_k_swiglu_bwd");
+    HIPCHK(launch_swiglu_bwd(da, gu, T, f, dgu, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_attention_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ldq, int32_t T,
+                                        int32_t n_heads, int32_t d_head, uint16_t* o, int32_t ldo, float* lse,
+                                        void* hip_stream) {
+    KARGS_OK(q && k && v && o && lse && T >= 0 && n_heads > 0 && (d_head == 64 || d_head == 128), "tl_k_attention_fwd");
+    HIPCHK(launch_attention_fwd(q, k, v, ldq, T, n_heads, d_head, o, ldo, lse, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_attention_bwd(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* o,
+                                        const uint16_t* d_o, const float* lse, int32_t ldq, int32_t ldo, int32_t T,
+                                        int32_t n_heads, int32_t d_head, uint16_t* dq, uint16_t* dk, uint16_t* dv,
+                                        float* delta, void* hip_stream) {
+    KARGS_OK(q && k && v && o && d_o && lse && dq && dk && dv && delta && T >= 0 && n_heads > 0 &&
+                 (d_head == 64 || d_head == 128), "tl_k_attention_bwd");
+    HIPCHK(launch_attention_bwd(q, k, v, o, d_o, lse, ldq, ldo, T, n_heads, d_head, dq, dk, dv, delta,
+                                (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_cross_entropy(const float* logits, const int32_t* labels, int32_t T, int32_t V,
+                                        int32_t first_target, int32_t n_targets, float* nll, uint16_t* dlogits,
+                                        float* loss_sum, void* hip_stream) {
+    KARGS_OK(logits && labels && nll && T >= 0 && V > 0 && n_targets > 0 && first_target >= 0, "tl_k_cross_entropy");
+    HIPCHK(launch_cross_entropy(logits, labels, T, V, first_target, n_targets, nll, dlogits, loss_sum,
+                                (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_adamw(float* p, const float* g, float* m, float* v, uint16_t* shadow, size_t n, int64_t step,
+                                float lr, float beta1, float beta2, float eps, float wd, void* hip_stream) {
+    KARGS_OK(p && g && m && v && step >= 1, "tl_k_adamw");
+    HIPCHK(launch_adamw(p, g, m, v, shadow, n, (long)step, lr, beta1, beta2, eps, wd, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_embed(const uint16_t* E, const int32_t* tokens, int32_t T, int32_t d, float* h,
+                                void* hip_stream) {
+    KARGS_OK(E && tokens && h && T >= 0 && d > 0 && (d & 7) == 0, "tl_k_embed");
+    HIPCHK(launch_embed(E, tokens, T, d, h, (hipStream_t)hip_stream));
+    return TL_OK;
+}

@@ -1,0 +1,60 @@
+// MFMA tile helpers shared by the GEMM and attention kernels (gfx950).
+//
+// v_mfma_f32_32x32x16_bf16 operand layout (lane = 32*g + l32):
+//   A fragment: row  i = l32, contraction slots k = 8g .. 8g+7   (8 bf16 = 16 bytes per lane)
+//   B fragment: col  j = l32, contraction slots k = 8g .. 8g+7
+//   D fragment: col  j = l32, rows i = 8*(v/4) + 4g + v%4 for v = 0..15
+// Because the contraction is a sum, any permutation of the 16 slots is allowed as long as A and B
+// use the same one.  A D fragment reused as a B operand (keeping j) supplies, for registers
+// v = 8h .. 8h+7, the slot order  i = 16h + {4g..4g+3, 8+4g..8+4g+3}; the A operand is then read
+// from a [row][i] LDS tile as two 8-byte pieces at i = 16h+4g and 16h+8+4g.
+#pragma once
+#include "common.h"
+
+#define BK 64
+#define LS 72  // LDS row stride (elements) of a 64-wide bf16 tile: 16-byte reads of 8 rows hit 32 distinct banks
+
+__device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16_t zero16() {
+    f32x16_t z;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) z[v] = 0.f;
+    return z;
+}
+
+// Offset of element (i, t) in a transposed [i][t] tile, t < 64.  The 8-element t-chunk index is XORed
+// with (i / 8) % 8 so that the 8 column groups written by one row of the source land in distinct banks.
+__device__ __forceinline__ int tn_off(int i, int t) { return i * LS + ((((t >> 3) ^ (i >> 3)) & 7) << 3) + (t & 7); }
+
+// Thread holds source rows t, t+1 (t even) and 8 columns i0..i0+7; writes 8 dwords into the [i][t] tile.
+__device__ __forceinline__ void store_transposed_pair(bf16_t* tile, int i0, int t, uint4 r0, uint4 r1) {
+    const uint32_t a[4] = {r0.x, r0.y, r0.z, r0.w}, b[4] = {r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint32_t lo = (a[e] & 0xffffu) | (b[e] << 16);
+        const uint32_t hi = (a[e] >> 16) | (b[e] & 0xffff0000u);
+        *(uint32_t*)(tile + tn_off(i0 + 2 * e, t)) = lo;
+        *(uint32_t*)(tile + tn_off(i0 + 2 * e + 1, t)) = hi;
+    }
+}
+
+// A operand for a D-fragment-as-B product: row i of the [row][t] transposed tile, slots for half h
+__device__ __forceinline__ bf16x8_t load_a_permuted(const bf16_t* tile, int row, int t16, int g) {
+    const bf16x4_t lo = *(const bf16x4_t*)(tile + tn_off(row, t16 + 4 * g));
+    const bf16x4_t hi = *(const bf16x4_t*)(tile + tn_off(row, t16 + 8 + 4 * g));
+    bf16x8_t a;
+    a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
+    a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
+    return a;
+}
+
+// registers v = 8h .. 8h+7 of a D fragment, rounded to bf16, as a B operand
+__device__ __forceinline__ bf16x8_t pack_b_from_d(const float* d, int h) {
+    bf16x8_t b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = (__bf16)d[8 * h + e];
+    return b;
+}

@@ -57,7 +57,7 @@ class Shape:
 SHAPES = {
     "tiny": Shape(2, 32, 2, 16, 48, 64, 4, 8.0),
     "small": Shape(2, 256, 4, 64, 704, 1000, 16, 16.0),
-    "small128": Shape(2, 256, 2, 128, 448, 777, 8, 16.0),
+    "small128": Shape(2, 256, 2, 128, 448, 776, 8, 16.0),
     "layer": Shape(1, 1024, 16, 64, 2816, 0, 16, 16.0),
     "7b": Shape(32, 4096, 32, 128, 11008, 32000, 64, 64.0),
 }
@@ -67,11 +67,24 @@ def rng(seed: int, *path: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(np.random.SeedSequence([int(seed), *map(int, path)])))
 
 
+def _round_bf16_inplace(x: np.ndarray) -> np.ndarray:
+    """Round a contiguous fp32 array to bf16-representable values in place (nearest-even; finite inputs)."""
+    u = x.reshape(-1).view(np.uint32)
+    step = 1 << 22  # bounded temporaries for multi-GB tensors
+    for i in range(0, u.size, step):
+        blk = u[i:i + step]
+        t = blk >> np.uint32(16)
+        t &= np.uint32(1)
+        t += np.uint32(0x7FFF)
+        blk += t
+        blk &= np.uint32(0xFFFF0000)
+    return x
+
+
 def bf16_bits(x: np.ndarray) -> np.ndarray:
     """fp32 -> bf16 bit patterns (uint16), round-to-nearest-even. Inputs are finite."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    return ((u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)).astype(np.uint16)
+    y = _round_bf16_inplace(np.array(x, dtype=np.float32, order="C", copy=True))
+    return (y.reshape(-1).view(np.uint32) >> np.uint32(16)).astype(np.uint16).reshape(np.shape(x))
 
 
 def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
@@ -80,13 +93,13 @@ def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
 
 def round_bf16(x: np.ndarray) -> np.ndarray:
     """fp32 array whose every value is exactly representable in bf16."""
-    return bf16_to_f32(bf16_bits(x)).reshape(np.shape(x))
+    return _round_bf16_inplace(np.array(x, dtype=np.float32, order="C", copy=True))
 
 
 def normal(seed: int, path, shape, std: float, bf16: bool) -> np.ndarray:
     x = rng(seed, *path).standard_normal(shape, dtype=np.float32)
     x *= np.float32(std)
-    return round_bf16(x) if bf16 else x
+    return _round_bf16_inplace(x) if bf16 else x
 
 
 def uniform_tokens(seed: int, n: int, vocab: int, stream: int = 0) -> np.ndarray:

@@ -1,0 +1,239 @@
+"""Per-kernel parity: every HIP kernel, called through the C ABI, against the CPU oracle.
+
+Inputs are seeded draws rounded to the storage type first, so both sides see the same
+values; the oracle works in fp64.  Tolerances: 2e-2 relative (bf16 storage), 1e-4 (fp32),
+as relative L2 error per tensor plus a max-abs bound of 10 * tol * RMS(oracle).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import templora_oracle as O  # noqa: E402
+from paper_2401_11504_amd import synth  # noqa: E402
+
+BF16_TOL, F32_TOL = 2e-2, 1e-4
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2401_11504_amd import api as _api
+    return _api
+
+
+@pytest.fixture(scope="module")
+def H():
+    from paper_2401_11504_amd import harness
+    return harness
+
+
+def check(gpu, ref, tol, name=""):
+    gpu, ref = np.asarray(gpu, np.float64), np.asarray(ref, np.float64)
+    assert gpu.shape == ref.shape, (name, gpu.shape, ref.shape)
+    assert np.all(np.isfinite(gpu)), name
+    nr = np.linalg.norm(ref)
+    if nr == 0:
+        assert np.all(gpu == 0), name
+        return
+    rel = np.linalg.norm(gpu - ref) / nr
+    rms = nr / np.sqrt(ref.size)
+    mx = np.abs(gpu - ref).max()
+    assert rel <= tol, f"{name}: rel L2 {rel:.3e} > {tol}"
+    assert mx <= 10 * tol * rms, f"{name}: max abs {mx:.3e} > {10 * tol * rms:.3e}"
+
+
+def rnd(seed, shape, std=1.0, bf16=True):
+    return synth.normal(seed, (77, len(shape), shape[0]), shape, std, bf16)
+
+
+# ------------------------------------------------------------------ GEMM NT
+@pytest.mark.parametrize("M,N,K,K2", [(128, 128, 64, 0), (1024, 512, 256, 16), (300, 200, 136, 8),
+                                      (77, 16, 264, 0), (1024, 64, 1024, 0), (256, 4096, 512, 64), (1, 8, 8, 0)])
+def test_gemm_nt_bf16(api, H, M, N, K, K2):
+    A, B = rnd(1, (M, K)), rnd(2, (N, K), 0.05)
+    A2 = rnd(3, (M, K2)) if K2 else None
+    B2 = rnd(4, (N, K2), 0.05) if K2 else None
+    ref = A.astype(np.float64) @ B.T.astype(np.float64)
+    if K2:
+        ref = ref + A2.astype(np.float64) @ B2.T.astype(np.float64)
+    Cd = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cd, H.to_dev_bf16(A2) if K2 else None,
+                     H.to_dev_bf16(B2) if K2 else None, alpha=0.5)
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(Cd), 0.5 * ref, BF16_TOL, "C bf16")
+    # fp32 output with residual
+    R = rnd(5, (M, N), 1.0, False)
+    Cf = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cf, H.to_dev_bf16(A2) if K2 else None,
+                     H.to_dev_bf16(B2) if K2 else None, alpha=1.0, R=H.to_dev_f32(R))
+    torch.cuda.synchronize()
+    check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")   # bf16 products are exact; only fp32 summation order differs
+
+
+def test_gemm_nt_strided_operands(api, H):
+    # operands that are column blocks of wider buffers (as q|k|v and gate|up are)
+    M, N, K = 200, 96, 128
+    Aw, Bw = rnd(1, (M, 3 * K)), rnd(2, (N, 2 * K), 0.05)
+    Ad, Bd = H.to_dev_bf16(Aw), H.to_dev_bf16(Bw)
+    Cw = torch.zeros(M, 2 * N, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_gemm_nt(Ad[:, K:2 * K], Bd[:, K:], Cw[:, N:])
+    torch.cuda.synchronize()
+    ref = Aw[:, K:2 * K].astype(np.float64) @ Bw[:, K:].T.astype(np.float64)
+    check(H.bf16_to_np(Cw[:, N:]), ref, BF16_TOL)
+    assert torch.all(Cw[:, :N] == 0)
+
+
+# ------------------------------------------------------------------ GEMM TN
+@pytest.mark.parametrize("T,Mo,No", [(64, 64, 64), (1024, 48, 256), (300, 200, 136), (1000, 16, 704), (5, 8, 8)])
+def test_gemm_tn(api, H, T, Mo, No):
+    P, Q = rnd(1, (T, Mo)), rnd(2, (T, No))
+    C = torch.empty(Mo, No, dtype=torch.float32, device="cuda")
+    api.tl_k_gemm_tn(H.to_dev_bf16(P), H.to_dev_bf16(Q), C, alpha=2.0)
+    torch.cuda.synchronize()
+    check(C.cpu().numpy(), 2.0 * P.T.astype(np.float64) @ Q.astype(np.float64), 1e-3)
+
+
+# ------------------------------------------------------------------ RMSNorm
+@pytest.mark.parametrize("T,d", [(5, 64), (130, 1024), (33, 4096)])
+def test_rmsnorm_fwd_bwd(api, H, T, d):
+    h = rnd(1, (T, d), 2.0, False)
+    g = 1.0 + 0.1 * rnd(2, (d,), 1.0, False)
+    dy = rnd(3, (T, d))
+    dres = rnd(4, (T, d), 1.0, False)
+    y = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_rmsnorm_fwd(H.to_dev_f32(h), H.to_dev_f32(g), 1e-5, y)
+    dh = torch.empty(T, d, dtype=torch.float32, device="cuda")
+    dhb = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_rmsnorm_bwd(H.to_dev_bf16(dy), H.to_dev_f32(h), H.to_dev_f32(g), H.to_dev_f32(dres), 1e-5, dh, dhb)
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(y), O.rmsnorm_fwd(h, g, 1e-5), BF16_TOL, "y")
+    ref = dres + O.rmsnorm_bwd(dy, h, g, 1e-5)
+    check(dh.cpu().numpy(), ref, F32_TOL, "dh")
+    check(H.bf16_to_np(dhb), ref, BF16_TOL, "dh bf16")
+    dh2 = torch.empty_like(dh)
+    api.tl_k_rmsnorm_bwd(H.to_dev_bf16(dy), H.to_dev_f32(h), H.to_dev_f32(g), None, 1e-5, dh2, None)
+    torch.cuda.synchronize()
+    check(dh2.cpu().numpy(), O.rmsnorm_bwd(dy, h, g, 1e-5), F32_TOL, "dh without residual")
+
+
+# ------------------------------------------------------------------ RoPE
+@pytest.mark.parametrize("T,nh,dh,pos0", [(70, 3, 64, 0), (1024, 2, 128, 0), (9, 1, 64, 1000)])
+def test_rope(api, H, T, nh, dh, pos0):
+    x = rnd(1, (T, nh * dh))
+    xd = H.to_dev_bf16(x)
+    api.tl_k_rope(xd, nh, dh, 10000.0, pos0, +1)
+    torch.cuda.synchronize()
+    ref = O.rope_fwd(x.reshape(T, nh, dh), 10000.0, pos0).reshape(T, nh * dh)
+    check(H.bf16_to_np(xd), ref, BF16_TOL, "fwd")
+    xb = H.to_dev_bf16(x)
+    api.tl_k_rope(xb, nh, dh, 10000.0, pos0, -1)
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(xb), O.rope_bwd(x.reshape(T, nh, dh), 10000.0, pos0).reshape(T, nh * dh), BF16_TOL, "bwd")
+
+
+# ------------------------------------------------------------------ SwiGLU
+@pytest.mark.parametrize("T,f", [(3, 8), (257, 704), (64, 11008)])
+def test_swiglu(api, H, T, f):
+    gu, da = rnd(1, (T, 2 * f), 2.0), rnd(2, (T, f))
+    a = torch.empty(T, f, dtype=torch.bfloat16, device="cuda")
+    dgu = torch.empty(T, 2 * f, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_swiglu_fwd(H.to_dev_bf16(gu), a)
+    api.tl_k_swiglu_bwd(H.to_dev_bf16(da), H.to_dev_bf16(gu), dgu)
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(a), O.swiglu_fwd(gu[:, :f], gu[:, f:]), BF16_TOL, "a")
+    dg, du = O.swiglu_bwd(da, gu[:, :f], gu[:, f:])
+    check(H.bf16_to_np(dgu), np.concatenate([dg, du], 1), BF16_TOL, "dgu")
+
+
+# ------------------------------------------------------------------ attention
+@pytest.mark.parametrize("T,nh,dh", [(64, 1, 64), (200, 2, 64), (333, 2, 128), (1024, 2, 128), (1, 1, 64), (129, 1, 128)])
+def test_attention_fwd_bwd(api, H, T, nh, dh):
+    qkv = rnd(1, (T, 3 * nh * dh), 1.0)
+    do = rnd(2, (T, nh * dh))
+    d = nh * dh
+    qkvd = H.to_dev_bf16(qkv)
+    o = torch.zeros(T, d, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(nh, T, dtype=torch.float32, device="cuda")
+    api.tl_k_attention_fwd(qkvd[:, :d], qkvd[:, d:2 * d], qkvd[:, 2 * d:], nh, dh, o, lse)
+    torch.cuda.synchronize()
+    q, k, v = (qkv[:, i * d:(i + 1) * d].reshape(T, nh, dh) for i in range(3))
+    ro, P = O.attention_fwd(q, k, v)
+    check(H.bf16_to_np(o), ro.reshape(T, d), BF16_TOL, "o")
+    S = np.einsum("thd,uhd->htu", q.astype(np.float64), k.astype(np.float64)) / np.sqrt(dh)
+    S = np.where(np.triu(np.ones((T, T), bool), 1)[None], -np.inf, S)
+    mx = S.max(-1)
+    ref_lse = np.log(np.exp(S - mx[..., None]).sum(-1)) + mx
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() < 2e-3
+    # backward takes the GPU's own (bf16-rounded) o, as the composed path does
+    dqkv = torch.zeros(T, 3 * d, dtype=torch.bfloat16, device="cuda")
+    delta = torch.zeros(nh, T, dtype=torch.float32, device="cuda")
+    api.tl_k_attention_bwd(qkvd[:, :d], qkvd[:, d:2 * d], qkvd[:, 2 * d:], o, H.to_dev_bf16(do), lse, nh, dh,
+                           dqkv[:, :d], dqkv[:, d:2 * d], dqkv[:, 2 * d:], delta)
+    torch.cuda.synchronize()
+    dq, dk, dv = O.attention_bwd(do.reshape(T, nh, dh), q, k, v, P)
+    g = H.bf16_to_np(dqkv)
+    check(g[:, :d], dq.reshape(T, d), BF16_TOL, "dq")
+    check(g[:, d:2 * d], dk.reshape(T, d), BF16_TOL, "dk")
+    check(g[:, 2 * d:], dv.reshape(T, d), BF16_TOL, "dv")
+
+
+# ------------------------------------------------------------------ cross entropy
+@pytest.mark.parametrize("T,V,n_ctx", [(9, 64, 0), (130, 1000, 0), (64, 32000, 0), (40, 776, 17)])
+def test_cross_entropy(api, H, T, V, n_ctx):
+    z = rnd(1, (T, V), 1.5, False)
+    tok = synth.uniform_tokens(3, T, V)
+    labels, mask, N = O.labels_and_mask(tok, n_ctx)
+    first = max(n_ctx, 1) - 1
+    assert np.array_equal(np.nonzero(mask)[0], np.arange(first, T - 1))
+    nll = torch.zeros(T, dtype=torch.float32, device="cuda")
+    dl = torch.zeros(T, V, dtype=torch.bfloat16, device="cuda")
+    ls = torch.zeros(4, dtype=torch.float32, device="cuda")
+    lab_d = torch.from_numpy(labels.astype(np.int32)).cuda()
+    api.tl_k_cross_entropy(H.to_dev_f32(z), lab_d, first, N, nll, dl, ls)
+    torch.cuda.synchronize()
+    loss, rnll, rdl = O.cross_entropy(z, labels, mask)
+    check(nll.cpu().numpy(), rnll, F32_TOL, "nll")
+    assert abs(ls[0].item() / N - loss) <= F32_TOL * loss
+    check(H.bf16_to_np(dl), rdl, BF16_TOL, "dlogits")
+    assert torch.all(dl[~torch.from_numpy(mask).cuda()] == 0)
+
+
+# ------------------------------------------------------------------ AdamW
+@pytest.mark.parametrize("n", [7, 4096, 1_000_003])
+def test_adamw_steps(api, H, n):
+    p = rnd(1, (n,), 0.02, False)
+    m, v = np.zeros(n), np.zeros(n)
+    pd, md, vd = H.to_dev_f32(p), torch.zeros(n, device="cuda"), torch.zeros(n, device="cuda")
+    sh = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    pr = p.astype(np.float64)
+    for step in (1, 2, 3):
+        g = rnd(10 + step, (n,), 1e-3, False)
+        g[::5] = 0.0
+        api.tl_k_adamw(pd, H.to_dev_f32(g), md, vd, sh, step, 5e-5, 0.9, 0.999, 1e-8, 0.01)
+        pr, m, v = O.adamw_step(pr, g, m, v, step, 5e-5, 0.9, 0.999, 1e-8, 0.01)
+    torch.cuda.synchronize()
+    check(pd.cpu().numpy() - p, pr - p, 1e-3, "delta p")      # the update itself, not p, carries the comparison
+    check(md.cpu().numpy(), m, F32_TOL, "m")
+    check(vd.cpu().numpy(), v, F32_TOL, "v")
+    assert torch.equal(sh, pd.bfloat16())
+
+
+def test_adamw_zero_grad_leaves_param_bit_identical(api, H):
+    p = rnd(1, (1000,), 0.02, False)
+    pd = H.to_dev_f32(p)
+    api.tl_k_adamw(pd, torch.zeros(1000, device="cuda"), torch.zeros(1000, device="cuda"),
+                   torch.zeros(1000, device="cuda"), None, 1, 5e-5)
+    torch.cuda.synchronize()
+    assert np.array_equal(pd.cpu().numpy(), p)
+
+
+# ------------------------------------------------------------------ embedding gather (bit exact)
+def test_embed_rows_bit_exact(api, H):
+    V, d, T = 1000, 256, 77
+    E = rnd(1, (V, d), 0.02)
+    tok = synth.uniform_tokens(5, T, V)
+    h = torch.zeros(T, d, device="cuda")
+    api.tl_k_embed(H.to_dev_bf16(E), torch.from_numpy(tok).cuda(), h)
+    torch.cuda.synchronize()
+    assert np.array_equal(h.cpu().numpy(), E[tok])

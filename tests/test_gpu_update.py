@@ -1,0 +1,256 @@
+"""Composed parity through the C ABI: the fp32 linear step, one decoder layer, the whole chunk update,
+state carry over chunks and epochs, and the module life cycle with its error paths."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import templora_oracle as O  # noqa: E402
+from paper_2401_11504_amd import synth  # noqa: E402
+from test_gpu_kernels import BF16_TOL, F32_TOL, check  # noqa: E402
+
+PROJ = synth.PROJ
+LR = 5e-5
+
+
+@pytest.fixture(scope="module")
+def api():
+    from paper_2401_11504_amd import api as _api
+    return _api
+
+
+@pytest.fixture(scope="module")
+def H():
+    from paper_2401_11504_amd import harness
+    return harness
+
+
+def _adam_sign_agreement(delta_gpu, g_ref, lr, name):
+    """Step 1 of AdamW moves an entry by -lr * sign(g) (closed form); compare where |g| is well above noise."""
+    g = np.asarray(g_ref)
+    big = np.abs(g) > 0.05 * np.sqrt(np.mean(g * g))
+    assert big.mean() > 0.5, name
+    want = -lr * np.sign(g[big])
+    got = np.asarray(delta_gpu)[big]
+    assert np.mean(np.sign(got) == np.sign(want)) > 0.9999, name
+    assert np.allclose(got, want, rtol=2e-2, atol=0), name
+
+
+# ------------------------------------------------------------------ single fp32 LoRA-adapted linear step
+@pytest.mark.parametrize("T,din,dout,r", [(128, 256, 256, 8), (77, 200, 136, 5), (1, 8, 8, 1)])
+def test_linear_step_fp32(api, H, T, din, dout, r):
+    c = synth.linear_case(1001, T, din, dout, r)
+    s = 16.0 / 8.0
+    dev = {k: H.to_dev_f32(v) for k, v in c.items()}
+    out = {k: torch.zeros(*shp, device="cuda") for k, shp in
+           dict(Y=(T, dout), dX=(T, din), dA=(r, din), dB=(dout, r), A1=(r, din), B1=(dout, r)).items()}
+    api.tl_linear_step(dev["X"], dev["W"], dev["A"], dev["B"], dev["dY"], s, LR, 0.9, 0.999, 1e-8, 0.0, True,
+                       out["Y"], out["dX"], out["dA"], out["dB"], out["A1"], out["B1"])
+    ref = O.linear_step(c["X"], c["W"], c["A"], c["B"], c["dY"], s, LR)
+    for k in ("Y", "dX", "dA", "dB", "A1", "B1"):
+        check(out[k].cpu().numpy(), ref[k], F32_TOL, k)
+    check(out["A1"].cpu().numpy() - c["A"], ref["A1"] - c["A"], 1e-3, "A step")
+    check(out["B1"].cpu().numpy() - c["B"], ref["B1"] - c["B"], 1e-3, "B step")
+
+
+# ------------------------------------------------------------------ one decoder layer
+def _layer_case(api, H, shape, T, seed, b_std=0.01):
+    model = H.Model(shape, seed, max_tokens=T)
+    lora, facs = H.new_lora(model, seed, b_std=b_std)
+    h = synth.hidden(seed, T, shape.d_model)
+    dy = synth.upstream_grad(seed, T, shape.d_model)
+    return model, lora, facs, h, dy
+
+
+@pytest.mark.parametrize("name,T", [("layer", 1024), ("small", 200), ("small128", 333)])
+def test_layer_step_bf16(api, H, name, T):
+    shape = synth.SHAPES[name].with_layers(1)
+    model, lora, facs, h, dy = _layer_case(api, H, shape, T, 2002)
+    h_out = torch.zeros(T, shape.d_model, device="cuda")
+    dh_in = torch.zeros(T, shape.d_model, device="cuda")
+    api.tl_layer_step(lora, 0, H.to_dev_f32(h), H.to_dev_f32(dy), h_out, dh_in, LR, True)
+    W = model.host_layers[0]
+    ref_out, cache = O.layer_fwd(h, W, facs[0], shape)
+    ref_dh, G = O.layer_bwd(dy, cache, W, facs[0], shape)
+    check(h_out.cpu().numpy(), ref_out, BF16_TOL, "h_out")
+    check(dh_in.cpu().numpy(), ref_dh, BF16_TOL, "dh_in")
+    for i, p in enumerate(PROJ):
+        dout, din = shape.proj_dims(p)
+        dA = api.tl_get_factor(lora, 0, i, api.GRAD_A, (shape.rank, din))
+        dB = api.tl_get_factor(lora, 0, i, api.GRAD_B, (dout, shape.rank))
+        check(dA, G[p][0], BF16_TOL, f"dA {p}")
+        check(dB, G[p][1], BF16_TOL, f"dB {p}")
+        A1 = api.tl_get_factor(lora, 0, i, api.FACTOR_A, (shape.rank, din))
+        B1 = api.tl_get_factor(lora, 0, i, api.FACTOR_B, (dout, shape.rank))
+        rA, _, _ = O.adamw_step(facs[0][p][0], G[p][0], 0, 0, 1, LR)
+        rB, _, _ = O.adamw_step(facs[0][p][1], G[p][1], 0, 0, 1, LR)
+        check(A1, rA, BF16_TOL, f"A' {p}")
+        check(B1, rB, BF16_TOL, f"B' {p}")
+        _adam_sign_agreement(A1 - facs[0][p][0], G[p][0], LR, f"A step {p}")
+        _adam_sign_agreement(B1 - facs[0][p][1], G[p][1], LR, f"B step {p}")
+    assert api.tl_get_step(lora) == 1
+    api.tl_lora_free(lora)
+    model.close()
+
+
+# ------------------------------------------------------------------ whole chunk update
+def _oracle_update(model, facs, opt, tok, n_ctx, lr, keep=()):
+    shape = model.shape
+    return O.chunk_update(tok, n_ctx, shape, model.emb, model.head, np.ones(shape.d_model),
+                          lambda l: model.host_layers[l], facs, opt, lr, keep=keep)
+
+
+def _compare_update(api, lora, shape, res, new_facs, T):
+    for l in range(shape.n_layers):
+        for i, p in enumerate(PROJ):
+            dout, din = shape.proj_dims(p)
+            check(api.tl_get_factor(lora, l, i, api.GRAD_A, (shape.rank, din)), res["grads"][l][p][0], BF16_TOL,
+                  f"dA l{l} {p}")
+            check(api.tl_get_factor(lora, l, i, api.GRAD_B, (dout, shape.rank)), res["grads"][l][p][1], BF16_TOL,
+                  f"dB l{l} {p}")
+            check(api.tl_get_factor(lora, l, i, api.FACTOR_A, (shape.rank, din)), new_facs[l][p][0], BF16_TOL,
+                  f"A' l{l} {p}")
+            check(api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank)), new_facs[l][p][1], BF16_TOL,
+                  f"B' l{l} {p}")
+
+
+@pytest.mark.parametrize("name,T,n_ctx,b_std", [("small", 200, 0, 0.01), ("small", 256, 100, 0.01),
+                                                ("small128", 333, 0, 0.01), ("small", 130, 0, 0.0),
+                                                ("small", 64, 1, 0.01), ("small", 2, 0, 0.01)])
+def test_chunk_update_matches_oracle(api, H, name, T, n_ctx, b_std):
+    shape = synth.SHAPES[name]
+    model = H.Model(shape, 3003, max_tokens=max(T, 8))
+    lora, facs = H.new_lora(model, 3003, b_std=b_std)
+    tok = synth.uniform_tokens(3003, T, shape.vocab)
+    loss, n = api.tl_chunk_update(lora, tok, n_ctx, LR)
+    res, new_facs, opt = _oracle_update(model, facs, O.new_opt_state(facs), tok, n_ctx, LR,
+                                        keep=range(shape.n_layers))
+    assert n == res["n_targets"]                                   # integer work: exact
+    assert abs(loss - res["loss"]) <= BF16_TOL * abs(res["loss"])
+    check(api.tl_get_nll(lora, T), res["nll"], BF16_TOL, "nll")
+    assert np.all(api.tl_get_nll(lora, T)[~res["mask"]] == 0)
+    check(api.tl_get_dh(lora, shape.n_layers, T, shape.d_model), res["dh"]["final"], BF16_TOL, "dh final")
+    for l in range(shape.n_layers):
+        check(api.tl_get_dh(lora, l, T, shape.d_model), res["dh"][l], BF16_TOL, f"dh layer {l}")
+    _compare_update(api, lora, shape, res, new_facs, T)
+    if b_std == 0.0:
+        # B = 0: dA is exactly zero and A is untouched; every B entry moved by ~lr (AdamW step-1 closed form)
+        for l in range(shape.n_layers):
+            for i, p in enumerate(PROJ):
+                dout, din = shape.proj_dims(p)
+                assert np.all(api.tl_get_factor(lora, l, i, api.GRAD_A, (shape.rank, din)) == 0)
+                assert np.array_equal(api.tl_get_factor(lora, l, i, api.FACTOR_A, (shape.rank, din)), facs[l][p][0])
+                B1 = api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank))
+                _adam_sign_agreement(B1, res["grads"][l][p][1], LR, f"B step l{l} {p}")
+    assert api.tl_get_step(lora) == 1
+    api.tl_lora_free(lora)
+    model.close()
+
+
+def test_state_carry_two_chunks_two_epochs(api, H):
+    """Pre-training on a long input: chunks in sequence, n = 2 epochs each, module state carried (Algorithm 1)."""
+    shape = synth.SHAPES["small"]
+    T = 128
+    model = H.Model(shape, 4004, max_tokens=T)
+    lora, facs = H.new_lora(model, 4004, b_std=0.01)
+    stream = synth.zipf_tokens(4004, 2 * T, shape.vocab)
+    opt = O.new_opt_state(facs)
+    # a larger rate than the paper's makes four steps visibly change the loss at this tiny size
+    lr = 2e-3
+    losses_g, losses_o = [], []
+    for c in range(2):
+        tok = stream[c * T:(c + 1) * T]
+        for _ in range(2):
+            loss, _ = api.tl_chunk_update(lora, tok, 0, lr)
+            res, facs, opt = _oracle_update(model, facs, opt, tok, 0, lr)
+            losses_g.append(loss), losses_o.append(res["loss"])
+    assert np.allclose(losses_g, losses_o, rtol=BF16_TOL, atol=0)
+    assert losses_g[1] < losses_g[0] and losses_g[3] < losses_g[2]     # second epoch on a chunk descends
+    assert api.tl_get_step(lora) == 4
+    for l in range(shape.n_layers):
+        for i, p in enumerate(PROJ):
+            dout, din = shape.proj_dims(p)
+            check(api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank)), facs[l][p][1], 5e-2, f"B l{l} {p}")
+            check(api.tl_get_factor(lora, l, i, api.M_B, (dout, shape.rank)), opt["m"][l][p][1], 5e-2, f"mB l{l} {p}")
+    api.tl_lora_free(lora)
+    model.close()
+
+
+def test_lifecycle_and_error_paths(api, H):
+    shape = synth.SHAPES["small"]
+    T = 64
+    model = H.Model(shape, 5005, max_tokens=T)
+    tok = synth.uniform_tokens(5005, T, shape.vocab)
+    lora, facs = H.new_lora(model, 5005, b_std=0.01)
+    first, _ = api.tl_chunk_loss(lora, tok)
+    # lr = 0: two updates return the same loss, the step counter still advances
+    l0, _ = api.tl_chunk_update(lora, tok, 0, 0.0)
+    l1, _ = api.tl_chunk_update(lora, tok, 0, 0.0)
+    assert l0 == l1 == first and api.tl_get_step(lora) == 2
+    # bad inputs are rejected and leave the module untouched
+    B_before = api.tl_get_factor(lora, 1, 6, api.FACTOR_B, (shape.d_model, shape.rank))
+    bad = tok.copy()
+    bad[7] = shape.vocab
+    for args, status in (((bad, 0, LR), -3), ((tok[:1], 0, LR), -4), ((np.r_[tok, tok], 0, LR), -4),
+                         ((tok, T, LR), -4), ((tok, 0, float("nan")), -1)):
+        with pytest.raises(api.TlError) as e:
+            api.tl_chunk_update(lora, *args)
+        assert e.value.status == status, (args[1:], e.value)
+    assert api.tl_get_step(lora) == 2
+    assert np.array_equal(B_before, api.tl_get_factor(lora, 1, 6, api.FACTOR_B, (shape.d_model, shape.rank)))
+    # a real update changes the loss; discard + fresh init (same factors) restores the first-ever loss bit for bit
+    api.tl_chunk_update(lora, tok, 0, 1e-2)
+    changed, _ = api.tl_chunk_loss(lora, tok)
+    assert changed != first
+    api.tl_discard(lora)
+    for fn in (lambda: api.tl_chunk_update(lora, tok), lambda: api.tl_chunk_loss(lora, tok),
+               lambda: api.tl_get_step(lora), lambda: api.tl_discard(lora)):
+        with pytest.raises(api.TlError) as e:
+            fn()
+        assert e.value.status == -7
+    api.tl_lora_free(lora)
+    lora2, _ = H.new_lora(model, 5005, b_std=0.01)
+    again, _ = api.tl_chunk_loss(lora2, tok)
+    assert again == first
+    api.tl_lora_free(lora2)
+    # a module straight from tl_lora_init has B = 0, so it scores exactly like any other B = 0 module (base model)
+    la, _ = H.new_lora(model, 1, set_from_synth=False)
+    lb, _ = H.new_lora(model, 2, set_from_synth=False)
+    assert api.tl_chunk_loss(la, tok)[0] == api.tl_chunk_loss(lb, tok)[0]
+    A = api.tl_get_factor(la, 0, 0, api.FACTOR_A, (shape.rank, shape.d_model))
+    assert abs(A.mean()) < 2e-3 and abs(A.std() - 0.02) < 2e-3
+    assert not np.array_equal(A, api.tl_get_factor(lb, 0, 0, api.FACTOR_A, (shape.rank, shape.d_model)))
+    api.tl_lora_free(la), api.tl_lora_free(lb)
+    model.close()
+
+
+def test_unsupported_shapes_are_rejected(api, H):
+    with pytest.raises(api.TlError) as e:
+        api.tl_model_create(1, 96, 2, 48, 64, 0, 16, [torch.zeros(1, device="cuda")] * 12)
+    assert e.value.status == -2
+    shape = synth.SHAPES["small"].with_layers(1)
+    model = H.Model(shape, 1, max_tokens=16)
+    for rank in (0, 4, 12, 512):
+        with pytest.raises(api.TlError) as e:
+            api.tl_lora_init(model.handle, rank, 16.0)
+        assert e.value.status == -2
+    model.close()
+
+
+def test_update_is_bit_reproducible(api, H):
+    """No atomics anywhere on the path: two runs from the same state give identical bits."""
+    shape = synth.SHAPES["small"]
+    T = 200
+    model = H.Model(shape, 6006, max_tokens=T)
+    tok = synth.uniform_tokens(6006, T, shape.vocab)
+    outs = []
+    for _ in range(2):
+        lora, _ = H.new_lora(model, 6006, b_std=0.01)
+        loss, _ = api.tl_chunk_update(lora, tok, 0, LR)
+        outs.append((loss, api.tl_get_factor(lora, 0, 4, api.GRAD_B, (shape.d_ffn, shape.rank)),
+                     api.tl_get_factor(lora, 1, 0, api.GRAD_A, (shape.rank, shape.d_model))))
+        api.tl_lora_free(lora)
+    assert outs[0][0] == outs[1][0]
+    assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
+    model.close()
