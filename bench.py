@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Throughput of the Temp-Lora chunk update on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A "step" is one complete tl_chunk_update call: forward + loss + backward + AdamW over one
+1024-token chunk on the 7B-shaped decoder with rank-64 LoRA on all seven projections
+(Section 3 "Setup" of the paper; Table 5 is its cost table for this operation).  Tokens go in
+as a host int32 array (4 KB) and the loss comes back as a host scalar; everything else is
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak (vendor figure, no sparsity)
+
+
+def cpu_baseline(shape, T, seed):
+    """The fp64 oracle as it stands, timed on this host: layer 0 of the 7B shape (forward + backward of one
+    layer, all 32 are identical in cost) and the embedding / final norm / lm_head / cross-entropy part, each
+    once.  Reported as trained tokens/s of the whole update = T / (n_layers * t_layer + t_head)."""
+    import numpy as np
+    from oracle import templora_oracle as O
+    from paper_2401_11504_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    W = synth.layer_weights(seed, shape, 0)
+    facs = synth.lora_factors(seed, shape, 0)
+    h = synth.hidden(seed, T, shape.d_model)
+    dy = synth.upstream_grad(seed, T, shape.d_model)
+    t0 = time.perf_counter()
+    _, cache = O.layer_fwd(h, W, facs, shape)
+    O.layer_bwd(dy, cache, W, facs, shape)
+    t_layer = time.perf_counter() - t0
+    del cache, W
+    head = synth.lm_head(seed, shape)
+    tok = synth.uniform_tokens(seed, T, shape.vocab)
+    t0 = time.perf_counter()
+    labels, mask, _ = O.labels_and_mask(tok, 0)
+    hf = O.rmsnorm_fwd(h, np.ones(shape.d_model), shape.rms_eps)
+    logits = hf @ head.T.astype(np.float64)
+    _, _, dlogits = O.cross_entropy(logits, labels, mask)
+    dhf = dlogits @ head.astype(np.float64)
+    O.rmsnorm_bwd(dhf, h, np.ones(shape.d_model), shape.rms_eps)
+    t_head = time.perf_counter() - t0
+    total = shape.n_layers * t_layer + t_head
+    return {"value": T / total, "unit": "trained tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 oracle: layer 0 fwd+bwd timed once ({t_layer:.2f} s, x{shape.n_layers} layers) + "
+                      f"final norm/lm_head/CE fwd+bwd timed once ({t_head:.2f} s); AdamW not included"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="debug only: fewer layers (marks the line invalid)")
+    ap.add_argument("--tokens", type=int, default=1024)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-events", action="store_true", help="do not bracket the GEMM launches with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the chunk update has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    from paper_2401_11504_amd import api, harness, synth
+
+    shape = synth.SHAPES["7b"].with_layers(args.layers)
+    T, seed = args.tokens, 3000
+    model = harness.Model(shape, seed, max_tokens=T, keep_host=False, device_random=True)
+    # config: A ~ N(0, 0.02^2), B = 0, AdamW lr 5e-5, betas (0.9, 0.999), wd 0
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    tok = synth.uniform_tokens(seed, T, shape.vocab)
+    lr = 5e-5
+
+    loss = None
+    for _ in range(args.warmup):
+        loss, n_targets = api.tl_chunk_update(lora, tok, 0, lr)
+    if not args.no_events:
+        api.tl_profile_enable(lora, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss, n_targets = api.tl_chunk_update(lora, tok, 0, lr)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    roof = None
+    if not args.no_events:
+        ms, launches, flop = api.tl_profile_read(lora)
+        api.tl_profile_enable(lora, False)
+        achieved = flop / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+        roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "gemm_nt_kernel (frozen W GEMM + low-rank K-extension)",
+                "launches_per_step": launches // max(args.steps, 1),
+                "avg_launch_us": round(ms * 1e3 / max(launches, 1), 2),
+                "flop_per_launch": flop / max(launches, 1),
+                "share_of_step_time": round(ms * 1e-3 / dt, 4)}
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
+
+    ms_step = dt / args.steps * 1e3
+    # whole-update algorithmic work: frozen GEMMs fwd + dX, LoRA low-rank products, causal attention fwd + bwd
+    d, f, V, L, r = shape.d_model, shape.d_ffn, shape.vocab, shape.n_layers, shape.rank
+    frozen = 2.0 * T * (L * (4 * d * d + 3 * d * f) + d * V)
+    lora_fl = 6.0 * T * r * L * (4 * 2 * d + 3 * (d + f))
+    attn = 3.5 * 2.0 * T * T * d * L
+    total_flop = 2 * frozen + lora_fl + attn
+    out = {
+        "metric": "trained tokens/sec per Temp-Lora chunk update (7B-shape, r=64); MFMA util %",
+        "value": round(T / (ms_step * 1e-3), 1),
+        "unit": "trained tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[2]: full Temp-Lora chunk update, 7B-shaped decoder (32 layers, d 4096, 32x128 "
+                               "heads, ffn 11008, vocab 32000), LoRA r=64 alpha=64 on q,k,v,o,gate,up,down, "
+                               "one 1024-token chunk, AdamW lr 5e-5" if args.layers == 32 and T == 1024 else
+                               f"DEBUG (not the benchmark): {args.layers} layers, {T} tokens",
+                   "n_tokens": T, "n_layers": args.layers, "rank": r, "loss": round(float(loss), 5),
+                   "n_targets": n_targets},
+        "mfma_util_whole_update": round(total_flop / (ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "algorithmic_tflop_per_step": round(total_flop / 1e12, 3),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(synth.SHAPES["7b"], T, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,15 @@ tl_status tl_get_nll(tl_lora* lora, float* host_out, size_t n);
  * (boundary = n_layers: the state entering the final RMSNorm): host fp32[n_tokens * d_model]. */
 tl_status tl_get_dh(tl_lora* lora, int32_t boundary, float* host_out, size_t n);
 
+/* ---- measurement hooks (not part of the paper's method) ----
+ * While enabled, every launch of the frozen-weight GEMM kernel (the LoRA-adapted projections forward and their
+ * dX backward, lm_head forward and backward) made by tl_chunk_update / tl_chunk_loss / tl_layer_step is bracketed
+ * by two HIP events on the model's stream.  tl_profile_read synchronises, returns the summed elapsed time of
+ * those launches in milliseconds, their number, and the floating-point operations they performed
+ * (2 M N (K + K2) per launch), and clears the counters. */
+tl_status tl_profile_enable(tl_lora* lora, int32_t on);
+tl_status tl_profile_read(tl_lora* lora, double* ms_total, int64_t* launches, double* flop_total);
+
 /*
  * One decoder layer alone: forward from a given hidden state, backward from a
  * given upstream gradient, gradients of that layer's 7 LoRA pairs, and

@@ -61,6 +61,8 @@ _SIGS = {
     "tl_get_step": [_vp, C.POINTER(_i64)],
     "tl_get_nll": [_vp, _vp, _sz],
     "tl_get_dh": [_vp, _i32, _vp, _sz],
+    "tl_profile_enable": [_vp, _i32],
+    "tl_profile_read": [_vp, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)],
     "tl_layer_step": [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _i32],
     "tl_linear_step": [_vp] * 5 + [_i32] * 4 + [_f32] * 6 + [_i32] + [_vp] * 6 + [_vp],
     "tl_k_gemm_nt": [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _i32, _vp],
@@ -192,6 +194,17 @@ def tl_get_dh(lora, boundary, n_tokens, d_model):
     out = np.empty((n_tokens, d_model), dtype=np.float32)
     _chk(_lib.tl_get_dh(lora, boundary, out.ctypes.data_as(_vp), out.size))
     return out
+
+
+def tl_profile_enable(lora, on=True):
+    _chk(_lib.tl_profile_enable(lora, int(on)))
+
+
+def tl_profile_read(lora):
+    """-> (milliseconds, launches, flop) of the frozen-weight GEMM launches since the last read"""
+    ms, n, fl = C.c_double(), _i64(), C.c_double()
+    _chk(_lib.tl_profile_read(lora, C.byref(ms), C.byref(n), C.byref(fl)))
+    return ms.value, n.value, fl.value
 
 
 def tl_layer_step(lora, layer, h_in, dh_out, h_out, dh_in, lr=0.0, apply_adamw=False):

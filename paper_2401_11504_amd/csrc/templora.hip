@@ -134,7 +134,30 @@ struct tl_lora {
     int *tok = nullptr, *labels = nullptr;
     int* tok_host = nullptr;      // pinned
     float* loss_host = nullptr;   // pinned
+    // optional timing of the frozen-weight GEMM launches (HIP events on the model's stream)
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_ev;
+    size_t prof_used = 0;
+    double prof_flop = 0.0;
 };
+
+static void prof_mark(tl_lora* L) {
+    if (!L->prof_on) return;
+    if (L->prof_used == L->prof_ev.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); L->prof_on = false; return; }
+        L->prof_ev.push_back(e);
+    }
+    (void)hipEventRecord(L->prof_ev[L->prof_used++], L->model->stream);
+}
+// run one frozen-weight GEMM, bracketed by events when timing is on
+static hipError_t timed_gemm(tl_lora* L, const GemmNT& g) {
+    prof_mark(L);
+    hipError_t e = launch_gemm_nt(g, L->model->stream);
+    prof_mark(L);
+    if (L->prof_on) L->prof_flop += 2.0 * g.M * (double)g.N * ((double)g.K + g.K2) * g.batch;
+    return e;
+}
 
 // ---------------------------------------------------------------- model
 extern "C" tl_status tl_model_create(const tl_model_cfg* cfg, const void* const* wp, void* hip_stream,
@@ -224,6 +247,10 @@ extern "C" tl_status tl_model_destroy(tl_model* m) {
 
 // ---------------------------------------------------------------- module life cycle
 static void lora_release(tl_lora* L) {
+    for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
+    L->prof_ev.clear();
+    L->prof_used = 0;
+    L->prof_on = false;
     L->pool.release();
     if (L->tok_host) (void)hipHostFree(L->tok_host);
     if (L->loss_host) (void)hipHostFree(L->loss_host);
@@ -405,7 +432,7 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     y.batch = G; y.bB = (long)dout * din; y.bA2 = r; y.bB2 = (long)dout * r; y.bC = dout;
     y.ldc = (long)G * dout;
     if (Y_f32) { y.C = Y_f32; y.c_f32 = 1; y.R = resid; } else { y.C = Y_bf; }
-    HIPCHK(launch_gemm_nt(y, s));
+    HIPCHK(timed_gemm(L, y));
     return TL_OK;
 }
 
@@ -428,7 +455,7 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         x.K = G * dout;
         x.A2 = L->dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r;
         x.C = dX; x.ldc = din;
-        HIPCHK(launch_gemm_nt(x, s));
+        HIPCHK(timed_gemm(L, x));
     }
     GemmTN a;
     a.P = L->dH; a.ldp = G * r; a.Q = X; a.ldq = din; a.T = T; a.Mo = G * r; a.No = din;
@@ -524,7 +551,7 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     GemmNT lg;
     lg.A = L->hf; lg.lda = d; lg.B = m->head; lg.ldb = d; lg.M = T; lg.N = V; lg.K = d;
     lg.C = L->logits; lg.ldc = V; lg.c_f32 = 1;
-    HIPCHK(launch_gemm_nt(lg, s));
+    HIPCHK(timed_gemm(L, lg));
     HIPCHK(launch_cross_entropy(L->logits, L->labels, T, V, first, N, L->nll, want_grad ? L->dlogits : nullptr,
                                 L->loss_sum, s));
     HIPCHK(hipMemcpyAsync(L->loss_host, L->loss_sum, sizeof(float), hipMemcpyDeviceToHost, s));
@@ -567,7 +594,7 @@ extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t 
     GemmNT dh;
     dh.A = L->dlogits; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T; dh.N = d; dh.K = V;
     dh.C = L->dhf; dh.ldc = d;
-    HIPCHK(launch_gemm_nt(dh, s));
+    HIPCHK(timed_gemm(L, dh));
     HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf, s));
     for (int l = nl - 1; l >= 0; --l)
         TLCHK(layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf, L->dhs[l], L->dh_bf, T));
@@ -668,6 +695,33 @@ extern "C" tl_status tl_get_dh(tl_lora* L, int32_t boundary, float* host_out, si
     if (!L->have_grads || n != (size_t)L->last_tokens * c.d_model) return fail(TL_ERR_ARG, "n must be n_tokens * d_model of the last update");
     HIPCHK(hipStreamSynchronize(L->model->stream));
     HIPCHK(hipMemcpy(host_out, L->dhs[boundary], n * sizeof(float), hipMemcpyDeviceToHost));
+    return TL_OK;
+}
+
+extern "C" tl_status tl_profile_enable(tl_lora* L, int32_t on) {
+    LIVE(L, "tl_profile_enable");
+    HIPCHK(hipStreamSynchronize(L->model->stream));
+    L->prof_on = on != 0;
+    L->prof_used = 0;
+    L->prof_flop = 0.0;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_profile_read(tl_lora* L, double* ms_total, int64_t* launches, double* flop_total) {
+    LIVE(L, "tl_profile_read");
+    if (!ms_total || !launches || !flop_total) return fail(TL_ERR_ARG, "tl_profile_read: null pointer");
+    HIPCHK(hipStreamSynchronize(L->model->stream));
+    double ms = 0.0;
+    for (size_t i = 0; i + 1 < L->prof_used; i += 2) {
+        float t = 0.f;
+        HIPCHK(hipEventElapsedTime(&t, L->prof_ev[i], L->prof_ev[i + 1]));
+        ms += t;
+    }
+    *ms_total = ms;
+    *launches = (int64_t)(L->prof_used / 2);
+    *flop_total = L->prof_flop;
+    L->prof_used = 0;
+    L->prof_flop = 0.0;
     return TL_OK;
 }
 
