@@ -13,6 +13,7 @@
 // reads of 8 consecutive rows fall into distinct banks.
 #include "kernels.h"
 #include "tiles.h"
+#include <cstdlib>
 
 // ======================================================================== NT
 template <int BM, int BN, int WM, int WN, bool PARTIAL>
@@ -142,6 +143,232 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT p, int tiles_m, int
         }
 }
 
+
+// ======================================================================== NT, direct-to-LDS pipeline
+// Same contract as gemm_nt_kernel for K % 64 == 0 and K2 % 64 == 0.  Operand tiles go from global
+// memory straight into LDS (global_load_lds_dwordx4: each lane's 16 bytes land at M0 + 16 * lane), so a
+// ring of STAGES tiles is in flight without staging registers.  A tile row is 64 bf16 = 8 chunks of
+// 16 bytes; chunk c of row r is kept at position c ^ ((r / 2) % 8), chosen by which global chunk each
+// lane fetches.  The LDS serves 16 lanes x 16 bytes per clock from 64 banks, and two 128-byte rows span
+// the 64 banks once, so 16 consecutive rows reading the same logical chunk must land on 8 distinct
+// positions in the even rows and 8 in the odd rows: that is what the (r / 2) term gives.
+// Rows beyond M / N are clamped to the last valid row: they only feed outputs that are never stored.
+__device__ __forceinline__ void load_lds16(unsigned voff, const void* sbase, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int ROWS = BM + BN;
+    constexpr int L = ROWS * 8 / NT;   // 16-byte loads per thread per stage
+    constexpr int LA = BM * 8 / NT;    // the first LA of them fetch A rows
+    constexpr int STAGE_BYTES = ROWS * 128;
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    static_assert((ROWS * 8) % NT == 0 && (BM * 8) % NT == 0 && FM >= 1 && FN >= 1 && STAGES >= 2, "tile shape");
+    static_assert((STAGES - 2) * L <= 63, "vmcnt range");  // s_waitcnt vmcnt is a 6-bit field
+    extern __shared__ __align__(16) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(size_t)smem;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, g = lane >> 5;
+
+    const int ntiles = tiles_m * tiles_n;
+    int pid = blockIdx.x;
+    if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+    const int tile_m = pid % tiles_m, tile_n = pid / tiles_m;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int z = blockIdx.z;
+
+    const bf16_t* A = p.A + (long)z * p.bA;
+    const bf16_t* B = p.B + (long)z * p.bB;
+    const bf16_t* A2 = p.A2 ? p.A2 + (long)z * p.bA2 : nullptr;
+    const bf16_t* B2 = p.B2 ? p.B2 + (long)z * p.bB2 : nullptr;
+    const int nk1 = p.K / BK, nk2 = p.K2 / BK, nk = nk1 + nk2;
+
+    // per-thread byte offsets of its L chunks, for the main and the low-rank operand pair
+    unsigned vo1[L], vo2[L];
+#pragma unroll
+    for (int j = 0; j < L; ++j) {
+        const int q = j * NT + tid, r = q >> 3, c = (q & 7) ^ ((r >> 1) & 7);
+        if (j < LA) {
+            const long row = min(m0 + r, p.M - 1);
+            vo1[j] = (unsigned)((row * p.lda + c * 8) * 2);
+            vo2[j] = (unsigned)((row * p.lda2 + c * 8) * 2);
+        } else {
+            const long row = min(n0 + r - BM, p.N - 1);
+            vo1[j] = (unsigned)((row * p.ldb + c * 8) * 2);
+            vo2[j] = (unsigned)((row * p.ldb2 + c * 8) * 2);
+        }
+    }
+    auto issue = [&](int kt) {
+        const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + (kt % STAGES) * STAGE_BYTES + wave * 1024);
+        if (kt < nk1) {
+            const bf16_t* ba = A + (long)kt * BK;
+            const bf16_t* bb = B + (long)kt * BK;
+#pragma unroll
+            for (int j = 0; j < L; ++j) load_lds16(vo1[j], j < LA ? (const void*)ba : (const void*)bb, dst + j * NT * 16);
+        } else {
+            const bf16_t* ba = A2 + (long)(kt - nk1) * BK;
+            const bf16_t* bb = B2 + (long)(kt - nk1) * BK;
+#pragma unroll
+            for (int j = 0; j < L; ++j) load_lds16(vo2[j], j < LA ? (const void*)ba : (const void*)bb, dst + j * NT * 16);
+        }
+    };
+
+    f32x16_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = zero16();
+
+    // fragment read offsets: row (w*T + l32) -> swizzle (l32 / 2) % 8; chunk (2 ks + g) ^ swizzle
+    int coff[BK / 16];
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) coff[ks] = (((2 * ks + g) ^ ((l32 >> 1) & 7)) << 4);
+    const int a_row = (wm * TM + l32) * 128, b_row = (BM + wn * TN + l32) * 128;
+
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s)
+        if (s < nk) issue(s);
+    if constexpr (STAGES >= 3) {
+        // Software pipeline: the fragments of k-step ks+1 are read while the MFMAs of ks run, and the
+        // hand-over to the next tile (wait, barrier, next global loads, first fragments) happens before
+        // the last k-step's MFMAs, so the matrix pipe never waits for LDS at a tile boundary.
+        auto read_frags = [&](int stage, int ks, bf16x8_t* fa, bf16x8_t* fb) {
+            const unsigned char* st = smem + stage * STAGE_BYTES;
+#pragma unroll
+            for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * 128 + coff[ks]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * 128 + coff[ks]);
+        };
+        if (STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * L>(); else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        bf16x8_t fa[2][FM], fb[2][FN];
+        read_frags(0, 0, fa[0], fb[0]);
+        for (int kt = 0; kt < nk; ++kt) {
+            const int stg = kt % STAGES;
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                if (ks < BK / 16 - 1) {
+                    if (!(DBG & 4)) read_frags(stg, ks + 1, fa[nxt], fb[nxt]);
+                } else if (kt + 1 < nk) {
+                    if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 3) * L>(); else wait_vmcnt<0>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    if (kt + STAGES - 1 < nk && !(DBG & 1)) issue(kt + STAGES - 1);
+                    if (!(DBG & 4)) read_frags((kt + 1) % STAGES, 0, fa[nxt], fb[nxt]);
+                }
+                if (DBG & 2) {
+                    asm volatile("" ::"v"(fa[cur][0]), "v"(fb[cur][0]), "v"(fa[cur][FM - 1]), "v"(fb[cur][FN - 1]));
+                    continue;
+                }
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) acc[i][j] = mfma32(fa[cur][i], fb[cur][j], acc[i][j]);
+            }
+        }
+    } else {
+        for (int kt = 0; kt < nk; ++kt) {
+            // tile kt has landed once at most the loads of the STAGES-2 younger tiles are outstanding
+            if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * L>(); else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);   // into the buffer every wave finished reading last iteration
+            const unsigned char* st = smem + (kt % STAGES) * STAGE_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < BK / 16; ++ks) {
+                bf16x8_t fa[FM], fb[FN];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * 128 + coff[ks]);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * 128 + coff[ks]);
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
+            }
+        }
+    }
+
+    if (p.c_f32) {
+        // fp32 output (+ fp32 residual): half a wave already writes 128 contiguous bytes per row
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn * TN + j * 32 + l32;
+                if (col >= p.N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = m0 + wm * TM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (row >= p.M) continue;
+                    const long off = (long)z * p.bC + (long)row * p.ldc + col;
+                    float val = p.alpha * acc[i][j][v];
+                    if (p.R) val += p.R[off];
+                    ((float*)p.C)[off] = val;
+                }
+            }
+    } else {
+        // bf16 output: each wave turns 32-row slabs of its tile around in LDS so that a row leaves as
+        // 16-byte pieces covering TN contiguous columns instead of 2-byte pieces
+        constexpr int SLD = TN + 8;  // slab row stride in elements
+        static_assert(WM * WN * 32 * SLD * 2 <= STAGES * STAGE_BYTES, "epilogue slab fits in the tile ring");
+        __builtin_amdgcn_s_barrier();  // every wave is done reading operand tiles
+        asm volatile("" ::: "memory");
+        bf16_t* slab = (bf16_t*)smem + wave * 32 * SLD;
+        bf16_t* Cb = (bf16_t*)p.C + (long)z * p.bC;
+        const bool vec_ok = ((p.ldc & 7) == 0) && ((p.bC & 7) == 0) && (((size_t)p.C & 15) == 0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    slab[(8 * (v >> 2) + 4 * g + (v & 3)) * SLD + j * 32 + l32] = f32_to_bf16(p.alpha * acc[i][j][v]);
+            __builtin_amdgcn_wave_barrier();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            constexpr int CPR = TN / 8;  // 16-byte chunks per slab row
+#pragma unroll
+            for (int c = lane; c < 32 * CPR; c += 64) {
+                const int r = c / CPR, cc = (c % CPR) * 8;
+                const int row = m0 + wm * TM + i * 32 + r, col = n0 + wn * TN + cc;
+                if (row >= p.M || col >= p.N) continue;
+                const uint4 val = *(const uint4*)(slab + r * SLD + cc);
+                bf16_t* dst = Cb + (long)row * p.ldc + col;
+                if (vec_ok && col + 8 <= p.N) {
+                    *(uint4*)dst = val;
+                } else {
+                    const bf16_t* e = (const bf16_t*)&val;
+                    for (int x = 0; x < 8 && col + x < p.N; ++x) dst[x] = e[x];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0>
+static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s) {
+    const int tiles_m = cdiv(g.M, BM), tiles_n = cdiv(g.N, BN);
+    const size_t lds = (size_t)STAGES * (BM + BN) * 128;
+    dim3 grid(tiles_m * tiles_n, 1, g.batch);
+    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
 // sum the split-K partials in a fixed order (deterministic), scale, add residual, convert
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmNT p, int split_k) {
     const long mn = (long)p.M * p.N;
@@ -193,6 +420,44 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     const long t128 = (long)cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch;
     const long t64n = (long)cdiv(g.M, 128) * cdiv(g.N, 64) * g.batch;
     int split = g.split_k;
+    const bool dl_ok = (g.K % BK) == 0 && (g.K2 % BK) == 0 && g.K > 0 && g.N > 64 &&
+                       (long)g.M * g.lda < (1L << 30) && (long)g.N * g.ldb < (1L << 30) &&
+                       (long)g.M * g.lda2 < (1L << 30) && (long)g.N * g.ldb2 < (1L << 30);
+    if (dl_ok && t128 >= 128) {
+        const char* env = getenv("TL_GEMM_TILE");  // tuning aid: force one tile configuration
+        int cfg = env ? atoi(env) : 0;
+        if (cfg == 0) {
+            // Measured on MI355X at M = 1024: the path is bound by the L2 -> LDS fill rate, so the largest tile
+            // that still gives every CU work wins.  256x256 tiles need >= ~160 tiles; when their last round of
+            // CUs would be mostly idle and 256x128 tiles quantise better, take those; otherwise 128x128.
+            const long t256 = (long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
+            const long t256x128 = (long)cdiv(g.M, 256) * cdiv(g.N, 128) * g.batch;
+            auto fill = [](long t) { return (double)t / (double)(((t + 255) / 256) * 256); };
+            if (t256 >= 160) cfg = (fill(t256) < 0.7 && fill(t256x128) >= 0.85) ? 2 : 6;
+            else cfg = 10;
+        }
+        switch (cfg) {
+            case 1: return run_nt_dl<128, 128, 2, 2, 3>(g, s);
+            case 2: return run_nt_dl<256, 128, 4, 2, 3>(g, s);
+            case 3: return run_nt_dl<256, 128, 2, 2, 3>(g, s);
+            case 4: return run_nt_dl<128, 256, 2, 2, 3>(g, s);
+            case 5: return run_nt_dl<256, 256, 2, 2, 2>(g, s);
+            case 6: return run_nt_dl<256, 256, 4, 2, 2>(g, s);
+            case 7: return run_nt_dl<128, 128, 2, 2, 2>(g, s);
+            case 8: return run_nt_dl<128, 256, 2, 4, 3>(g, s);
+            case 9: return run_nt<128, 128, 2, 2>(g, 1, s);
+#ifdef TL_GEMM_ABLATE
+            case 101: return run_nt_dl<128, 128, 2, 2, 4, 1>(g, s);
+            case 102: return run_nt_dl<128, 128, 2, 2, 4, 2>(g, s);
+            case 103: return run_nt_dl<128, 128, 2, 2, 4, 3>(g, s);
+            case 104: return run_nt_dl<128, 128, 2, 2, 4, 4>(g, s);
+            case 105: return run_nt_dl<128, 128, 2, 2, 4, 5>(g, s);
+            case 106: return run_nt_dl<128, 128, 2, 2, 4, 6>(g, s);
+            case 107: return run_nt_dl<128, 128, 2, 2, 4, 7>(g, s);
+#endif
+            default: return run_nt_dl<128, 128, 2, 2, 4>(g, s);
+        }
+    }
     if (g.N > 64 && t128 >= 200) {
         return run_nt<128, 128, 2, 2>(g, 1, s);
     }

@@ -71,6 +71,25 @@ def test_gemm_nt_bf16(api, H, M, N, K, K2):
     check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")   # bf16 products are exact; only fp32 summation order differs
 
 
+@pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5", "6", "7", "8"])
+@pytest.mark.parametrize("M,N,K,K2", [(1024, 2048, 256, 64), (1000, 2056, 128, 0), (520, 4104, 192, 128)])
+def test_gemm_nt_pipelined_tiles(api, H, monkeypatch, tile, M, N, K, K2):
+    """The direct-to-LDS kernel in each of its tile configurations (K, K2 multiples of 64; ragged M and N)."""
+    monkeypatch.setenv("TL_GEMM_TILE", tile)
+    A, B = rnd(1, (M, K)), rnd(2, (N, K), 0.05)
+    A2 = rnd(3, (M, K2)) if K2 else None
+    B2 = rnd(4, (N, K2), 0.05) if K2 else None
+    ref = A.astype(np.float64) @ B.T.astype(np.float64)
+    if K2:
+        ref = ref + A2.astype(np.float64) @ B2.T.astype(np.float64)
+    R = rnd(5, (M, N), 1.0, False)
+    Cf = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cf, H.to_dev_bf16(A2) if K2 else None,
+                     H.to_dev_bf16(B2) if K2 else None, alpha=1.0, R=H.to_dev_f32(R))
+    torch.cuda.synchronize()
+    check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")
+
+
 def test_gemm_nt_strided_operands(api, H):
     # operands that are column blocks of wider buffers (as q|k|v and gate|up are)
     M, N, K = 200, 96, 128
