@@ -144,6 +144,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT p, int tiles_m, int
 }
 
 
+__global__ void splitk_reduce_kernel(GemmNT p, int split_k);
+
 // ======================================================================== NT, direct-to-LDS pipeline
 // Same contract as gemm_nt_kernel for K % 64 == 0 and K2 % 64 == 0.  Operand tiles go from global
 // memory straight into LDS (global_load_lds_dwordx4: each lane's 16 bytes land at M0 + 16 * lane), so a
@@ -161,16 +163,21 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0>
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
     constexpr int NT = WM * WN * 64;
     constexpr int ROWS = BM + BN;
-    constexpr int L = ROWS * 8 / NT;   // 16-byte loads per thread per stage
-    constexpr int LA = BM * 8 / NT;    // the first LA of them fetch A rows
-    constexpr int STAGE_BYTES = ROWS * 128;
+    constexpr int CPRW = BKT / 8;             // 16-byte chunks per tile row
+    constexpr int RP = 256 / (BKT * 2);       // tile rows per 256 bytes of LDS (one pass over the 64 banks)
+    constexpr int KS = BKT / 16;              // MFMA k-steps per tile
+    constexpr int L = ROWS * CPRW / NT;       // 16-byte loads per thread per stage
+    constexpr int LA = BM * CPRW / NT;        // the first LA of them fetch A rows
+    constexpr int ROWB = BKT * 2;             // bytes per tile row
+    constexpr int STAGE_BYTES = ROWS * ROWB;
     constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
-    static_assert((ROWS * 8) % NT == 0 && (BM * 8) % NT == 0 && FM >= 1 && FN >= 1 && STAGES >= 2, "tile shape");
+    static_assert((ROWS * CPRW) % NT == 0 && (BM * CPRW) % NT == 0 && FM >= 1 && FN >= 1 && STAGES >= 2, "tile shape");
     static_assert((STAGES - 2) * L <= 63, "vmcnt range");  // s_waitcnt vmcnt is a 6-bit field
+    static_assert(BKT == 64 || BKT == 32, "tile depth");
     extern __shared__ __align__(16) unsigned char smem[];
     const unsigned lds0 = (unsigned)(size_t)smem;
 
@@ -189,13 +196,17 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     const bf16_t* B = p.B + (long)z * p.bB;
     const bf16_t* A2 = p.A2 ? p.A2 + (long)z * p.bA2 : nullptr;
     const bf16_t* B2 = p.B2 ? p.B2 + (long)z * p.bB2 : nullptr;
-    const int nk1 = p.K / BK, nk2 = p.K2 / BK, nk = nk1 + nk2;
+    const int nk1 = p.K / BKT, nk2 = p.K2 / BKT;
+    // with SPLITK, grid.y workgroups share one output tile: this one takes k-tiles [kt0, kt0 + nk)
+    const int n_split = SPLITK ? (int)gridDim.y : 1, split = SPLITK ? (int)blockIdx.y : 0;
+    const int kt0 = (int)((long)(nk1 + nk2) * split / n_split);
+    const int nk = (int)((long)(nk1 + nk2) * (split + 1) / n_split) - kt0;
 
     // per-thread byte offsets of its L chunks, for the main and the low-rank operand pair
     unsigned vo1[L], vo2[L];
 #pragma unroll
     for (int j = 0; j < L; ++j) {
-        const int q = j * NT + tid, r = q >> 3, c = (q & 7) ^ ((r >> 1) & 7);
+        const int q = j * NT + tid, r = q / CPRW, c = (q % CPRW) ^ ((r / RP) % CPRW);
         if (j < LA) {
             const long row = min(m0 + r, p.M - 1);
             vo1[j] = (unsigned)((row * p.lda + c * 8) * 2);
@@ -206,16 +217,17 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             vo2[j] = (unsigned)((row * p.ldb2 + c * 8) * 2);
         }
     }
-    auto issue = [&](int kt) {
-        const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + (kt % STAGES) * STAGE_BYTES + wave * 1024);
+    auto issue = [&](int ktl) {
+        const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + (ktl % STAGES) * STAGE_BYTES + wave * 1024);
+        const int kt = kt0 + ktl;
         if (kt < nk1) {
-            const bf16_t* ba = A + (long)kt * BK;
-            const bf16_t* bb = B + (long)kt * BK;
+            const bf16_t* ba = A + (long)kt * BKT;
+            const bf16_t* bb = B + (long)kt * BKT;
 #pragma unroll
             for (int j = 0; j < L; ++j) load_lds16(vo1[j], j < LA ? (const void*)ba : (const void*)bb, dst + j * NT * 16);
         } else {
-            const bf16_t* ba = A2 + (long)(kt - nk1) * BK;
-            const bf16_t* bb = B2 + (long)(kt - nk1) * BK;
+            const bf16_t* ba = A2 + (long)(kt - nk1) * BKT;
+            const bf16_t* bb = B2 + (long)(kt - nk1) * BKT;
 #pragma unroll
             for (int j = 0; j < L; ++j) load_lds16(vo2[j], j < LA ? (const void*)ba : (const void*)bb, dst + j * NT * 16);
         }
@@ -227,11 +239,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = zero16();
 
-    // fragment read offsets: row (w*T + l32) -> swizzle (l32 / 2) % 8; chunk (2 ks + g) ^ swizzle
-    int coff[BK / 16];
+    // fragment read offsets: row (w*T + l32) -> swizzle (l32 / RP) % CPRW; chunk (2 ks + g) ^ swizzle
+    int coff[KS];
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) coff[ks] = (((2 * ks + g) ^ ((l32 >> 1) & 7)) << 4);
-    const int a_row = (wm * TM + l32) * 128, b_row = (BM + wn * TN + l32) * 128;
+    for (int ks = 0; ks < KS; ++ks) coff[ks] = (((2 * ks + g) ^ ((l32 / RP) % CPRW)) << 4);
+    const int a_row = (wm * TM + l32) * ROWB, b_row = (BM + wn * TN + l32) * ROWB;
 
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s)
@@ -243,9 +255,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         auto read_frags = [&](int stage, int ks, bf16x8_t* fa, bf16x8_t* fb) {
             const unsigned char* st = smem + stage * STAGE_BYTES;
 #pragma unroll
-            for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * 128 + coff[ks]);
+            for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * ROWB + coff[ks]);
 #pragma unroll
-            for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * 128 + coff[ks]);
+            for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * ROWB + coff[ks]);
         };
         if (STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * L>(); else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
@@ -255,9 +267,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         for (int kt = 0; kt < nk; ++kt) {
             const int stg = kt % STAGES;
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1;
-                if (ks < BK / 16 - 1) {
+                if (ks < KS - 1) {
                     if (!(DBG & 4)) read_frags(stg, ks + 1, fa[nxt], fb[nxt]);
                 } else if (kt + 1 < nk) {
                     if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 3) * L>(); else wait_vmcnt<0>();
@@ -285,12 +297,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);   // into the buffer every wave finished reading last iteration
             const unsigned char* st = smem + (kt % STAGES) * STAGE_BYTES;
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
                 bf16x8_t fa[FM], fb[FN];
 #pragma unroll
-                for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * 128 + coff[ks]);
+                for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * ROWB + coff[ks]);
 #pragma unroll
-                for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * 128 + coff[ks]);
+                for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * ROWB + coff[ks]);
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -299,6 +311,24 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         }
     }
 
+    if constexpr (SPLITK) {
+        // each split stores its fp32 tile; splitk_reduce_kernel adds the splits in index order afterwards
+        // (a second launch: device-wide fences inside a kernel cost a full L2 write-back on this chip)
+        float* part = p.partial + ((long)z * n_split + split) * (long)p.M * p.N;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = n0 + wn * TN + j * 32 + l32;
+                if (col >= p.N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = m0 + wm * TM + i * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                    if (row < p.M) part[(long)row * p.N + col] = acc[i][j][v];
+                }
+            }
+        return;
+    }
     if (p.c_f32) {
         // fp32 output (+ fp32 residual): half a wave already writes 128 contiguous bytes per row
 #pragma unroll
@@ -357,15 +387,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0>
-static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false>
+static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     const int tiles_m = cdiv(g.M, BM), tiles_n = cdiv(g.N, BN);
-    const size_t lds = (size_t)STAGES * (BM + BN) * 128;
-    dim3 grid(tiles_m * tiles_n, 1, g.batch);
-    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG>;
+    const size_t lds = (size_t)STAGES * (BM + BN) * BKT * 2;
+    dim3 grid(tiles_m * tiles_n, SPLITK ? n_split : 1, g.batch);
+    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n);
+    if (SPLITK) {
+        const long n = (long)g.M * g.N * g.batch;
+        splitk_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, n_split);
+    }
     return hipGetLastError();
 }
 
@@ -446,6 +480,12 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 7: return run_nt_dl<128, 128, 2, 2, 2>(g, s);
             case 8: return run_nt_dl<128, 256, 2, 4, 3>(g, s);
             case 9: return run_nt<128, 128, 2, 2>(g, 1, s);
+            case 11: return run_nt_dl<256, 256, 2, 2, 4, 0, 32>(g, s);
+            case 12: return run_nt_dl<256, 256, 2, 2, 3, 0, 32>(g, s);
+            case 13: return run_nt_dl<256, 256, 4, 2, 4, 0, 32>(g, s);
+            case 14: return run_nt_dl<256, 128, 2, 2, 4, 0, 32>(g, s);
+            case 15: return run_nt_dl<128, 128, 2, 2, 6, 0, 32>(g, s);
+            case 16: return run_nt_dl<256, 128, 4, 2, 4, 0, 32>(g, s);
 #ifdef TL_GEMM_ABLATE
             case 101: return run_nt_dl<128, 128, 2, 2, 4, 1>(g, s);
             case 102: return run_nt_dl<128, 128, 2, 2, 4, 2>(g, s);
@@ -466,6 +506,8 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     }
     // few output tiles: 64x64 tiles, and split the contraction when scratch is available
     const long t64 = (long)cdiv(g.M, 64) * cdiv(g.N, 64) * g.batch;
+    const bool dl_small = (g.K % BK) == 0 && g.K2 == 0 && g.K > 0 && (long)g.M * g.lda < (1L << 30) &&
+                          (long)g.N * g.ldb < (1L << 30);
     if (split == 0) {
         split = 1;
         if (g.partial && t64 < 256) {
@@ -477,6 +519,10 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     }
     if (split > 1 && (!g.partial || (size_t)split * g.M * g.N * g.batch > g.partial_elems)) return hipErrorInvalidValue;
     if (split > nk) split = nk > 0 ? nk : 1;
+    if (dl_small) {
+        if (split > 1) return run_nt_dl<64, 64, 2, 2, 4, 0, 64, true>(g, s, split);
+        if (split == 1) return run_nt_dl<64, 64, 2, 2, 4>(g, s);
+    }
     return run_nt<64, 64, 2, 2>(g, split, s);
 }
 
@@ -484,60 +530,110 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
 // Transposing store of a [64 t][64 i] operand tile: thread (tp, ic) holds rows t = 2tp, 2tp+1 and the
 // 8 columns i = 8ic..8ic+7, and writes 8 dwords (t, t+1) pairs into the [i][t] LDS tile.  The 8-element
 // t-chunk index is XORed with (i / 8) % 8 so that the 8 column groups of one row land in distinct banks.
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p) {
-    __shared__ __align__(16) bf16_t sP[64 * LS];
-    __shared__ __align__(16) bf16_t sQ[64 * LS];
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
+    // Two LDS buffers per operand (one barrier per 64-token tile) and the next tile's global loads are
+    // issued a full tile ahead.  grid.y = Mo tiles x n_split: each split covers a contiguous token range;
+    // with n_split > 1 the splits are stored as fp32 partials and added by tn_reduce_kernel.
+    __shared__ __align__(16) bf16_t sP[2][64 * LS];
+    __shared__ __align__(16) bf16_t sQ[2][64 * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
-    const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64, z = blockIdx.z;
+    const int tiles_i = (p.Mo + 63) / 64;
+    const int ti = blockIdx.y % tiles_i, split = blockIdx.y / tiles_i;
+    const int i0 = ti * 64, j0 = blockIdx.x * 64, z = blockIdx.z;
     const bf16_t* P = p.P + (long)z * p.bP;
     const bf16_t* Q = p.Q + (long)z * p.bQ;
     const int tp = tid >> 3, ic = tid & 7;
+    const int nt_all = (p.T + 63) / 64;
+    const int it0 = (int)((long)nt_all * split / n_split), it1 = (int)((long)nt_all * (split + 1) / n_split);
 
-    f32x16_t acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-
+    f32x16_t acc = zero16();
     auto ld = [&](const bf16_t* base, long ldx, int c0, int cmax, int t) -> uint4 {
         const int c = c0 + ic * 8;
         return (t < p.T && c < cmax) ? *(const uint4*)(base + (long)t * ldx + c) : make_uint4(0, 0, 0, 0);
     };
-    const int nt = (p.T + 63) / 64;
     uint4 p0, p1, q0, q1;
-    p0 = ld(P, p.ldp, i0, p.Mo, 2 * tp); p1 = ld(P, p.ldp, i0, p.Mo, 2 * tp + 1);
-    q0 = ld(Q, p.ldq, j0, p.No, 2 * tp); q1 = ld(Q, p.ldq, j0, p.No, 2 * tp + 1);
-    for (int it = 0; it < nt; ++it) {
-        __syncthreads();
-        store_transposed_pair(sP, ic * 8, 2 * tp, p0, p1);
-        store_transposed_pair(sQ, ic * 8, 2 * tp, q0, q1);
-        __syncthreads();
-        if (it + 1 < nt) {
-            const int t = (it + 1) * 64 + 2 * tp;
-            p0 = ld(P, p.ldp, i0, p.Mo, t); p1 = ld(P, p.ldp, i0, p.Mo, t + 1);
-            q0 = ld(Q, p.ldq, j0, p.No, t); q1 = ld(Q, p.ldq, j0, p.No, t + 1);
+    auto gload = [&](int it) {
+        const int t = it * 64 + 2 * tp;
+        p0 = ld(P, p.ldp, i0, p.Mo, t); p1 = ld(P, p.ldp, i0, p.Mo, t + 1);
+        q0 = ld(Q, p.ldq, j0, p.No, t); q1 = ld(Q, p.ldq, j0, p.No, t + 1);
+    };
+    if (it0 < it1) {
+        gload(it0);
+        store_transposed_pair(sP[0], ic * 8, 2 * tp, p0, p1);
+        store_transposed_pair(sQ[0], ic * 8, 2 * tp, q0, q1);
+        if (it0 + 1 < it1) gload(it0 + 1);
+    }
+    __syncthreads();
+    const int ri = wi * 32 + l32, rj = wj * 32 + l32;
+    for (int it = it0; it < it1; ++it) {
+        const int buf = (it - it0) & 1;
+        // registers hold tile it+1: park it in the other buffer, then fetch tile it+2
+        if (it + 1 < it1) {
+            store_transposed_pair(sP[buf ^ 1], ic * 8, 2 * tp, p0, p1);
+            store_transposed_pair(sQ[buf ^ 1], ic * 8, 2 * tp, q0, q1);
+            if (it + 2 < it1) gload(it + 2);
         }
-        const int ri = wi * 32 + l32, rj = wj * 32 + l32;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8_t a = *(const bf16x8_t*)(sP + tn_off(ri, ks * 16 + g * 8));
-            bf16x8_t b = *(const bf16x8_t*)(sQ + tn_off(rj, ks * 16 + g * 8));
+            bf16x8_t a = *(const bf16x8_t*)(sP[buf] + tn_off(ri, ks * 16 + g * 8));
+            bf16x8_t b = *(const bf16x8_t*)(sQ[buf] + tn_off(rj, ks * 16 + g * 8));
             acc = mfma32(a, b, acc);
         }
+        __syncthreads();
     }
     const int col = j0 + wj * 32 + l32;
+    if (n_split == 1) {
+        if (col < p.No) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = i0 + wi * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+                if (row < p.Mo) p.C[(long)z * p.bC + (long)row * p.ldc + col] = p.alpha * acc[v];
+            }
+        }
+        return;
+    }
+    const long mn = (long)p.Mo * p.No;
+    float* part = p.partial + ((long)z * n_split + split) * mn;
     if (col < p.No) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = i0 + wi * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (row < p.Mo) p.C[(long)z * p.bC + (long)row * p.ldc + col] = p.alpha * acc[v];
+            if (row < p.Mo) part[(long)row * p.No + col] = acc[v];
         }
     }
+}
+
+// adds the token splits of gemm_tn_kernel in index order
+__global__ __launch_bounds__(256) void tn_reduce_kernel(GemmTN p, int n_split) {
+    const long mn = (long)p.Mo * p.No;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= mn * p.batch) return;
+    const int z = (int)(idx / mn);
+    const long r = idx % mn;
+    float sum = 0.f;
+    for (int sp = 0; sp < n_split; ++sp) sum += p.partial[((long)z * n_split + sp) * mn + r];
+    p.C[(long)z * p.bC + (r / p.No) * p.ldc + (r % p.No)] = p.alpha * sum;
 }
 
 hipError_t launch_gemm_tn(const GemmTN& g, hipStream_t s) {
     if (g.Mo <= 0 || g.No <= 0 || g.batch <= 0) return hipSuccess;
     if ((g.ldp & 7) || (g.ldq & 7) || (g.Mo & 7) || (g.No & 7) || (g.bP & 7) || (g.bQ & 7)) return hipErrorInvalidValue;
-    dim3 grid(cdiv(g.No, 64), cdiv(g.Mo, 64), g.batch);
-    gemm_tn_kernel<<<grid, 256, 0, s>>>(g);
+    const long tiles = (long)cdiv(g.No, 64) * cdiv(g.Mo, 64) * g.batch;
+    int split = 1;
+    if (g.partial && tiles < 512) {
+        split = (int)(768 / tiles);
+        const int max_split = cdiv(g.T, 64) / 2;   // at least two token tiles per split
+        if (split > max_split) split = max_split;
+        if (split > 8) split = 8;
+        if (split < 1) split = 1;
+        while (split > 1 && (size_t)split * g.Mo * g.No * g.batch > g.partial_elems) --split;
+    }
+    dim3 grid(cdiv(g.No, 64), cdiv(g.Mo, 64) * split, g.batch);
+    gemm_tn_kernel<<<grid, 256, 0, s>>>(g, split);
+    if (split > 1) {
+        const long n = (long)g.Mo * g.No * g.batch;
+        tn_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, split);
+    }
     return hipGetLastError();
 }

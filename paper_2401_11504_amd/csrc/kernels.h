@@ -32,6 +32,8 @@ struct GemmTN {
     float* C = nullptr; long ldc = 0;
     int batch = 1;
     long bP = 0, bQ = 0, bC = 0;
+    float* partial = nullptr;                   // optional scratch for splitting the token dimension
+    size_t partial_elems = 0;
 };
 hipError_t launch_gemm_tn(const GemmTN& g, hipStream_t s);
 

@@ -360,8 +360,15 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         TLCHK(L->pool.alloc(&L->dqkv, 3 * Td));
         TLCHK(L->pool.alloc(&L->dH, (size_t)Tm * 3 * r));
         TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
-        L->partial_elems = (size_t)Tm * 3 * r * 16;
+        // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r];
+        // dA / dB of one group: at most max(3r*d, 2f*r) elements, up to 8 token splits)
+        {
+            const size_t skinny = (size_t)Tm * 3 * r * 16;
+            const size_t grads = (size_t)8 * r * (size_t)(3 * d > 2 * f ? 3 * d : 2 * f);
+            L->partial_elems = skinny > grads ? skinny : grads;
+        }
         TLCHK(L->pool.alloc(&L->partial, L->partial_elems));
+
         TLCHK(L->pool.alloc(&L->tok, (size_t)Tm));
         TLCHK(L->pool.alloc(&L->labels, (size_t)Tm));
         TLCHK(L->pool.alloc(&L->nll, (size_t)Tm));
@@ -460,11 +467,13 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
     GemmTN a;
     a.P = L->dH; a.ldp = G * r; a.Q = X; a.ldq = din; a.T = T; a.Mo = G * r; a.No = din;
     a.C = L->G + o.A[g]; a.ldc = din;
+    a.partial = L->partial; a.partial_elems = L->partial_elems;
     HIPCHK(launch_gemm_tn(a, s));
     GemmTN b;
     b.P = dY; b.ldp = (long)G * dout; b.Q = Hs; b.ldq = G * r; b.T = T; b.Mo = dout; b.No = r;
     b.C = L->G + o.B[g]; b.ldc = r;
     b.batch = G; b.bP = dout; b.bQ = r; b.bC = (long)dout * r;
+    b.partial = L->partial; b.partial_elems = L->partial_elems;
     HIPCHK(launch_gemm_tn(b, s));
     return TL_OK;
 }
