@@ -19,6 +19,7 @@ SOURCES = ["templora.hip", "gemm_bf16.hip", "gemm_f32.hip", "attention.hip", "el
 # packed-fp32 VALU forms are switched off for device code on purpose ("Build flags")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
+FLAGS += os.environ.get("TL_EXTRA_HIPCC_FLAGS", "").split()  # tuning builds, e.g. -DATTN_NW=4
 if os.environ.get("TL_GEMM_ABLATE"):  # tuning builds only: kernels with loads / MFMAs / LDS reads removed
     FLAGS.append("-DTL_GEMM_ABLATE")
 

@@ -22,46 +22,58 @@ struct AttnCfg {
     static constexpr int ND = DH / 32;  // 32-wide d tiles
 };
 
-// load a [64 rows][DH] tile (rows r0.., zero beyond T) into a padded LDS tile
-template <int DH>
+// load a [64 rows][DH] tile (rows r0.., zero beyond T) into registers; NT = threads of the workgroup
+template <int DH, int NT>
 __device__ __forceinline__ void load_tile_regs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs) {
     constexpr int CH = DH / 8;  // chunks per row
 #pragma unroll
-    for (int i = 0; i < DH / 32; ++i) {
-        const int c = threadIdx.x + 256 * i, row = c / CH, ch = c % CH;
+    for (int i = 0; i < 8 * DH / NT; ++i) {
+        const int c = threadIdx.x + NT * i, row = c / CH, ch = c % CH;
         regs[i] = (r0 + row < T) ? *(const uint4*)(base + (long)(r0 + row) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
     }
 }
-template <int DH>
+template <int DH, int NT>
 __device__ __forceinline__ void store_tile_normal(bf16_t* tile, const uint4* regs) {
     constexpr int CH = DH / 8;
 #pragma unroll
-    for (int i = 0; i < DH / 32; ++i) {
-        const int c = threadIdx.x + 256 * i, row = c / CH, ch = c % CH;
+    for (int i = 0; i < 8 * DH / NT; ++i) {
+        const int c = threadIdx.x + NT * i, row = c / CH, ch = c % CH;
         *(uint4*)(tile + row * AttnCfg<DH>::LSK + ch * 8) = regs[i];
     }
 }
 // the same tile as row pairs for the transposing store: unit = (row pair, 8-column chunk)
-template <int DH>
+template <int DH, int NT>
 __device__ __forceinline__ void load_tile_pairs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs) {
     constexpr int CH = DH / 8;
 #pragma unroll
-    for (int i = 0; i < DH / 64; ++i) {
-        const int c = threadIdx.x + 256 * i, rp = c / CH, ch = c % CH;
+    for (int i = 0; i < 4 * DH / NT; ++i) {
+        const int c = threadIdx.x + NT * i, rp = c / CH, ch = c % CH;
         const int r = r0 + 2 * rp;
         regs[2 * i] = (r < T) ? *(const uint4*)(base + (long)r * ld + ch * 8) : make_uint4(0, 0, 0, 0);
         regs[2 * i + 1] = (r + 1 < T) ? *(const uint4*)(base + (long)(r + 1) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
     }
 }
-template <int DH>
+template <int DH, int NT>
 __device__ __forceinline__ void store_tile_transposed(bf16_t* tile, const uint4* regs) {
     constexpr int CH = DH / 8;
 #pragma unroll
-    for (int i = 0; i < DH / 64; ++i) {
-        const int c = threadIdx.x + 256 * i, rp = c / CH, ch = c % CH;
+    for (int i = 0; i < 4 * DH / NT; ++i) {
+        const int c = threadIdx.x + NT * i, rp = c / CH, ch = c % CH;
         store_transposed_pair(tile, ch * 8, 2 * rp, regs[2 * i], regs[2 * i + 1]);
     }
 }
+// registers loaded by load_tile_pairs stored as an ordinary [row][d] tile
+template <int DH, int NT>
+__device__ __forceinline__ void store_pairs_normal(bf16_t* tile, const uint4* regs) {
+    constexpr int CH = DH / 8;
+#pragma unroll
+    for (int i = 0; i < 4 * DH / NT; ++i) {
+        const int c = threadIdx.x + NT * i, rp = c / CH, ch = c % CH;
+        *(uint4*)(tile + (2 * rp) * AttnCfg<DH>::LSK + ch * 8) = regs[2 * i];
+        *(uint4*)(tile + (2 * rp + 1) * AttnCfg<DH>::LSK + ch * 8) = regs[2 * i + 1];
+    }
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // write a D fragment set holding X^T[d][row] (lane = row) as bf16 rows of X
 template <int DH>
@@ -78,18 +90,21 @@ __device__ __forceinline__ void write_rows_from_dT(bf16_t* __restrict__ dst, con
 }
 
 // ======================================================================== forward
-template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                       const bf16_t* __restrict__ v, long ldq, int T,
-                                                       bf16_t* __restrict__ o, long ldo, float* __restrict__ lse,
-                                                       float scale_log2e) {
+// NW waves per workgroup, 32 queries per wave.  K and V tiles of 64 keys are fetched one tile ahead into
+// registers (the loads fly during the MFMAs of the current tile) and parked in LDS between two barriers.
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                           const bf16_t* __restrict__ v, long ldq, int T,
+                                                           bf16_t* __restrict__ o, long ldo, float* __restrict__ lse,
+                                                           float scale_log2e) {
     using C = AttnCfg<DH>;
+    constexpr int NT = NW * 64, QB = NW * 32;
     __shared__ __align__(16) bf16_t sK[64 * C::LSK];
     __shared__ __align__(16) bf16_t sVt[DH * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int qb = gridDim.x - 1 - blockIdx.x;  // heaviest (latest) query blocks first
     const int head = blockIdx.y;
-    const int q0 = qb * 128, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
+    const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const bf16_t* qh = q + (long)head * DH;
     const bf16_t* kh = k + (long)head * DH;
     const bf16_t* vh = v + (long)head * DH;
@@ -105,61 +120,77 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t* __restrict_
     for (int dt = 0; dt < C::ND; ++dt) oacc[dt] = zero16();
     float m = NEG_BIG, lpart = 0.f;
 
-    const int kend = min(q0 + 128, T);
+    const int kend = min(q0 + QB, T);
     const int n_tiles = (kend + 63) / 64;
-    uint4 rk[DH / 32], rv[DH / 32];
+    uint4 rk[8 * DH / NT], rv[8 * DH / NT];
+    load_tile_regs<DH, NT>(kh, ldq, 0, T, rk);
+    load_tile_pairs<DH, NT>(vh, ldq, 0, T, rv);
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int u0 = tile * 64;
-        load_tile_regs<DH>(kh, ldq, u0, T, rk);
-        load_tile_pairs<DH>(vh, ldq, u0, T, rv);
         __syncthreads();
-        store_tile_normal<DH>(sK, rk);
-        store_tile_transposed<DH>(sVt, rv);
+        store_tile_normal<DH, NT>(sK, rk);
+        store_tile_transposed<DH, NT>(sVt, rv);
         __syncthreads();
+        if (tile + 1 < n_tiles) {
+            load_tile_regs<DH, NT>(kh, ldq, u0 + 64, T, rk);
+            load_tile_pairs<DH, NT>(vh, ldq, u0 + 64, T, rv);
+        }
         if (u0 > tq0 + 31) continue;  // wave-uniform: every key of this tile is in the future
+        // both 32-key halves of the tile at once: two independent MFMA chains, one softmax update
+        f32x16_t s0 = zero16(), s1 = zero16();
 #pragma unroll
-        for (int us = 0; us < 2; ++us) {
-            const int usub0 = u0 + us * 32;
-            if (usub0 > tq0 + 31) continue;
-            f32x16_t sacc = zero16();
-#pragma unroll
-            for (int ks = 0; ks < C::NKS; ++ks) {
-                bf16x8_t a = *(const bf16x8_t*)(sK + (us * 32 + l32) * C::LSK + ks * 16 + g * 8);
-                sacc = mfma32(a, qf[ks], sacc);
-            }
-            float x[16];
-            float mloc = NEG_BIG;
-#pragma unroll
-            for (int vv = 0; vv < 16; ++vv) {
-                const int u = usub0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
-                x[vv] = (u > t_abs) ? NEG_BIG : sacc[vv] * scale_log2e;
-                mloc = fmaxf(mloc, x[vv]);
-            }
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-            const float m_new = fmaxf(m, mloc);
-            const float alpha = exp2f(m - m_new);
-            float psum = 0.f;
+        for (int ks = 0; ks < C::NKS; ++ks) {
+            const bf16x8_t a0 = *(const bf16x8_t*)(sK + l32 * C::LSK + ks * 16 + g * 8);
+            const bf16x8_t a1 = *(const bf16x8_t*)(sK + (32 + l32) * C::LSK + ks * 16 + g * 8);
+            s0 = mfma32(a0, qf[ks], s0);
+            s1 = mfma32(a1, qf[ks], s1);
+        }
+        float x[32];
+        float mloc = NEG_BIG;
+        if (u0 + 63 > tq0) {  // the tile touches the diagonal: causal mask
 #pragma unroll
             for (int vv = 0; vv < 16; ++vv) {
-                x[vv] = exp2f(x[vv] - m_new);
-                psum += x[vv];
+                const int u = u0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
+                x[vv] = (u > t_abs) ? NEG_BIG : s0[vv] * scale_log2e;
+                x[16 + vv] = (u + 32 > t_abs) ? NEG_BIG : s1[vv] * scale_log2e;
             }
-            lpart = lpart * alpha + psum;
-            m = m_new;
+        } else {
+#pragma unroll
+            for (int vv = 0; vv < 16; ++vv) {
+                x[vv] = s0[vv] * scale_log2e;
+                x[16 + vv] = s1[vv] * scale_log2e;
+            }
+        }
+#pragma unroll
+        for (int vv = 0; vv < 32; ++vv) mloc = fmaxf(mloc, x[vv]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        const float m_new = fmaxf(m, mloc);
+        const float alpha = fast_exp2(m - m_new);
+        float psum = 0.f;
+#pragma unroll
+        for (int vv = 0; vv < 32; ++vv) {
+            x[vv] = fast_exp2(x[vv] - m_new);
+            psum += x[vv];
+        }
+        lpart = lpart * alpha + psum;
+        m = m_new;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {  // skip the rescale once the running max has settled
 #pragma unroll
             for (int dt = 0; dt < C::ND; ++dt)
 #pragma unroll
                 for (int vv = 0; vv < 16; ++vv) oacc[dt][vv] *= alpha;
+        }
+#pragma unroll
+        for (int us = 0; us < 2; ++us)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const bf16x8_t b = pack_b_from_d(x, h);
+                const bf16x8_t b = pack_b_from_d(x + 16 * us, h);
 #pragma unroll
                 for (int dt = 0; dt < C::ND; ++dt) {
                     const bf16x8_t a = load_a_permuted(sVt, dt * 32 + l32, us * 32 + 16 * h, g);
                     oacc[dt] = mfma32(a, b, oacc[dt]);
                 }
             }
-        }
     }
     const float ltot = lpart + __shfl_xor(lpart, 32, 64);
     if (t_abs < T) {
@@ -192,21 +223,22 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
 }
 
 // ======================================================================== backward: dQ
-template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                          const bf16_t* __restrict__ v,
-                                                          const bf16_t* __restrict__ d_o,
-                                                          const float* __restrict__ lse,
-                                                          const float* __restrict__ delta, long ldq, long ldo, int T,
-                                                          bf16_t* __restrict__ dq, float scale) {
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                              const bf16_t* __restrict__ v,
+                                                              const bf16_t* __restrict__ d_o,
+                                                              const float* __restrict__ lse,
+                                                              const float* __restrict__ delta, long ldq, long ldo,
+                                                              int T, bf16_t* __restrict__ dq, float scale) {
     using C = AttnCfg<DH>;
+    constexpr int NT = NW * 64, QB = NW * 32;
     __shared__ __align__(16) bf16_t sK[64 * C::LSK];
     __shared__ __align__(16) bf16_t sV[64 * C::LSK];
     __shared__ __align__(16) bf16_t sKt[DH * LS];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int qb = gridDim.x - 1 - blockIdx.x;
     const int head = blockIdx.y;
-    const int q0 = qb * 128, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
+    const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
     const bf16_t* qh = q + (long)head * DH;
     const bf16_t* kh = k + (long)head * DH;
@@ -227,63 +259,71 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t* __restri
 #pragma unroll
     for (int dt = 0; dt < C::ND; ++dt) acc[dt] = zero16();
 
-    const int kend = min(q0 + 128, T);
+    const int kend = min(q0 + QB, T);
     const int n_tiles = (kend + 63) / 64;
-    uint4 rk[DH / 32], rv[DH / 32], rkp[DH / 32];
+    uint4 rk[8 * DH / NT], rv[8 * DH / NT];
+    load_tile_pairs<DH, NT>(kh, ldq, 0, T, rk);
+    load_tile_regs<DH, NT>(vh, ldq, 0, T, rv);
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int u0 = tile * 64;
-        load_tile_regs<DH>(kh, ldq, u0, T, rk);
-        load_tile_regs<DH>(vh, ldq, u0, T, rv);
-        load_tile_pairs<DH>(kh, ldq, u0, T, rkp);
         __syncthreads();
-        store_tile_normal<DH>(sK, rk);
-        store_tile_normal<DH>(sV, rv);
-        store_tile_transposed<DH>(sKt, rkp);
+        store_pairs_normal<DH, NT>(sK, rk);
+        store_tile_transposed<DH, NT>(sKt, rk);
+        store_tile_normal<DH, NT>(sV, rv);
         __syncthreads();
+        if (tile + 1 < n_tiles) {
+            load_tile_pairs<DH, NT>(kh, ldq, u0 + 64, T, rk);
+            load_tile_regs<DH, NT>(vh, ldq, u0 + 64, T, rv);
+        }
         if (u0 > tq0 + 31) continue;
+        f32x16_t s0 = zero16(), s1 = zero16(), dp0 = zero16(), dp1 = zero16();
 #pragma unroll
-        for (int us = 0; us < 2; ++us) {
-            const int usub0 = u0 + us * 32;
-            if (usub0 > tq0 + 31) continue;
-            f32x16_t sacc = zero16(), dpacc = zero16();
+        for (int ks = 0; ks < C::NKS; ++ks) {
+            const int o0 = l32 * C::LSK + ks * 16 + g * 8, o1 = o0 + 32 * C::LSK;
+            s0 = mfma32(*(const bf16x8_t*)(sK + o0), qf[ks], s0);
+            s1 = mfma32(*(const bf16x8_t*)(sK + o1), qf[ks], s1);
+            dp0 = mfma32(*(const bf16x8_t*)(sV + o0), dof[ks], dp0);
+            dp1 = mfma32(*(const bf16x8_t*)(sV + o1), dof[ks], dp1);
+        }
+        float ds[32];
+        const bool diag = u0 + 63 > tq0;
 #pragma unroll
-            for (int ks = 0; ks < C::NKS; ++ks) {
-                bf16x8_t a = *(const bf16x8_t*)(sK + (us * 32 + l32) * C::LSK + ks * 16 + g * 8);
-                sacc = mfma32(a, qf[ks], sacc);
-                bf16x8_t b = *(const bf16x8_t*)(sV + (us * 32 + l32) * C::LSK + ks * 16 + g * 8);
-                dpacc = mfma32(b, dof[ks], dpacc);
-            }
-            float ds[16];
+        for (int vv = 0; vv < 16; ++vv) {
+            const int u = u0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
+            const float pe0 = fast_exp2(s0[vv] * scale_log2e - lse2);
+            const float pe1 = fast_exp2(s1[vv] * scale_log2e - lse2);
+            const float p0 = (diag && u > t_abs) ? 0.f : pe0;
+            const float p1 = (diag && u + 32 > t_abs) ? 0.f : pe1;
+            ds[vv] = p0 * (dp0[vv] - dlt);
+            ds[16 + vv] = p1 * (dp1[vv] - dlt);
+        }
 #pragma unroll
-            for (int vv = 0; vv < 16; ++vv) {
-                const int u = usub0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
-                const float p = (u > t_abs) ? 0.f : exp2f(sacc[vv] * scale_log2e - lse2);
-                ds[vv] = p * (dpacc[vv] - dlt);
-            }
+        for (int us = 0; us < 2; ++us)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const bf16x8_t b = pack_b_from_d(ds, h);
+                const bf16x8_t b = pack_b_from_d(ds + 16 * us, h);
 #pragma unroll
                 for (int dt = 0; dt < C::ND; ++dt) {
                     const bf16x8_t a = load_a_permuted(sKt, dt * 32 + l32, us * 32 + 16 * h, g);
                     acc[dt] = mfma32(a, b, acc[dt]);
                 }
             }
-        }
     }
     if (t_abs < T) write_rows_from_dT<DH>(dq + (long)t_abs * ldq + (long)head * DH, acc, scale, g);
 }
 
 // ======================================================================== backward: dK, dV
-template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                           const bf16_t* __restrict__ v,
-                                                           const bf16_t* __restrict__ d_o,
-                                                           const float* __restrict__ lse,
-                                                           const float* __restrict__ delta, long ldq, long ldo, int T,
-                                                           bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
-                                                           float scale) {
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ q,
+                                                               const bf16_t* __restrict__ k,
+                                                               const bf16_t* __restrict__ v,
+                                                               const bf16_t* __restrict__ d_o,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ delta, long ldq, long ldo,
+                                                               int T, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
+                                                               float scale) {
     using C = AttnCfg<DH>;
+    constexpr int NT = NW * 64, KB = NW * 32;
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* sQ = (bf16_t*)smem;             // [64][LSK]
     bf16_t* sdO = sQ + 64 * C::LSK;         // [64][LSK]
@@ -294,7 +334,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int kb = blockIdx.x;  // early key blocks see the most queries and are scheduled first
     const int head = blockIdx.y;
-    const int u0 = kb * 128, uw0 = u0 + 32 * wave, u_abs = uw0 + l32;
+    const int u0 = kb * KB, uw0 = u0 + 32 * wave, u_abs = uw0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
     const bf16_t* qh = q + (long)head * DH;
     const bf16_t* kh = k + (long)head * DH;
@@ -314,26 +354,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
     for (int dt = 0; dt < C::ND; ++dt) { dkacc[dt] = zero16(); dvacc[dt] = zero16(); }
 
     const int n_tiles = (T + 63) / 64;
-    uint4 rq[DH / 32], rdo[DH / 32], rqp[DH / 32], rdop[DH / 32];
-    for (int tile = u0 / 64; tile < n_tiles; ++tile) {
+    const int tile0 = u0 / 64;
+    uint4 rq[8 * DH / NT], rdo[8 * DH / NT];
+    float lse_v = 0.f, dl_v = 0.f;
+    auto fetch = [&](int tile) {
         const int t0 = tile * 64;
-        load_tile_regs<DH>(qh, ldq, t0, T, rq);
-        load_tile_regs<DH>(doh, ldo, t0, T, rdo);
-        load_tile_pairs<DH>(qh, ldq, t0, T, rqp);
-        load_tile_pairs<DH>(doh, ldo, t0, T, rdop);
-        float lse_v = 0.f, dl_v = 0.f;
+        load_tile_pairs<DH, NT>(qh, ldq, t0, T, rq);
+        load_tile_pairs<DH, NT>(doh, ldo, t0, T, rdo);
         if (tid < 64) {
             const int t = t0 + tid;
             lse_v = (t < T) ? lse[(long)head * T + t] * 1.4426950408889634f : 1.0e30f;
             dl_v = (t < T) ? delta[(long)head * T + t] : 0.f;
         }
+    };
+    if (tile0 < n_tiles) fetch(tile0);
+    for (int tile = tile0; tile < n_tiles; ++tile) {
+        const int t0 = tile * 64;
         __syncthreads();
-        store_tile_normal<DH>(sQ, rq);
-        store_tile_normal<DH>(sdO, rdo);
-        store_tile_transposed<DH>(sQt, rqp);
-        store_tile_transposed<DH>(sdOt, rdop);
+        store_pairs_normal<DH, NT>(sQ, rq);
+        store_pairs_normal<DH, NT>(sdO, rdo);
+        store_tile_transposed<DH, NT>(sQt, rq);
+        store_tile_transposed<DH, NT>(sdOt, rdo);
         if (tid < 64) { sLse[tid] = lse_v; sDelta[tid] = dl_v; }
         __syncthreads();
+        if (tile + 1 < n_tiles) fetch(tile + 1);
 #pragma unroll
         for (int ts = 0; ts < 2; ++ts) {
             const int tsub0 = t0 + ts * 32;
@@ -347,6 +391,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
                 dpacc = mfma32(b, vf[ks], dpacc);
             }
             float p[16], ds[16];
+            const bool diag = tsub0 < uw0 + 32;
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
                 const int tl = ts * 32 + 8 * vq + 4 * g;
@@ -357,7 +402,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
                 for (int e = 0; e < 4; ++e) {
                     const int vv = 4 * vq + e;
                     const int t = t0 + tl + e;
-                    const float pv = (u_abs > t) ? 0.f : exp2f(sacc[vv] * scale_log2e - ll[e]);
+                    const float pe = fast_exp2(sacc[vv] * scale_log2e - ll[e]);
+                    const float pv = (diag && u_abs > t) ? 0.f : pe;
                     p[vv] = pv;
                     ds[vv] = pv * (dpacc[vv] - dd[e]);
                 }
@@ -383,14 +429,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16_t* __restr
 }
 
 // ======================================================================== launchers
+// waves per workgroup (32 queries / keys each), fixed at build time.  Measured at T = 1024, 32 heads of 128:
+// 4 waves beat 2 (a K/V tile is shared by more queries; the extra workgroups of 2 do not overlap enough).
+#ifndef ATTN_NW
+#define ATTN_NW 4
+#endif
+
 hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ldq, int T, int n_heads,
                                 int d_head, bf16_t* o, long ldo, float* lse, hipStream_t s) {
     if (T <= 0 || n_heads <= 0) return hipSuccess;
     if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
     const float sl2 = (1.f / sqrtf((float)d_head)) * 1.4426950408889634f;
-    dim3 grid(cdiv(T, 128), n_heads);
-    if (d_head == 128) attn_fwd_kernel<128><<<grid, 256, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
-    else if (d_head == 64) attn_fwd_kernel<64><<<grid, 256, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
+    constexpr int NW = ATTN_NW;
+    dim3 grid(cdiv(T, NW * 32), n_heads);
+    if (d_head == 128) attn_fwd_kernel<128, NW><<<grid, NW * 64, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
+    else if (d_head == 64) attn_fwd_kernel<64, NW><<<grid, NW * 64, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -400,14 +453,15 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
                           const float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
                           bf16_t* dv, hipStream_t s) {
     using C = AttnCfg<DH>;
+    constexpr int NW = ATTN_NW;
     const float scale = 1.f / sqrtf((float)DH);
-    dim3 grid(cdiv(T, 128), n_heads);
-    attn_bwd_dq_kernel<DH><<<grid, 256, 0, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, scale);
+    dim3 grid(cdiv(T, NW * 32), n_heads);
+    attn_bwd_dq_kernel<DH, NW><<<grid, NW * 64, 0, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, scale);
     const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LS) * sizeof(bf16_t) + 128 * sizeof(float);
-    auto kern = attn_bwd_dkv_kernel<DH>;
+    auto kern = attn_bwd_dkv_kernel<DH, NW>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, 256, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale);
+    kern<<<grid, NW * 64, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale);
     return hipGetLastError();
 }
 

@@ -294,15 +294,26 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * L>(); else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);   // into the buffer every wave finished reading last iteration
+            if (kt + STAGES - 1 < nk && !(DBG & 1)) issue(kt + STAGES - 1);   // into the buffer every wave finished reading last iteration
             const unsigned char* st = smem + (kt % STAGES) * STAGE_BYTES;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 bf16x8_t fa[FM], fb[FN];
+                if (!(DBG & 4)) {
 #pragma unroll
-                for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * ROWB + coff[ks]);
+                    for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * ROWB + coff[ks]);
 #pragma unroll
-                for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * ROWB + coff[ks]);
+                    for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * ROWB + coff[ks]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < FM; ++i) for (int e = 0; e < 8; ++e) fa[i][e] = (__bf16)(float)(lane + ks);
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) for (int e = 0; e < 8; ++e) fb[j][e] = (__bf16)(float)(lane - ks);
+                }
+                if (DBG & 2) {
+                    asm volatile("" ::"v"(fa[0]), "v"(fb[0]), "v"(fa[FM - 1]), "v"(fb[FN - 1]));
+                    continue;
+                }
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -494,6 +505,13 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 105: return run_nt_dl<128, 128, 2, 2, 4, 5>(g, s);
             case 106: return run_nt_dl<128, 128, 2, 2, 4, 6>(g, s);
             case 107: return run_nt_dl<128, 128, 2, 2, 4, 7>(g, s);
+            case 201: return run_nt_dl<256, 256, 4, 2, 2, 1>(g, s);
+            case 202: return run_nt_dl<256, 256, 4, 2, 2, 2>(g, s);
+            case 203: return run_nt_dl<256, 256, 4, 2, 2, 3>(g, s);
+            case 204: return run_nt_dl<256, 256, 4, 2, 2, 4>(g, s);
+            case 205: return run_nt_dl<256, 256, 4, 2, 2, 5>(g, s);
+            case 206: return run_nt_dl<256, 256, 4, 2, 2, 6>(g, s);
+            case 207: return run_nt_dl<256, 256, 4, 2, 2, 7>(g, s);
 #endif
             default: return run_nt_dl<128, 128, 2, 2, 4>(g, s);
         }
