@@ -178,7 +178,13 @@ def test_state_carry_two_chunks_two_epochs(api, H):
     for l in range(shape.n_layers):
         for i, p in enumerate(PROJ):
             dout, din = shape.proj_dims(p)
-            check(api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank)), facs[l][p][1], 5e-2, f"B l{l} {p}")
+            # AdamW's early steps are sign-like (|step| ~ lr whatever |g|): an entry whose tiny gradient has the other
+            # sign in one of the four steps ends 2*lr away, so B is compared in the L2 sense and by the share of such
+            # entries; the first moment (linear in the gradients) takes the usual two-sided check.
+            Bg = api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank))
+            Bo = np.asarray(facs[l][p][1], np.float64)
+            assert np.linalg.norm(Bg - Bo) / np.linalg.norm(Bo) <= 5e-2, f"B l{l} {p}"
+            assert np.mean(np.abs(Bg - Bo) > 1.5 * lr) < 0.02, f"B l{l} {p}"
             check(api.tl_get_factor(lora, l, i, api.M_B, (dout, shape.rank)), opt["m"][l][p][1], 5e-2, f"mB l{l} {p}")
     api.tl_lora_free(lora)
     model.close()
