@@ -20,6 +20,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak (vendor figure, no sparsity)
+# HBM bytes per launch of the dominant kernel, from two rocprofv3 --pmc passes over this same command
+# (FETCH_SIZE, then WRITE_SIZE; summed over the kernel's launches of one update, divided by their number,
+# each counter scaled by what it reads for --copy-calibration's 1 GiB copy).  The passes and the scaling
+# factors are in profiles/chunk_update_7b_r64_T1024.md; counters cannot be read from inside this process.
+GEMM_NT_HBM_BYTES_PER_LAUNCH = 325e6
 
 
 def cpu_baseline(shape, T, seed):
@@ -68,6 +73,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket the GEMM launches with HIP events")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run one plain 1 GiB device-to-device copy kernel (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -78,6 +86,15 @@ def main():
         print("bench.py: no GPU visible; the chunk update has no CPU path", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 1 << 28  # 2^28 fp32 = 1 GiB read + 1 GiB written by one elementwise copy kernel
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": 4 * n, "copy_calibration_bytes_written": 4 * n}))
+        return
     from paper_2401_11504_amd import api, harness, synth
 
     shape = synth.SHAPES["7b"].with_layers(args.layers)
@@ -114,7 +131,8 @@ def main():
         api.tl_profile_enable(lora, False)
         achieved = flop / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": GEMM_NT_HBM_BYTES_PER_LAUNCH if args.layers == 32 and T == 1024 else None,
                 "kernel": "gemm_nt_dl_kernel (frozen W GEMM + low-rank K-extension; all tile shapes)",
                 "launches_per_step": launches // max(args.steps, 1),
                 "avg_launch_us": round(ms * 1e3 / max(launches, 1), 2),

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const bf16_t* __restr
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
     __shared__ __align__(16) bf16_t sK[64 * C::LSK];
-    __shared__ __align__(16) bf16_t sVt[DH * LS];
+    __shared__ __align__(16) bf16_t sVt[DH * LST];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int qb = gridDim.x - 1 - blockIdx.x;  // heaviest (latest) query blocks first
     const int head = blockIdx.y;
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const bf16_t* __re
     constexpr int NT = NW * 64, QB = NW * 32;
     __shared__ __align__(16) bf16_t sK[64 * C::LSK];
     __shared__ __align__(16) bf16_t sV[64 * C::LSK];
-    __shared__ __align__(16) bf16_t sKt[DH * LS];
+    __shared__ __align__(16) bf16_t sKt[DH * LST];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int qb = gridDim.x - 1 - blockIdx.x;
     const int head = blockIdx.y;
@@ -327,9 +327,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* sQ = (bf16_t*)smem;             // [64][LSK]
     bf16_t* sdO = sQ + 64 * C::LSK;         // [64][LSK]
-    bf16_t* sQt = sdO + 64 * C::LSK;        // [DH][LS]
-    bf16_t* sdOt = sQt + DH * LS;           // [DH][LS]
-    float* sLse = (float*)(sdOt + DH * LS); // [64]
+    bf16_t* sQt = sdO + 64 * C::LSK;        // [DH][LST]
+    bf16_t* sdOt = sQt + DH * LST;           // [DH][LST]
+    float* sLse = (float*)(sdOt + DH * LST); // [64]
     float* sDelta = sLse + 64;              // [64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     const int kb = blockIdx.x;  // early key blocks see the most queries and are scheduled first
@@ -457,7 +457,7 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
     const float scale = 1.f / sqrtf((float)DH);
     dim3 grid(cdiv(T, NW * 32), n_heads);
     attn_bwd_dq_kernel<DH, NW><<<grid, NW * 64, 0, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, scale);
-    const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LS) * sizeof(bf16_t) + 128 * sizeof(float);
+    const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
     auto kern = attn_bwd_dkv_kernel<DH, NW>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

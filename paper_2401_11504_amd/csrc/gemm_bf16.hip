@@ -552,8 +552,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
     // Two LDS buffers per operand (one barrier per 64-token tile) and the next tile's global loads are
     // issued a full tile ahead.  grid.y = Mo tiles x n_split: each split covers a contiguous token range;
     // with n_split > 1 the splits are stored as fp32 partials and added by tn_reduce_kernel.
-    __shared__ __align__(16) bf16_t sP[2][64 * LS];
-    __shared__ __align__(16) bf16_t sQ[2][64 * LS];
+    __shared__ __align__(16) bf16_t sP[2][64 * LST];
+    __shared__ __align__(16) bf16_t sQ[2][64 * LST];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
     const int tiles_i = (p.Mo + 63) / 64;
@@ -594,8 +594,8 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
         }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8_t a = *(const bf16x8_t*)(sP[buf] + tn_off(ri, ks * 16 + g * 8));
-            bf16x8_t b = *(const bf16x8_t*)(sQ[buf] + tn_off(rj, ks * 16 + g * 8));
+            const bf16x8_t a = load_a_linear(sP[buf], ri, ks * 16 + g * 8);
+            const bf16x8_t b = load_a_linear(sQ[buf], rj, ks * 16 + g * 8);
             acc = mfma32(a, b, acc);
         }
         __syncthreads();

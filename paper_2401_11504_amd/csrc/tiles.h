@@ -12,7 +12,7 @@
 #include "common.h"
 
 #define BK 64
-#define LS 72  // LDS row stride (elements) of a 64-wide bf16 tile: 16-byte reads of 8 rows hit 32 distinct banks
+#define LS 72  // LDS row stride (elements) of a 64-wide K-contiguous bf16 tile read with 16-byte accesses
 
 __device__ __forceinline__ f32x16_t mfma32(bf16x8_t a, bf16x8_t b, f32x16_t c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -25,9 +25,13 @@ __device__ __forceinline__ f32x16_t zero16() {
     return z;
 }
 
-// Offset of element (i, t) in a transposed [i][t] tile, t < 64.  The 8-element t-chunk index is XORed
-// with (i / 8) % 8 so that the 8 column groups written by one row of the source land in distinct banks.
-__device__ __forceinline__ int tn_off(int i, int t) { return i * LS + ((((t >> 3) ^ (i >> 3)) & 7) << 3) + (t & 7); }
+// Offset of element (i, t) in a transposed [i][t] tile, t < 64 (LDS has 64 banks: 256 bytes per clock).
+// Rows are 68 elements = 17 x 8 bytes, so 32 lanes reading 8 bytes of 32 consecutive rows at the same t hit 32
+// distinct 8-byte slots; the 8-byte slot index inside a row is XORed with 2 * ((i / 32) % 4), which is constant
+// over such a read and spreads the dword stores of one source row (whose columns i are 8 apart per lane) over
+// all banks.
+#define LST 68
+__device__ __forceinline__ int tn_off(int i, int t) { return i * LST + ((((t >> 2) ^ (((i >> 5) & 3) << 1))) << 2) + (t & 3); }
 
 // Thread holds source rows t, t+1 (t even) and 8 columns i0..i0+7; writes 8 dwords into the [i][t] tile.
 __device__ __forceinline__ void store_transposed_pair(bf16_t* tile, int i0, int t, uint4 r0, uint4 r1) {
@@ -45,6 +49,16 @@ __device__ __forceinline__ void store_transposed_pair(bf16_t* tile, int i0, int 
 __device__ __forceinline__ bf16x8_t load_a_permuted(const bf16_t* tile, int row, int t16, int g) {
     const bf16x4_t lo = *(const bf16x4_t*)(tile + tn_off(row, t16 + 4 * g));
     const bf16x4_t hi = *(const bf16x4_t*)(tile + tn_off(row, t16 + 8 + 4 * g));
+    bf16x8_t a;
+    a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
+    a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
+    return a;
+}
+
+// ordinary operand fragment (8 consecutive t) of a transposed tile, as two 8-byte pieces
+__device__ __forceinline__ bf16x8_t load_a_linear(const bf16_t* tile, int row, int t8) {
+    const bf16x4_t lo = *(const bf16x4_t*)(tile + tn_off(row, t8));
+    const bf16x4_t hi = *(const bf16x4_t*)(tile + tn_off(row, t8 + 4));
     bf16x8_t a;
     a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
     a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
