@@ -14,6 +14,7 @@
 #include "kernels.h"
 #include "tiles.h"
 #include <cstdlib>
+#include <type_traits>
 
 // ======================================================================== NT
 template <int BM, int BN, int WM, int WN, bool PARTIAL>
@@ -163,7 +164,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false>
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, bool PIPE = false>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
     constexpr int NT = WM * WN * 64;
     constexpr int ROWS = BM + BN;
@@ -245,10 +246,109 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     for (int ks = 0; ks < KS; ++ks) coff[ks] = (((2 * ks + g) ^ ((l32 / RP) % CPRW)) << 4);
     const int a_row = (wm * TM + l32) * ROWB, b_row = (BM + wn * TN + l32) * ROWB;
 
+    if constexpr (PIPE) {
+        // One wave per SIMD: the matrix pipe only stays busy if the wave never waits, so inside the steady-state
+        // loop nothing is issued in bursts.  Tile kt+STAGES-1 is fetched during iteration kt, one 16-byte
+        // global->LDS load after every fourth MFMA (a burst of L loads would hold the wave at the address
+        // unit for hundreds of clocks), and the fragments of the next k-step are read one per MFMA slot while
+        // the current k-step's MFMAs run.  The loop body has no branches; the last STAGES-1 tiles, which
+        // fetch nothing, run in a peeled tail.  The host only picks this path for nk >= STAGES.
+        static_assert(STAGES >= 3 && FM * FN >= FM + FN && KS * FM * FN >= L, "slots");
+        constexpr int NMF = FM * FN, NRD = FM + FN, NSLOT = KS * NMF;
+        // load j of a tile goes into slot j * NSLOT / L; LBH = loads issued before the hand-over (the last k-step)
+        constexpr int LBH = ((KS - 1) * NMF * L + NSLOT - 1) / NSLOT;
+        const unsigned char* a_ptr = smem + a_row;
+        const unsigned char* b_ptr = smem + b_row;
+        bf16x8_t fa[2][FM], fb[2][FN];
+        // one k-step: NMF MFMAs on fragment set `cur`; the slot after MFMA e carries the next fragment read into
+        // set `nxt` (slots 0 .. NRD-1); the tile's L DMA loads are spread evenly over its KS * NMF slots
+        auto kstep = [&](auto loads_c, unsigned ext, auto reads_c, int ks, size_t rd_stage, int rd_ks,
+                         const bf16_t* pa, const bf16_t* pb, unsigned dst) {
+            constexpr bool LOADS = decltype(loads_c)::value, READS = decltype(reads_c)::value;
+            const int cur = ks & 1, nxt = cur ^ 1;
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (s < nk) issue(s);
-    if constexpr (STAGES >= 3) {
+            for (int e = 0; e < NMF; ++e) {
+                acc[e / FN][e % FN] = mfma32(fa[cur][e / FN], fb[cur][e % FN], acc[e / FN][e % FN]);
+                if constexpr (READS) {
+                    // order A0, B0..B(FN-1), A1..: what the next k-step's first MFMAs need comes first
+                    if (e == 0) fa[nxt][0] = *(const bf16x8_t*)(a_ptr + rd_stage + coff[rd_ks]);
+                    else if (e <= FN) fb[nxt][e - 1] = *(const bf16x8_t*)(b_ptr + rd_stage + (e - 1) * 32 * ROWB + coff[rd_ks]);
+                    else if (e < NRD) fa[nxt][e - FN] = *(const bf16x8_t*)(a_ptr + rd_stage + (e - FN) * 32 * ROWB + coff[rd_ks]);
+                }
+                if constexpr (LOADS) {
+                    const int gs = ks * NMF + e;          // slot number within the tile
+                    const int j = (gs * L + NSLOT - 1) / NSLOT;   // first load with j * NSLOT / L >= gs
+                    if (j < L && j * NSLOT / L == gs) {
+                        // vo2 - vo1 is folded in arithmetically (ext is 0 or 1, wave-uniform): one loop body serves both pairs
+                        load_lds16(vo1[j] + ext * vo2[j], j < LA ? (const void*)pa : (const void*)pb, dst + j * NT * 16);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        // one tile; HW = loads that may still be outstanding at the hand-over so that tile kt+1 has landed
+        auto tile = [&](auto loads_c, auto hw_c, auto last_c, int kt) {
+            constexpr int HW = decltype(hw_c)::value;
+            constexpr bool LAST = decltype(last_c)::value;
+            const int tn = kt + STAGES - 1;
+            const int ktn = kt0 + tn;
+            const unsigned ext_c = ktn >= nk1 ? 1u : 0u;
+            const bf16_t* pa = ext_c ? A2 + (long)(ktn - nk1) * BKT : A + (long)ktn * BKT;
+            const bf16_t* pb = ext_c ? B2 + (long)(ktn - nk1) * BKT : B + (long)ktn * BKT;
+            const unsigned dst = __builtin_amdgcn_readfirstlane(lds0 + (tn % STAGES) * STAGE_BYTES + wave * 1024);
+            const size_t st_cur = (size_t)(kt % STAGES) * STAGE_BYTES, st_nxt = (size_t)((kt + 1) % STAGES) * STAGE_BYTES;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks < KS - 1) {
+                    kstep(loads_c, ext_c, std::true_type{}, ks, st_cur, ks + 1, pa, pb, dst);
+                } else if constexpr (!LAST) {
+                    // hand-over: every wave's reads of this tile are complete (so its buffer may be refilled from
+                    // the next iteration on) and tile kt+1 has landed for every wave
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    wait_vmcnt<HW>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    kstep(loads_c, ext_c, std::true_type{}, ks, st_nxt, 0, pa, pb, dst);
+                } else {
+                    kstep(std::false_type{}, 0u, std::false_type{}, ks, 0, 0, pa, pb, dst);
+                }
+            }
+        };
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s) issue(s);
+#pragma unroll
+        for (int j = 0; j < L; ++j) vo2[j] -= vo1[j];
+        wait_vmcnt<(STAGES - 2) * L>();
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int i = 0; i < FM; ++i) fa[0][i] = *(const bf16x8_t*)(a_ptr + i * 32 * ROWB + coff[0]);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) fb[0][j] = *(const bf16x8_t*)(b_ptr + j * 32 * ROWB + coff[0]);
+        // at the hand-over of a steady-state tile, tile kt+2.. and the LBH loads of tile kt+STAGES-1 issued
+        // so far may be outstanding
+        constexpr int HW_STEADY = (STAGES - 3) * L + LBH;
+        static_assert(HW_STEADY <= 63, "vmcnt range");
+        using T_ = std::true_type; using F_ = std::false_type;
+        int kt = 0;
+        // (vo2 now holds the difference to vo1, see kstep)
+        for (; kt + STAGES - 1 < nk; ++kt) tile(T_{}, std::integral_constant<int, HW_STEADY>{}, F_{}, kt);
+        // tail: tiles nk-STAGES+1 .. nk-1 fetch nothing; with r tiles after this one, r-1 of them may be in flight
+        auto tail = [&](auto self, auto r_c) -> void {
+            constexpr int R = decltype(r_c)::value;
+            if constexpr (R > 0) {
+                tile(F_{}, std::integral_constant<int, (R - 1) * L>{}, F_{}, kt);
+                ++kt;
+                self(self, std::integral_constant<int, R - 1>{});
+            } else {
+                tile(F_{}, std::integral_constant<int, 0>{}, T_{}, kt);
+            }
+        };
+        tail(tail, std::integral_constant<int, STAGES - 2>{});
+    } else if constexpr (STAGES >= 3) {
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < nk) issue(s);
         // Software pipeline: the fragments of k-step ks+1 are read while the MFMAs of ks run, and the
         // hand-over to the next tile (wait, barrier, next global loads, first fragments) happens before
         // the last k-step's MFMAs, so the matrix pipe never waits for LDS at a tile boundary.
@@ -289,6 +389,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             }
         }
     } else {
+#pragma unroll
+        for (int s = 0; s < STAGES - 1; ++s)
+            if (s < nk) issue(s);
         for (int kt = 0; kt < nk; ++kt) {
             // tile kt has landed once at most the loads of the STAGES-2 younger tiles are outstanding
             if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * L>(); else wait_vmcnt<0>();
@@ -398,12 +501,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false>
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, bool PIPE = false>
 static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     const int tiles_m = cdiv(g.M, BM), tiles_n = cdiv(g.N, BN);
     const size_t lds = (size_t)STAGES * (BM + BN) * BKT * 2;
     dim3 grid(tiles_m * tiles_n, SPLITK ? n_split : 1, g.batch);
-    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK>;
+    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, PIPE>;
+    if constexpr (PIPE) {  // the branch-free steady-state loop assumes every split has at least STAGES k-tiles
+        const int nkt = g.K / BKT + g.K2 / BKT;
+        if (nkt / n_split < STAGES) return run_nt_dl<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, false>(g, s, n_split);
+    }
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n);
@@ -472,14 +579,17 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
         const char* env = getenv("TL_GEMM_TILE");  // tuning aid: force one tile configuration
         int cfg = env ? atoi(env) : 0;
         if (cfg == 0) {
-            // Measured on MI355X at M = 1024: the path is bound by the L2 -> LDS fill rate, so the largest tile
-            // that still gives every CU work wins.  256x256 tiles need >= ~160 tiles; when their last round of
-            // CUs would be mostly idle and 256x128 tiles quantise better, take those; otherwise 128x128.
+            // Measured on MI355X at M = 1024.  Every tile shape is limited by how fast a CU can pull operand
+            // bytes out of L2 (about 64 bytes per clock at best), so the largest tile that still gives every CU
+            // work wins: 256x256 when its tiles fill the 256 CUs well, 256x128 when that quantises better, and
+            // 128x128 with the interleaved four-stage loop when there are only a few hundred tiles in all.
             const long t256 = (long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
             const long t256x128 = (long)cdiv(g.M, 256) * cdiv(g.N, 128) * g.batch;
             auto fill = [](long t) { return (double)t / (double)(((t + 255) / 256) * 256); };
-            if (t256 >= 160) cfg = (fill(t256) < 0.7 && fill(t256x128) >= 0.85) ? 2 : 6;
-            else cfg = 10;
+            if (t256 < 160) cfg = 25;
+            else if (fill(t256) >= 0.9) cfg = 6;
+            else if (fill(t256x128) >= 0.85) cfg = 28;
+            else cfg = g.batch > 1 ? 22 : 6;
         }
         switch (cfg) {
             case 1: return run_nt_dl<128, 128, 2, 2, 3>(g, s);
@@ -497,6 +607,16 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 14: return run_nt_dl<256, 128, 2, 2, 4, 0, 32>(g, s);
             case 15: return run_nt_dl<128, 128, 2, 2, 6, 0, 32>(g, s);
             case 16: return run_nt_dl<256, 128, 4, 2, 4, 0, 32>(g, s);
+            case 21: return run_nt_dl<256, 256, 2, 2, 4, 0, 32, false, true>(g, s);
+            case 22: return run_nt_dl<256, 256, 4, 2, 4, 0, 32, false, true>(g, s);
+            case 23: return run_nt_dl<256, 256, 2, 2, 3, 0, 32, false, true>(g, s);
+            case 24: return run_nt_dl<256, 128, 2, 2, 4, 0, 32, false, true>(g, s);
+            case 25: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, true>(g, s);
+            case 26: return run_nt_dl<128, 128, 2, 2, 3, 0, 64, false, true>(g, s);
+            case 27: return run_nt_dl<256, 128, 2, 2, 3, 0, 64, false, true>(g, s);
+            case 28: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, true>(g, s);
+            case 29: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, true>(g, s);
+            case 30: return run_nt_dl<128, 256, 2, 2, 3, 0, 64, false, true>(g, s);
 #ifdef TL_GEMM_ABLATE
             case 101: return run_nt_dl<128, 128, 2, 2, 4, 1>(g, s);
             case 102: return run_nt_dl<128, 128, 2, 2, 4, 2>(g, s);
@@ -513,7 +633,8 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 206: return run_nt_dl<256, 256, 4, 2, 2, 6>(g, s);
             case 207: return run_nt_dl<256, 256, 4, 2, 2, 7>(g, s);
 #endif
-            default: return run_nt_dl<128, 128, 2, 2, 4>(g, s);
+            case 10: return run_nt_dl<128, 128, 2, 2, 4>(g, s);
+            default: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, true>(g, s);
         }
     }
     if (g.N > 64 && t128 >= 200) {
