@@ -669,33 +669,25 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
 // Transposing store of a [64 t][64 i] operand tile: thread (tp, ic) holds rows t = 2tp, 2tp+1 and the
 // 8 columns i = 8ic..8ic+7, and writes 8 dwords (t, t+1) pairs into the [i][t] LDS tile.  The 8-element
 // t-chunk index is XORed with (i / 8) % 8 so that the 8 column groups of one row land in distinct banks.
-__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
-    // Two LDS buffers per operand (one barrier per 64-token tile) and the next tile's global loads are
-    // issued a full tile ahead.  grid.y = Mo tiles x n_split: each split covers a contiguous token range;
-    // with n_split > 1 the splits are stored as fp32 partials and added by tn_reduce_kernel.
+// One 64x64 output tile of P^T Q over the 64-token tiles [it0, it1): two LDS buffers per operand (one barrier per
+// token tile), the next tile's global loads issued a full tile ahead.  Returns this wave's 32x32 accumulator.
+__device__ __forceinline__ f32x16_t tn_tile(const bf16_t* P, long ldp, int Mo, const bf16_t* Q, long ldq, int No, int T,
+                                            int i0, int j0, int it0, int it1) {
     __shared__ __align__(16) bf16_t sP[2][64 * LST];
     __shared__ __align__(16) bf16_t sQ[2][64 * LST];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
-    const int tiles_i = (p.Mo + 63) / 64;
-    const int ti = blockIdx.y % tiles_i, split = blockIdx.y / tiles_i;
-    const int i0 = ti * 64, j0 = blockIdx.x * 64, z = blockIdx.z;
-    const bf16_t* P = p.P + (long)z * p.bP;
-    const bf16_t* Q = p.Q + (long)z * p.bQ;
     const int tp = tid >> 3, ic = tid & 7;
-    const int nt_all = (p.T + 63) / 64;
-    const int it0 = (int)((long)nt_all * split / n_split), it1 = (int)((long)nt_all * (split + 1) / n_split);
-
     f32x16_t acc = zero16();
     auto ld = [&](const bf16_t* base, long ldx, int c0, int cmax, int t) -> uint4 {
         const int c = c0 + ic * 8;
-        return (t < p.T && c < cmax) ? *(const uint4*)(base + (long)t * ldx + c) : make_uint4(0, 0, 0, 0);
+        return (t < T && c < cmax) ? *(const uint4*)(base + (long)t * ldx + c) : make_uint4(0, 0, 0, 0);
     };
     uint4 p0, p1, q0, q1;
     auto gload = [&](int it) {
         const int t = it * 64 + 2 * tp;
-        p0 = ld(P, p.ldp, i0, p.Mo, t); p1 = ld(P, p.ldp, i0, p.Mo, t + 1);
-        q0 = ld(Q, p.ldq, j0, p.No, t); q1 = ld(Q, p.ldq, j0, p.No, t + 1);
+        p0 = ld(P, ldp, i0, Mo, t); p1 = ld(P, ldp, i0, Mo, t + 1);
+        q0 = ld(Q, ldq, j0, No, t); q1 = ld(Q, ldq, j0, No, t + 1);
     };
     if (it0 < it1) {
         gload(it0);
@@ -721,6 +713,20 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
         }
         __syncthreads();
     }
+    return acc;
+}
+
+__global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
+    // grid.y = Mo tiles x n_split: each split covers a contiguous token range; with n_split > 1 the splits are
+    // stored as fp32 partials and added by tn_reduce_kernel.
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
+    const int tiles_i = (p.Mo + 63) / 64;
+    const int ti = blockIdx.y % tiles_i, split = blockIdx.y / tiles_i;
+    const int i0 = ti * 64, j0 = blockIdx.x * 64, z = blockIdx.z;
+    const int nt_all = (p.T + 63) / 64;
+    const int it0 = (int)((long)nt_all * split / n_split), it1 = (int)((long)nt_all * (split + 1) / n_split);
+    const f32x16_t acc = tn_tile(p.P + (long)z * p.bP, p.ldp, p.Mo, p.Q + (long)z * p.bQ, p.ldq, p.No, p.T, i0, j0, it0, it1);
     const int col = j0 + wj * 32 + l32;
     if (n_split == 1) {
         if (col < p.No) {
@@ -739,6 +745,28 @@ __global__ __launch_bounds__(256) void gemm_tn_kernel(GemmTN p, int n_split) {
         for (int v = 0; v < 16; ++v) {
             const int row = i0 + wi * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
             if (row < p.Mo) part[(long)row * p.No + col] = acc[v];
+        }
+    }
+}
+
+// Several independent P^T Q products over the same T tokens in one launch: workgroup b takes output tile
+// b - tile0 of the problem whose tile range holds b.  Every tile runs over all tokens, so nothing is split or reduced.
+__global__ __launch_bounds__(256) void gemm_tn_grouped_kernel(GemmTNGroup grp) {
+    const int b = blockIdx.x;
+    int k = 0;
+    while (k + 1 < grp.n && b >= grp.p[k + 1].tile0) ++k;
+    const TnProblem& q = grp.p[k];
+    const int t = b - q.tile0, tiles_j = (q.No + 63) / 64;
+    const int i0 = (t / tiles_j) * 64, j0 = (t % tiles_j) * 64;
+    const f32x16_t acc = tn_tile(q.P, q.ldp, q.Mo, q.Q, q.ldq, q.No, grp.T, i0, j0, 0, (grp.T + 63) / 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
+    const int col = j0 + wj * 32 + l32;
+    if (col < q.No) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = i0 + wi * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
+            if (row < q.Mo) q.C[(long)row * q.ldc + col] = acc[v];
         }
     }
 }
@@ -774,5 +802,19 @@ hipError_t launch_gemm_tn(const GemmTN& g, hipStream_t s) {
         const long n = (long)g.Mo * g.No * g.batch;
         tn_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, split);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_tn_grouped(GemmTNGroup& g, hipStream_t s) {
+    if (g.n <= 0 || g.T <= 0) return hipSuccess;
+    if (g.n > TN_GROUP_MAX) return hipErrorInvalidValue;
+    int tiles = 0;
+    for (int k = 0; k < g.n; ++k) {
+        TnProblem& q = g.p[k];
+        if (q.Mo <= 0 || q.No <= 0 || (q.ldp & 7) || (q.ldq & 7) || (q.Mo & 7) || (q.No & 7)) return hipErrorInvalidValue;
+        q.tile0 = tiles;
+        tiles += cdiv(q.Mo, 64) * cdiv(q.No, 64);
+    }
+    gemm_tn_grouped_kernel<<<tiles, 256, 0, s>>>(g);
     return hipGetLastError();
 }

@@ -37,6 +37,24 @@ struct GemmTN {
 };
 hipError_t launch_gemm_tn(const GemmTN& g, hipStream_t s);
 
+// Up to TN_GROUP_MAX products C_k[Mo_k, No_k] (fp32) = P_k[T, Mo_k]^T Q_k[T, No_k] over the same T tokens in one
+// launch (the dA and dB of every projection of a decoder layer).  tile0 is filled in by the launcher.
+constexpr int TN_GROUP_MAX = 12;
+struct TnProblem {
+    const bf16_t* P = nullptr; const bf16_t* Q = nullptr; float* C = nullptr;
+    long ldp = 0, ldq = 0, ldc = 0;
+    int Mo = 0, No = 0, tile0 = 0, pad = 0;
+};
+struct GemmTNGroup {
+    TnProblem p[TN_GROUP_MAX];
+    int n = 0, T = 0;
+    void add(const bf16_t* P, long ldp, int Mo, const bf16_t* Q, long ldq, int No, float* C, long ldc) {
+        if (n < TN_GROUP_MAX) { TnProblem& q = p[n]; q.P = P; q.ldp = ldp; q.Mo = Mo; q.Q = Q; q.ldq = ldq; q.No = No; q.C = C; q.ldc = ldc; }
+        ++n;
+    }
+};
+hipError_t launch_gemm_tn_grouped(GemmTNGroup& g, hipStream_t s);
+
 // fp32 reference-precision GEMM for the single-layer fp32 step: C = alpha * op(A) op(B) + beta * C
 // ta/tb: 0 = as stored [rows, cols] row-major, 1 = transposed use.  (gemm_f32.hip)
 hipError_t launch_sgemm(int ta, int tb, int M, int N, int K, float alpha, const float* A, int lda, const float* B,

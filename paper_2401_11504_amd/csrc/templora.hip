@@ -126,7 +126,7 @@ struct tl_lora {
     std::vector<LayerSave> save;
     std::vector<float*> hs, dhs;   // residual stream / its gradient at the L+1 layer boundaries
     // shared temporaries
-    bf16_t *hf = nullptr, *dlogits = nullptr, *dhf = nullptr, *dh_bf = nullptr, *d_act = nullptr, *dgu = nullptr,
+    bf16_t *hf = nullptr, *dlogits = nullptr, *dhf = nullptr, *dh_bf[2] = {nullptr, nullptr}, *d_act = nullptr, *dgu = nullptr,
            *dx = nullptr, *dhmid_bf = nullptr, *d_o = nullptr, *dqkv = nullptr, *dH = nullptr;
     float *logits = nullptr, *nll = nullptr, *loss_sum = nullptr, *dhmid = nullptr, *delta = nullptr,
           *partial = nullptr;
@@ -134,13 +134,15 @@ struct tl_lora {
     int *tok = nullptr, *labels = nullptr;
     int* tok_host = nullptr;      // pinned
     float* loss_host = nullptr;   // pinned
-    // dA / dB are off the critical path of the backward pass: they run on a second stream (default priority)
+    // dA / dB of a layer (one grouped launch) are off the critical path of the backward pass: they run on a second
+    // stream (default priority) while the main stream goes on with the layer below.  Everything that launch reads and
+    // the layer below would overwrite too early exists twice, indexed by layer parity: dH of each projection group and
+    // the bf16 copy of the residual-stream gradient.
     hipStream_t side = nullptr;
-    hipEvent_t ev_ready[N_GROUPS] = {};   // main: dH of the group is written
-    hipEvent_t ev_done[N_GROUPS] = {};    // side: dA, dB of the group are finished (dH, dY may be overwritten)
-    bf16_t* dHg[N_GROUPS] = {};
-    float* partial2 = nullptr;
-    size_t partial2_elems = 0;
+    hipEvent_t ev_ready[2] = {};          // main: every operand of the layer's dA / dB launch is written
+    hipEvent_t ev_done[2] = {};           // side: the launch has finished
+    bool tn_pending[2] = {false, false};
+    bf16_t* dHg[2][N_GROUPS] = {};
     // optional timing of the frozen-weight GEMM launches (HIP events on the model's stream)
     bool prof_on = false;
     std::vector<hipEvent_t> prof_ev;
@@ -255,10 +257,11 @@ extern "C" tl_status tl_model_destroy(tl_model* m) {
 // ---------------------------------------------------------------- module life cycle
 static void lora_release(tl_lora* L) {
     if (L->side) { (void)hipStreamSynchronize(L->side); (void)hipStreamDestroy(L->side); L->side = nullptr; }
-    for (int g = 0; g < N_GROUPS; ++g) {
-        if (L->ev_ready[g]) (void)hipEventDestroy(L->ev_ready[g]);
-        if (L->ev_done[g]) (void)hipEventDestroy(L->ev_done[g]);
-        L->ev_ready[g] = L->ev_done[g] = nullptr;
+    for (int k = 0; k < 2; ++k) {
+        if (L->ev_ready[k]) (void)hipEventDestroy(L->ev_ready[k]);
+        if (L->ev_done[k]) (void)hipEventDestroy(L->ev_done[k]);
+        L->ev_ready[k] = L->ev_done[k] = nullptr;
+        L->tn_pending[k] = false;
     }
     for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
     L->prof_ev.clear();
@@ -363,7 +366,8 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
             TLCHK(L->pool.alloc(&sv.lse, (size_t)mc.n_heads * Tm));
             TLCHK(L->pool.alloc(&sv.hmid, Td));
         }
-        TLCHK(L->pool.alloc(&L->dh_bf, Td));
+        TLCHK(L->pool.alloc(&L->dh_bf[0], Td));
+        TLCHK(L->pool.alloc(&L->dh_bf[1], Td));
         TLCHK(L->pool.alloc(&L->d_act, (size_t)Tm * f));
         TLCHK(L->pool.alloc(&L->dgu, (size_t)Tm * 2 * f));
         TLCHK(L->pool.alloc(&L->dx, Td));
@@ -372,14 +376,12 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         TLCHK(L->pool.alloc(&L->d_o, Td));
         TLCHK(L->pool.alloc(&L->dqkv, 3 * Td));
         TLCHK(L->pool.alloc(&L->dH, (size_t)Tm * 3 * r));
-        for (int g = 0; g < N_GROUPS; ++g) TLCHK(L->pool.alloc(&L->dHg[g], (size_t)Tm * kGroupCount[g] * r));
-        L->partial2_elems = (size_t)8 * r * (size_t)(3 * d > 2 * f ? 3 * d : 2 * f);
-        TLCHK(L->pool.alloc(&L->partial2, L->partial2_elems));
-        HIPCHK(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
-        for (int g = 0; g < N_GROUPS; ++g) {
-            HIPCHK(hipEventCreateWithFlags(&L->ev_ready[g], hipEventDisableTiming));
-            HIPCHK(hipEventCreateWithFlags(&L->ev_done[g], hipEventDisableTiming));
+        for (int k = 0; k < 2; ++k) {
+            for (int g = 0; g < N_GROUPS; ++g) TLCHK(L->pool.alloc(&L->dHg[k][g], (size_t)Tm * kGroupCount[g] * r));
+            HIPCHK(hipEventCreateWithFlags(&L->ev_ready[k], hipEventDisableTiming));
+            HIPCHK(hipEventCreateWithFlags(&L->ev_done[k], hipEventDisableTiming));
         }
+        HIPCHK(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
         TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
         // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r];
         // dA / dB of one group: at most max(3r*d, 2f*r) elements, up to 8 token splits)
@@ -464,23 +466,22 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     return TL_OK;
 }
 
-// backward: dH = s dY B;  dX = dY W + dH A  on the main stream;  dA = dH^T X;  dB = dY^T Hs  on the side stream.
-// The caller must make the main stream wait for ev_done[g] before anything overwrites dY (see layer_backward).
-static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf16_t* X, int T, bf16_t* dX) {
+// backward: dH = s dY B;  dX = dY W + dH A;  the products dA = dH^T X and dB = dY^T Hs are appended to `tn`, which
+// the caller launches once per layer (dY, dH, X and Hs must stay untouched until then).
+static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf16_t* X, int T, bf16_t* dX,
+                           GemmTNGroup& tn) {
     tl_model* m = L->model;
     hipStream_t s = m->stream;
     const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
     const LayerOff& o = L->off[l];
     const bf16_t* Hs = L->save[l].hs[g];
-    bf16_t* dH = L->dHg[g];
-    HIPCHK(hipStreamWaitEvent(s, L->ev_done[g], 0));   // the previous layer's dA of this group still reads dH
+    bf16_t* dH = L->dHg[l & 1][g];
     GemmNT h;
     h.A = dY; h.lda = (long)G * dout; h.B = L->ST + o.BT[g]; h.ldb = dout; h.M = T; h.N = r; h.K = dout;
     h.alpha = L->s; h.C = dH; h.ldc = G * r;
     h.batch = G; h.bA = dout; h.bB = (long)r * dout; h.bC = r;
     h.partial = L->partial; h.partial_elems = L->partial_elems;
     HIPCHK(launch_gemm_nt(h, s));
-    HIPCHK(hipEventRecord(L->ev_ready[g], s));
     if (dX) {
         GemmNT x;
         x.A = dY; x.lda = (long)G * dout; x.B = m->layers[l].wt[g]; x.ldb = (long)G * dout; x.M = T; x.N = din;
@@ -489,25 +490,10 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         x.C = dX; x.ldc = din;
         HIPCHK(timed_gemm(L, x));
     }
-    hipStream_t s2 = L->side;
-    HIPCHK(hipStreamWaitEvent(s2, L->ev_ready[g], 0));
-    GemmTN a;
-    a.P = dH; a.ldp = G * r; a.Q = X; a.ldq = din; a.T = T; a.Mo = G * r; a.No = din;
-    a.C = L->G + o.A[g]; a.ldc = din;
-    a.partial = L->partial2; a.partial_elems = L->partial2_elems;
-    HIPCHK(launch_gemm_tn(a, s2));
-    GemmTN b;
-    b.P = dY; b.ldp = (long)G * dout; b.Q = Hs; b.ldq = G * r; b.T = T; b.Mo = dout; b.No = r;
-    b.C = L->G + o.B[g]; b.ldc = r;
-    b.batch = G; b.bP = dout; b.bQ = r; b.bC = (long)dout * r;
-    b.partial = L->partial2; b.partial_elems = L->partial2_elems;
-    HIPCHK(launch_gemm_tn(b, s2));
-    HIPCHK(hipEventRecord(L->ev_done[g], s2));
-    return TL_OK;
-}
-// main stream: do not overwrite the dY buffer of group g before the side stream has finished with it
-static tl_status wait_group(tl_lora* L, int g) {
-    HIPCHK(hipStreamWaitEvent(L->model->stream, L->ev_done[g], 0));
+    tn.add(dH, (long)G * r, G * r, X, din, din, L->G + o.A[g], din);                    // dA [G r, d_in]
+    for (int k = 0; k < G; ++k)                                                            // dB_k [d_out, r]
+        tn.add(dY + (long)k * dout, (long)G * dout, dout, Hs + (long)k * r, (long)G * r, r,
+               L->G + o.B[g] + (size_t)k * dout * r, r);
     return TL_OK;
 }
 
@@ -531,6 +517,15 @@ static tl_status layer_forward(tl_lora* L, int l, const float* h_in, float* h_ou
     return TL_OK;
 }
 
+// main stream: wait until the dA / dB launch of the given layer parity has finished
+static tl_status wait_tn(tl_lora* L, int par) {
+    if (L->tn_pending[par]) {
+        HIPCHK(hipStreamWaitEvent(L->model->stream, L->ev_done[par], 0));
+        L->tn_pending[par] = false;
+    }
+    return TL_OK;
+}
+
 // dh_out (fp32) and its bf16 copy dh_out_bf -> dh_in (fp32) and, if dh_in_bf != null, its bf16 copy
 static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const float* dh_out, const bf16_t* dh_out_bf,
                                 float* dh_in, bf16_t* dh_in_bf, int T) {
@@ -540,26 +535,35 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     const int d = c.d_model, f = c.d_ffn;
     LayerSave& sv = L->save[l];
     const LayerW& W = m->layers[l];
-    TLCHK(group_bwd(L, l, G_DOWN, dh_out_bf, sv.act, T, L->d_act));
-    TLCHK(wait_group(L, G_GU));      // dB of gate|up (previous layer) reads dgu
+    GemmTNGroup tn;
+    tn.T = T;
+    const int par = l & 1;
+    TLCHK(group_bwd(L, l, G_DOWN, dh_out_bf, sv.act, T, L->d_act, tn));
+    // the dA / dB launch of the layer above still reads dgu, dhmid_bf, dqkv (and the other parity's dH): everything
+    // below this point overwrites them
+    TLCHK(wait_tn(L, par ^ 1));
     HIPCHK(launch_swiglu_bwd(L->d_act, sv.gu, T, f, L->dgu, s));
-    TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx));
-    TLCHK(wait_group(L, G_O));       // dB of o (previous layer) reads dhmid_bf
+    TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx, tn));
     HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s));
-    TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o));
-    TLCHK(wait_group(L, G_QKV));     // dB of q|k|v (previous layer) reads dqkv
+    TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o, tn));
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
                                 c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, s));
     HIPCHK(launch_rope(L->dqkv, 3L * d, T, 2 * c.n_heads, c.d_head, c.rope_base, 0, -1, m->rope, s));
-    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx));
-    TLCHK(wait_group(L, G_DOWN));    // dB of down (this layer) reads the incoming gradient, which dh_in_bf may alias
+    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx, tn));
+    // all eleven dA / dB products of the layer in one launch on the side stream
+    if (tn.n > TN_GROUP_MAX) return fail(TL_ERR_ARG, "too many products for one grouped launch");
+    HIPCHK(hipEventRecord(L->ev_ready[par], s));
+    HIPCHK(hipStreamWaitEvent(L->side, L->ev_ready[par], 0));
+    HIPCHK(launch_gemm_tn_grouped(tn, L->side));
+    HIPCHK(hipEventRecord(L->ev_done[par], L->side));
+    L->tn_pending[par] = true;
+    // dh_in_bf must not be the buffer dh_out_bf (dB of the down projection is still reading it): callers alternate
     HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s));
     return TL_OK;
 }
 
 static tl_status optimizer_step(tl_lora* L, float lr, size_t off, size_t n) {
     hipStream_t s = L->model->stream;
-    for (int g = 0; g < N_GROUPS; ++g) TLCHK(wait_group(L, g));   // every dA, dB is in the gradient arena
     HIPCHK(launch_adamw(L->P + off, L->G + off, L->M + off, L->V + off, L->S + off, n, (long)(L->step + 1), lr,
                         L->cfg.beta1, L->cfg.beta2, L->cfg.eps, L->cfg.weight_decay, s));
     TLCHK(refresh_transposed(L));
@@ -642,10 +646,11 @@ extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t 
     dh.A = L->dlogits; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T; dh.N = d; dh.K = V;
     dh.C = L->dhf; dh.ldc = d;
     HIPCHK(timed_gemm(L, dh));
-    HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf, s));
+    HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf[nl & 1], s));
     for (int l = nl - 1; l >= 0; --l)
-        TLCHK(layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf, L->dhs[l], L->dh_bf, T));
-    for (int g = 0; g < N_GROUPS; ++g) TLCHK(wait_group(L, g));
+        TLCHK(layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf[(l + 1) & 1], L->dhs[l], L->dh_bf[l & 1], T));
+    TLCHK(wait_tn(L, 0));
+    TLCHK(wait_tn(L, 1));
     L->have_grads = true;
     TLCHK(optimizer_step(L, lr, 0, L->n_params));
     HIPCHK(hipStreamSynchronize(s));
@@ -665,9 +670,10 @@ extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in,
     if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
     hipStream_t s = L->model->stream;
     TLCHK(layer_forward(L, layer, h_in, h_out, n_tokens));
-    HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf, (size_t)n_tokens * c.d_model, s));
-    TLCHK(layer_backward(L, layer, h_in, dh_out, L->dh_bf, dh_in, nullptr, n_tokens));
-    for (int g = 0; g < N_GROUPS; ++g) TLCHK(wait_group(L, g));
+    HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf[0], (size_t)n_tokens * c.d_model, s));
+    TLCHK(layer_backward(L, layer, h_in, dh_out, L->dh_bf[0], dh_in, nullptr, n_tokens));
+    TLCHK(wait_tn(L, 0));
+    TLCHK(wait_tn(L, 1));
     L->have_grads = true;
     L->last_tokens = n_tokens;
     if (apply_adamw) {
