@@ -515,29 +515,45 @@ static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     if (e != hipSuccess) return e;
     kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n);
     if (SPLITK) {
-        const long n = (long)g.M * g.N * g.batch;
+        const long n = (long)g.M * (g.N >> 2) * g.batch;
         splitk_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, n_split);
     }
     return hipGetLastError();
 }
 
-// sum the split-K partials in a fixed order (deterministic), scale, add residual, convert
+// sum the split-K partials in a fixed order (deterministic), scale, add residual, convert.  One thread owns four
+// consecutive columns; the partials are fetched eight splits at a time before they are added, so that the loads
+// of a batch are all in flight together instead of one L2 round trip per split.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmNT p, int split_k) {
     const long mn = (long)p.M * p.N;
+    const int n4 = p.N >> 2;                      // N % 4 == 0 (checked by the launcher)
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= mn * p.batch) return;
-    const int z = (int)(idx / mn);
-    const long r = idx % mn;
-    const int row = (int)(r / p.N), col = (int)(r % p.N);
-    float s = 0.f;
-    for (int k = 0; k < split_k; ++k) s += p.partial[((long)z * split_k + k) * mn + r];
+    if (idx >= (long)p.M * n4 * p.batch) return;
+    const int z = (int)(idx / ((long)p.M * n4));
+    const long q = idx % ((long)p.M * n4);
+    const int row = (int)(q / n4), col = (int)(q % n4) * 4;
+    const float* src = p.partial + (long)z * split_k * mn + (long)row * p.N + col;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    int k = 0;
+    for (; k + 8 <= split_k; k += 8) {
+        float4 t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) t[j] = *(const float4*)(src + (long)(k + j) * mn);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { s.x += t[j].x; s.y += t[j].y; s.z += t[j].z; s.w += t[j].w; }
+    }
+    for (; k < split_k; ++k) {
+        const float4 t = *(const float4*)(src + (long)k * mn);
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
     const long off = (long)z * p.bC + (long)row * p.ldc + col;
-    float val = p.alpha * s;
+    const float v[4] = {p.alpha * s.x, p.alpha * s.y, p.alpha * s.z, p.alpha * s.w};
     if (p.c_f32) {
-        if (p.R) val += p.R[off];
-        ((float*)p.C)[off] = val;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ((float*)p.C)[off + e] = v[e] + (p.R ? p.R[off + e] : 0.f);
     } else {
-        ((bf16_t*)p.C)[off] = f32_to_bf16(val);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ((bf16_t*)p.C)[off + e] = f32_to_bf16(v[e]);
     }
 }
 
@@ -552,7 +568,7 @@ static hipError_t run_nt(const GemmNT& g, int split_k, hipStream_t s) {
         e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         kern<<<grid, 256, lds, s>>>(g, tiles_m, tiles_n, split_k);
-        const long n = (long)g.M * g.N * g.batch;
+        const long n = (long)g.M * (g.N >> 2) * g.batch;
         splitk_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, split_k);
     } else {
         auto kern = gemm_nt_kernel<BM, BN, WM, WN, false>;
@@ -658,6 +674,7 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     }
     if (split > 1 && (!g.partial || (size_t)split * g.M * g.N * g.batch > g.partial_elems)) return hipErrorInvalidValue;
     if (split > nk) split = nk > 0 ? nk : 1;
+    if (g.N & 3) split = 1;   // the reduce kernel works on groups of four columns
     if (dl_small) {
         if (split > 1) return run_nt_dl<64, 64, 2, 2, 4, 0, 64, true>(g, s, split);
         if (split == 1) return run_nt_dl<64, 64, 2, 2, 4>(g, s);

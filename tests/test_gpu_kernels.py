@@ -71,6 +71,21 @@ def test_gemm_nt_bf16(api, H, M, N, K, K2):
     check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")   # bf16 products are exact; only fp32 summation order differs
 
 
+@pytest.mark.parametrize("M,N,K", [(1024, 64, 4096), (1000, 192, 1024), (333, 72, 512), (16, 8, 2048), (1024, 128, 11008)])
+def test_gemm_nt_skinny(api, H, M, N, K):
+    """Small-N, long-K products (the shape of the LoRA down-projections)."""
+    A, B = rnd(1, (M, K)), rnd(2, (N, K), 0.05)
+    ref = A.astype(np.float64) @ B.T.astype(np.float64)
+    Cd = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cd, alpha=0.25)
+    R = rnd(5, (M, N), 1.0, False)
+    Cf = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cf, alpha=1.0, R=H.to_dev_f32(R))
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(Cd), 0.25 * ref, BF16_TOL, "C bf16")
+    check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")
+
+
 @pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5", "6", "7", "8", "10", "11", "12", "13", "14", "15", "16", "21", "22", "23", "24", "25", "26", "27", "28", "29", "30"])
 @pytest.mark.parametrize("M,N,K,K2", [(1024, 2048, 256, 64), (1000, 2056, 128, 0), (520, 4104, 192, 128)])
 def test_gemm_nt_pipelined_tiles(api, H, monkeypatch, tile, M, N, K, K2):
