@@ -24,51 +24,53 @@ struct AttnCfg {
 
 // load a [64 rows][DH] tile (rows r0.., zero beyond T) into registers; NT = threads of the workgroup
 template <int DH, int NT>
-__device__ __forceinline__ void load_tile_regs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs) {
+__device__ __forceinline__ void load_tile_regs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs,
+                                               int tid = threadIdx.x) {
     constexpr int CH = DH / 8;  // chunks per row
 #pragma unroll
     for (int i = 0; i < 8 * DH / NT; ++i) {
-        const int c = threadIdx.x + NT * i, row = c / CH, ch = c % CH;
+        const int c = tid + NT * i, row = c / CH, ch = c % CH;
         regs[i] = (r0 + row < T) ? *(const uint4*)(base + (long)(r0 + row) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
     }
 }
 template <int DH, int NT>
-__device__ __forceinline__ void store_tile_normal(bf16_t* tile, const uint4* regs) {
+__device__ __forceinline__ void store_tile_normal(bf16_t* tile, const uint4* regs, int tid = threadIdx.x) {
     constexpr int CH = DH / 8;
 #pragma unroll
     for (int i = 0; i < 8 * DH / NT; ++i) {
-        const int c = threadIdx.x + NT * i, row = c / CH, ch = c % CH;
+        const int c = tid + NT * i, row = c / CH, ch = c % CH;
         *(uint4*)(tile + row * AttnCfg<DH>::LSK + ch * 8) = regs[i];
     }
 }
 // the same tile as row pairs for the transposing store: unit = (row pair, 8-column chunk)
 template <int DH, int NT>
-__device__ __forceinline__ void load_tile_pairs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs) {
+__device__ __forceinline__ void load_tile_pairs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs,
+                                                int tid = threadIdx.x) {
     constexpr int CH = DH / 8;
 #pragma unroll
     for (int i = 0; i < 4 * DH / NT; ++i) {
-        const int c = threadIdx.x + NT * i, rp = c / CH, ch = c % CH;
+        const int c = tid + NT * i, rp = c / CH, ch = c % CH;
         const int r = r0 + 2 * rp;
         regs[2 * i] = (r < T) ? *(const uint4*)(base + (long)r * ld + ch * 8) : make_uint4(0, 0, 0, 0);
         regs[2 * i + 1] = (r + 1 < T) ? *(const uint4*)(base + (long)(r + 1) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
     }
 }
 template <int DH, int NT>
-__device__ __forceinline__ void store_tile_transposed(bf16_t* tile, const uint4* regs) {
+__device__ __forceinline__ void store_tile_transposed(bf16_t* tile, const uint4* regs, int tid = threadIdx.x) {
     constexpr int CH = DH / 8;
 #pragma unroll
     for (int i = 0; i < 4 * DH / NT; ++i) {
-        const int c = threadIdx.x + NT * i, rp = c / CH, ch = c % CH;
+        const int c = tid + NT * i, rp = c / CH, ch = c % CH;
         store_transposed_pair(tile, ch * 8, 2 * rp, regs[2 * i], regs[2 * i + 1]);
     }
 }
 // registers loaded by load_tile_pairs stored as an ordinary [row][d] tile
 template <int DH, int NT>
-__device__ __forceinline__ void store_pairs_normal(bf16_t* tile, const uint4* regs) {
+__device__ __forceinline__ void store_pairs_normal(bf16_t* tile, const uint4* regs, int tid = threadIdx.x) {
     constexpr int CH = DH / 8;
 #pragma unroll
     for (int i = 0; i < 4 * DH / NT; ++i) {
-        const int c = threadIdx.x + NT * i, rp = c / CH, ch = c % CH;
+        const int c = tid + NT * i, rp = c / CH, ch = c % CH;
         *(uint4*)(tile + (2 * rp) * AttnCfg<DH>::LSK + ch * 8) = regs[2 * i];
         *(uint4*)(tile + (2 * rp + 1) * AttnCfg<DH>::LSK + ch * 8) = regs[2 * i + 1];
     }
@@ -90,18 +92,26 @@ __device__ __forceinline__ void write_rows_from_dT(bf16_t* __restrict__ dst, con
 }
 
 // ======================================================================== forward
-// NW waves per workgroup, 32 queries per wave.  K and V tiles of 64 keys are fetched one tile ahead into
-// registers (the loads fly during the MFMAs of the current tile) and parked in LDS between two barriers.
-template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                           const bf16_t* __restrict__ v, long ldq, int T,
-                                                           bf16_t* __restrict__ o, long ldo, float* __restrict__ lse,
-                                                           float scale_log2e) {
+// KG key groups of NW waves each; a wave owns 32 queries, and the key tiles (64 keys) of the causal range are dealt
+// out to the key groups in turn (group kg takes tiles kg, kg + KG, ..).  Every group keeps its own running max, row
+// sum and output accumulator over its tiles and the groups are merged once at the end through LDS (the usual
+// two-state softmax merge).  With KG = 2 a SIMD runs two waves, so one wave's softmax arithmetic overlaps the other's
+// MFMAs; at T = 1024 with 32 heads there are otherwise only as many 32-query waves as the chip has SIMDs.
+// K and V tiles are fetched one tile ahead into registers (the loads fly during the MFMAs of the current tile) and
+// parked in the group's LDS buffers between two barriers.
+template <int DH, int NW, int KG>
+__global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                                const bf16_t* __restrict__ v, long ldq, int T,
+                                                                bf16_t* __restrict__ o, long ldo, float* __restrict__ lse,
+                                                                float scale_log2e) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
-    __shared__ __align__(16) bf16_t sK[64 * C::LSK];
-    __shared__ __align__(16) bf16_t sVt[DH * LST];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    constexpr int GROUP_ELEMS = 64 * C::LSK + DH * LST;          // bf16 elements of one group's K and V^T tiles
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / NT);
+    const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
+    bf16_t* sVt = sK + 64 * C::LSK;
     const int qb = gridDim.x - 1 - blockIdx.x;  // heaviest (latest) query blocks first
     const int head = blockIdx.y;
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
@@ -122,18 +132,19 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const bf16_t* __restr
 
     const int kend = min(q0 + QB, T);
     const int n_tiles = (kend + 63) / 64;
+    const int n_iter = (n_tiles + KG - 1) / KG;   // a group's surplus tile lies wholly in the future and is skipped
     uint4 rk[8 * DH / NT], rv[8 * DH / NT];
-    load_tile_regs<DH, NT>(kh, ldq, 0, T, rk);
-    load_tile_pairs<DH, NT>(vh, ldq, 0, T, rv);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int u0 = tile * 64;
+    load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
+    load_tile_pairs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
+    for (int it = 0; it < n_iter; ++it) {
+        const int u0 = (it * KG + kg) * 64;
         __syncthreads();
-        store_tile_normal<DH, NT>(sK, rk);
-        store_tile_transposed<DH, NT>(sVt, rv);
+        store_tile_normal<DH, NT>(sK, rk, tid);
+        store_tile_transposed<DH, NT>(sVt, rv, tid);
         __syncthreads();
-        if (tile + 1 < n_tiles) {
-            load_tile_regs<DH, NT>(kh, ldq, u0 + 64, T, rk);
-            load_tile_pairs<DH, NT>(vh, ldq, u0 + 64, T, rv);
+        if (it + 1 < n_iter) {
+            load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
+            load_tile_pairs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
         }
         if (u0 > tq0 + 31) continue;  // wave-uniform: every key of this tile is in the future
         // both 32-key halves of the tile at once: two independent MFMA chains, one softmax update
@@ -191,6 +202,31 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const bf16_t* __restr
                     oacc[dt] = mfma32(a, b, oacc[dt]);
                 }
             }
+    }
+    if constexpr (KG > 1) {
+        // merge the key groups into group 0: values of thread `tid` are kept NT apart (no bank conflicts)
+        static_assert(KG == 2, "two key groups");
+        float* mg = (float*)smem_raw;
+        __syncthreads();                            // every group is done with its K / V tiles
+        if (kg == 1) {
+#pragma unroll
+            for (int dt = 0; dt < C::ND; ++dt)
+#pragma unroll
+                for (int vv = 0; vv < 16; ++vv) mg[(dt * 16 + vv) * NT + tid] = oacc[dt][vv];
+            mg[(C::ND * 16) * NT + tid] = m;
+            mg[(C::ND * 16 + 1) * NT + tid] = lpart;
+        }
+        __syncthreads();
+        if (kg == 1) return;
+        const float m1 = mg[(C::ND * 16) * NT + tid], l1 = mg[(C::ND * 16 + 1) * NT + tid];
+        const float mt = fmaxf(m, m1);
+        const float a0 = fast_exp2(m - mt), a1 = fast_exp2(m1 - mt);
+#pragma unroll
+        for (int dt = 0; dt < C::ND; ++dt)
+#pragma unroll
+            for (int vv = 0; vv < 16; ++vv) oacc[dt][vv] = oacc[dt][vv] * a0 + mg[(dt * 16 + vv) * NT + tid] * a1;
+        lpart = lpart * a0 + l1 * a1;
+        m = mt;
     }
     const float ltot = lpart + __shfl_xor(lpart, 32, 64);
     if (t_abs < T) {
@@ -435,17 +471,35 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
 #define ATTN_NW 4
 #endif
 
+// key groups of the forward kernel (see attn_fwd_kernel)
+#ifndef ATTN_KG
+#define ATTN_KG 2
+#endif
+
+template <int DH, int NW, int KG>
+static hipError_t run_fwd(dim3 grid, const bf16_t* q, const bf16_t* k, const bf16_t* v, long ldq, int T, bf16_t* o,
+                          long ldo, float* lse, float sl2, hipStream_t s) {
+    using C = AttnCfg<DH>;
+    size_t lds = (size_t)KG * (64 * C::LSK + DH * LST) * sizeof(bf16_t);
+    const size_t merge = KG > 1 ? (size_t)NW * 64 * (C::ND * 16 + 2) * sizeof(float) : 0;
+    if (merge > lds) lds = merge;
+    auto kern = attn_fwd_kernel<DH, NW, KG>;
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
+    return hipGetLastError();
+}
+
 hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ldq, int T, int n_heads,
                                 int d_head, bf16_t* o, long ldo, float* lse, hipStream_t s) {
     if (T <= 0 || n_heads <= 0) return hipSuccess;
     if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
     const float sl2 = (1.f / sqrtf((float)d_head)) * 1.4426950408889634f;
-    constexpr int NW = ATTN_NW;
+    constexpr int NW = ATTN_NW, KG = ATTN_KG;
     dim3 grid(cdiv(T, NW * 32), n_heads);
-    if (d_head == 128) attn_fwd_kernel<128, NW><<<grid, NW * 64, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
-    else if (d_head == 64) attn_fwd_kernel<64, NW><<<grid, NW * 64, 0, s>>>(q, k, v, ldq, T, o, ldo, lse, sl2);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
+    if (d_head == 128) return run_fwd<128, NW, KG>(grid, q, k, v, ldq, T, o, ldo, lse, sl2, s);
+    if (d_head == 64) return run_fwd<64, NW, KG>(grid, q, k, v, ldq, T, o, ldo, lse, sl2, s);
+    return hipErrorInvalidValue;
 }
 
 template <int DH>

@@ -31,46 +31,65 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restric
 }
 
 // dh_out = dres + rho (g*dy) - h rho^3 mean(h g dy); gain is frozen, so no gain gradient.
+// One workgroup per row.  With d <= 256 * 4 * NV the row is read once and kept in registers between the two
+// reductions and the output pass (NV float4 per thread); wider rows take the two-pass form (NV = 0).
+template <int NV>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restrict__ dy, const float* __restrict__ h,
                                                           const float* __restrict__ g, const float* __restrict__ dres,
                                                           int d, float eps, float* __restrict__ dh_out,
                                                           bf16_t* __restrict__ dh_bf) {
-    __shared__ float red[16];
+    __shared__ float red[32];
     const long row = blockIdx.x;
     const float4* hp = (const float4*)(h + row * d);
     const float4* gp = (const float4*)g;
     const uint2* dp = (const uint2*)(dy + row * d);
-    const int n4 = d >> 2;
-    float ss = 0.f, dot = 0.f;
-    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-        float4 x = hp[i];
-        float4 w = gp[i];
-        uint2 r = dp[i];
-        float d0 = bf16_to_f32(r.x & 0xffff), d1 = bf16_to_f32(r.x >> 16);
-        float d2 = bf16_to_f32(r.y & 0xffff), d3 = bf16_to_f32(r.y >> 16);
-        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-        dot += x.x * w.x * d0 + x.y * w.y * d1 + x.z * w.z * d2 + x.w * w.w * d3;
-    }
-    ss = block_sum(ss, red);
-    dot = block_sum(dot, red);
-    const float rho = rsqrtf(ss / (float)d + eps);
-    const float c = rho * rho * rho * (dot / (float)d);
     const float4* rp = dres ? (const float4*)(dres + row * d) : nullptr;
     float4* op = (float4*)(dh_out + row * d);
     uint2* bp = dh_bf ? (uint2*)(dh_bf + row * d) : nullptr;
-    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-        float4 x = hp[i];
-        float4 w = gp[i];
-        uint2 r = dp[i];
-        float d0 = bf16_to_f32(r.x & 0xffff), d1 = bf16_to_f32(r.x >> 16);
-        float d2 = bf16_to_f32(r.y & 0xffff), d3 = bf16_to_f32(r.y >> 16);
-        float4 o;
-        o.x = rho * w.x * d0 - x.x * c;
-        o.y = rho * w.y * d1 - x.y * c;
-        o.z = rho * w.z * d2 - x.z * c;
-        o.w = rho * w.w * d3 - x.w * c;
+    const int n4 = d >> 2;
+    float ss = 0.f, dot = 0.f;
+    constexpr int NR = NV > 0 ? NV : 1;
+    float4 xs[NR], gd[NR];   // h and g * dy of this thread's chunks
+    if constexpr (NV > 0) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + 256 * j;
+            xs[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            gd[j] = xs[j];
+            if (i < n4) {
+                const float4 x = hp[i], w = gp[i];
+                const uint2 r = dp[i];
+                xs[j] = x;
+                gd[j] = make_float4(w.x * bf16_to_f32(r.x & 0xffff), w.y * bf16_to_f32(r.x >> 16),
+                                    w.z * bf16_to_f32(r.y & 0xffff), w.w * bf16_to_f32(r.y >> 16));
+                ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+                dot += x.x * gd[j].x + x.y * gd[j].y + x.z * gd[j].z + x.w * gd[j].w;
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+            const float4 x = hp[i], w = gp[i];
+            const uint2 r = dp[i];
+            const float d0 = bf16_to_f32(r.x & 0xffff), d1 = bf16_to_f32(r.x >> 16);
+            const float d2 = bf16_to_f32(r.y & 0xffff), d3 = bf16_to_f32(r.y >> 16);
+            ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+            dot += x.x * w.x * d0 + x.y * w.y * d1 + x.z * w.z * d2 + x.w * w.w * d3;
+        }
+    }
+    // both sums through one pair of barriers
+    ss = wave_sum(ss);
+    dot = wave_sum(dot);
+    const int wv = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { red[wv] = ss; red[4 + wv] = dot; }
+    __syncthreads();
+    ss = (red[0] + red[1]) + (red[2] + red[3]);
+    dot = (red[4] + red[5]) + (red[6] + red[7]);
+    const float rho = rsqrtf(ss / (float)d + eps);
+    const float c = rho * rho * rho * (dot / (float)d);
+    auto emit = [&](int i, const float4& x, const float4& wd) {
+        float4 o = make_float4(rho * wd.x - x.x * c, rho * wd.y - x.y * c, rho * wd.z - x.z * c, rho * wd.w - x.w * c);
         if (rp) {
-            float4 q = rp[i];
+            const float4 q = rp[i];
             o.x += q.x; o.y += q.y; o.z += q.z; o.w += q.w;
         }
         op[i] = o;
@@ -79,6 +98,20 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
             b.x = pack_bf16x2(o.x, o.y);
             b.y = pack_bf16x2(o.z, o.w);
             bp[i] = b;
+        }
+    };
+    if constexpr (NV > 0) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + 256 * j;
+            if (i < n4) emit(i, xs[j], gd[j]);
+        }
+    } else {
+        for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+            const float4 x = hp[i], w = gp[i];
+            const uint2 r = dp[i];
+            emit(i, x, make_float4(w.x * bf16_to_f32(r.x & 0xffff), w.y * bf16_to_f32(r.x >> 16),
+                                   w.z * bf16_to_f32(r.y & 0xffff), w.w * bf16_to_f32(r.y >> 16)));
         }
     }
 }
@@ -91,7 +124,9 @@ hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, floa
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
                               float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s) {
     if (T <= 0) return hipSuccess;
-    rmsnorm_bwd_kernel<<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
+    if (d <= 4096) rmsnorm_bwd_kernel<4><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
+    else if (d <= 8192) rmsnorm_bwd_kernel<8><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
+    else rmsnorm_bwd_kernel<0><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
     return hipGetLastError();
 }
 

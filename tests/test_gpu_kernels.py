@@ -129,7 +129,7 @@ def test_gemm_tn(api, H, T, Mo, No):
 
 
 # ------------------------------------------------------------------ RMSNorm
-@pytest.mark.parametrize("T,d", [(5, 64), (130, 1024), (33, 4096)])
+@pytest.mark.parametrize("T,d", [(5, 64), (130, 1024), (33, 4096), (7, 8192), (3, 12288)])
 def test_rmsnorm_fwd_bwd(api, H, T, d):
     h = rnd(1, (T, d), 2.0, False)
     g = 1.0 + 0.1 * rnd(2, (d,), 1.0, False)
