@@ -235,43 +235,44 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
     }
 }
 
-// ======================================================================== delta = rowsum(dO * O)
-__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
-                                                         long ldo, int T, int n_heads, int d_head,
-                                                         float* __restrict__ delta) {
-    const int t = blockIdx.x;
-    const int sub = d_head >> 3;  // lanes per head
-    const int chunks = n_heads * sub;
-    for (int c = threadIdx.x; c < ((chunks + 63) & ~63); c += blockDim.x) {
-        float s = 0.f;
-        if (c < chunks) {
-            uint4 a = *(const uint4*)(o + (long)t * ldo + c * 8);
-            uint4 b = *(const uint4*)(d_o + (long)t * ldo + c * 8);
-            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+// Rotate the (d, d + DH/2) pairs of a transposed fragment set X^T[d][row] (lane = row at position `pos`) by the RoPE
+// angle of that position, sign = -1 for the inverse rotation (the adjoint of the forward rotation): both members of a
+// pair sit in the same lane and register index of fragments dt and dt + ND/2, so nothing crosses lanes.
+template <int DH>
+__device__ __forceinline__ void rope_rotate_dT(f32x16_t* acc, const float2* __restrict__ table, int pos, float sign, int g) {
+    constexpr int ND = DH / 32, HALF = DH / 2;
+    const float2* row = table + (long)pos * HALF;
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                s += bf16_to_f32(aw[e] & 0xffff) * bf16_to_f32(bw[e] & 0xffff) +
-                     bf16_to_f32(aw[e] >> 16) * bf16_to_f32(bw[e] >> 16);
+    for (int dt = 0; dt < ND / 2; ++dt)
+#pragma unroll
+        for (int vv = 0; vv < 16; ++vv) {
+            const int i = dt * 32 + 8 * (vv >> 2) + 4 * g + (vv & 3);
+            const float2 cs = row[i];
+            const float a = acc[dt][vv], b = acc[dt + ND / 2][vv], sn = cs.y * sign;
+            acc[dt][vv] = a * cs.x - b * sn;
+            acc[dt + ND / 2][vv] = b * cs.x + a * sn;
         }
-        for (int off = sub >> 1; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (c < chunks && (c % sub) == 0) delta[(long)(c / sub) * T + t] = s;
-    }
 }
 
 // ======================================================================== backward: dQ
-template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                              const bf16_t* __restrict__ v,
-                                                              const bf16_t* __restrict__ d_o,
-                                                              const float* __restrict__ lse,
-                                                              const float* __restrict__ delta, long ldq, long ldo,
-                                                              int T, bf16_t* __restrict__ dq, float scale) {
+// Same shape as the forward kernel: KG key groups share the causal range tile by tile and their dQ partial sums are
+// added through LDS at the end.  delta[t] = dO[t] . O[t] is formed here from the rows the wave already holds (and
+// written out for the dK/dV kernel, which runs afterwards); with a RoPE table the gradient is rotated back before it
+// is stored, so no separate pass over dq is needed.
+template <int DH, int NW, int KG>
+__global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, float* __restrict__ delta, long ldq, long ldo, int T,
+    bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
-    __shared__ __align__(16) bf16_t sK[64 * C::LSK];
-    __shared__ __align__(16) bf16_t sV[64 * C::LSK];
-    __shared__ __align__(16) bf16_t sKt[DH * LST];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    constexpr int GROUP_ELEMS = 2 * 64 * C::LSK + DH * LST;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / NT);
+    const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
+    bf16_t* sV = sK + 64 * C::LSK;
+    bf16_t* sKt = sV + 64 * C::LSK;
     const int qb = gridDim.x - 1 - blockIdx.x;
     const int head = blockIdx.y;
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
@@ -280,36 +281,45 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const bf16_t* __re
     const bf16_t* kh = k + (long)head * DH;
     const bf16_t* vh = v + (long)head * DH;
     const bf16_t* doh = d_o + (long)head * DH;
+    const bf16_t* oh = o + (long)head * DH;
 
     bf16x8_t qf[C::NKS], dof[C::NKS];
+    float dlt = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::NKS; ++ks) {
         uint4 r = (t_abs < T) ? *(const uint4*)(qh + (long)t_abs * ldq + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
         qf[ks] = *(bf16x8_t*)&r;
         uint4 r2 = (t_abs < T) ? *(const uint4*)(doh + (long)t_abs * ldo + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
         dof[ks] = *(bf16x8_t*)&r2;
+        const uint4 r3 = (t_abs < T) ? *(const uint4*)(oh + (long)t_abs * ldo + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
+        const uint32_t aw[4] = {r2.x, r2.y, r2.z, r2.w}, bw[4] = {r3.x, r3.y, r3.z, r3.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            dlt += bf16_to_f32(aw[e] & 0xffff) * bf16_to_f32(bw[e] & 0xffff) + bf16_to_f32(aw[e] >> 16) * bf16_to_f32(bw[e] >> 16);
     }
+    dlt += __shfl_xor(dlt, 32, 64);   // the partner lane holds the other eight of every sixteen columns
+    if (kg == 0 && g == 0 && t_abs < T) delta[(long)head * T + t_abs] = dlt;
     const float lse2 = (t_abs < T) ? lse[(long)head * T + t_abs] * 1.4426950408889634f : 1.0e30f;
-    const float dlt = (t_abs < T) ? delta[(long)head * T + t_abs] : 0.f;
     f32x16_t acc[C::ND];
 #pragma unroll
     for (int dt = 0; dt < C::ND; ++dt) acc[dt] = zero16();
 
     const int kend = min(q0 + QB, T);
     const int n_tiles = (kend + 63) / 64;
+    const int n_iter = (n_tiles + KG - 1) / KG;
     uint4 rk[8 * DH / NT], rv[8 * DH / NT];
-    load_tile_pairs<DH, NT>(kh, ldq, 0, T, rk);
-    load_tile_regs<DH, NT>(vh, ldq, 0, T, rv);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int u0 = tile * 64;
+    load_tile_pairs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
+    load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
+    for (int it = 0; it < n_iter; ++it) {
+        const int u0 = (it * KG + kg) * 64;
         __syncthreads();
-        store_pairs_normal<DH, NT>(sK, rk);
-        store_tile_transposed<DH, NT>(sKt, rk);
-        store_tile_normal<DH, NT>(sV, rv);
+        store_pairs_normal<DH, NT>(sK, rk, tid);
+        store_tile_transposed<DH, NT>(sKt, rk, tid);
+        store_tile_normal<DH, NT>(sV, rv, tid);
         __syncthreads();
-        if (tile + 1 < n_tiles) {
-            load_tile_pairs<DH, NT>(kh, ldq, u0 + 64, T, rk);
-            load_tile_regs<DH, NT>(vh, ldq, u0 + 64, T, rv);
+        if (it + 1 < n_iter) {
+            load_tile_pairs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
+            load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
         }
         if (u0 > tq0 + 31) continue;
         f32x16_t s0 = zero16(), s1 = zero16(), dp0 = zero16(), dp1 = zero16();
@@ -345,7 +355,27 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const bf16_t* __re
                 }
             }
     }
-    if (t_abs < T) write_rows_from_dT<DH>(dq + (long)t_abs * ldq + (long)head * DH, acc, scale, g);
+    if constexpr (KG > 1) {
+        static_assert(KG == 2, "two key groups");
+        float* mg = (float*)smem_raw;
+        __syncthreads();
+        if (kg == 1) {
+#pragma unroll
+            for (int dt = 0; dt < C::ND; ++dt)
+#pragma unroll
+                for (int vv = 0; vv < 16; ++vv) mg[(dt * 16 + vv) * NT + tid] = acc[dt][vv];
+        }
+        __syncthreads();
+        if (kg == 1) return;
+#pragma unroll
+        for (int dt = 0; dt < C::ND; ++dt)
+#pragma unroll
+            for (int vv = 0; vv < 16; ++vv) acc[dt][vv] += mg[(dt * 16 + vv) * NT + tid];
+    }
+    if (t_abs < T) {
+        if (rope) rope_rotate_dT<DH>(acc, rope, t_abs, -1.f, g);
+        write_rows_from_dT<DH>(dq + (long)t_abs * ldq + (long)head * DH, acc, scale, g);
+    }
 }
 
 // ======================================================================== backward: dK, dV
@@ -357,7 +387,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ delta, long ldq, long ldo,
                                                                int T, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
-                                                               float scale) {
+                                                               float scale, const float2* __restrict__ rope) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, KB = NW * 32;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -459,6 +489,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
         }
     }
     if (u_abs < T) {
+        if (rope) rope_rotate_dT<DH>(dkacc, rope, u_abs, -1.f, g);   // linear, so it commutes with the scale below
         write_rows_from_dT<DH>(dk + (long)u_abs * ldq + (long)head * DH, dkacc, scale, g);
         write_rows_from_dT<DH>(dv + (long)u_abs * ldq + (long)head * DH, dvacc, 1.f, g);
     }
@@ -503,29 +534,39 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
 }
 
 template <int DH>
-static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* d_o, const float* lse,
-                          const float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
-                          bf16_t* dv, hipStream_t s) {
+static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
+                          const float* lse, float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
+                          bf16_t* dv, const float2* rope, hipStream_t s) {
     using C = AttnCfg<DH>;
-    constexpr int NW = ATTN_NW;
+    constexpr int NW = ATTN_NW, KG = ATTN_KG;
     const float scale = 1.f / sqrtf((float)DH);
     dim3 grid(cdiv(T, NW * 32), n_heads);
-    attn_bwd_dq_kernel<DH, NW><<<grid, NW * 64, 0, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, scale);
+    {
+        size_t lds = (size_t)KG * (2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
+        const size_t merge = KG > 1 ? (size_t)NW * 64 * (C::ND * 16) * sizeof(float) : 0;
+        if (merge > lds) lds = merge;
+        auto kern = attn_bwd_dq_kernel<DH, NW, KG>;
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, scale, rope);
+    }
     const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
     auto kern = attn_bwd_dkv_kernel<DH, NW>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, NW * 64, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale);
+    kern<<<grid, NW * 64, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope);
     return hipGetLastError();
 }
 
+// delta (fp32 [n_heads, T]) is written by the dQ kernel and read by the dK/dV kernel.  rope != null: q and k were
+// rotated by RoPE (table of (cos, sin) per position and pair, positions 0 .. T-1) before the forward pass, and dq, dk
+// come out as gradients with respect to the UNROTATED projections.
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
-                                bf16_t* dk, bf16_t* dv, float* delta, hipStream_t s) {
+                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s) {
     if (T <= 0 || n_heads <= 0) return hipSuccess;
     if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
-    attn_delta_kernel<<<T, 256, 0, s>>>(o, d_o, ldo, T, n_heads, d_head, delta);
-    if (d_head == 128) return run_bwd<128>(q, k, v, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, s);
-    if (d_head == 64) return run_bwd<64>(q, k, v, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, s);
+    if (d_head == 128) return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s);
+    if (d_head == 64) return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s);
     return hipErrorInvalidValue;
 }

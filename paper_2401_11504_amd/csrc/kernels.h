@@ -65,7 +65,7 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
                                 int d_head, bf16_t* o, long ldo, float* lse, hipStream_t s);
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
-                                bf16_t* dk, bf16_t* dv, float* delta, hipStream_t s);
+                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise / reductions (elementwise.hip)
 hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s);

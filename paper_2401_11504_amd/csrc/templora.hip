@@ -547,8 +547,7 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s));
     TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o, tn));
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
-                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, s));
-    HIPCHK(launch_rope(L->dqkv, 3L * d, T, 2 * c.n_heads, c.d_head, c.rope_base, 0, -1, m->rope, s));
+                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s));   // dq, dk rotated back inside
     TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx, tn));
     // all eleven dA / dB products of the layer in one launch on the side stream
     if (tn.n > TN_GROUP_MAX) return fail(TL_ERR_ARG, "too many products for one grouped launch");
@@ -889,7 +888,7 @@ extern "C" tl_status tl_k_attention_bwd(const uint16_t* q, const uint16_t* k, co
                                         float* delta, void* hip_stream) {
     KARGS_OK(q && k && v && o && d_o && lse && dq && dk && dv && delta && T >= 0 && n_heads > 0 &&
                  (d_head == 64 || d_head == 128), "tl_k_attention_bwd");
-    HIPCHK(launch_attention_bwd(q, k, v, o, d_o, lse, ldq, ldo, T, n_heads, d_head, dq, dk, dv, delta,
+    HIPCHK(launch_attention_bwd(q, k, v, o, d_o, lse, ldq, ldo, T, n_heads, d_head, dq, dk, dv, delta, nullptr,
                                 (hipStream_t)hip_stream));
     return TL_OK;
 }
