@@ -59,4 +59,18 @@ __device__ __forceinline__ float block_max(float x, float* red) {
     return t;
 }
 
+// eight bf16 in a 16-byte word <-> eight floats
+__device__ __forceinline__ void unpack8(uint4 r, float* f) {
+    f[0] = bf16_to_f32(r.x & 0xffff); f[1] = bf16_to_f32(r.x >> 16);
+    f[2] = bf16_to_f32(r.y & 0xffff); f[3] = bf16_to_f32(r.y >> 16);
+    f[4] = bf16_to_f32(r.z & 0xffff); f[5] = bf16_to_f32(r.z >> 16);
+    f[6] = bf16_to_f32(r.w & 0xffff); f[7] = bf16_to_f32(r.w >> 16);
+}
+__device__ __forceinline__ uint4 pack8(const float* f) {
+    uint4 r;
+    r.x = pack_bf16x2(f[0], f[1]); r.y = pack_bf16x2(f[2], f[3]);
+    r.z = pack_bf16x2(f[4], f[5]); r.w = pack_bf16x2(f[6], f[7]);
+    return r;
+}
+
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }

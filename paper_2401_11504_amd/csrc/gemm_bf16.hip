@@ -164,7 +164,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, bool PIPE = false>
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, int PIPE = 0>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
     constexpr int NT = WM * WN * 64;
     constexpr int ROWS = BM + BN;
@@ -246,34 +246,41 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     for (int ks = 0; ks < KS; ++ks) coff[ks] = (((2 * ks + g) ^ ((l32 / RP) % CPRW)) << 4);
     const int a_row = (wm * TM + l32) * ROWB, b_row = (BM + wn * TN + l32) * ROWB;
 
-    if constexpr (PIPE) {
+    if constexpr (PIPE != 0) {
         // One wave per SIMD: the matrix pipe only stays busy if the wave never waits, so inside the steady-state
-        // loop nothing is issued in bursts.  Tile kt+STAGES-1 is fetched during iteration kt, one 16-byte
-        // global->LDS load after every fourth MFMA (a burst of L loads would hold the wave at the address
-        // unit for hundreds of clocks), and the fragments of the next k-step are read one per MFMA slot while
-        // the current k-step's MFMAs run.  The loop body has no branches; the last STAGES-1 tiles, which
-        // fetch nothing, run in a peeled tail.  The host only picks this path for nk >= STAGES.
-        static_assert(STAGES >= 3 && FM * FN >= FM + FN && KS * FM * FN >= L, "slots");
-        constexpr int NMF = FM * FN, NRD = FM + FN, NSLOT = KS * NMF;
-        // load j of a tile goes into slot j * NSLOT / L; LBH = loads issued before the hand-over (the last k-step)
-        constexpr int LBH = ((KS - 1) * NMF * L + NSLOT - 1) / NSLOT;
+        // loop nothing is issued in bursts.  Tile kt+STAGES-1 is fetched during iteration kt, its 16-byte
+        // global->LDS loads spread evenly between the MFMAs (a burst of L loads would hold the wave at the address
+        // unit for hundreds of clocks), and the fragments of the k-step PD steps ahead are read one per MFMA slot
+        // while the current k-step's MFMAs run (PD = PIPE; with 64x64 wave tiles a k-step is only 128 clocks of
+        // MFMA, less than an LDS round trip under load, hence PD = 2 there).  The loop body has no branches; the
+        // last STAGES-1 tiles, which fetch nothing, run in a peeled tail.  The host only picks this path for
+        // nk >= STAGES.
+        constexpr int PD = PIPE, NSETS = PD == 1 ? 2 : 4, HS = KS - PD;   // hand-over happens before k-step HS
+        static_assert(PD == 1 || (PD == 2 && KS == 4), "prefetch distance");
+        static_assert(STAGES >= 3 && KS * FM * FN >= L && KS % NSETS == 0, "slots");
+        constexpr int NMF = FM * FN, NRD = FM + FN, NSLOT = KS * NMF, RPS = (NRD + NMF - 1) / NMF;
+        // load j of a tile goes into slot j * NSLOT / L; LBH = loads issued before the hand-over
+        constexpr int LBH = (HS * NMF * L + NSLOT - 1) / NSLOT;
         const unsigned char* a_ptr = smem + a_row;
         const unsigned char* b_ptr = smem + b_row;
-        bf16x8_t fa[2][FM], fb[2][FN];
-        // one k-step: NMF MFMAs on fragment set `cur`; the slot after MFMA e carries the next fragment read into
-        // set `nxt` (slots 0 .. NRD-1); the tile's L DMA loads are spread evenly over its KS * NMF slots
+        bf16x8_t fa[NSETS][FM], fb[NSETS][FN];
+        // one k-step: NMF MFMAs on fragment set ks % NSETS; the slot after MFMA e carries one fragment read of the
+        // k-step PD ahead (RPS per slot until all NRD are issued); the tile's L DMA loads are spread evenly over its KS * NMF slots
         auto kstep = [&](auto loads_c, unsigned ext, auto reads_c, int ks, size_t rd_stage, int rd_ks,
                          const bf16_t* pa, const bf16_t* pb, unsigned dst) {
             constexpr bool LOADS = decltype(loads_c)::value, READS = decltype(reads_c)::value;
-            const int cur = ks & 1, nxt = cur ^ 1;
+            const int cur = ks % NSETS, nxt = (ks + PD) % NSETS;
 #pragma unroll
             for (int e = 0; e < NMF; ++e) {
                 acc[e / FN][e % FN] = mfma32(fa[cur][e / FN], fb[cur][e % FN], acc[e / FN][e % FN]);
                 if constexpr (READS) {
-                    // order A0, B0..B(FN-1), A1..: what the next k-step's first MFMAs need comes first
-                    if (e == 0) fa[nxt][0] = *(const bf16x8_t*)(a_ptr + rd_stage + coff[rd_ks]);
-                    else if (e <= FN) fb[nxt][e - 1] = *(const bf16x8_t*)(b_ptr + rd_stage + (e - 1) * 32 * ROWB + coff[rd_ks]);
-                    else if (e < NRD) fa[nxt][e - FN] = *(const bf16x8_t*)(a_ptr + rd_stage + (e - FN) * 32 * ROWB + coff[rd_ks]);
+                    // RPS reads per slot, in the order A0, B0..B(FN-1), A1..: what that k-step's first MFMAs need first
+#pragma unroll
+                    for (int r = e * RPS; r < (e + 1) * RPS && r < NRD; ++r) {
+                        if (r == 0) fa[nxt][0] = *(const bf16x8_t*)(a_ptr + rd_stage + coff[rd_ks]);
+                        else if (r <= FN) fb[nxt][r - 1] = *(const bf16x8_t*)(b_ptr + rd_stage + (r - 1) * 32 * ROWB + coff[rd_ks]);
+                        else fa[nxt][r - FN] = *(const bf16x8_t*)(a_ptr + rd_stage + (r - FN) * 32 * ROWB + coff[rd_ks]);
+                    }
                 }
                 if constexpr (LOADS) {
                     const int gs = ks * NMF + e;          // slot number within the tile
@@ -299,16 +306,18 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             const size_t st_cur = (size_t)(kt % STAGES) * STAGE_BYTES, st_nxt = (size_t)((kt + 1) % STAGES) * STAGE_BYTES;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                if (ks < KS - 1) {
-                    kstep(loads_c, ext_c, std::true_type{}, ks, st_cur, ks + 1, pa, pb, dst);
+                if (ks < HS) {
+                    kstep(loads_c, ext_c, std::true_type{}, ks, st_cur, ks + PD, pa, pb, dst);
                 } else if constexpr (!LAST) {
-                    // hand-over: every wave's reads of this tile are complete (so its buffer may be refilled from
-                    // the next iteration on) and tile kt+1 has landed for every wave
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                    wait_vmcnt<HW>();
-                    __builtin_amdgcn_s_barrier();
-                    asm volatile("" ::: "memory");
-                    kstep(loads_c, ext_c, std::true_type{}, ks, st_nxt, 0, pa, pb, dst);
+                    if (ks == HS) {
+                        // hand-over: every wave's reads of this tile are complete (so its buffer may be refilled from
+                        // the next iteration on) and tile kt+1 has landed for every wave
+                        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                        wait_vmcnt<HW>();
+                        __builtin_amdgcn_s_barrier();
+                        asm volatile("" ::: "memory");
+                    }
+                    kstep(loads_c, ext_c, std::true_type{}, ks, st_nxt, ks + PD - KS, pa, pb, dst);
                 } else {
                     kstep(std::false_type{}, 0u, std::false_type{}, ks, 0, 0, pa, pb, dst);
                 }
@@ -322,9 +331,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
 #pragma unroll
-        for (int i = 0; i < FM; ++i) fa[0][i] = *(const bf16x8_t*)(a_ptr + i * 32 * ROWB + coff[0]);
+        for (int ks = 0; ks < PD; ++ks) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j) fb[0][j] = *(const bf16x8_t*)(b_ptr + j * 32 * ROWB + coff[0]);
+            for (int i = 0; i < FM; ++i) fa[ks][i] = *(const bf16x8_t*)(a_ptr + i * 32 * ROWB + coff[ks]);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[ks][j] = *(const bf16x8_t*)(b_ptr + j * 32 * ROWB + coff[ks]);
+        }
         // at the hand-over of a steady-state tile, tile kt+2.. and the LBH loads of tile kt+STAGES-1 issued
         // so far may be outstanding
         constexpr int HW_STEADY = (STAGES - 3) * L + LBH;
@@ -501,15 +513,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, bool PIPE = false>
+template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, int PIPE = 0>
 static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     const int tiles_m = cdiv(g.M, BM), tiles_n = cdiv(g.N, BN);
     const size_t lds = (size_t)STAGES * (BM + BN) * BKT * 2;
     dim3 grid(tiles_m * tiles_n, SPLITK ? n_split : 1, g.batch);
     auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, PIPE>;
-    if constexpr (PIPE) {  // the branch-free steady-state loop assumes every split has at least STAGES k-tiles
+    if constexpr (PIPE != 0) {  // the branch-free steady-state loop assumes every split has at least STAGES k-tiles
         const int nkt = g.K / BKT + g.K2 / BKT;
-        if (nkt / n_split < STAGES) return run_nt_dl<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, false>(g, s, n_split);
+        if (nkt / n_split < STAGES) return run_nt_dl<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, 0>(g, s, n_split);
     }
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -623,16 +635,23 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 14: return run_nt_dl<256, 128, 2, 2, 4, 0, 32>(g, s);
             case 15: return run_nt_dl<128, 128, 2, 2, 6, 0, 32>(g, s);
             case 16: return run_nt_dl<256, 128, 4, 2, 4, 0, 32>(g, s);
-            case 21: return run_nt_dl<256, 256, 2, 2, 4, 0, 32, false, true>(g, s);
-            case 22: return run_nt_dl<256, 256, 4, 2, 4, 0, 32, false, true>(g, s);
-            case 23: return run_nt_dl<256, 256, 2, 2, 3, 0, 32, false, true>(g, s);
-            case 24: return run_nt_dl<256, 128, 2, 2, 4, 0, 32, false, true>(g, s);
-            case 25: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, true>(g, s);
-            case 26: return run_nt_dl<128, 128, 2, 2, 3, 0, 64, false, true>(g, s);
-            case 27: return run_nt_dl<256, 128, 2, 2, 3, 0, 64, false, true>(g, s);
-            case 28: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, true>(g, s);
-            case 29: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, true>(g, s);
-            case 30: return run_nt_dl<128, 256, 2, 2, 3, 0, 64, false, true>(g, s);
+            case 21: return run_nt_dl<256, 256, 2, 2, 4, 0, 32, false, 1>(g, s);
+            case 22: return run_nt_dl<256, 256, 4, 2, 4, 0, 32, false, 1>(g, s);
+            case 23: return run_nt_dl<256, 256, 2, 2, 3, 0, 32, false, 1>(g, s);
+            case 24: return run_nt_dl<256, 128, 2, 2, 4, 0, 32, false, 1>(g, s);
+            case 25: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, 1>(g, s);
+            case 26: return run_nt_dl<128, 128, 2, 2, 3, 0, 64, false, 1>(g, s);
+            case 27: return run_nt_dl<256, 128, 2, 2, 3, 0, 64, false, 1>(g, s);
+            case 28: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, 1>(g, s);
+            case 29: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, 1>(g, s);
+            case 30: return run_nt_dl<128, 256, 2, 2, 3, 0, 64, false, 1>(g, s);
+            case 35: return run_nt_dl<128, 128, 4, 2, 4, 0, 64, false, 1>(g, s);
+            case 36: return run_nt_dl<128, 128, 2, 4, 4, 0, 64, false, 1>(g, s);
+            case 37: return run_nt_dl<128, 128, 4, 2, 4, 0, 64, false, 2>(g, s);
+            case 31: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, 2>(g, s);
+            case 32: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, 2>(g, s);
+            case 33: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, 2>(g, s);
+            case 34: return run_nt_dl<256, 128, 2, 2, 3, 0, 64, false, 2>(g, s);
 #ifdef TL_GEMM_ABLATE
             case 101: return run_nt_dl<128, 128, 2, 2, 4, 1>(g, s);
             case 102: return run_nt_dl<128, 128, 2, 2, 4, 2>(g, s);
@@ -650,7 +669,7 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 207: return run_nt_dl<256, 256, 4, 2, 2, 7>(g, s);
 #endif
             case 10: return run_nt_dl<128, 128, 2, 2, 4>(g, s);
-            default: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, true>(g, s);
+            default: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, 1>(g, s);
         }
     }
     if (g.N > 64 && t128 >= 200) {

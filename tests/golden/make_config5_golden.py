@@ -1,0 +1,90 @@
+#!/usr/bin/env python3
+"""Writes tests/golden/config5_7b_seed5000.npz: the CPU oracle's results for the first four optimizer steps of the
+streaming workload on the full 7B shape (Algorithm 1 with n = 2 epochs: chunk 0 twice, then chunk 1 twice, the
+module and its AdamW state carried from step to step).
+
+Calls only oracle/ and the seeded input generator.  The paper prints no per-step numbers, so these are the pinned
+oracle's values on the synthetic stand-in for its long-text stream: token ids whose rank follows a Zipf law with
+exponent 1.1 over the 32000-entry vocabulary, chunks of 1024, A ~ N(0, 0.02^2), B = 0, lr 5e-5 constant.  From
+step 2 on B != 0, so dA != 0 and the low-rank path carries signal in both directions.
+
+Stored: loss and per-position nll of every step; for layers 0, 16, 31 and every projection, samples of dA and dB at
+every step and of A and B after the last step (two rows each, 256 columns of the wide ones), with full-tensor norms.
+
+    python tests/golden/make_config5_golden.py [n_layers]      (about an hour on 8 cores, ~35 GB peak)
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+from oracle import templora_oracle as O  # noqa: E402
+from paper_2401_11504_amd import synth  # noqa: E402
+
+SEED, T, N_CHUNKS, N_EPOCHS, LR = 5000, 1024, 2, 2, 5e-5
+OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "config5_7b_seed5000.npz")
+SAMPLE_ROWS = 2
+SAMPLE_COLS = 256   # columns of the sampled dA / A rows
+
+
+def main(n_layers=32):
+    shape = synth.SHAPES["7b"].with_layers(n_layers)
+    stream = synth.zipf_tokens(SEED, N_CHUNKS * T, shape.vocab)
+    emb, head = synth.embedding(SEED, shape), synth.lm_head(SEED, shape)
+    lora = [synth.lora_factors(SEED, shape, l) for l in range(shape.n_layers)]
+    opt = O.new_opt_state(lora)
+    cache = {}
+
+    def get_layer(l):
+        if l not in cache:
+            cache.clear()
+            cache[l] = synth.layer_weights(SEED, shape, l)
+        return cache[l]
+
+    keep = sorted({0, shape.n_layers // 2, shape.n_layers - 1})
+    rs = np.random.default_rng(SEED)
+    f32 = lambda x: np.asarray(x, dtype=np.float32)
+    out = {"n_layers": np.int64(shape.n_layers), "seed": np.int64(SEED), "keep": np.array(keep),
+           "lr": np.float64(LR), "tokens": stream}
+    rows = {}
+    for l in keep:
+        for i, p in enumerate(synth.PROJ):
+            d_out, d_in = shape.proj_dims(p)
+            rows[(l, i, 0)] = np.sort(rs.choice(shape.rank, SAMPLE_ROWS, replace=False))   # rows of A / dA  [r, d_in]
+            rows[(l, i, 1)] = np.sort(rs.choice(d_out, SAMPLE_ROWS, replace=False))        # rows of B / dB  [d_out, r]
+            rows[(l, i, 2)] = np.sort(rs.choice(d_in, min(SAMPLE_COLS, d_in), replace=False))   # columns of A / dA
+            out[f"rowsA_{l}_{i}"], out[f"rowsB_{l}_{i}"], out[f"colsA_{l}_{i}"] = rows[(l, i, 0)], rows[(l, i, 1)], rows[(l, i, 2)]
+    step = 0
+    for c in range(N_CHUNKS):
+        tok = stream[c * T:(c + 1) * T]
+        for e in range(N_EPOCHS):
+            t0 = time.time()
+            res, lora, opt = O.chunk_update(tok, 0, shape, emb, head, np.ones(shape.d_model), get_layer, lora, opt, LR)
+            print(f"step {step} (chunk {c}, epoch {e}): {time.time() - t0:.1f} s, loss {res['loss']:.6f}", flush=True)
+            out[f"loss_{step}"] = np.float64(res["loss"])
+            out[f"n_targets_{step}"] = np.int64(res["n_targets"])
+            out[f"nll_{step}"] = f32(res["nll"])
+            for l in keep:
+                for i, p in enumerate(synth.PROJ):
+                    dA, dB = res["grads"][l][p]
+                    out[f"dA_{step}_{l}_{i}"] = f32(dA[np.ix_(rows[(l, i, 0)], rows[(l, i, 2)])])
+                    out[f"dB_{step}_{l}_{i}"] = f32(dB[rows[(l, i, 1)]])
+                    out[f"dA_norm_{step}_{l}_{i}"] = np.float64(np.linalg.norm(dA))
+                    out[f"dB_norm_{step}_{l}_{i}"] = np.float64(np.linalg.norm(dB))
+            del res
+            step += 1
+    for l in keep:
+        for i, p in enumerate(synth.PROJ):
+            A, B = lora[l][p]
+            out[f"A_final_{l}_{i}"] = f32(np.asarray(A)[np.ix_(rows[(l, i, 0)], rows[(l, i, 2)])])
+            out[f"B_final_{l}_{i}"] = f32(np.asarray(B)[rows[(l, i, 1)]])
+    out["n_steps"] = np.int64(step)
+    np.savez_compressed(OUT if n_layers == 32 else OUT.replace(".npz", f"_L{n_layers}.npz"), **out)
+    print("wrote", OUT, flush=True)
+
+
+if __name__ == "__main__":
+    main(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
