@@ -112,7 +112,11 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
     const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
     bf16_t* sVt = sK + 64 * C::LSK;
-    const int qb = gridDim.x - 1 - blockIdx.x;  // heaviest (latest) query blocks first
+    // Heaviest (latest) query blocks first; the second half of the heads takes the mirrored block, so that two
+    // workgroups placed on one CU by round-robin dispatch (ids i and i + n/2 in dispatch order, x fastest) carry the
+    // same total number of key tiles whichever CU they land on.
+    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;
+    const int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
     const int head = blockIdx.y;
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const bf16_t* qh = q + (long)head * DH;
@@ -273,7 +277,8 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
     bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
     bf16_t* sV = sK + 64 * C::LSK;
     bf16_t* sKt = sV + 64 * C::LSK;
-    const int qb = gridDim.x - 1 - blockIdx.x;
+    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;   // see attn_fwd_kernel
+    const int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
     const int head = blockIdx.y;
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
@@ -398,7 +403,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
     float* sLse = (float*)(sdOt + DH * LST); // [64]
     float* sDelta = sLse + 64;              // [64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-    const int kb = blockIdx.x;  // early key blocks see the most queries and are scheduled first
+    // early key blocks see the most queries and are scheduled first; second half of the grid mirrored (see attn_fwd_kernel)
+    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;
+    const int kb = mirror ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
     const int head = blockIdx.y;
     const int u0 = kb * KB, uw0 = u0 + 32 * wave, u_abs = uw0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
