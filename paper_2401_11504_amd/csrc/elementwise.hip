@@ -5,28 +5,50 @@
 
 // ---------------------------------------------------------------- RMSNorm
 // One block per token row.  y = h * rsqrt(mean(h^2) + eps) * g   (Llama2 decoder norm).
+// With d <= 256 * 4 * NV the row stays in registers between the reduction and the output pass (NV float4 per
+// thread); wider rows are read twice (NV = 0).
+template <int NV>
 __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ h, const float* __restrict__ g,
                                                           int d, float eps, bf16_t* __restrict__ y) {
     __shared__ float red[16];
     const long row = blockIdx.x;
     const float4* hp = (const float4*)(h + row * d);
     const float4* gp = (const float4*)g;
+    uint2* yp = (uint2*)(y + row * d);
     const int n4 = d >> 2;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-        float4 x = hp[i];
-        ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+    constexpr int NR = NV > 0 ? NV : 1;
+    float4 xs[NR];
+    if constexpr (NV > 0) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + 256 * j;
+            xs[j] = i < n4 ? hp[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            ss += xs[j].x * xs[j].x + xs[j].y * xs[j].y + xs[j].z * xs[j].z + xs[j].w * xs[j].w;
+        }
+    } else {
+        for (int i = threadIdx.x; i < n4; i += blockDim.x) {
+            const float4 x = hp[i];
+            ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        }
     }
     ss = block_sum(ss, red);
     const float rho = rsqrtf(ss / (float)d + eps);
-    uint2* yp = (uint2*)(y + row * d);
-    for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-        float4 x = hp[i];
-        float4 w = gp[i];
+    auto emit = [&](int i, const float4& x) {
+        const float4 w = gp[i];
         uint2 o;
         o.x = pack_bf16x2(x.x * rho * w.x, x.y * rho * w.y);
         o.y = pack_bf16x2(x.z * rho * w.z, x.w * rho * w.w);
         yp[i] = o;
+    };
+    if constexpr (NV > 0) {
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int i = threadIdx.x + 256 * j;
+            if (i < n4) emit(i, xs[j]);
+        }
+    } else {
+        for (int i = threadIdx.x; i < n4; i += blockDim.x) emit(i, hp[i]);
     }
 }
 
@@ -118,7 +140,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
 
 hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s) {
     if (T <= 0) return hipSuccess;
-    rmsnorm_fwd_kernel<<<T, 256, 0, s>>>(h, g, d, eps, y);
+    if (d <= 4096) rmsnorm_fwd_kernel<4><<<T, 256, 0, s>>>(h, g, d, eps, y);
+    else if (d <= 8192) rmsnorm_fwd_kernel<8><<<T, 256, 0, s>>>(h, g, d, eps, y);
+    else rmsnorm_fwd_kernel<0><<<T, 256, 0, s>>>(h, g, d, eps, y);
     return hipGetLastError();
 }
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
@@ -333,25 +357,39 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ p, const
                                                     float b1, float b2, float eps, float decay, float inv_bc1,
                                                     float inv_bc2) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
-        float4 P = ((float4*)p)[i], G = ((const float4*)g)[i], Mm = ((float4*)m)[i], Vv = ((float4*)v)[i];
-        float pp[4] = {P.x, P.y, P.z, P.w}, gg[4] = {G.x, G.y, G.z, G.w};
-        float mm[4] = {Mm.x, Mm.y, Mm.z, Mm.w}, vv[4] = {Vv.x, Vv.y, Vv.z, Vv.w};
+    // two independent groups of four per trip: eight 16-byte loads are in flight before the first one is used
+    for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < n4; i0 += 2 * stride) {
+        const size_t i1 = i0 + stride;
+        const bool two = i1 < n4;
+        const size_t ii[2] = {i0, two ? i1 : i0};
+        float4 P[2], G[2], Mm[2], Vv[2];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            pp[e] *= decay;
-            mm[e] = b1 * mm[e] + (1.f - b1) * gg[e];
-            vv[e] = b2 * vv[e] + (1.f - b2) * gg[e] * gg[e];
-            pp[e] -= lr * (mm[e] * inv_bc1) / (sqrtf(vv[e] * inv_bc2) + eps);
+        for (int k = 0; k < 2; ++k) {
+            P[k] = ((float4*)p)[ii[k]]; G[k] = ((const float4*)g)[ii[k]];
+            Mm[k] = ((float4*)m)[ii[k]]; Vv[k] = ((float4*)v)[ii[k]];
         }
-        ((float4*)p)[i] = make_float4(pp[0], pp[1], pp[2], pp[3]);
-        ((float4*)m)[i] = make_float4(mm[0], mm[1], mm[2], mm[3]);
-        ((float4*)v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
-        if (shadow) {
-            uint2 b;
-            b.x = pack_bf16x2(pp[0], pp[1]);
-            b.y = pack_bf16x2(pp[2], pp[3]);
-            ((uint2*)shadow)[i] = b;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            if (k == 1 && !two) break;
+            float pp[4] = {P[k].x, P[k].y, P[k].z, P[k].w}, gg[4] = {G[k].x, G[k].y, G[k].z, G[k].w};
+            float mm[4] = {Mm[k].x, Mm[k].y, Mm[k].z, Mm[k].w}, vv[4] = {Vv[k].x, Vv[k].y, Vv[k].z, Vv[k].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                pp[e] *= decay;
+                mm[e] = b1 * mm[e] + (1.f - b1) * gg[e];
+                vv[e] = b2 * vv[e] + (1.f - b2) * gg[e] * gg[e];
+                pp[e] -= lr * (mm[e] * inv_bc1) / (sqrtf(vv[e] * inv_bc2) + eps);
+            }
+            const size_t i = ii[k];
+            ((float4*)p)[i] = make_float4(pp[0], pp[1], pp[2], pp[3]);
+            ((float4*)m)[i] = make_float4(mm[0], mm[1], mm[2], mm[3]);
+            ((float4*)v)[i] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+            if (shadow) {
+                uint2 b;
+                b.x = pack_bf16x2(pp[0], pp[1]);
+                b.y = pack_bf16x2(pp[2], pp[3]);
+                ((uint2*)shadow)[i] = b;
+            }
         }
     }
     // tail (n not a multiple of 4)

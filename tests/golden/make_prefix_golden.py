@@ -1,0 +1,75 @@
+#!/usr/bin/env python3
+"""Writes tests/golden/prefix_7bwidth_L4_seed2048.npz: the CPU oracle's results for one update on the paper's actual
+training sample layout -- L_T = 1024 conditioning tokens followed by a chunk of 1024 (Section 2, "use the preceding
+L_T tokens as the input and the chunk as the output"), i.e. 2048 tokens with n_ctx = 1024 so that only the chunk
+positions carry loss -- on a decoder of the 7B width (d 4096, 32x128 heads, ffn 11008, vocab 32000, r = 64) cut to
+four layers so that the oracle finishes in minutes and every tensor can be held to the bf16 tolerance.
+
+Calls only oracle/ and the seeded input generator.  Zipf(1.1) token ids, A ~ N(0, 0.02^2), B ~ N(0, 0.01^2) (so that
+dA != 0).  Stored: loss, n_targets, per-position nll, samples of the hidden-state gradient at every layer boundary and
+of dA / dB of every projection of every layer, with full-tensor norms.
+
+    python tests/golden/make_prefix_golden.py
+"""
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+from oracle import templora_oracle as O  # noqa: E402
+from paper_2401_11504_amd import synth  # noqa: E402
+
+SEED, T, N_CTX, N_LAYERS, B_STD = 2048, 2048, 1024, 4, 0.01
+OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "prefix_7bwidth_L4_seed2048.npz")
+ROWS, COLS = 2, 256
+
+
+def main():
+    shape = synth.SHAPES["7b"].with_layers(N_LAYERS)
+    tok = synth.zipf_tokens(SEED, T, shape.vocab)
+    emb, head = synth.embedding(SEED, shape), synth.lm_head(SEED, shape)
+    lora = [synth.lora_factors(SEED, shape, l, b_std=B_STD) for l in range(shape.n_layers)]
+    W = {}
+
+    def get_layer(l):
+        if l not in W:
+            W[l] = synth.layer_weights(SEED, shape, l)
+        return W[l]
+
+    keep = list(range(shape.n_layers))
+    t0 = time.time()
+    res = O.model_fwd_bwd(tok, N_CTX, shape, emb, head, np.ones(shape.d_model), get_layer, lora, keep=keep)
+    print(f"oracle forward+backward: {time.time() - t0:.1f} s, loss {res['loss']:.6f}, targets {res['n_targets']}", flush=True)
+    rs = np.random.default_rng(SEED)
+    f32 = lambda x: np.asarray(x, dtype=np.float32)
+    out = {"loss": np.float64(res["loss"]), "n_targets": np.int64(res["n_targets"]), "nll": f32(res["nll"]),
+           "n_layers": np.int64(shape.n_layers), "seed": np.int64(SEED), "n_ctx": np.int64(N_CTX), "b_std": np.float64(B_STD),
+           "tokens": tok}
+    rows_t = np.sort(rs.choice(T, 4, replace=False))
+    cols_d = np.sort(rs.choice(shape.d_model, COLS, replace=False))
+    out["dh_rows"], out["dh_cols"] = rows_t, cols_d
+    out["dh_final"] = f32(res["dh"]["final"][np.ix_(rows_t, cols_d)])
+    out["dh_final_norm"] = np.float64(np.linalg.norm(res["dh"]["final"]))
+    for l in keep:
+        out[f"dh_{l}"] = f32(res["dh"][l][np.ix_(rows_t, cols_d)])
+        out[f"dh_norm_{l}"] = np.float64(np.linalg.norm(res["dh"][l]))
+        for i, p in enumerate(synth.PROJ):
+            dA, dB = res["grads"][l][p]
+            d_out, d_in = shape.proj_dims(p)
+            ra = np.sort(rs.choice(shape.rank, ROWS, replace=False))
+            ca = np.sort(rs.choice(d_in, COLS, replace=False))
+            rb = np.sort(rs.choice(d_out, ROWS, replace=False))
+            out[f"rowsA_{l}_{i}"], out[f"colsA_{l}_{i}"], out[f"rowsB_{l}_{i}"] = ra, ca, rb
+            out[f"dA_{l}_{i}"] = f32(dA[np.ix_(ra, ca)])
+            out[f"dB_{l}_{i}"] = f32(dB[rb])
+            out[f"dA_norm_{l}_{i}"] = np.float64(np.linalg.norm(dA))
+            out[f"dB_norm_{l}_{i}"] = np.float64(np.linalg.norm(dB))
+    np.savez_compressed(OUT, **out)
+    print("wrote", OUT, flush=True)
+
+
+if __name__ == "__main__":
+    main()

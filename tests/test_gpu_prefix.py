@@ -1,0 +1,91 @@
+"""The paper's training-sample layout at full width: L_T = 1024 conditioning tokens + a 1024-token chunk in one call
+(n_tokens = 2048, n_ctx = 1024; only chunk positions carry loss -- Section 2 and Algorithm 1), on a four-layer decoder
+of the 7B width so that the stored oracle run is a matter of minutes and every tensor meets the bf16 tolerance.
+Expected values: tests/golden/prefix_7bwidth_L4_seed2048.npz, written by tests/golden/make_prefix_golden.py (oracle only).
+The full 32-layer model is then run in the same layout and checked through what holds at any size (mask, count,
+normalisation, conditioning, descent)."""
+import os
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2401_11504_amd import synth  # noqa: E402
+from test_gpu_kernels import BF16_TOL, check  # noqa: E402
+
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "prefix_7bwidth_L4_seed2048.npz")
+LR = 5e-5
+
+
+@pytest.mark.skipif(not os.path.exists(GOLD), reason="stored oracle values not generated")
+def test_prefix_sample_7b_width_matches_stored_oracle():
+    from paper_2401_11504_amd import api, harness
+    gold = np.load(GOLD)
+    seed, T, n_ctx = int(gold["seed"]), 2048, int(gold["n_ctx"])
+    shape = synth.SHAPES["7b"].with_layers(int(gold["n_layers"]))
+    tok = synth.zipf_tokens(seed, T, shape.vocab)
+    assert np.array_equal(tok, gold["tokens"])
+    model = harness.Model(shape, seed, max_tokens=T, keep_host=False, workers=16)
+    lora, facs = harness.new_lora(model, seed, b_std=float(gold["b_std"]))
+    loss, n = api.tl_chunk_update(lora, tok, n_ctx, LR)
+    assert n == int(gold["n_targets"]) == T - n_ctx                      # integer work: exact
+    ref = float(gold["loss"])
+    assert abs(loss - ref) <= 2e-3 * ref, (loss, ref)
+    nll = api.tl_get_nll(lora, T)
+    assert not nll[:n_ctx - 1].any() and nll[T - 1] == 0.0              # conditioning positions carry no loss
+    check(nll, gold["nll"], BF16_TOL, "per-position nll")
+    rows, cols = gold["dh_rows"], gold["dh_cols"]
+    for name, boundary in [("dh_final", shape.n_layers)] + [(f"dh_{l}", l) for l in range(shape.n_layers)]:
+        dh = api.tl_get_dh(lora, boundary, T, shape.d_model)
+        check(dh[np.ix_(rows, cols)], gold[name], BF16_TOL, name)
+        key = "dh_final_norm" if name == "dh_final" else f"dh_norm_{boundary}"
+        assert abs(np.linalg.norm(dh.astype(np.float64)) - float(gold[key])) <= BF16_TOL * float(gold[key]), name
+    for l in range(shape.n_layers):
+        for i, p in enumerate(synth.PROJ):
+            dout, din = shape.proj_dims(p)
+            dA = api.tl_get_factor(lora, l, i, api.GRAD_A, (shape.rank, din))
+            dB = api.tl_get_factor(lora, l, i, api.GRAD_B, (dout, shape.rank))
+            check(dA[np.ix_(gold[f"rowsA_{l}_{i}"], gold[f"colsA_{l}_{i}"])], gold[f"dA_{l}_{i}"], BF16_TOL, f"dA l{l} {p}")
+            check(dB[gold[f"rowsB_{l}_{i}"]], gold[f"dB_{l}_{i}"], BF16_TOL, f"dB l{l} {p}")
+            for g, key in ((dA, f"dA_norm_{l}_{i}"), (dB, f"dB_norm_{l}_{i}")):
+                assert abs(np.linalg.norm(g.astype(np.float64)) - float(gold[key])) <= BF16_TOL * float(gold[key]), key
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
+
+
+def test_prefix_sample_full_depth_properties():
+    """32 layers, 2048 tokens, n_ctx = 1024: mask, count, normalisation, conditioning and descent."""
+    from paper_2401_11504_amd import api, harness
+    shape = synth.SHAPES["7b"]
+    seed, T, n_ctx = 2049, 2048, 1024
+    tok = synth.zipf_tokens(seed, T, shape.vocab)
+    model = harness.Model(shape, seed, max_tokens=T, keep_host=False, device_random=True)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    loss0, n0 = api.tl_chunk_loss(lora, tok, n_ctx)
+    assert n0 == T - n_ctx
+    nll = api.tl_get_nll(lora, T).astype(np.float64)
+    assert not nll[:n_ctx - 1].any() and nll[T - 1] == 0.0 and (nll[n_ctx - 1:T - 1] > 0).all()
+    assert abs(loss0 - nll.sum() / n0) <= 1e-5 * loss0                   # mean over the targets only
+    # a change inside the conditioning prefix moves the chunk's losses (it is context) but adds no target
+    tok2 = tok.copy()
+    tok2[7] = (tok2[7] + 1) % shape.vocab
+    loss_ctx, n_ctx_targets = api.tl_chunk_loss(lora, tok2, n_ctx)
+    nll2 = api.tl_get_nll(lora, T).astype(np.float64)
+    assert n_ctx_targets == n0 and not nll2[:n_ctx - 1].any() and loss_ctx != loss0
+    # causality: the last token is only ever a label
+    tok3 = tok.copy()
+    tok3[T - 1] = (tok3[T - 1] + 1) % shape.vocab
+    api.tl_chunk_loss(lora, tok3, n_ctx)
+    nll3 = api.tl_get_nll(lora, T).astype(np.float64)
+    assert np.array_equal(nll3[:T - 2], nll[:T - 2]) and nll3[T - 2] != nll[T - 2]
+    # two epochs on the sample: same first loss as the forward-only call, then descent
+    l1, _ = api.tl_chunk_update(lora, tok, n_ctx, LR)
+    l2, _ = api.tl_chunk_update(lora, tok, n_ctx, LR)
+    assert l1 == loss0 and l2 < l1
+    assert api.tl_get_step(lora) == 2
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
