@@ -272,8 +272,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             const int cur = ks % NSETS, nxt = (ks + PD) % NSETS;
 #pragma unroll
             for (int e = 0; e < NMF; ++e) {
-                acc[e / FN][e % FN] = mfma32(fa[cur][e / FN], fb[cur][e % FN], acc[e / FN][e % FN]);
-                if constexpr (READS) {
+                if constexpr (!(DBG & 2)) acc[e / FN][e % FN] = mfma32(fa[cur][e / FN], fb[cur][e % FN], acc[e / FN][e % FN]);
+                else asm volatile("" ::"v"(fa[cur][e / FN]), "v"(fb[cur][e % FN]));
+                if constexpr (READS && !(DBG & 4)) {
                     // RPS reads per slot, in the order A0, B0..B(FN-1), A1..: what that k-step's first MFMAs need first
 #pragma unroll
                     for (int r = e * RPS; r < (e + 1) * RPS && r < NRD; ++r) {
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
                         else fa[nxt][r - FN] = *(const bf16x8_t*)(a_ptr + rd_stage + (r - FN) * 32 * ROWB + coff[rd_ks]);
                     }
                 }
-                if constexpr (LOADS) {
+                if constexpr (LOADS && !(DBG & 1)) {
                     const int gs = ks * NMF + e;          // slot number within the tile
                     const int j = (gs * L + NSLOT - 1) / NSLOT;   // first load with j * NSLOT / L >= gs
                     if (j < L && j * NSLOT / L == gs) {
@@ -614,7 +615,15 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             const long t256 = (long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
             const long t256x128 = (long)cdiv(g.M, 256) * cdiv(g.N, 128) * g.batch;
             auto fill = [](long t) { return (double)t / (double)(((t + 255) / 256) * 256); };
-            if (t256 < 160) cfg = 25;
+            // few tiles but a long contraction: 256x128 tiles with the contraction split in two give every CU a tile
+            // with three quarters of the operand bytes per flop of a 128x128 one (the loop is bound by the rate at
+            // which a CU can pull operand bytes in, not by the matrix pipe); the fp32 partials cost one extra pass,
+            // which pays from K of about 10k on (measured: K 11008 -7 %, 12288 -13 %, 22016 -17 %, 32000 -15 %)
+            const long need = (long)2 * g.M * g.N * g.batch;
+            if (t256 < 160 && fill(2 * t256x128) >= 0.85 && nk >= 160 && g.partial && (size_t)need <= g.partial_elems &&
+                (g.N & 3) == 0)
+                cfg = 45;
+            else if (t256 < 160) cfg = 25;
             else if (fill(t256) >= 0.9) cfg = 6;
             else if (fill(t256x128) >= 0.85) cfg = 28;
             else cfg = g.batch > 1 ? 22 : 6;
@@ -645,6 +654,16 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 28: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, 1>(g, s);
             case 29: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, 1>(g, s);
             case 30: return run_nt_dl<128, 256, 2, 2, 3, 0, 64, false, 1>(g, s);
+            case 41: case 42: case 43: case 44: {
+                const int sp = cfg == 41 ? 4 : (cfg == 42 ? 2 : (cfg == 43 ? 3 : 8));
+                if (!g.partial || (size_t)sp * g.M * g.N * g.batch > g.partial_elems || (g.N & 3)) return hipErrorInvalidValue;
+                return run_nt_dl<256, 256, 4, 2, 4, 0, 32, true, 1>(g, s, sp);
+            }
+            case 45: case 46: {
+                const int sp = cfg == 45 ? 2 : 4;
+                if (!g.partial || (size_t)sp * g.M * g.N * g.batch > g.partial_elems || (g.N & 3)) return hipErrorInvalidValue;
+                return run_nt_dl<256, 128, 4, 2, 3, 0, 64, true, 1>(g, s, sp);
+            }
             case 35: return run_nt_dl<128, 128, 4, 2, 4, 0, 64, false, 1>(g, s);
             case 36: return run_nt_dl<128, 128, 2, 4, 4, 0, 64, false, 1>(g, s);
             case 37: return run_nt_dl<128, 128, 4, 2, 4, 0, 64, false, 2>(g, s);
@@ -660,6 +679,26 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             case 105: return run_nt_dl<128, 128, 2, 2, 4, 5>(g, s);
             case 106: return run_nt_dl<128, 128, 2, 2, 4, 6>(g, s);
             case 107: return run_nt_dl<128, 128, 2, 2, 4, 7>(g, s);
+            case 500: return run_nt_dl<256, 256, 2, 2, 5, 0, 32, false, 1>(g, s);
+            case 506: return run_nt_dl<256, 256, 2, 2, 5, 6, 32, false, 1>(g, s);
+            case 600: return run_nt_dl<256, 256, 4, 2, 5, 0, 32, false, 1>(g, s);
+            case 606: return run_nt_dl<256, 256, 4, 2, 5, 6, 32, false, 1>(g, s);
+            case 700: return run_nt_dl<256, 256, 2, 2, 3, 0, 32, false, 1>(g, s);
+            case 706: return run_nt_dl<256, 256, 2, 2, 3, 6, 32, false, 1>(g, s);
+            case 301: return run_nt_dl<256, 256, 2, 2, 4, 1, 32, false, 1>(g, s);
+            case 302: return run_nt_dl<256, 256, 2, 2, 4, 2, 32, false, 1>(g, s);
+            case 303: return run_nt_dl<256, 256, 2, 2, 4, 3, 32, false, 1>(g, s);
+            case 304: return run_nt_dl<256, 256, 2, 2, 4, 4, 32, false, 1>(g, s);
+            case 305: return run_nt_dl<256, 256, 2, 2, 4, 5, 32, false, 1>(g, s);
+            case 306: return run_nt_dl<256, 256, 2, 2, 4, 6, 32, false, 1>(g, s);
+            case 307: return run_nt_dl<256, 256, 2, 2, 4, 7, 32, false, 1>(g, s);
+            case 401: return run_nt_dl<256, 256, 4, 2, 4, 1, 32, false, 1>(g, s);
+            case 402: return run_nt_dl<256, 256, 4, 2, 4, 2, 32, false, 1>(g, s);
+            case 403: return run_nt_dl<256, 256, 4, 2, 4, 3, 32, false, 1>(g, s);
+            case 404: return run_nt_dl<256, 256, 4, 2, 4, 4, 32, false, 1>(g, s);
+            case 405: return run_nt_dl<256, 256, 4, 2, 4, 5, 32, false, 1>(g, s);
+            case 406: return run_nt_dl<256, 256, 4, 2, 4, 6, 32, false, 1>(g, s);
+            case 407: return run_nt_dl<256, 256, 4, 2, 4, 7, 32, false, 1>(g, s);
             case 201: return run_nt_dl<256, 256, 4, 2, 2, 1>(g, s);
             case 202: return run_nt_dl<256, 256, 4, 2, 2, 2>(g, s);
             case 203: return run_nt_dl<256, 256, 4, 2, 2, 3>(g, s);

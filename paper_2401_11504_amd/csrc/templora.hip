@@ -383,12 +383,12 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         }
         HIPCHK(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
         TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
-        // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r];
-        // dA / dB of one group: at most max(3r*d, 2f*r) elements, up to 8 token splits)
+        // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r]) or four of a
+        // [T, d_model] output (long-K GEMMs with few output tiles)
         {
             const size_t skinny = (size_t)Tm * 3 * r * 16;
-            const size_t grads = (size_t)8 * r * (size_t)(3 * d > 2 * f ? 3 * d : 2 * f);
-            L->partial_elems = skinny > grads ? skinny : grads;
+            const size_t wide = (size_t)Tm * d * 4;     // four-way split of a GEMM with d_model output columns
+            L->partial_elems = skinny > wide ? skinny : wide;
         }
         TLCHK(L->pool.alloc(&L->partial, L->partial_elems));
 
@@ -462,6 +462,7 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     y.batch = G; y.bB = (long)dout * din; y.bA2 = r; y.bB2 = (long)dout * r; y.bC = dout;
     y.ldc = (long)G * dout;
     if (Y_f32) { y.C = Y_f32; y.c_f32 = 1; y.R = resid; } else { y.C = Y_bf; }
+    y.partial = L->partial; y.partial_elems = L->partial_elems;
     HIPCHK(timed_gemm(L, y));
     return TL_OK;
 }
@@ -488,6 +489,7 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         x.K = G * dout;
         x.A2 = dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r;
         x.C = dX; x.ldc = din;
+        x.partial = L->partial; x.partial_elems = L->partial_elems;
         HIPCHK(timed_gemm(L, x));
     }
     tn.add(dH, (long)G * r, G * r, X, din, din, L->G + o.A[g], din);                    // dA [G r, d_in]
@@ -644,6 +646,7 @@ extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t 
     GemmNT dh;
     dh.A = L->dlogits; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T; dh.N = d; dh.K = V;
     dh.C = L->dhf; dh.ldc = d;
+    dh.partial = L->partial; dh.partial_elems = L->partial_elems;
     HIPCHK(timed_gemm(L, dh));
     HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf[nl & 1], s));
     for (int l = nl - 1; l >= 0; --l)
@@ -835,6 +838,19 @@ extern "C" tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.M = M; g.N = N; g.K = K;
     g.A2 = K2 ? A2 : nullptr; g.lda2 = lda2; g.B2 = K2 ? B2 : nullptr; g.ldb2 = ldb2; g.K2 = K2;
     g.alpha = alpha; g.R = R; g.C = C; g.ldc = ldc; g.c_f32 = c_f32;
+    if (getenv("TL_GEMM_TILE") && M > 0 && N > 0) {
+        // tuning aid only: forced split-contraction configurations need scratch, kept for the life of the process
+        static float* scratch = nullptr;
+        static size_t scratch_elems = 0;
+        const size_t want = (size_t)8 * M * N;
+        if (want > scratch_elems) {
+            if (scratch) (void)hipFree(scratch);
+            scratch = nullptr; scratch_elems = 0;
+            HIPCHK(hipMalloc((void**)&scratch, want * sizeof(float)));
+            scratch_elems = want;
+        }
+        g.partial = scratch; g.partial_elems = scratch_elems;
+    }
     HIPCHK(launch_gemm_nt(g, (hipStream_t)hip_stream));
     return TL_OK;
 }
