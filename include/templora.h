@@ -138,6 +138,23 @@ tl_status tl_chunk_loss(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, 
  * other call return TL_ERR_DISCARDED.  The base model is untouched by design. */
 tl_status tl_discard(tl_lora* lora);
 
+/* ---- generation side (Algorithm 1, the token loop between two updates; Section 2, "cache reuse" / recomputation) ----
+ * Greedy decoding with the module applied, over a key/value cache owned by the module.  The cache holds the
+ * rotated keys and the values of every layer for positions 0 .. kv_length-1 (positions count from the start of the
+ * window handed to tl_prefill).  It is (re)built by tl_prefill and extended by tl_decode_step; every
+ * tl_chunk_update / tl_chunk_loss / tl_layer_step invalidates it, which is the paper's default of recomputing the
+ * cache with the updated module after each chunk (call tl_prefill on the last L_X tokens).
+ *
+ * tl_prefill: tokens host int32[n_tokens], 1 <= n_tokens <= max_tokens.  Runs the LoRA-adapted forward pass over the
+ * window, fills the cache, and returns in *next_token the greedy continuation (index of the largest last-position
+ * logit; the lowest index wins among equal logits).  logits_out: host fp32[vocab] for the last position, or NULL.
+ * tl_decode_step: appends `token` at position kv_length and returns the next greedy token (and its logits).
+ * Errors: TL_ERR_ARG (null pointer; decode without a cache), TL_ERR_WINDOW (n_tokens out of range; cache full),
+ * TL_ERR_TOKEN_RANGE, TL_ERR_SHAPE (vocab = 0), TL_ERR_DISCARDED, TL_ERR_DEVICE.  Outputs written only on TL_OK. */
+tl_status tl_prefill(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int32_t* next_token, float* logits_out);
+tl_status tl_decode_step(tl_lora* lora, int32_t token, int32_t* next_token, float* logits_out);
+tl_status tl_kv_length(tl_lora* lora, int32_t* n_out);
+
 /* Release the (discarded or not) handle itself. NULL is accepted. */
 tl_status tl_lora_free(tl_lora* lora);
 
@@ -222,6 +239,19 @@ tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_heads, int32_t
                     int32_t sign, void* hip_stream);
 /* a = silu(g) * u, gu bf16 [T, 2f] = [gate | up], a bf16 [T, f]. */
 tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a, void* hip_stream);
+/* One-token kernels of the generation side.
+ * tl_k_gemv: y[N] = alpha * (W[N,K] x[K] + sum_j lora_b[n,j] lora_h[(n / rows_per_group) r + j]) (+ resid[n]).
+ *   W, x, lora_b bf16; lora_h fp32 (already scaled); lora_b may be NULL.  y_f32 != 0: y and resid fp32, else y bf16
+ *   and resid must be NULL.  K, ldw multiples of 8.
+ * tl_k_attention_decode: o[n_heads * d_head] (bf16) = softmax(q K^T / sqrt(d_head)) V per head, q one row, K and V
+ *   rows 0 .. n_keys-1 with row stride ld (elements), every key visible.
+ * tl_k_argmax: index of the largest of n fp32 values, lowest index among equals; out is a device int32. */
+tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x, int32_t N, int32_t K, const uint16_t* lora_b,
+                    const float* lora_h, int32_t r, int32_t rows_per_group, float alpha, const float* resid, void* y,
+                    int32_t y_f32, void* hip_stream);
+tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ld, int32_t n_keys,
+                                int32_t n_heads, int32_t d_head, uint16_t* o, void* hip_stream);
+tl_status tl_k_argmax(const float* x, int32_t n, int32_t* out, void* hip_stream);
 /* dgu bf16 [T, 2f] from da bf16 [T, f] and gu. */
 tl_status tl_k_swiglu_bwd(const uint16_t* da, const uint16_t* gu, int32_t T, int32_t f, uint16_t* dgu,
                           void* hip_stream);

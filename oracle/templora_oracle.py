@@ -19,7 +19,8 @@ weight W + s*B*A gives the same forward; central finite differences and an
 independent autograd graph agree with every gradient; the loss is a valid NLL
 (ln V on uniform logits, agreement with a library log-softmax); AdamW agrees
 with its step-1 closed form and with a library optimizer over several steps;
-RoPE and RMSNorm invariants; causality.  Absolute loss / gradient values at the
+RoPE and RMSNorm invariants; causality; window_logits agrees with the autograd
+graph's logits and is causal (a longer window leaves earlier rows unchanged).  Absolute loss / gradient values at the
 workload shapes are printed nowhere in the paper: they are pinned only through
 these properties.
 
@@ -297,6 +298,36 @@ def model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, kee
         if l in keep:
             out["dh"][l] = dh
     return out
+
+
+# --------------------------------------------------------------------------
+# Generation side (Algorithm 1: the token loop between two updates).
+# --------------------------------------------------------------------------
+def window_logits(tokens, shape, emb, head, g_final, get_layer, lora):
+    """Logits of every position of a window under the LoRA-adapted model (no cache, no shortcuts:
+    the whole window is recomputed, which is what a key/value cache must reproduce)."""
+    tok = np.asarray(tokens, dtype=np.int64)
+    if tok.size < 1 or tok.min() < 0 or tok.max() >= shape.vocab:
+        raise ValueError("token id out of range")
+    h = _f(emb)[tok]
+    for l in range(shape.n_layers):
+        h, _ = layer_fwd(h, get_layer(l), lora[l], shape)
+    return rmsnorm_fwd(h, g_final, shape.rms_eps) @ _f(head).T
+
+
+def greedy_next(tokens, shape, emb, head, g_final, get_layer, lora):
+    """(next token, last-position logits): the largest logit, lowest index among equals."""
+    logits = window_logits(tokens, shape, emb, head, g_final, get_layer, lora)[-1]
+    return int(np.argmax(logits)), logits
+
+
+def greedy_decode(prompt, n_new, shape, emb, head, g_final, get_layer, lora):
+    """Algorithm 1's inner loop: append the greedy token n_new times, recomputing the window each time."""
+    seq = [int(t) for t in prompt]
+    for _ in range(n_new):
+        nxt, _ = greedy_next(seq, shape, emb, head, g_final, get_layer, lora)
+        seq.append(nxt)
+    return seq[len(prompt):]
 
 
 def new_opt_state(lora):

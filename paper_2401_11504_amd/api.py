@@ -54,6 +54,9 @@ _SIGS = {
     "tl_lora_init": [_vp, C.POINTER(tl_lora_cfg), C.POINTER(_vp)],
     "tl_chunk_update": [_vp, _vp, _i32, _i32, _f32, C.POINTER(_f32), C.POINTER(_i32)],
     "tl_chunk_loss": [_vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_i32)],
+    "tl_prefill": [_vp, _vp, _i32, C.POINTER(_i32), _vp],
+    "tl_decode_step": [_vp, _i32, C.POINTER(_i32), _vp],
+    "tl_kv_length": [_vp, C.POINTER(_i32)],
     "tl_discard": [_vp],
     "tl_lora_free": [_vp],
     "tl_get_factor": [_vp, _i32, _i32, _i32, _vp, _sz],
@@ -72,6 +75,9 @@ _SIGS = {
     "tl_k_rope": [_vp, _i32, _i32, _i32, _i32, _f32, _i32, _i32, _vp],
     "tl_k_swiglu_fwd": [_vp, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_bwd": [_vp, _vp, _i32, _i32, _vp, _vp],
+    "tl_k_gemv": [_vp, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _vp],
+    "tl_k_attention_decode": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp],
+    "tl_k_argmax": [_vp, _i32, _vp, _vp],
     "tl_k_attention_fwd": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _vp],
     "tl_k_attention_bwd": [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp],
     "tl_k_cross_entropy": [_vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
@@ -156,6 +162,29 @@ def tl_chunk_loss(lora, tokens, n_ctx=0):
     loss, n = _f32(), _i32()
     _chk(_lib.tl_chunk_loss(lora, p, a.size, n_ctx, C.byref(loss), C.byref(n)))
     return loss.value, n.value
+
+
+def tl_prefill(lora, tokens, vocab=0):
+    """-> (next_token, logits fp32[vocab] or None)"""
+    a, p = _tok(tokens)
+    nxt = _i32()
+    logits = np.empty(vocab, np.float32) if vocab else None
+    _chk(_lib.tl_prefill(lora, p, a.size, C.byref(nxt), logits.ctypes.data if vocab else None))
+    return nxt.value, logits
+
+
+def tl_decode_step(lora, token, vocab=0):
+    """-> (next_token, logits fp32[vocab] or None)"""
+    nxt = _i32()
+    logits = np.empty(vocab, np.float32) if vocab else None
+    _chk(_lib.tl_decode_step(lora, int(token), C.byref(nxt), logits.ctypes.data if vocab else None))
+    return nxt.value, logits
+
+
+def tl_kv_length(lora):
+    n = _i32()
+    _chk(_lib.tl_kv_length(lora, C.byref(n)))
+    return n.value
 
 
 def tl_discard(lora):
@@ -261,6 +290,21 @@ def tl_k_swiglu_fwd(gu, a, stream=None):
 
 def tl_k_swiglu_bwd(da, gu, dgu, stream=None):
     _chk(_lib.tl_k_swiglu_bwd(_dp(da), _dp(gu), gu.shape[0], gu.shape[1] // 2, _dp(dgu), _s(stream)))
+
+
+def tl_k_gemv(W, x, y, lora_b=None, lora_h=None, rows_per_group=0, alpha=1.0, resid=None, stream=None):
+    N, K = W.shape
+    r = lora_b.shape[1] if lora_b is not None else 0
+    _chk(_lib.tl_k_gemv(_dp(W), W.stride(0), _dp(x), N, K, _dp(lora_b), _dp(lora_h), r, rows_per_group, alpha, _dp(resid),
+                        _dp(y), int(y.dtype == torch.float32), _s(stream)))
+
+
+def tl_k_attention_decode(q, k, v, n_heads, d_head, o, stream=None):
+    _chk(_lib.tl_k_attention_decode(_dp(q), _dp(k), _dp(v), k.stride(0), k.shape[0], n_heads, d_head, _dp(o), _s(stream)))
+
+
+def tl_k_argmax(x, out, stream=None):
+    _chk(_lib.tl_k_argmax(_dp(x), x.numel(), _dp(out), _s(stream)))
 
 
 def tl_k_attention_fwd(q, k, v, n_heads, d_head, o, lse, stream=None):

@@ -94,3 +94,14 @@ hipError_t launch_transpose_table(const bf16_t* src_base, bf16_t* dst_base, cons
                                   int n_desc, int total_tiles, hipStream_t s);
 // copy rows [rows, cols] bf16 from src (stride lds) to dst (stride ldd)
 hipError_t launch_copy2d_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd, hipStream_t s);
+
+// ---------------------------------------------------------------- one-token decoding (decode.hip)
+// y[N] = alpha * (W[N, K] x[K] + sum_j lora_b[n, j] lora_h[(n / rows_per_group) r + j]) (+ resid, fp32 output only)
+hipError_t launch_gemv(const bf16_t* W, long ldw, const bf16_t* x, int N, int K, const bf16_t* lora_b, const float* lora_h,
+                       int r, int rows_per_group, float alpha, const float* resid, bf16_t* y_bf, float* y_f32,
+                       hipStream_t s);
+// one query row against cache rows 0 .. n_keys-1 (row stride ld), per head
+hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
+                                   int d_head, bf16_t* o, hipStream_t s);
+// index of the largest of n floats, lowest index among equals
+hipError_t launch_argmax(const float* x, int n, int* out, hipStream_t s);

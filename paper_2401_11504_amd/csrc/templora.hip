@@ -134,6 +134,13 @@ struct tl_lora {
     int *tok = nullptr, *labels = nullptr;
     int* tok_host = nullptr;      // pinned
     float* loss_host = nullptr;   // pinned
+    // generation side: the key/value cache is the q|k|v buffer the forward pass keeps per layer (rows = positions);
+    // kv_len rows are valid.  Any training-side forward overwrites it, which matches the method (the cache is
+    // recomputed with the updated module after every chunk update).
+    int kv_len = 0;
+    float* lora_h = nullptr;      // [3 r] scaled low-rank activations of the projection group in flight
+    int* next_dev = nullptr;
+    int* next_host = nullptr;     // pinned
     // dA / dB of a layer (one grouped launch) are off the critical path of the backward pass: they run on a second
     // stream (default priority) while the main stream goes on with the layer below.  Everything that launch reads and
     // the layer below would overwrite too early exists twice, indexed by layer parity: dH of each projection group and
@@ -270,8 +277,11 @@ static void lora_release(tl_lora* L) {
     L->pool.release();
     if (L->tok_host) (void)hipHostFree(L->tok_host);
     if (L->loss_host) (void)hipHostFree(L->loss_host);
+    if (L->next_host) (void)hipHostFree(L->next_host);
     L->tok_host = nullptr;
     L->loss_host = nullptr;
+    L->next_host = nullptr;
+    L->kv_len = 0;
     L->P = L->G = L->M = L->V = nullptr;
 }
 
@@ -404,6 +414,9 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         }
         HIPCHK(hipHostMalloc((void**)&L->tok_host, (size_t)Tm * sizeof(int), hipHostMallocDefault));
         HIPCHK(hipHostMalloc((void**)&L->loss_host, 4 * sizeof(float), hipHostMallocDefault));
+        HIPCHK(hipHostMalloc((void**)&L->next_host, 4 * sizeof(int), hipHostMallocDefault));
+        TLCHK(L->pool.alloc(&L->lora_h, (size_t)3 * r));
+        TLCHK(L->pool.alloc(&L->next_dev, (size_t)4));
         HIPCHK(hipStreamSynchronize(s));
         return TL_OK;
     };
@@ -594,6 +607,7 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     const int first = (n_ctx > 1 ? n_ctx : 1) - 1;
     const int N = (T - 1) - first;
     *n_targets = N;
+    L->kv_len = 0;   // the forward pass below overwrites the buffers the key/value cache lives in
     memcpy(L->tok_host, tokens, (size_t)T * sizeof(int));
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(launch_labels(L->tok, T, L->labels, s));
@@ -662,6 +676,103 @@ extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t 
     return TL_OK;
 }
 
+// ---------------------------------------------------------------- generation side (Algorithm 1, the token loop)
+// Last-position logits -> greedy token; optional copy of the logits to the host.
+static tl_status emit_next(tl_lora* L, const float* h_last, int32_t* next_token, float* logits_out) {
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    hipStream_t s = m->stream;
+    HIPCHK(launch_rmsnorm_fwd(h_last, m->gf, 1, c.d_model, c.rms_eps, L->hf, s));
+    HIPCHK(launch_gemv(m->head, c.d_model, L->hf, c.vocab, c.d_model, nullptr, nullptr, 0, 0, 1.f, nullptr, nullptr,
+                       L->logits, s));
+    HIPCHK(launch_argmax(L->logits, c.vocab, L->next_dev, s));
+    HIPCHK(hipMemcpyAsync(L->next_host, L->next_dev, sizeof(int), hipMemcpyDeviceToHost, s));
+    if (logits_out)
+        HIPCHK(hipMemcpyAsync(logits_out, L->logits, (size_t)c.vocab * sizeof(float), hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    *next_token = L->next_host[0];
+    return TL_OK;
+}
+
+extern "C" tl_status tl_prefill(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t* next_token,
+                                float* logits_out) {
+    LIVE(L, "tl_prefill");
+    if (!next_token) return fail(TL_ERR_ARG, "next_token is null");
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    if (!tokens) return fail(TL_ERR_ARG, "tokens is null");
+    if (c.vocab <= 0) return fail(TL_ERR_SHAPE, "model was created without embedding / lm_head (vocab = 0)");
+    if (n_tokens < 1 || n_tokens > c.max_tokens)
+        return fail(TL_ERR_WINDOW, "n_tokens = %d outside [1, max_tokens = %d]", n_tokens, c.max_tokens);
+    for (int i = 0; i < n_tokens; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab)
+            return fail(TL_ERR_TOKEN_RANGE, "tokens[%d] = %d outside [0, %d)", i, tokens[i], c.vocab);
+    hipStream_t s = m->stream;
+    const int T = n_tokens, d = c.d_model;
+    L->kv_len = 0;
+    memcpy(L->tok_host, tokens, (size_t)T * sizeof(int));
+    HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
+    HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
+    // the chunk path's forward: it leaves q|k|v (q, k rotated) of every position in save[l].qkv, which is the cache
+    for (int l = 0; l < c.n_layers; ++l) TLCHK(layer_forward(L, l, L->hs[l], L->hs[l + 1], T));
+    TLCHK(emit_next(L, L->hs[c.n_layers] + (size_t)(T - 1) * d, next_token, logits_out));
+    L->kv_len = T;
+    return TL_OK;
+}
+
+// One LoRA-adapted projection group of a single token: h = s A x, then y = W x + B h (+ residual)
+static tl_status group_decode(tl_lora* L, int l, int g, const bf16_t* x, bf16_t* y_bf, float* y_f32, const float* resid) {
+    tl_model* m = L->model;
+    hipStream_t s = m->stream;
+    const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
+    const LayerOff& o = L->off[l];
+    HIPCHK(launch_gemv(L->S + o.A[g], din, x, G * r, din, nullptr, nullptr, 0, 0, L->s, nullptr, nullptr, L->lora_h, s));
+    HIPCHK(launch_gemv(m->layers[l].w[g], din, x, G * dout, din, L->S + o.B[g], L->lora_h, r, dout, 1.f, resid, y_bf,
+                       y_f32, s));
+    return TL_OK;
+}
+
+extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_token, float* logits_out) {
+    LIVE(L, "tl_decode_step");
+    if (!next_token) return fail(TL_ERR_ARG, "next_token is null");
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    if (L->kv_len <= 0) return fail(TL_ERR_ARG, "tl_decode_step: no key/value cache (call tl_prefill after every update)");
+    if (L->kv_len >= c.max_tokens) return fail(TL_ERR_WINDOW, "the window is full (%d positions)", c.max_tokens);
+    if (token < 0 || token >= c.vocab) return fail(TL_ERR_TOKEN_RANGE, "token = %d outside [0, %d)", token, c.vocab);
+    hipStream_t s = m->stream;
+    const int d = c.d_model, f = c.d_ffn, p = L->kv_len;
+    L->tok_host[0] = token;
+    HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, sizeof(int), hipMemcpyHostToDevice, s));
+    HIPCHK(launch_embed(m->emb, L->tok, 1, d, L->hs[0], s));
+    for (int l = 0; l < c.n_layers; ++l) {
+        LayerSave& sv = L->save[l];
+        const LayerW& W = m->layers[l];
+        const float* h_in = L->hs[l];
+        float* h_out = L->hs[l + 1];
+        bf16_t* row = sv.qkv + (size_t)p * 3 * d;                 // the new cache row: q | k | v of position p
+        HIPCHK(launch_rmsnorm_fwd(h_in, W.g1, 1, d, c.rms_eps, sv.x1, s));
+        TLCHK(group_decode(L, l, G_QKV, sv.x1, row, nullptr, nullptr));
+        HIPCHK(launch_rope(row, 3L * d, 1, 2 * c.n_heads, c.d_head, c.rope_base, p, +1, m->rope, s));
+        HIPCHK(launch_attention_decode(row, sv.qkv + d, sv.qkv + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o, s));
+        TLCHK(group_decode(L, l, G_O, sv.o, nullptr, sv.hmid, h_in));
+        HIPCHK(launch_rmsnorm_fwd(sv.hmid, W.g2, 1, d, c.rms_eps, sv.x2, s));
+        TLCHK(group_decode(L, l, G_GU, sv.x2, sv.gu, nullptr, nullptr));
+        HIPCHK(launch_swiglu_fwd(sv.gu, 1, f, sv.act, s));
+        TLCHK(group_decode(L, l, G_DOWN, sv.act, nullptr, h_out, sv.hmid));
+    }
+    TLCHK(emit_next(L, L->hs[c.n_layers], next_token, logits_out));
+    L->kv_len = p + 1;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_kv_length(tl_lora* L, int32_t* n_out) {
+    LIVE(L, "tl_kv_length");
+    if (!n_out) return fail(TL_ERR_ARG, "n_out is null");
+    *n_out = L->kv_len;
+    return TL_OK;
+}
+
 extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in, const float* dh_out, int32_t n_tokens,
                                    float* h_out, float* dh_in, float lr, int32_t apply_adamw) {
     LIVE(L, "tl_layer_step");
@@ -671,6 +782,7 @@ extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in,
     if (n_tokens < 1 || n_tokens > c.max_tokens) return fail(TL_ERR_WINDOW, "n_tokens outside [1, max_tokens]");
     if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
     hipStream_t s = L->model->stream;
+    L->kv_len = 0;
     TLCHK(layer_forward(L, layer, h_in, h_out, n_tokens));
     HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf[0], (size_t)n_tokens * c.d_model, s));
     TLCHK(layer_backward(L, layer, h_in, dh_out, L->dh_bf[0], dh_in, nullptr, n_tokens));
@@ -883,6 +995,28 @@ extern "C" tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_hea
 extern "C" tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a, void* hip_stream) {
     KARGS_OK(gu && a && T >= 0 && f > 0 && (f & 7) == 0, "tl_k_swiglu_fwd");
     HIPCHK(launch_swiglu_fwd(gu, T, f, a, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x, int32_t N, int32_t K,
+                               const uint16_t* lora_b, const float* lora_h, int32_t r, int32_t rows_per_group, float alpha,
+                               const float* resid, void* y, int32_t y_f32, void* hip_stream) {
+    KARGS_OK(W && x && y && N >= 0 && K > 0 && (K & 7) == 0 && (ldw & 7) == 0 && (!lora_b || (lora_h && r > 0)) &&
+                 (y_f32 || !resid), "tl_k_gemv");
+    HIPCHK(launch_gemv(W, ldw, x, N, K, lora_b, lora_h, r, rows_per_group, alpha, resid, y_f32 ? nullptr : (bf16_t*)y,
+                       y_f32 ? (float*)y : nullptr, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ld,
+                                           int32_t n_keys, int32_t n_heads, int32_t d_head, uint16_t* o,
+                                           void* hip_stream) {
+    KARGS_OK(q && k && v && o && n_keys > 0 && n_heads > 0 && (d_head == 64 || d_head == 128) && (ld & 7) == 0,
+             "tl_k_attention_decode");
+    HIPCHK(launch_attention_decode(q, k, v, ld, n_keys, n_heads, d_head, o, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_argmax(const float* x, int32_t n, int32_t* out, void* hip_stream) {
+    KARGS_OK(x && out && n > 0, "tl_k_argmax");
+    HIPCHK(launch_argmax(x, n, out, (hipStream_t)hip_stream));
     return TL_OK;
 }
 extern "C" tl_status tl_k_swiglu_bwd(const uint16_t* da, const uint16_t* gu, int32_t T, int32_t f, uint16_t* dgu,

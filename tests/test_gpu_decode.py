@@ -1,0 +1,133 @@
+"""Generation side of Algorithm 1 (greedy decoding with the temporary module over a key/value cache) against the
+oracle, which recomputes the whole window for every token (no cache): logits to the bf16 tolerance at every step, the
+chosen token wherever the oracle's two best logits are further apart than that tolerance allows to confuse, cache
+consistency on the GPU itself, and the error paths."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import templora_oracle as O  # noqa: E402
+from paper_2401_11504_amd import synth  # noqa: E402
+from test_gpu_kernels import BF16_TOL, H, api, check, rnd  # noqa: E402,F401
+
+
+# ------------------------------------------------------------------ kernels
+@pytest.mark.parametrize("N,K,r,G", [(64, 64, 0, 1), (1000, 4096, 16, 1), (3 * 256, 256, 8, 3), (776, 11008, 64, 1)])
+def test_gemv_with_lora_term(api, H, N, K, r, G):
+    W, x = rnd(1, (N, K), 0.05), rnd(2, (1, K))[0]
+    ref = W.astype(np.float64) @ x.astype(np.float64)
+    lb = lh = None
+    if r:
+        lb = rnd(3, (N, r), 0.05)
+        lh = rnd(4, (G, r), 1.0, False)
+        rows = N // G
+        ref = ref + np.concatenate([lb[g * rows:(g + 1) * rows].astype(np.float64) @ lh[g].astype(np.float64) for g in range(G)])
+    res = rnd(5, (1, N), 1.0, False)[0]
+    y32 = torch.empty(N, dtype=torch.float32, device="cuda")
+    ybf = torch.empty(N, dtype=torch.bfloat16, device="cuda")
+    args = dict(lora_b=H.to_dev_bf16(lb) if r else None, lora_h=H.to_dev_f32(lh.reshape(-1)) if r else None, rows_per_group=N // G)
+    api.tl_k_gemv(H.to_dev_bf16(W), H.to_dev_bf16(x), y32, alpha=0.5, resid=H.to_dev_f32(res), **args)
+    api.tl_k_gemv(H.to_dev_bf16(W), H.to_dev_bf16(x), ybf, alpha=1.0, **args)
+    torch.cuda.synchronize()
+    check(y32.cpu().numpy(), 0.5 * ref + res, 1e-4, "y fp32 + resid")      # bf16 products are exact; fp32 sums
+    check(H.bf16_to_np(ybf), ref, BF16_TOL, "y bf16")
+
+
+@pytest.mark.parametrize("n_keys,nh,dh", [(1, 2, 64), (77, 3, 64), (1024, 2, 128), (2048, 1, 128)])
+def test_attention_decode_is_last_row_of_causal_attention(api, H, n_keys, nh, dh):
+    d = nh * dh
+    qkv = rnd(1, (n_keys, 3 * d), 1.0)
+    q, k, v = (qkv[:, i * d:(i + 1) * d].reshape(n_keys, nh, dh) for i in range(3))
+    ro, _ = O.attention_fwd(q, k, v)
+    dev = H.to_dev_bf16(qkv)
+    o = torch.zeros(d, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_attention_decode(dev[n_keys - 1, :d], dev[:, d:2 * d], dev[:, 2 * d:], nh, dh, o)
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(o), ro[-1].reshape(d), BF16_TOL, "o")
+
+
+def test_argmax_lowest_index_among_equals(api, H):
+    x = rnd(1, (1, 32000), 1.0, False)[0]
+    x[[17, 4000, 31999]] = x.max() + 1.0          # three equal maxima
+    out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.tl_k_argmax(H.to_dev_f32(x), out)
+    assert int(out.item()) == 17                   # integer work: exact
+    x[5] = np.inf
+    api.tl_k_argmax(H.to_dev_f32(x), out)
+    assert int(out.item()) == 5
+
+
+# ------------------------------------------------------------------ prefill + decode against the oracle
+def _oracle_args(model, facs):
+    shape = model.shape
+    return (shape, model.emb, model.head, np.ones(shape.d_model), lambda l: model.host_layers[l], facs)
+
+
+@pytest.mark.parametrize("name,n_prompt,n_new", [("small", 37, 12), ("small128", 130, 8)])
+def test_prefill_and_decode_follow_the_oracle(api, H, name, n_prompt, n_new):
+    shape = synth.SHAPES[name]
+    seed = 4100
+    model = H.Model(shape, seed, max_tokens=n_prompt + n_new + 1)
+    lora, facs = H.new_lora(model, seed, b_std=0.01)
+    prompt = synth.zipf_tokens(seed, n_prompt, shape.vocab)
+    seq = [int(t) for t in prompt]
+    nxt, logits = api.tl_prefill(lora, prompt, shape.vocab)
+    assert api.tl_kv_length(lora) == n_prompt
+    for step in range(n_new + 1):
+        ref_next, ref = O.greedy_next(seq, *_oracle_args(model, facs))
+        check(logits, ref, BF16_TOL, f"logits at step {step}")
+        assert nxt == int(np.argmax(logits))                               # the GPU's own argmax: exact
+        top = np.sort(ref)[-2:]
+        if top[1] - top[0] > 4 * BF16_TOL * np.sqrt(np.mean(ref * ref)):    # unambiguous for a bf16 path
+            assert nxt == ref_next, f"step {step}"
+        if step == n_new:
+            break
+        seq.append(nxt)                                                    # teacher forcing with the GPU's choice
+        nxt, logits = api.tl_decode_step(lora, nxt, shape.vocab)
+        assert api.tl_kv_length(lora) == len(seq)
+    # the cache is what a fresh prefill of the same window computes
+    nxt2, logits2 = api.tl_prefill(lora, np.array(seq, np.int32), shape.vocab)
+    check(logits2, logits, 1e-2, "cached decode vs prefill of the whole window")
+    api.tl_lora_free(lora)
+    model.close()
+
+
+def test_decode_lifecycle_and_errors(api, H):
+    shape = synth.SHAPES["small"]
+    model = H.Model(shape, 4200, max_tokens=16)
+    lora, _ = H.new_lora(model, 4200, b_std=0.01)
+    tok = synth.uniform_tokens(4200, 12, shape.vocab)
+    with pytest.raises(api.TlError) as e:
+        api.tl_decode_step(lora, 1)
+    assert e.value.status == -1                                # no cache yet
+    with pytest.raises(api.TlError) as e:
+        api.tl_prefill(lora, np.arange(17) % shape.vocab)
+    assert e.value.status == -4
+    with pytest.raises(api.TlError) as e:
+        api.tl_prefill(lora, np.array([0, shape.vocab]))
+    assert e.value.status == -3
+    nxt, _ = api.tl_prefill(lora, tok)
+    for _ in range(4):
+        nxt, _ = api.tl_decode_step(lora, nxt)
+    assert api.tl_kv_length(lora) == 16
+    with pytest.raises(api.TlError) as e:
+        api.tl_decode_step(lora, nxt)
+    assert e.value.status == -4                             # window full
+    # an update invalidates the cache (the paper recomputes it with the new module)
+    api.tl_chunk_update(lora, tok, 0, 5e-5)
+    assert api.tl_kv_length(lora) == 0
+    with pytest.raises(api.TlError) as e:
+        api.tl_decode_step(lora, 1)
+    assert e.value.status == -1
+    # the updated module changes the continuation's logits; a second prefill is deterministic
+    a1, l1 = api.tl_prefill(lora, tok, shape.vocab)
+    a2, l2 = api.tl_prefill(lora, tok, shape.vocab)
+    assert a1 == a2 and np.array_equal(l1, l2)
+    api.tl_discard(lora)
+    with pytest.raises(api.TlError) as e:
+        api.tl_prefill(lora, tok)
+    assert e.value.status == -7
+    api.tl_lora_free(lora)
+    model.close()

@@ -320,7 +320,7 @@ def test_attention_is_causal():
 
 
 # ---------------------------------------------------------------- whole model
-def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape):
+def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape, want_logits=False):
     """The same network written as an independent autograd graph with library ops.
 
     RoPE is formed as a complex multiplication by exp(i p theta) (a different
@@ -359,6 +359,8 @@ def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape):
         h = h + lin(a, W["down"], L["down"])
     hf = F.rms_norm(h, (shape.d_model,), t64(gf), eps=shape.rms_eps)
     logits = F.linear(hf, t64(head))
+    if want_logits:
+        return logits.detach().numpy()
     lab = torch.full((T,), -100, dtype=torch.int64)
     first = max(n_ctx, 1) - 1
     lab[first: T - 1] = torch.tensor(np.asarray(tok[first + 1:], np.int64))
@@ -507,3 +509,32 @@ def test_layer_dh_matches_autograd():
         num = (np.sum(O.layer_fwd(hp, Ws[0], lora[0], shape)[0] * dy)
                - np.sum(O.layer_fwd(hm, Ws[0], lora[0], shape)[0] * dy)) / (2 * eps)
         assert abs(num - dh[idx]) < 1e-6 * max(1.0, abs(dh[idx]))
+
+
+# ------------------------------------------------------------------ generation side (Algorithm 1, token loop)
+def test_window_logits_match_independent_graph_and_are_causal():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    get = lambda l: Ws[l]
+    lg = O.window_logits(tok, TINY, emb, head, gf, get, lora)
+    ref = _torch_model_loss(Ws, lora, emb, head, gf, tok, 0, TINY, want_logits=True)
+    assert _rel(lg, ref) < 1e-12
+    # a shorter window gives the same rows: what a key/value cache relies on
+    n = len(tok) // 2
+    assert np.allclose(O.window_logits(tok[:n], TINY, emb, head, gf, get, lora), lg[:n], rtol=0, atol=1e-12)
+
+
+def test_greedy_decode_follows_the_largest_logit_and_breaks_ties_low():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    get = lambda l: Ws[l]
+    prompt = list(tok[:5])
+    new = O.greedy_decode(prompt, 6, TINY, emb, head, gf, get, lora)
+    seq = prompt + new
+    for i in range(6):          # every generated id is the library graph's argmax at that point
+        ref = _torch_model_loss(Ws, lora, emb, head, gf, np.array(seq[:5 + i]), 0, TINY, want_logits=True)[-1]
+        assert new[i] == int(np.argmax(ref))
+    head2 = np.array(head, copy=True)
+    nxt, logits = O.greedy_next(prompt, TINY, emb, head2, gf, get, lora)
+    other = (nxt + 3) % TINY.vocab
+    head2[other] = head2[nxt]   # two vocabulary rows with identical logits: the lower index must win
+    n2, l2 = O.greedy_next(prompt, TINY, emb, head2, gf, get, lora)
+    assert l2[other] == l2[nxt] and n2 == min(nxt, other)
