@@ -20,7 +20,21 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ W,
     if (n >= N) return;
     const bf16_t* w = W + (long)n * ldw;
     float acc = 0.f;
-    for (int k = lane * 8; k < K; k += 64 * 8) {
+    int k = lane * 8;
+    for (; k + 3 * 512 < K; k += 4 * 512) {          // four 16-byte loads of the row in flight per lane
+        uint4 wv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wv[u] = *(const uint4*)(w + k + u * 512);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float a[8], b[8];
+            unpack8(wv[u], a);
+            unpack8(*(const uint4*)(sx + k + u * 512), b);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc += a[e] * b[e];
+        }
+    }
+    for (; k < K; k += 512) {
         float a[8], b[8];
         unpack8(*(const uint4*)(w + k), a);
         unpack8(*(const uint4*)(sx + k), b);
@@ -57,50 +71,50 @@ hipError_t launch_gemv(const bf16_t* W, long ldw, const bf16_t* x, int N, int K,
 // One workgroup per head.  q: the query row (already rotated); K, V: rows 0 .. n_keys-1 of the cache with row stride
 // ld (the layout q|k|v of the chunk path, so the cache IS the forward pass's saved projections).  Scores and the
 // softmax are fp32; the output row is written in bf16.
-__global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                                                          const bf16_t* __restrict__ v, long ld, int n_keys, int d_head,
-                                                          float scale, bf16_t* __restrict__ o) {
+__global__ __launch_bounds__(1024) void attn_decode_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                           const bf16_t* __restrict__ v, long ld, int n_keys, int d_head,
+                                                           float scale, bf16_t* __restrict__ o) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sp = (float*)smem;                 // [n_keys] scores, then probabilities
-    float* sq = sp + ((n_keys + 3) & ~3);     // [d_head] query in fp32
+    float* part_buf = sp + ((n_keys + 3) & ~3);   // [parts][d_head] partial outputs
     __shared__ float red[16];
-    const int head = blockIdx.x, tid = threadIdx.x;
+    const int head = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
     const bf16_t* qh = q + (long)head * d_head;
     const bf16_t* kh = k + (long)head * d_head;
     const bf16_t* vh = v + (long)head * d_head;
-    for (int i = tid; i < d_head; i += blockDim.x) sq[i] = bf16_to_f32(qh[i]);
-    __syncthreads();
+    // scores: a key row (d_head * 2 bytes, contiguous) is read by d_head / 8 adjacent lanes, 16 bytes each
+    const int lpk = d_head >> 3, sub = tid % lpk, kpp = nthr / lpk;   // lanes per key, keys per pass
+    float qv[8];
+    unpack8(*(const uint4*)(qh + sub * 8), qv);
     float mx = -1.0e30f;
-    for (int u = tid; u < n_keys; u += blockDim.x) {
-        const bf16_t* kr = kh + (long)u * ld;
+    for (int u0 = 0; u0 < n_keys; u0 += kpp) {
+        const int u = u0 + tid / lpk;
         float sdot = 0.f;
-        for (int i = 0; i < d_head; i += 8) {
+        if (u < n_keys) {
             float a[8];
-            unpack8(*(const uint4*)(kr + i), a);
+            unpack8(*(const uint4*)(kh + (long)u * ld + sub * 8), a);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sdot += a[e] * sq[i + e];
+            for (int e = 0; e < 8; ++e) sdot += a[e] * qv[e];
         }
-        sdot *= scale;
-        sp[u] = sdot;
-        mx = fmaxf(mx, sdot);
+        for (int off = lpk >> 1; off > 0; off >>= 1) sdot += __shfl_xor(sdot, off, 64);
+        if (u < n_keys && sub == 0) sp[u] = sdot * scale;
     }
+    __syncthreads();
+    for (int u = tid; u < n_keys; u += nthr) mx = fmaxf(mx, sp[u]);
     mx = block_max(mx, red);
     float sum = 0.f;
-    for (int u = tid; u < n_keys; u += blockDim.x) {
+    for (int u = tid; u < n_keys; u += nthr) {
         const float p = __expf(sp[u] - mx);
         sp[u] = p;
         sum += p;
     }
     sum = block_sum(sum, red);
     __syncthreads();
-    // thread (c, part): column c of the head, keys part, part + parts, ..
-    const int parts = blockDim.x / d_head, c = tid % d_head, part = tid / d_head;
+    // thread (c, part): column c of the head over keys part, part + parts, .. (a V row is read by d_head adjacent lanes)
+    const int parts = nthr / d_head, c = tid % d_head, part = tid / d_head;
     float acc = 0.f;
-    if (part < parts)
-        for (int u = part; u < n_keys; u += parts) acc += sp[u] * bf16_to_f32(vh[(long)u * ld + c]);
-    __syncthreads();                          // every thread is done with the query: its LDS region is reused
-    float* part_buf = sq;                     // [parts][d_head] partial outputs (the launcher sizes the region for it)
-    if (part < parts) part_buf[part * d_head + c] = acc;
+    for (int u = part; u < n_keys; u += parts) acc += sp[u] * bf16_to_f32(vh[(long)u * ld + c]);
+    part_buf[part * d_head + c] = acc;
     __syncthreads();
     if (tid < d_head) {
         float t = 0.f;
@@ -113,12 +127,13 @@ hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_
                                    int d_head, bf16_t* o, hipStream_t s) {
     if (n_keys <= 0 || n_heads <= 0) return hipErrorInvalidValue;
     if ((d_head != 64 && d_head != 128) || (ld & 7)) return hipErrorInvalidValue;
-    const int parts = 256 / d_head;
+    const int nthr = n_keys > 128 ? 1024 : 256;
+    const int parts = nthr / d_head;
     const size_t lds = ((size_t)((n_keys + 3) & ~3) + (size_t)parts * d_head) * sizeof(float);
     if (lds > 150 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)attn_decode_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attn_decode_kernel<<<n_heads, 256, lds, s>>>(q, k, v, ld, n_keys, d_head, 1.f / sqrtf((float)d_head), o);
+    attn_decode_kernel<<<n_heads, nthr, lds, s>>>(q, k, v, ld, n_keys, d_head, 1.f / sqrtf((float)d_head), o);
     return hipGetLastError();
 }
 

@@ -131,3 +131,38 @@ def test_decode_lifecycle_and_errors(api, H):
     assert e.value.status == -7
     api.tl_lora_free(lora)
     model.close()
+
+
+def test_algorithm1_stream_decode_then_update(api, H):
+    """Algorithm 1 end to end at a small size: decode a chunk greedily over the window, train the module on
+    (preceding L_T tokens -> chunk) for two epochs, rebuild the cache from the last L_X tokens with the updated module,
+    and go on.  The oracle replays the same token stream (teacher forcing with the GPU's choices) with its own module
+    and AdamW state, so every step's logits are compared under an independently evolved module."""
+    shape = synth.SHAPES["small"]
+    seed, L_X, L_T, DELTA, N_CHUNKS, EPOCHS, lr = 4300, 24, 24, 16, 2, 2, 5e-5
+    model = H.Model(shape, seed, max_tokens=L_X + DELTA)
+    lora, facs = H.new_lora(model, seed, b_std=0.01)
+    args = lambda f: (shape, model.emb, model.head, np.ones(shape.d_model), lambda l: model.host_layers[l], f)
+    opt = O.new_opt_state(facs)
+    stream = [int(t) for t in synth.zipf_tokens(seed, L_X, shape.vocab)]
+    for k in range(N_CHUNKS):
+        window = stream[-L_X:]
+        nxt, logits = api.tl_prefill(lora, np.array(window, np.int32), shape.vocab)
+        for i in range(DELTA):
+            _, ref = O.greedy_next(window, *args(facs))
+            check(logits, ref, BF16_TOL, f"chunk {k} token {i}")
+            window.append(nxt)
+            stream.append(nxt)
+            if i + 1 < DELTA:
+                nxt, logits = api.tl_decode_step(lora, nxt, shape.vocab)
+        sample = np.array(stream[-(L_T + DELTA):], np.int32)               # X_T followed by the chunk
+        for e in range(EPOCHS):
+            loss, n = api.tl_chunk_update(lora, sample, L_T, lr)
+            res, facs, opt = O.chunk_update(sample, L_T, *args(facs)[:5], facs, opt, lr)
+            assert n == res["n_targets"] == DELTA
+            assert abs(loss - res["loss"]) <= BF16_TOL * res["loss"], (k, e, loss, res["loss"])
+        assert api.tl_kv_length(lora) == 0                                 # the cache must be rebuilt with the new module
+    assert api.tl_get_step(lora) == N_CHUNKS * EPOCHS
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
