@@ -133,6 +133,40 @@ tl_status tl_chunk_update(tl_lora* lora, const int32_t* tokens, int32_t n_tokens
 tl_status tl_chunk_loss(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float* loss_out,
                         int32_t* n_targets_out);
 
+/*
+ * The whole module update for one chunk: Algorithm 1's "Train Theta_k" with the
+ * Section 3 "Setup" recipe (n epochs, linear learning-rate warm-up) and the batch
+ * sizes of Table 5 (a chunk of Delta tokens trained in Delta / batch steps per epoch).
+ *   tokens  : host int32[n_tokens]; the LAST n_chunk tokens are the chunk, whatever
+ *             precedes them is text the stream already holds (conditioning only).
+ *   The chunk is cut into consecutive pieces of cfg->batch tokens (the last may be
+ *   shorter; batch = 0 or >= n_chunk means one piece).  Each piece is one training
+ *   sample: the up to cfg->n_ctx_max tokens before the piece (L_T; earlier pieces
+ *   of the same chunk included) as conditioning, loss on the piece only; one
+ *   AdamW step per piece, pieces in order, the whole pass repeated cfg->epochs times.
+ *   The rate of each step is tl_warmup_lr(cfg->lr, step counter, cfg->warmup_steps).
+ *   losses_out : host fp32[epochs * ceil(n_chunk / batch)] or NULL: the loss of each step, in order.
+ *   n_steps_out: steps completed (also written when a later step fails), or NULL.
+ * All samples are validated before the first step (TL_ERR_ARG, TL_ERR_WINDOW: a sample
+ * longer than max_tokens or without a target, TL_ERR_TOKEN_RANGE): then nothing
+ * changes.  A non-finite loss in step i returns TL_ERR_NONFINITE with the first i
+ * steps applied.
+ */
+typedef struct {
+    int32_t n_ctx_max;    /* L_T (Setup: 1024) */
+    int32_t batch;        /* tokens per optimizer step; 0 = the whole chunk */
+    int32_t epochs;       /* n (Setup: 2) */
+    int32_t warmup_steps; /* optimizer steps of linear warm-up, counted over the module's life; 0 = none.
+                             Setup warms up over the first 2 chunks: 2 * epochs * pieces. */
+    float lr;             /* peak learning rate (Setup: 5e-5) */
+} tl_train_cfg;
+tl_status tl_chunk_train(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int32_t n_chunk,
+                         const tl_train_cfg* cfg, float* losses_out, int32_t* n_steps_out);
+
+/* Linear warm-up (Setup): the rate of the optimizer step with 0-based index `step`
+ * is lr * min(1, (step + 1) / warmup_steps); lr itself if warmup_steps <= 0. */
+float tl_warmup_lr(float lr, int64_t step, int32_t warmup_steps);
+
 /* Destroy the module (Algorithm 1, last line: Theta_k <- Theta).  Frees all its
  * device memory; the handle stays valid only for tl_lora_free and makes every
  * other call return TL_ERR_DISCARDED.  The base model is untouched by design. */

@@ -20,7 +20,10 @@ independent autograd graph agree with every gradient; the loss is a valid NLL
 (ln V on uniform logits, agreement with a library log-softmax); AdamW agrees
 with its step-1 closed form and with a library optimizer over several steps;
 RoPE and RMSNorm invariants; causality; window_logits agrees with the autograd
-graph's logits and is causal (a longer window leaves earlier rows unchanged).  Absolute loss / gradient values at the
+graph's logits and is causal (a longer window leaves earlier rows unchanged);
+chunk_train's samples cover every chunk position exactly once per epoch with at
+most L_T conditioning tokens, its warm-up is checked against hand-computed
+rates, and with one piece, one epoch and no warm-up it is chunk_update.  Absolute loss / gradient values at the
 workload shapes are printed nowhere in the paper: they are pinned only through
 these properties.
 
@@ -354,6 +357,44 @@ def chunk_update(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, opt,
             Ll[p], Ml[p], Vl[p] = tuple(facs), tuple(ms), tuple(vs)
         new_lora.append(Ll), new_m.append(Ml), new_v.append(Vl)
     return res, new_lora, {"tau": tau, "m": new_m, "v": new_v}
+
+
+# --------------------------------------------------------------------------
+# The whole module update for one chunk (Algorithm 1, "Train Theta_k"; Section 3 "Setup": n epochs,
+# linear warm-up; Table 5: a chunk of Delta tokens trained in Delta / batch steps per epoch).
+# --------------------------------------------------------------------------
+def warmup_lr(lr: float, step: int, warmup_steps: int) -> float:
+    """Rate of the optimizer step with 0-based index `step`: rises linearly and reaches lr at step warmup_steps - 1."""
+    if warmup_steps <= 0:
+        return lr
+    return lr * min(1.0, (max(step, 0) + 1) / warmup_steps)
+
+
+def training_samples(n_before: int, n_chunk: int, L_T: int, batch: int):
+    """[(first token, n_ctx, end)] of one epoch: the chunk occupies positions n_before .. n_before + n_chunk - 1 of the
+    stream; each piece of `batch` chunk tokens is trained with the up to L_T tokens before it as conditioning."""
+    if batch <= 0 or batch > n_chunk:
+        batch = n_chunk
+    out = []
+    for start in range(n_before, n_before + n_chunk, batch):
+        end = min(start + batch, n_before + n_chunk)
+        n_ctx = min(start, L_T)
+        out.append((start - n_ctx, n_ctx, end))
+    return out
+
+
+def chunk_train(tokens, n_chunk, L_T, batch, epochs, lr, warmup_steps, shape, emb, head, g_final, get_layer, lora, opt,
+                beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0):
+    """-> (losses of every step in order, new lora, new opt).  tokens: the stream so far, the chunk last."""
+    tok = np.asarray(tokens, dtype=np.int64)
+    losses = []
+    for _ in range(epochs):
+        for first, n_ctx, end in training_samples(tok.size - n_chunk, n_chunk, L_T, batch):
+            rate = warmup_lr(lr, opt["tau"], warmup_steps)
+            res, lora, opt = chunk_update(tok[first:end], n_ctx, shape, emb, head, g_final, get_layer, lora, opt, rate,
+                                          beta1, beta2, eps, wd)
+            losses.append(res["loss"])
+    return losses, lora, opt
 
 
 def linear_step(X, W, A, B, dY, s, lr, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0):

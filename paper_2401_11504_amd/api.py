@@ -47,6 +47,11 @@ class tl_lora_cfg(C.Structure):
                 ("eps", C.c_float), ("weight_decay", C.c_float), ("a_init_std", C.c_float), ("seed", C.c_uint64)]
 
 
+class tl_train_cfg(C.Structure):
+    _fields_ = [("n_ctx_max", C.c_int32), ("batch", C.c_int32), ("epochs", C.c_int32), ("warmup_steps", C.c_int32),
+                ("lr", C.c_float)]
+
+
 _vp, _i32, _i64, _f32, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
 _SIGS = {
     "tl_model_create": [C.POINTER(tl_model_cfg), C.POINTER(_vp), _vp, C.POINTER(_vp)],
@@ -54,6 +59,7 @@ _SIGS = {
     "tl_lora_init": [_vp, C.POINTER(tl_lora_cfg), C.POINTER(_vp)],
     "tl_chunk_update": [_vp, _vp, _i32, _i32, _f32, C.POINTER(_f32), C.POINTER(_i32)],
     "tl_chunk_loss": [_vp, _vp, _i32, _i32, C.POINTER(_f32), C.POINTER(_i32)],
+    "tl_chunk_train": [_vp, _vp, _i32, _i32, C.POINTER(tl_train_cfg), _vp, C.POINTER(_i32)],
     "tl_prefill": [_vp, _vp, _i32, C.POINTER(_i32), _vp],
     "tl_decode_step": [_vp, _i32, C.POINTER(_i32), _vp],
     "tl_kv_length": [_vp, C.POINTER(_i32)],
@@ -84,11 +90,13 @@ _SIGS = {
     "tl_k_adamw": [_vp, _vp, _vp, _vp, _vp, _sz, _i64, _f32, _f32, _f32, _f32, _f32, _vp],
     "tl_k_embed": [_vp, _vp, _i32, _i32, _vp, _vp],
 }
-EXPORTS = tuple(_SIGS) + ("tl_last_error", "tl_version")
+EXPORTS = tuple(_SIGS) + ("tl_warmup_lr", "tl_last_error", "tl_version")
 for _n, _a in _SIGS.items():
     _f = getattr(_lib, _n)
     _f.argtypes = _a
     _f.restype = C.c_int
+_lib.tl_warmup_lr.argtypes = [_f32, _i64, _i32]
+_lib.tl_warmup_lr.restype = _f32
 _lib.tl_last_error.restype = C.c_char_p
 _lib.tl_version.restype = C.c_char_p
 
@@ -162,6 +170,21 @@ def tl_chunk_loss(lora, tokens, n_ctx=0):
     loss, n = _f32(), _i32()
     _chk(_lib.tl_chunk_loss(lora, p, a.size, n_ctx, C.byref(loss), C.byref(n)))
     return loss.value, n.value
+
+
+def tl_chunk_train(lora, tokens, n_chunk, n_ctx_max=1024, batch=0, epochs=2, lr=5e-5, warmup_steps=0):
+    """-> list of per-step losses (epochs * ceil(n_chunk / batch) of them)"""
+    a, p = _tok(tokens)
+    cfg = tl_train_cfg(n_ctx_max, batch, epochs, warmup_steps, lr)
+    b = batch if 0 < batch < n_chunk else max(n_chunk, 1)
+    losses = np.zeros(max(epochs, 1) * (-(-max(n_chunk, 1) // b)), dtype=np.float32)
+    n = _i32()
+    _chk(_lib.tl_chunk_train(lora, p, a.size, n_chunk, C.byref(cfg), losses.ctypes.data_as(_vp), C.byref(n)))
+    return [float(x) for x in losses[:n.value]]
+
+
+def tl_warmup_lr(lr, step, warmup_steps):
+    return float(_lib.tl_warmup_lr(lr, step, warmup_steps))
 
 
 def tl_prefill(lora, tokens, vocab=0):

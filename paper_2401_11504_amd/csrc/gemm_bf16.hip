@@ -615,15 +615,27 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
             const long t256 = (long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
             const long t256x128 = (long)cdiv(g.M, 256) * cdiv(g.N, 128) * g.batch;
             auto fill = [](long t) { return (double)t / (double)(((t + 255) / 256) * 256); };
-            // few tiles but a long contraction: 256x128 tiles with the contraction split in two give every CU a tile
-            // with three quarters of the operand bytes per flop of a 128x128 one (the loop is bound by the rate at
-            // which a CU can pull operand bytes in, not by the matrix pipe); the fp32 partials cost one extra pass,
-            // which pays from K of about 10k on (measured: K 11008 -7 %, 12288 -13 %, 22016 -17 %, 32000 -15 %)
-            const long need = (long)2 * g.M * g.N * g.batch;
-            if (t256 < 160 && fill(2 * t256x128) >= 0.85 && nk >= 160 && g.partial && (size_t)need <= g.partial_elems &&
-                (g.N & 3) == 0)
-                cfg = 45;
-            else if (t256 < 160) cfg = 25;
+            // Few 256x256 tiles: pick among 128x128 tiles, 256x128 tiles, and 256x128 tiles with the contraction split
+            // 2..4 ways, by the operand bytes the busiest CU has to pull in (the loop is bound by that rate, about
+            // 53 GB/s per CU, not by the matrix pipe): rounds of tiles x (BM + BN) x K x 2 bytes.  A split adds one
+            // pass over its fp32 partials (written and read back at about 5 TB/s, plus a launch).  At M = 1024 this
+            // picks the two-way split from K of about 10k on (measured: K 11008 -7 %, 12288 -13 %, 22016 -17 %,
+            // 32000 -15 % against 128x128) and 128x128 below; at M = 2048 plain 256x128 tiles fill the chip.
+            if (t256 < 160) {
+                const double ktot = (double)g.K + g.K2, per_us = 53e3;
+                auto rounds = [](long t) { return (double)((t + 255) / 256); };
+                double best = rounds(t128) * 256.0 * ktot * 2.0 / per_us;
+                cfg = 25;
+                const double c28 = rounds(t256x128) * 384.0 * ktot * 2.0 / per_us;
+                if (c28 < best) { best = c28; cfg = 28; }
+                for (int sp = 2; sp <= 4; ++sp) {
+                    const size_t need = (size_t)sp * g.M * g.N * g.batch;
+                    if (!g.partial || need > g.partial_elems || (g.N & 3) || nk / sp < 8) continue;
+                    const double c = rounds(t256x128 * sp) * 384.0 * (ktot / sp) * 2.0 / per_us +
+                                     (double)need * 8.0 / 5e6 + 5.0;
+                    if (c < 0.97 * best) { best = c; cfg = 43 + sp; }   // 45, 46, 47 = split 2, 3, 4
+                }
+            }
             else if (fill(t256) >= 0.9) cfg = 6;
             else if (fill(t256x128) >= 0.85) cfg = 28;
             else cfg = g.batch > 1 ? 22 : 6;
@@ -659,8 +671,8 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
                 if (!g.partial || (size_t)sp * g.M * g.N * g.batch > g.partial_elems || (g.N & 3)) return hipErrorInvalidValue;
                 return run_nt_dl<256, 256, 4, 2, 4, 0, 32, true, 1>(g, s, sp);
             }
-            case 45: case 46: {
-                const int sp = cfg == 45 ? 2 : 4;
+            case 45: case 46: case 47: {
+                const int sp = cfg - 43;
                 if (!g.partial || (size_t)sp * g.M * g.N * g.batch > g.partial_elems || (g.N & 3)) return hipErrorInvalidValue;
                 return run_nt_dl<256, 128, 4, 2, 3, 0, 64, true, 1>(g, s, sp);
             }

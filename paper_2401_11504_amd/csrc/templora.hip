@@ -640,12 +640,9 @@ extern "C" tl_status tl_chunk_loss(tl_lora* L, const int32_t* tokens, int32_t n_
     return TL_OK;
 }
 
-extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float lr,
-                                     float* loss_out, int32_t* n_targets_out) {
-    LIVE(L, "tl_chunk_update");
-    if (!loss_out) return fail(TL_ERR_ARG, "loss_out is null");
-    if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
-    TLCHK(check_tokens(L, tokens, n_tokens, n_ctx));
+// One optimizer step on an already validated sample (forward, loss, backward, AdamW).
+static tl_status update_step(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float lr,
+                             float* loss_out, int32_t* n_targets_out) {
     tl_model* m = L->model;
     const tl_model_cfg& c = m->cfg;
     hipStream_t s = m->stream;
@@ -673,6 +670,68 @@ extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t 
     L->step += 1;
     *loss_out = loss;
     if (n_targets_out) *n_targets_out = N;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_chunk_update(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float lr,
+                                     float* loss_out, int32_t* n_targets_out) {
+    LIVE(L, "tl_chunk_update");
+    if (!loss_out) return fail(TL_ERR_ARG, "loss_out is null");
+    if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
+    TLCHK(check_tokens(L, tokens, n_tokens, n_ctx));
+    return update_step(L, tokens, n_tokens, n_ctx, lr, loss_out, n_targets_out);
+}
+
+// Rate of the optimizer step with 0-based index `step` under a linear warm-up over `warmup_steps` steps.
+extern "C" float tl_warmup_lr(float lr, int64_t step, int32_t warmup_steps) {
+    if (warmup_steps <= 0 || step + 1 >= (int64_t)warmup_steps) return lr;
+    if (step < 0) step = 0;
+    return (float)((double)lr * (double)(step + 1) / (double)warmup_steps);
+}
+
+// The whole module update for one chunk (Algorithm 1, "Train Theta_k"; Table 5's batch sizes): n epochs over the
+// chunk, each epoch cut into pieces of `batch` tokens, one optimizer step per piece.
+extern "C" tl_status tl_chunk_train(tl_lora* L, const int32_t* tokens, int32_t n_tokens, int32_t n_chunk,
+                                    const tl_train_cfg* cfg, float* losses_out, int32_t* n_steps_out) {
+    LIVE(L, "tl_chunk_train");
+    if (!cfg) return fail(TL_ERR_ARG, "cfg is null");
+    if (!tokens) return fail(TL_ERR_ARG, "tokens is null");
+    const tl_model_cfg& c = L->model->cfg;
+    if (c.vocab <= 0) return fail(TL_ERR_SHAPE, "model was created without embedding / lm_head (vocab = 0)");
+    if (!(cfg->lr >= 0.f) || !std::isfinite(cfg->lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
+    if (cfg->epochs < 1) return fail(TL_ERR_ARG, "epochs = %d must be >= 1", cfg->epochs);
+    if (cfg->n_ctx_max < 0 || cfg->batch < 0 || cfg->warmup_steps < 0)
+        return fail(TL_ERR_ARG, "n_ctx_max, batch and warmup_steps must be >= 0");
+    if (n_chunk < 1 || n_chunk > n_tokens)
+        return fail(TL_ERR_WINDOW, "n_chunk = %d outside [1, n_tokens = %d]", n_chunk, n_tokens);
+    const int batch = cfg->batch > 0 && cfg->batch < n_chunk ? cfg->batch : n_chunk;
+    const int n_before = n_tokens - n_chunk;
+    const int pieces = (n_chunk + batch - 1) / batch;
+    // every sample is checked before the first step, so that an error leaves the module as it was
+    for (int j = 0; j < pieces; ++j) {
+        const int start = n_before + j * batch, end = std::min(start + batch, n_tokens);
+        const int ctx = std::min(start, cfg->n_ctx_max);
+        if (end - (start - ctx) > c.max_tokens)
+            return fail(TL_ERR_WINDOW, "piece %d: %d conditioning + %d chunk tokens exceed max_tokens = %d", j, ctx,
+                        end - start, c.max_tokens);
+        if (end - (start - ctx) < 2)
+            return fail(TL_ERR_WINDOW, "piece %d has a single token and nothing before it: no prediction target", j);
+    }
+    for (int i = 0; i < n_tokens; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab)
+            return fail(TL_ERR_TOKEN_RANGE, "tokens[%d] = %d outside [0, %d)", i, tokens[i], c.vocab);
+    int steps = 0;
+    for (int e = 0; e < cfg->epochs; ++e)
+        for (int j = 0; j < pieces; ++j) {
+            const int start = n_before + j * batch, end = std::min(start + batch, n_tokens);
+            const int ctx = std::min(start, cfg->n_ctx_max);
+            float loss = 0.f;
+            const float lr = tl_warmup_lr(cfg->lr, L->step, cfg->warmup_steps);
+            TLCHK(update_step(L, tokens + (start - ctx), end - (start - ctx), ctx, lr, &loss, nullptr));
+            if (losses_out) losses_out[steps] = loss;
+            ++steps;
+            if (n_steps_out) *n_steps_out = steps;
+        }
     return TL_OK;
 }
 

@@ -1,0 +1,116 @@
+"""tl_chunk_train: the whole module update for one chunk (n epochs, Table 5's batch sizes, Setup's linear
+warm-up) through the C ABI, against the oracle's chunk_train on the same seeded stream."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+
+from oracle import templora_oracle as O  # noqa: E402
+from paper_2401_11504_amd import synth  # noqa: E402
+from test_gpu_kernels import BF16_TOL, H, api, check  # noqa: E402,F401
+
+pytestmark = pytest.mark.gpu
+PROJ = synth.PROJ
+ERR_ARG, ERR_TOKEN_RANGE, ERR_WINDOW = -1, -3, -4
+
+
+def _oracle_train(model, facs, opt, tok, n_chunk, L_T, batch, epochs, lr, wu):
+    shape = model.shape
+    return O.chunk_train(tok, n_chunk, L_T, batch, epochs, lr, wu, shape, model.emb, model.head,
+                         np.ones(shape.d_model), lambda l: model.host_layers[l], facs, opt)
+
+
+@pytest.mark.parametrize("n_before,n_chunk,L_T,batch,epochs,wu", [
+    (40, 96, 32, 32, 2, 4),      # Table 5's layout in small: three pieces per epoch, warm-up over the first four steps
+    (0, 70, 48, 32, 2, 0),       # stream start: first piece has no conditioning, last piece is ragged (6 tokens)
+    (64, 64, 64, 0, 2, 0),       # batch = chunk: the paper's default (one step per epoch)
+    (10, 33, 0, 16, 1, 2),       # L_T = 0: every piece stands alone; a one-token tail piece would have no target
+])
+def test_chunk_train_matches_oracle(api, H, n_before, n_chunk, L_T, batch, epochs, wu):
+    shape = synth.SHAPES["small"]
+    seed, lr = 5100 + n_chunk, 2e-3
+    if L_T == 0 and n_chunk % batch == 1:
+        n_chunk += 1
+    model = H.Model(shape, seed, max_tokens=L_T + (batch if batch > 0 else n_chunk))
+    lora, facs = H.new_lora(model, seed, b_std=0.01)
+    tok = synth.zipf_tokens(seed, n_before + n_chunk, shape.vocab)
+    losses = api.tl_chunk_train(lora, tok, n_chunk, L_T, batch, epochs, lr, wu)
+    ref, new, opt = _oracle_train(model, facs, O.new_opt_state(facs), tok, n_chunk, L_T, batch, epochs, lr, wu)
+    assert len(losses) == len(ref) == opt["tau"] == api.tl_get_step(lora)      # step counts: exact
+    assert np.allclose(losses, ref, rtol=BF16_TOL, atol=0), (losses, ref)
+    for l in range(shape.n_layers):
+        for i, p in enumerate(PROJ):
+            dout, din = shape.proj_dims(p)
+            # AdamW's early steps are sign-like: an entry whose tiny gradient flips sign between the two sides ends a
+            # few lr apart, so the factors are compared in the L2 sense, the first moments two-sided.
+            Bg = api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank))
+            Bo = np.asarray(new[l][p][1], np.float64)
+            assert np.linalg.norm(Bg - Bo) / np.linalg.norm(Bo) <= 5e-2, f"B l{l} {p}"
+            check(api.tl_get_factor(lora, l, i, api.M_B, (dout, shape.rank)), opt["m"][l][p][1], 5e-2, f"mB l{l} {p}")
+            check(api.tl_get_factor(lora, l, i, api.M_A, (shape.rank, din)), opt["m"][l][p][0], 5e-2, f"mA l{l} {p}")
+    api.tl_lora_free(lora)
+    model.close()
+
+
+def test_chunk_train_equals_the_same_steps_made_by_hand(api, H):
+    """Bit-exact against tl_chunk_update called on the same windows with the same rates (integer / host work of
+    tl_chunk_train: piece boundaries, conditioning length, warm-up)."""
+    shape = synth.SHAPES["small"]
+    seed, n_before, n_chunk, L_T, batch, epochs, lr, wu = 5200, 21, 50, 30, 20, 2, 1e-3, 5
+    model = H.Model(shape, seed, max_tokens=L_T + batch)
+    tok = synth.zipf_tokens(seed, n_before + n_chunk, shape.vocab)
+    la, _ = H.new_lora(model, seed, b_std=0.01)
+    lb, _ = H.new_lora(model, seed, b_std=0.01)
+    losses = api.tl_chunk_train(la, tok, n_chunk, L_T, batch, epochs, lr, wu)
+    by_hand, step = [], 0
+    for _ in range(epochs):
+        for start in (21, 41, 61):
+            end, ctx = min(start + batch, len(tok)), min(start, L_T)
+            rate = lr * min(1.0, (step + 1) / wu)
+            by_hand.append(api.tl_chunk_update(lb, tok[start - ctx:end], ctx, api.tl_warmup_lr(lr, step, wu))[0])
+            assert abs(api.tl_warmup_lr(lr, step, wu) - rate) <= 1e-7 * lr
+            step += 1
+    assert losses == by_hand
+    for l in range(shape.n_layers):
+        for i, p in enumerate(PROJ):
+            dout, din = shape.proj_dims(p)
+            for sel, shp in ((api.FACTOR_A, (shape.rank, din)), (api.FACTOR_B, (dout, shape.rank))):
+                assert np.array_equal(api.tl_get_factor(la, l, i, sel, shp), api.tl_get_factor(lb, l, i, sel, shp))
+    for h in (la, lb):
+        api.tl_lora_free(h)
+    model.close()
+
+
+def test_chunk_train_errors_leave_the_module_unchanged(api, H):
+    shape = synth.SHAPES["small"]
+    model = H.Model(shape, 5300, max_tokens=48)
+    lora, facs = H.new_lora(model, 5300, b_std=0.01)
+    tok = synth.zipf_tokens(5300, 80, shape.vocab)
+    bad = np.array(tok, copy=True)
+    bad[-1] = shape.vocab
+    cases = [
+        (lambda: api.tl_chunk_train(lora, tok, 64, 32, 32, 2, 1e-3, 0), ERR_WINDOW),     # 32 + 32 > 48
+        (lambda: api.tl_chunk_train(lora, tok, 0, 16, 16, 2, 1e-3, 0), ERR_WINDOW),      # empty chunk
+        (lambda: api.tl_chunk_train(lora, tok, 81, 16, 16, 2, 1e-3, 0), ERR_WINDOW),     # chunk longer than the text
+        (lambda: api.tl_chunk_train(lora, tok, 32, 16, 16, 0, 1e-3, 0), ERR_ARG),        # no epochs
+        (lambda: api.tl_chunk_train(lora, tok, 32, 16, 16, 2, float("nan"), 0), ERR_ARG),
+        (lambda: api.tl_chunk_train(lora, tok, 32, -1, 16, 2, 1e-3, 0), ERR_ARG),
+        (lambda: api.tl_chunk_train(lora, bad, 32, 16, 16, 2, 1e-3, 0), ERR_TOKEN_RANGE),
+        (lambda: api.tl_chunk_train(lora, tok[:33], 33, 0, 16, 1, 1e-3, 0), ERR_WINDOW),  # lone last token, L_T = 0
+    ]
+    for fn, code in cases:
+        with pytest.raises(api.TlError) as e:
+            fn()
+        assert e.value.status == code, (e.value.status, code, str(e.value))
+    assert api.tl_get_step(lora) == 0
+    for l in range(shape.n_layers):
+        for i, p in enumerate(PROJ):
+            dout, din = shape.proj_dims(p)
+            assert np.array_equal(api.tl_get_factor(lora, l, i, api.FACTOR_A, (shape.rank, din)),
+                                  np.asarray(facs[l][p][0], np.float32))
+    assert len(api.tl_chunk_train(lora, tok, 32, 16, 16, 2, 1e-3, 0)) == 4                      # and it still works
+    api.tl_lora_free(lora)
+    model.close()

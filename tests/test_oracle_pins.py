@@ -538,3 +538,75 @@ def test_greedy_decode_follows_the_largest_logit_and_breaks_ties_low():
     head2[other] = head2[nxt]   # two vocabulary rows with identical logits: the lower index must win
     n2, l2 = O.greedy_next(prompt, TINY, emb, head2, gf, get, lora)
     assert l2[other] == l2[nxt] and n2 == min(nxt, other)
+
+
+# ------------------------------------------------------------------ the whole module update for one chunk
+def test_training_samples_hand_example_and_exact_cover():
+    # 5 tokens of earlier text, a 7-token chunk in pieces of 3, at most 4 conditioning tokens
+    assert O.training_samples(5, 7, 4, 3) == [(1, 4, 8), (4, 4, 11), (7, 4, 12)]
+    assert O.training_samples(0, 4, 8, 0) == [(0, 0, 4)]          # batch 0: the whole chunk, nothing before it
+    for n_before in (0, 3, 20):
+        for n_chunk in range(1, 10):
+            for L_T in (0, 4, 100):
+                for batch in (0, 1, 2, 3, 4, 100):
+                    seen = []
+                    for first, n_ctx, end in O.training_samples(n_before, n_chunk, L_T, batch):
+                        assert 0 <= first and n_ctx <= L_T and n_ctx == min(first + n_ctx, L_T)
+                        mask = O.labels_and_mask(np.zeros(end - first, np.int64), n_ctx)[1]
+                        seen += [first + t + 1 for t in np.nonzero(mask)[0]]   # stream positions that are predicted
+                    # every chunk token is predicted exactly once, in order; the exceptions are tokens with nothing
+                    # before them in their sample: the stream's first token, and with L_T = 0 each piece's first
+                    firsts = {f for f, c, _ in O.training_samples(n_before, n_chunk, L_T, batch) if c == 0}
+                    want = [p for p in range(n_before, n_before + n_chunk) if p not in firsts]
+                    assert seen == want, (n_before, n_chunk, L_T, batch)
+                    assert L_T == 0 or firsts <= {0}
+
+
+def test_warmup_lr_hand_values():
+    assert [O.warmup_lr(8.0, i, 4) for i in range(6)] == [2.0, 4.0, 6.0, 8.0, 8.0, 8.0]
+    assert O.warmup_lr(8.0, 0, 0) == 8.0 and O.warmup_lr(8.0, 0, 1) == 8.0
+
+
+def test_chunk_train_one_piece_one_epoch_is_chunk_update():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    get = lambda l: Ws[l]
+    r, l1, o1 = O.chunk_update(tok[2:], 3, TINY, emb, head, gf, get, lora, O.new_opt_state(lora), lr=1e-3)
+    losses, l2, o2 = O.chunk_train(tok, len(tok) - 5, 3, 0, 1, 1e-3, 0, TINY, emb, head, gf, get, lora,
+                                   O.new_opt_state(lora))
+    assert losses == [r["loss"]] and o2["tau"] == 1
+    for l in range(TINY.n_layers):
+        for p in PROJ:
+            for i in (0, 1):
+                assert np.array_equal(l1[l][p][i], l2[l][p][i])
+
+
+def test_chunk_train_matches_a_library_training_loop():
+    """Two epochs over an 8-token chunk in pieces of 4 with 3 tokens of earlier text, at most 5 conditioning
+    tokens and a 3-step warm-up, against the autograd graph driven by a library AdamW.  The four samples are
+    written out by hand here."""
+    Ws, lora, emb, head, gf, tok = _tiny_model(n_tokens=11)
+    get = lambda l: Ws[l]
+    lr, wu = 2e-3, 3
+    losses, new, opt = O.chunk_train(tok, 8, 5, 4, 2, lr, wu, TINY, emb, head, gf, get, lora, O.new_opt_state(lora))
+    samples = [(tok[0:7], 3), (tok[2:11], 5)] * 2       # (window, conditioning tokens)
+    rates = [lr / 3, 2 * lr / 3, lr, lr]
+    P = [[[torch.tensor(np.asarray(lora[l][p][i], np.float64), requires_grad=True) for i in (0, 1)] for p in PROJ]
+         for l in range(TINY.n_layers)]
+    flat = [t for L in P for ab in L for t in ab]
+    optim = torch.optim.AdamW(flat, lr=lr, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.0)
+    for step, ((window, n_ctx), rate) in enumerate(zip(samples, rates)):
+        cur = [{p: (P[l][j][0].detach().numpy(), P[l][j][1].detach().numpy()) for j, p in enumerate(PROJ)}
+               for l in range(TINY.n_layers)]
+        loss, params = _torch_model_loss(Ws, cur, emb, head, gf, window, n_ctx, TINY)
+        loss.backward()
+        for t, (A, B) in zip([ab for L in P for ab in L], params):
+            t[0].grad, t[1].grad = A.grad.clone(), B.grad.clone()
+        for gpar in optim.param_groups:
+            gpar["lr"] = rate
+        optim.step()
+        assert abs(losses[step] - float(loss.detach())) < 1e-10
+    assert opt["tau"] == 4 and losses[2] < losses[0] and losses[3] < losses[1]
+    for l in range(TINY.n_layers):
+        for j, p in enumerate(PROJ):
+            for i in (0, 1):
+                assert _rel(new[l][p][i], P[l][j][i].detach().numpy()) < 1e-8, (l, p, i)
