@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=32, help="debug only: fewer layers (marks the line invalid)")
     ap.add_argument("--tokens", type=int, default=1024)
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="debug only: LoRA dropout rate (the benchmark configuration has none; marks the line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket the GEMM launches with HIP events")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -99,9 +101,11 @@ def main():
 
     shape = synth.SHAPES["7b"].with_layers(args.layers)
     T, seed = args.tokens, 3000
+    headline = args.layers == 32 and T == 1024 and args.dropout == 0.0
     model = harness.Model(shape, seed, max_tokens=T, keep_host=False, device_random=True)
     # config: A ~ N(0, 0.02^2), B = 0, AdamW lr 5e-5, betas (0.9, 0.999), wd 0
-    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed,
+                            dropout=args.dropout)
     tok = synth.uniform_tokens(seed, T, shape.vocab)
     lr = 5e-5
 
@@ -132,7 +136,7 @@ def main():
         achieved = flop / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                "traffic": GEMM_NT_HBM_BYTES_PER_LAUNCH if args.layers == 32 and T == 1024 else None,
+                "traffic": GEMM_NT_HBM_BYTES_PER_LAUNCH if headline else None,
                 "kernel": "gemm_nt_dl_kernel (frozen W GEMM + low-rank K-extension; all tile shapes)",
                 "launches_per_step": launches // max(args.steps, 1),
                 "avg_launch_us": round(ms * 1e3 / max(launches, 1), 2),
@@ -160,8 +164,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[2]: full Temp-Lora chunk update, 7B-shaped decoder (32 layers, d 4096, 32x128 "
                                "heads, ffn 11008, vocab 32000), LoRA r=64 alpha=64 on q,k,v,o,gate,up,down, "
-                               "one 1024-token chunk, AdamW lr 5e-5" if args.layers == 32 and T == 1024 else
-                               f"DEBUG (not the benchmark): {args.layers} layers, {T} tokens",
+                               "one 1024-token chunk, AdamW lr 5e-5" if headline else
+                               f"DEBUG (not the benchmark): {args.layers} layers, {T} tokens, dropout {args.dropout}",
                    "n_tokens": T, "n_layers": args.layers, "rank": r, "loss": round(float(loss), 5),
                    "n_targets": n_targets},
         "mfma_util_whole_update": round(total_flop / (ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),

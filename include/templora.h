@@ -74,8 +74,22 @@ typedef struct {
     float eps;          /* AdamW epsilon, added after the bias-corrected square root */
     float weight_decay; /* decoupled weight decay (0) */
     float a_init_std;   /* A ~ N(0, a_init_std^2) from a counter-based generator; B = 0 */
-    uint64_t seed;      /* seed of that generator */
+    uint64_t seed;      /* seed of that generator and of the dropout masks */
+    float dropout;      /* LoRA dropout probability p in [0, 1) (Setup: 0.05; 0 = off), see below */
 } tl_lora_cfg;
+
+/*
+ * LoRA dropout (Section 3 "Setup").  It acts on the input of the low-rank branch only and only in
+ * tl_chunk_update / tl_chunk_train / tl_layer_step (tl_chunk_loss and the generation side run without it):
+ *     Y = X W^T + s ((D o X) A^T) B^T,   D[t, c] = 0 with probability p, else 1 / (1 - p).
+ * One mask per projection group input: group 0 = q|k|v (their common input), 1 = o, 2 = gate|up, 3 = down.
+ * The mask is a pure function of (seed, step, layer, group, t, c), step = the optimizer step counter when the
+ * pass starts, so that a caller (or a checker) can reproduce it:
+ *     mix64(z): z += 0x9E3779B97F4A7C15; z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9;
+ *               z = (z ^ z >> 27) * 0x94D049BB133111EB; return z ^ z >> 31        (64-bit wrap-around)
+ *     key  = mix64(seed ^ mix64(2^63 | step << 16 | layer << 3 | group))
+ *     kept = (mix64(key + t * d_in + c) >> 32) >= floor(p * 2^32)
+ */
 
 /* Number of device pointers tl_model_create expects: 9 per layer + 3. */
 #define TL_PTRS_PER_LAYER 9
@@ -272,6 +286,9 @@ tl_status tl_k_rmsnorm_bwd(const uint16_t* dy, const float* h, const float* g, c
 tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_heads, int32_t d_head, float base, int32_t pos0,
                     int32_t sign, void* hip_stream);
 /* a = silu(g) * u, gu bf16 [T, 2f] = [gate | up], a bf16 [T, f]. */
+/* y = D o x for one projection group input (bf16 [T, d_in]), D as defined with tl_lora_cfg.dropout. */
+tl_status tl_k_dropout(const uint16_t* x, int32_t T, int32_t d_in, float p, uint64_t seed, int64_t step,
+                       int32_t layer, int32_t group, uint16_t* y, void* hip_stream);
 tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a, void* hip_stream);
 /* One-token kernels of the generation side.
  * tl_k_gemv: y[N] = alpha * (W[N,K] x[K] + sum_j lora_b[n,j] lora_h[(n / rows_per_group) r + j]) (+ resid[n]).

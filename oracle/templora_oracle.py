@@ -23,7 +23,11 @@ RoPE and RMSNorm invariants; causality; window_logits agrees with the autograd
 graph's logits and is causal (a longer window leaves earlier rows unchanged);
 chunk_train's samples cover every chunk position exactly once per epoch with at
 most L_T conditioning tokens, its warm-up is checked against hand-computed
-rates, and with one piece, one epoch and no warm-up it is chunk_update.  Absolute loss / gradient values at the
+rates, and with one piece, one epoch and no warm-up it is chunk_update; the
+dropout generator reproduces SplitMix64's published first outputs, its masks
+drop a fraction p and keep the mean, p = 0 is exactly the path without dropout,
+and gradients under a fixed mask agree with the autograd graph given the same
+mask.  Absolute loss / gradient values at the
 workload shapes are printed nowhere in the paper: they are pinned only through
 these properties.
 
@@ -64,25 +68,61 @@ def labels_and_mask(tokens, n_ctx: int):
 # --------------------------------------------------------------------------
 # LoRA-adapted linear layer (Section 2: a temporary LoRA module on a frozen LM).
 # --------------------------------------------------------------------------
-def lora_linear_fwd(X, W, A, B, s: float):
-    """Y = X W^T + s (X A^T) B^T.  Returns (Y, H) with H = X A^T."""
+def lora_linear_fwd(X, W, A, B, s: float, D=None):
+    """Y = X W^T + s ((D o X) A^T) B^T.  Returns (Y, H) with H = (D o X) A^T.
+
+    D is the dropout factor on the input of the low-rank branch (Section 3 "Setup": dropout 0.05): 0 where an
+    element is dropped, 1 / (1 - p) where it is kept; None means no dropout (D = 1)."""
     X, W, A, B = _f(X), _f(W), _f(A), _f(B)
-    H = X @ A.T
+    Xl = X if D is None else X * _f(D)
+    H = Xl @ A.T
     Y = X @ W.T + s * (H @ B.T)
     return Y, H
 
 
-def lora_linear_bwd(dY, X, W, A, B, s: float):
+def lora_linear_bwd(dY, X, W, A, B, s: float, D=None):
     """Gradients of <dY, Y> w.r.t. X, A, B; W is frozen so no dW exists.
 
-    dH = s dY B;  dX = dY W + dH A;  dA = dH^T X;  dB = s dY^T (X A^T).
+    dH = s dY B;  dX = dY W + D o (dH A);  dA = dH^T (D o X);  dB = s dY^T ((D o X) A^T).
     """
     dY, X, W, A, B = _f(dY), _f(X), _f(W), _f(A), _f(B)
+    Xl = X if D is None else X * _f(D)
     dH = s * (dY @ B)
-    dX = dY @ W + dH @ A
-    dA = dH.T @ X
-    dB = s * (dY.T @ (X @ A.T))
+    dX = dY @ W + (dH @ A if D is None else _f(D) * (dH @ A))
+    dA = dH.T @ Xl
+    dB = s * (dY.T @ (Xl @ A.T))
     return dX, dA, dB
+
+
+# --------------------------------------------------------------------------
+# Dropout masks.  The paper only names the rate; which elements fall is an encoding this build fixes so that two
+# implementations can draw the same mask: a counter-based generator (the 64-bit finaliser of the SplitMix64
+# generator) keyed by (seed, optimizer step, layer, projection group) and indexed by the element.
+# --------------------------------------------------------------------------
+GROUPS = ("qkv", "o", "gu", "down")      # projection groups that share an input, in mask-stream order 0..3
+_M64 = (1 << 64) - 1
+
+
+def _mix64(z):
+    """SplitMix64's output function of the state z + golden-ratio increment, on numpy uint64 (wrap-around)."""
+    z = np.asarray(z, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        z = z + np.uint64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+def dropout_factor(seed: int, step: int, layer: int, group: int, T: int, d_in: int, p: float):
+    """D [T, d_in]: 0 where element (t, c) is dropped, 1 / (1 - p) where it is kept.  p is taken in fp32."""
+    p32 = float(np.float32(p))
+    stream = ((1 << 63) | (int(step) << 16) | (int(layer) << 3) | int(group)) & _M64
+    key = _mix64(np.uint64(int(seed) & _M64) ^ _mix64(np.uint64(stream)))
+    with np.errstate(over="ignore"):
+        bits = _mix64(key + np.arange(T * d_in, dtype=np.uint64)) >> np.uint64(32)
+    thr = min(int(np.floor(p32 * 4294967296.0)), 4294967295)
+    keep = bits >= np.uint64(max(thr, 0))
+    return (keep.astype(F64) / (1.0 - p32)).reshape(T, d_in)
 
 
 # --------------------------------------------------------------------------
@@ -218,28 +258,31 @@ def adamw_step(p, g, m, v, tau: int, lr: float, beta1=0.9, beta2=0.999, eps=1e-8
 # --------------------------------------------------------------------------
 # One decoder layer with LoRA on q, k, v, o, gate, up, down.
 # --------------------------------------------------------------------------
-def layer_fwd(h, W: dict, L: dict, shape, pos0: int = 0):
-    """h [T, d] -> (h_out, cache).  W[p] frozen [d_out, d_in], W['g1'|'g2'] gains; L[p] = (A, B)."""
+def layer_fwd(h, W: dict, L: dict, shape, pos0: int = 0, D=None):
+    """h [T, d] -> (h_out, cache).  W[p] frozen [d_out, d_in], W['g1'|'g2'] gains; L[p] = (A, B).
+    D: None, or {group: dropout factor of that group's input} for the groups in GROUPS."""
     h = _f(h)
+    D = D or {}
+    Dq, Do, Dg, Dd = (D.get(g) for g in GROUPS)
     T = h.shape[0]
     nh, dh, s = shape.n_heads, shape.d_head, shape.scale
-    c = {"h0": h}
+    c = {"h0": h, "D": (Dq, Do, Dg, Dd)}
     c["x1"] = rmsnorm_fwd(h, W["g1"], shape.rms_eps)
-    q, _ = lora_linear_fwd(c["x1"], W["q"], *L["q"], s)
-    k, _ = lora_linear_fwd(c["x1"], W["k"], *L["k"], s)
-    v, _ = lora_linear_fwd(c["x1"], W["v"], *L["v"], s)
+    q, _ = lora_linear_fwd(c["x1"], W["q"], *L["q"], s, Dq)
+    k, _ = lora_linear_fwd(c["x1"], W["k"], *L["k"], s, Dq)
+    v, _ = lora_linear_fwd(c["x1"], W["v"], *L["v"], s, Dq)
     c["q"] = rope_fwd(q.reshape(T, nh, dh), shape.rope_base, pos0)
     c["k"] = rope_fwd(k.reshape(T, nh, dh), shape.rope_base, pos0)
     c["v"] = v.reshape(T, nh, dh)
     o, c["P"] = attention_fwd(c["q"], c["k"], c["v"])
     c["o"] = o.reshape(T, nh * dh)
-    yo, _ = lora_linear_fwd(c["o"], W["o"], *L["o"], s)
+    yo, _ = lora_linear_fwd(c["o"], W["o"], *L["o"], s, Do)
     c["h1"] = h + yo
     c["x2"] = rmsnorm_fwd(c["h1"], W["g2"], shape.rms_eps)
-    c["g"], _ = lora_linear_fwd(c["x2"], W["gate"], *L["gate"], s)
-    c["u"], _ = lora_linear_fwd(c["x2"], W["up"], *L["up"], s)
+    c["g"], _ = lora_linear_fwd(c["x2"], W["gate"], *L["gate"], s, Dg)
+    c["u"], _ = lora_linear_fwd(c["x2"], W["up"], *L["up"], s, Dg)
     c["a"] = swiglu_fwd(c["g"], c["u"])
-    yd, _ = lora_linear_fwd(c["a"], W["down"], *L["down"], s)
+    yd, _ = lora_linear_fwd(c["a"], W["down"], *L["down"], s, Dd)
     return c["h1"] + yd, c
 
 
@@ -249,19 +292,20 @@ def layer_bwd(dh_out, c: dict, W: dict, L: dict, shape, pos0: int = 0):
     T = dh_out.shape[0]
     nh, dh, s = shape.n_heads, shape.d_head, shape.scale
     G = {}
-    da, *G["down"] = lora_linear_bwd(dh_out, c["a"], W["down"], *L["down"], s)
+    Dq, Do, Dg, Dd = c["D"]
+    da, *G["down"] = lora_linear_bwd(dh_out, c["a"], W["down"], *L["down"], s, Dd)
     dg, du = swiglu_bwd(da, c["g"], c["u"])
-    dx2_g, *G["gate"] = lora_linear_bwd(dg, c["x2"], W["gate"], *L["gate"], s)
-    dx2_u, *G["up"] = lora_linear_bwd(du, c["x2"], W["up"], *L["up"], s)
+    dx2_g, *G["gate"] = lora_linear_bwd(dg, c["x2"], W["gate"], *L["gate"], s, Dg)
+    dx2_u, *G["up"] = lora_linear_bwd(du, c["x2"], W["up"], *L["up"], s, Dg)
     dh1 = dh_out + rmsnorm_bwd(dx2_g + dx2_u, c["h1"], W["g2"], shape.rms_eps)
-    do, *G["o"] = lora_linear_bwd(dh1, c["o"], W["o"], *L["o"], s)
+    do, *G["o"] = lora_linear_bwd(dh1, c["o"], W["o"], *L["o"], s, Do)
     dq, dk, dv = attention_bwd(do.reshape(T, nh, dh), c["q"], c["k"], c["v"], c["P"])
     dq = rope_bwd(dq, shape.rope_base, pos0).reshape(T, nh * dh)
     dk = rope_bwd(dk, shape.rope_base, pos0).reshape(T, nh * dh)
     dv = dv.reshape(T, nh * dh)
-    dx1_q, *G["q"] = lora_linear_bwd(dq, c["x1"], W["q"], *L["q"], s)
-    dx1_k, *G["k"] = lora_linear_bwd(dk, c["x1"], W["k"], *L["k"], s)
-    dx1_v, *G["v"] = lora_linear_bwd(dv, c["x1"], W["v"], *L["v"], s)
+    dx1_q, *G["q"] = lora_linear_bwd(dq, c["x1"], W["q"], *L["q"], s, Dq)
+    dx1_k, *G["k"] = lora_linear_bwd(dk, c["x1"], W["k"], *L["k"], s, Dq)
+    dx1_v, *G["v"] = lora_linear_bwd(dv, c["x1"], W["v"], *L["v"], s, Dq)
     dh0 = dh1 + rmsnorm_bwd(dx1_q + dx1_k + dx1_v, c["h0"], W["g1"], shape.rms_eps)
     return dh0, {p: tuple(G[p]) for p in PROJ}
 
@@ -269,7 +313,16 @@ def layer_bwd(dh_out, c: dict, W: dict, L: dict, shape, pos0: int = 0):
 # --------------------------------------------------------------------------
 # The whole chunk update.
 # --------------------------------------------------------------------------
-def model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, keep=()):
+def layer_dropout(drop, shape, layer: int, T: int):
+    """drop = None or (p, seed, optimizer step index) -> {group: factor} for one layer's four group inputs."""
+    if not drop or drop[0] <= 0.0:
+        return None
+    p, seed, step = drop
+    d_in = {"qkv": shape.d_model, "o": shape.d_model, "gu": shape.d_model, "down": shape.d_ffn}
+    return {g: dropout_factor(seed, step, layer, gi, T, d_in[g], p) for gi, g in enumerate(GROUPS)}
+
+
+def model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, keep=(), drop=None):
     """Forward + backward of one call's tokens.
 
     get_layer(l) returns layer l's frozen dict (so a 7B-shape caller can build
@@ -286,7 +339,7 @@ def model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, kee
     h = _f(emb)[tok]
     caches = []
     for l in range(shape.n_layers):
-        h, c = layer_fwd(h, get_layer(l), lora[l], shape)
+        h, c = layer_fwd(h, get_layer(l), lora[l], shape, 0, layer_dropout(drop, shape, l, tok.size))
         caches.append(c)
     hf = rmsnorm_fwd(h, g_final, shape.rms_eps)
     logits = hf @ _f(head).T
@@ -341,9 +394,11 @@ def new_opt_state(lora):
 
 
 def chunk_update(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, opt, lr,
-                 beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0, keep=()):
-    """One optimizer step on one chunk: returns (result dict, new lora, new opt)."""
-    res = model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, keep)
+                 beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0, keep=(), dropout=0.0, seed=0):
+    """One optimizer step on one chunk: returns (result dict, new lora, new opt).
+    With dropout > 0 the masks of this step are those of (seed, number of steps taken so far)."""
+    res = model_fwd_bwd(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, keep,
+                        (dropout, seed, opt["tau"]) if dropout > 0.0 else None)
     tau = opt["tau"] + 1
     new_lora, new_m, new_v = [], [], []
     for l in range(shape.n_layers):
@@ -384,7 +439,7 @@ def training_samples(n_before: int, n_chunk: int, L_T: int, batch: int):
 
 
 def chunk_train(tokens, n_chunk, L_T, batch, epochs, lr, warmup_steps, shape, emb, head, g_final, get_layer, lora, opt,
-                beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0):
+                beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0, dropout=0.0, seed=0):
     """-> (losses of every step in order, new lora, new opt).  tokens: the stream so far, the chunk last."""
     tok = np.asarray(tokens, dtype=np.int64)
     losses = []
@@ -392,7 +447,7 @@ def chunk_train(tokens, n_chunk, L_T, batch, epochs, lr, warmup_steps, shape, em
         for first, n_ctx, end in training_samples(tok.size - n_chunk, n_chunk, L_T, batch):
             rate = warmup_lr(lr, opt["tau"], warmup_steps)
             res, lora, opt = chunk_update(tok[first:end], n_ctx, shape, emb, head, g_final, get_layer, lora, opt, rate,
-                                          beta1, beta2, eps, wd)
+                                          beta1, beta2, eps, wd, (), dropout, seed)
             losses.append(res["loss"])
     return losses, lora, opt
 

@@ -44,7 +44,8 @@ class tl_model_cfg(C.Structure):
 
 class tl_lora_cfg(C.Structure):
     _fields_ = [("rank", C.c_int32), ("alpha", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
-                ("eps", C.c_float), ("weight_decay", C.c_float), ("a_init_std", C.c_float), ("seed", C.c_uint64)]
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("a_init_std", C.c_float), ("seed", C.c_uint64),
+                ("dropout", C.c_float)]
 
 
 class tl_train_cfg(C.Structure):
@@ -79,6 +80,7 @@ _SIGS = {
     "tl_k_rmsnorm_fwd": [_vp, _vp, _i32, _i32, _f32, _vp, _vp],
     "tl_k_rmsnorm_bwd": [_vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp],
     "tl_k_rope": [_vp, _i32, _i32, _i32, _i32, _f32, _i32, _i32, _vp],
+    "tl_k_dropout": [_vp, _i32, _i32, _f32, C.c_uint64, _i64, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_fwd": [_vp, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_bwd": [_vp, _vp, _i32, _i32, _vp, _vp],
     "tl_k_gemv": [_vp, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _vp],
@@ -145,8 +147,9 @@ def tl_model_destroy(model):
     _chk(_lib.tl_model_destroy(model))
 
 
-def tl_lora_init(model, rank, alpha, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, a_init_std=0.02, seed=0):
-    cfg = tl_lora_cfg(rank, alpha, beta1, beta2, eps, weight_decay, a_init_std, seed)
+def tl_lora_init(model, rank, alpha, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, a_init_std=0.02, seed=0,
+                 dropout=0.0):
+    cfg = tl_lora_cfg(rank, alpha, beta1, beta2, eps, weight_decay, a_init_std, seed, dropout)
     out = _vp()
     _chk(_lib.tl_lora_init(model, C.byref(cfg), C.byref(out)))
     return out
@@ -305,6 +308,10 @@ def tl_k_rmsnorm_bwd(dy, h, g, dres, eps, dh_out, dh_out_bf16=None, stream=None)
 
 def tl_k_rope(x, n_heads, d_head, base=10000.0, pos0=0, sign=1, stream=None):
     _chk(_lib.tl_k_rope(_dp(x), x.stride(0), x.shape[0], n_heads, d_head, base, pos0, sign, _s(stream)))
+
+
+def tl_k_dropout(x, y, p, seed, step, layer, group, stream=None):
+    _chk(_lib.tl_k_dropout(_dp(x), x.shape[0], x.shape[1], p, seed, step, layer, group, _dp(y), _s(stream)))
 
 
 def tl_k_swiglu_fwd(gu, a, stream=None):

@@ -444,7 +444,7 @@ hipError_t launch_fill_f32(float* p, size_t n, float value, hipStream_t s) {
 
 // Counter-based normal draws for the initial A factors: a 64-bit mix of (seed, stream, index)
 // gives two uniforms, Box-Muller gives the value.  Element i depends only on (seed, stream, i).
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+__host__ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
     z += 0x9E3779B97F4A7C15ull;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
@@ -464,6 +464,67 @@ hipError_t launch_init_normal(float* p, size_t n, float std, uint64_t seed, uint
     size_t blocks = (n + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     init_normal_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, n, std, seed, stream_id);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- LoRA dropout (Section 3 "Setup": dropout = 0.05)
+// Dropout sits on the input of the low-rank branch only: Y = X W^T + s (D o X) A^T B^T with D = 0 (dropped) or
+// 1 / (1 - p) (kept).  One mask per projection group input (q|k|v share theirs, gate|up theirs).  The mask is a pure
+// function of (seed, optimizer step, layer, group, element): element e = t * d_in + c is kept iff the upper 32 bits of
+// mix64(key + e) are >= floor(p * 2^32), with key = mix64(seed ^ mix64(2^63 | step << 16 | layer << 3 | group)); the top
+// bit keeps these streams apart from the ones that draw the initial A.
+uint64_t dropout_key(uint64_t seed, int64_t step, int layer, int group) {
+    const uint64_t stream_id = (1ull << 63) | ((uint64_t)step << 16) | ((uint64_t)layer << 3) | (uint64_t)group;
+    return mix64(seed ^ mix64(stream_id));
+}
+uint32_t dropout_threshold(float p) {
+    const double t = floor((double)p * 4294967296.0);
+    return t <= 0.0 ? 0u : (t >= 4294967295.0 ? 4294967295u : (uint32_t)t);
+}
+__device__ __forceinline__ bool dropout_keep(uint64_t key, uint64_t e, uint32_t thr) {
+    return (uint32_t)(mix64(key + e) >> 32) >= thr;
+}
+// y = D o x, eight elements per thread
+__global__ __launch_bounds__(256) void dropout_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y, size_t n8,
+                                                          uint64_t key, uint32_t thr, float scale) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+        float v[8];
+        unpack8(*(const uint4*)(x + i * 8), v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = dropout_keep(key, i * 8 + e, thr) ? v[e] * scale : 0.f;
+        *(uint4*)(y + i * 8) = pack8(v);
+    }
+}
+// dx += D o z   (the low-rank branch's share of the input gradient)
+__global__ __launch_bounds__(256) void dropout_add_kernel(bf16_t* __restrict__ dx, const float* __restrict__ z, size_t n8,
+                                                          uint64_t key, uint32_t thr, float scale) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+        float v[8];
+        unpack8(*(const uint4*)(dx + i * 8), v);
+        const float4 z0 = *(const float4*)(z + i * 8), z1 = *(const float4*)(z + i * 8 + 4);
+        const float zz[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (dropout_keep(key, i * 8 + e, thr)) v[e] += zz[e] * scale;
+        *(uint4*)(dx + i * 8) = pack8(v);
+    }
+}
+static unsigned dropout_blocks(size_t n8) {
+    size_t b = (n8 + 255) / 256;
+    return (unsigned)(b > 16384 ? 16384 : b);
+}
+hipError_t launch_dropout_fwd(const bf16_t* x, bf16_t* y, size_t n, uint64_t key, float p, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    if ((n & 7) || !(p >= 0.f && p < 1.f)) return hipErrorInvalidValue;
+    dropout_fwd_kernel<<<dropout_blocks(n / 8), 256, 0, s>>>(x, y, n / 8, key, dropout_threshold(p), 1.f / (1.f - p));
+    return hipGetLastError();
+}
+hipError_t launch_dropout_add(bf16_t* dx, const float* z, size_t n, uint64_t key, float p, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    if ((n & 7) || !(p >= 0.f && p < 1.f)) return hipErrorInvalidValue;
+    dropout_add_kernel<<<dropout_blocks(n / 8), 256, 0, s>>>(dx, z, n / 8, key, dropout_threshold(p), 1.f / (1.f - p));
     return hipGetLastError();
 }
 

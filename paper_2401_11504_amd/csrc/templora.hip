@@ -105,6 +105,7 @@ struct LayerOff {           // element offsets into the LoRA arenas
 
 struct LayerSave {          // activations kept from forward to backward
     bf16_t *x1, *qkv, *o, *x2, *gu, *act, *hs[N_GROUPS];
+    bf16_t* xd[N_GROUPS] = {};   // dropped copy of each group's input (only with dropout > 0)
     float *lse, *hmid;
 };
 
@@ -137,6 +138,9 @@ struct tl_lora {
     // generation side: the key/value cache is the q|k|v buffer the forward pass keeps per layer (rows = positions);
     // kv_len rows are valid.  Any training-side forward overwrites it, which matches the method (the cache is
     // recomputed with the updated module after every chunk update).
+    // LoRA dropout (training-side forward / backward only): on for the pass in flight?
+    bool drop_on = false;
+    float* zdrop = nullptr;       // [max_tokens, max(d_model, d_ffn)] fp32: dH A before the mask is applied
     int kv_len = 0;
     float* lora_h = nullptr;      // [3 r] scaled low-rank activations of the projection group in flight
     int* next_dev = nullptr;
@@ -295,7 +299,7 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
     const tl_lora_cfg c = *cfg;
     if (c.rank < 8 || (c.rank & 7) || c.rank > 256) return fail(TL_ERR_SHAPE, "rank must be a multiple of 8 in [8, 256]");
     if (!(c.alpha > 0.f) || !(c.beta1 >= 0.f && c.beta1 < 1.f) || !(c.beta2 >= 0.f && c.beta2 < 1.f) ||
-        !(c.eps >= 0.f) || !(c.weight_decay >= 0.f) || !(c.a_init_std >= 0.f))
+        !(c.eps >= 0.f) || !(c.weight_decay >= 0.f) || !(c.a_init_std >= 0.f) || !(c.dropout >= 0.f && c.dropout < 1.f))
         return fail(TL_ERR_ARG, "tl_lora_init: bad hyper-parameter");
     TLCHK(require_gfx950());
     tl_lora* L = new (std::nothrow) tl_lora();
@@ -375,7 +379,10 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
             for (int g = 0; g < N_GROUPS; ++g) TLCHK(L->pool.alloc(&sv.hs[g], (size_t)Tm * kGroupCount[g] * r));
             TLCHK(L->pool.alloc(&sv.lse, (size_t)mc.n_heads * Tm));
             TLCHK(L->pool.alloc(&sv.hmid, Td));
+            if (c.dropout > 0.f)
+                for (int g = 0; g < N_GROUPS; ++g) TLCHK(L->pool.alloc(&sv.xd[g], (size_t)Tm * m->d_in(g)));
         }
+        if (c.dropout > 0.f) TLCHK(L->pool.alloc(&L->zdrop, (size_t)Tm * (d > f ? d : f)));
         TLCHK(L->pool.alloc(&L->dh_bf[0], Td));
         TLCHK(L->pool.alloc(&L->dh_bf[1], Td));
         TLCHK(L->pool.alloc(&L->d_act, (size_t)Tm * f));
@@ -464,8 +471,14 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
     const LayerOff& o = L->off[l];
     bf16_t* Hs = L->save[l].hs[g];
+    const bf16_t* Xl = X;        // input of the low-rank branch
+    if (L->drop_on) {
+        HIPCHK(launch_dropout_fwd(X, L->save[l].xd[g], (size_t)T * din, dropout_key(L->cfg.seed, L->step, l, g),
+                                  L->cfg.dropout, s));
+        Xl = L->save[l].xd[g];
+    }
     GemmNT h;
-    h.A = X; h.lda = din; h.B = L->S + o.A[g]; h.ldb = din; h.M = T; h.N = G * r; h.K = din;
+    h.A = Xl; h.lda = din; h.B = L->S + o.A[g]; h.ldb = din; h.M = T; h.N = G * r; h.K = din;
     h.alpha = L->s; h.C = Hs; h.ldc = G * r;
     h.partial = L->partial; h.partial_elems = L->partial_elems;
     HIPCHK(launch_gemm_nt(h, s));
@@ -480,7 +493,8 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     return TL_OK;
 }
 
-// backward: dH = s dY B;  dX = dY W + dH A;  the products dA = dH^T X and dB = dY^T Hs are appended to `tn`, which
+// backward: dH = s dY B;  dX = dY W + D o (dH A)  (D = 1 without dropout: then one GEMM with the contraction extended
+// by dH | A);  the products dA = dH^T X and dB = dY^T Hs are appended to `tn`, which
 // the caller launches once per layer (dY, dH, X and Hs must stay untouched until then).
 static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf16_t* X, int T, bf16_t* dX,
                            GemmTNGroup& tn) {
@@ -500,11 +514,20 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         GemmNT x;
         x.A = dY; x.lda = (long)G * dout; x.B = m->layers[l].wt[g]; x.ldb = (long)G * dout; x.M = T; x.N = din;
         x.K = G * dout;
-        x.A2 = dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r;
+        if (!L->drop_on) { x.A2 = dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r; }
         x.C = dX; x.ldc = din;
         x.partial = L->partial; x.partial_elems = L->partial_elems;
         HIPCHK(timed_gemm(L, x));
+        if (L->drop_on) {
+            GemmNT z;
+            z.A = dH; z.lda = G * r; z.B = L->ST + o.AT[g]; z.ldb = G * r; z.M = T; z.N = din; z.K = G * r;
+            z.C = L->zdrop; z.ldc = din; z.c_f32 = 1;
+            HIPCHK(launch_gemm_nt(z, s));
+            HIPCHK(launch_dropout_add(dX, L->zdrop, (size_t)T * din, dropout_key(L->cfg.seed, L->step, l, g),
+                                      L->cfg.dropout, s));
+        }
     }
+    if (L->drop_on) X = L->save[l].xd[g];                                                  // dA = dH^T (D o X)
     tn.add(dH, (long)G * r, G * r, X, din, din, L->G + o.A[g], din);                    // dA [G r, d_in]
     for (int k = 0; k < G; ++k)                                                            // dB_k [d_out, r]
         tn.add(dY + (long)k * dout, (long)G * dout, dout, Hs + (long)k * r, (long)G * r, r,
@@ -608,6 +631,7 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     const int N = (T - 1) - first;
     *n_targets = N;
     L->kv_len = 0;   // the forward pass below overwrites the buffers the key/value cache lives in
+    L->drop_on = want_grad && L->cfg.dropout > 0.f;   // scoring (no gradient) runs the module without dropout
     memcpy(L->tok_host, tokens, (size_t)T * sizeof(int));
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(launch_labels(L->tok, T, L->labels, s));
@@ -769,6 +793,7 @@ extern "C" tl_status tl_prefill(tl_lora* L, const int32_t* tokens, int32_t n_tok
     hipStream_t s = m->stream;
     const int T = n_tokens, d = c.d_model;
     L->kv_len = 0;
+    L->drop_on = false;   // generation runs the module without dropout
     memcpy(L->tok_host, tokens, (size_t)T * sizeof(int));
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
@@ -842,6 +867,7 @@ extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in,
     if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
     hipStream_t s = L->model->stream;
     L->kv_len = 0;
+    L->drop_on = L->cfg.dropout > 0.f;
     TLCHK(layer_forward(L, layer, h_in, h_out, n_tokens));
     HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf[0], (size_t)n_tokens * c.d_model, s));
     TLCHK(layer_backward(L, layer, h_in, dh_out, L->dh_bf[0], dh_in, nullptr, n_tokens));
@@ -1051,6 +1077,16 @@ extern "C" tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_hea
     HIPCHK(launch_rope(x, ld, T, n_heads, d_head, base, pos0, sign, nullptr, (hipStream_t)hip_stream));
     return TL_OK;
 }
+extern "C" tl_status tl_k_dropout(const uint16_t* x, int32_t T, int32_t d_in, float p, uint64_t seed, int64_t step,
+                                  int32_t layer, int32_t group, uint16_t* y, void* hip_stream) {
+    if (!x || !y) return fail(TL_ERR_ARG, "tl_k_dropout: null pointer");
+    if (T < 0 || d_in < 0 || (d_in & 7) || !(p >= 0.f && p < 1.f) || step < 0 || layer < 0 || group < 0 || group > 3)
+        return fail(TL_ERR_ARG, "tl_k_dropout: bad argument");
+    TLCHK(require_gfx950());
+    HIPCHK(launch_dropout_fwd(x, y, (size_t)T * d_in, dropout_key(seed, step, layer, group), p, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+
 extern "C" tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a, void* hip_stream) {
     KARGS_OK(gu && a && T >= 0 && f > 0 && (f & 7) == 0, "tl_k_swiglu_fwd");
     HIPCHK(launch_swiglu_fwd(gu, T, f, a, (hipStream_t)hip_stream));

@@ -320,7 +320,7 @@ def test_attention_is_causal():
 
 
 # ---------------------------------------------------------------- whole model
-def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape, want_logits=False):
+def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape, want_logits=False, D=None):
     """The same network written as an independent autograd graph with library ops.
 
     RoPE is formed as a complex multiplication by exp(i p theta) (a different
@@ -340,23 +340,25 @@ def _torch_model_loss(Ws, lora, emb, head, gf, tok, n_ctx, shape, want_logits=Fa
         z = torch.complex(x[..., : dh // 2], x[..., dh // 2:]) * rot[:, None, :]
         return torch.cat([z.real, z.imag], -1)
 
-    def lin(x, W, AB):
+    def lin(x, W, AB, mask=None):
         A = t64(AB[0]).requires_grad_()
         B = t64(AB[1]).requires_grad_()
         params.append((A, B))
-        return F.linear(x, t64(W)) + s * F.linear(F.linear(x, A), B)
+        xl = x if mask is None else x * t64(mask)        # dropout factor on the low-rank branch's input only
+        return F.linear(x, t64(W)) + s * F.linear(F.linear(xl, A), B)
 
     for l in range(shape.n_layers):
         W, L = Ws[l], lora[l]
+        Dl = D[l] if D is not None else {}
         x1 = F.rms_norm(h, (shape.d_model,), t64(W["g1"]), eps=shape.rms_eps)
-        q, k, v = lin(x1, W["q"], L["q"]), lin(x1, W["k"], L["k"]), lin(x1, W["v"], L["v"])
+        q, k, v = (lin(x1, W[p], L[p], Dl.get("qkv")) for p in ("q", "k", "v"))
         q, k, v = rope(q), rope(k), v.view(T, nh, dh)
         o = F.scaled_dot_product_attention(q.transpose(0, 1), k.transpose(0, 1), v.transpose(0, 1),
                                            is_causal=True).transpose(0, 1).reshape(T, nh * dh)
-        h = h + lin(o, W["o"], L["o"])
+        h = h + lin(o, W["o"], L["o"], Dl.get("o"))
         x2 = F.rms_norm(h, (shape.d_model,), t64(W["g2"]), eps=shape.rms_eps)
-        a = F.silu(lin(x2, W["gate"], L["gate"])) * lin(x2, W["up"], L["up"])
-        h = h + lin(a, W["down"], L["down"])
+        a = F.silu(lin(x2, W["gate"], L["gate"], Dl.get("gu"))) * lin(x2, W["up"], L["up"], Dl.get("gu"))
+        h = h + lin(a, W["down"], L["down"], Dl.get("down"))
     hf = F.rms_norm(h, (shape.d_model,), t64(gf), eps=shape.rms_eps)
     logits = F.linear(hf, t64(head))
     if want_logits:
@@ -610,3 +612,97 @@ def test_chunk_train_matches_a_library_training_loop():
         for j, p in enumerate(PROJ):
             for i in (0, 1):
                 assert _rel(new[l][p][i], P[l][j][i].detach().numpy()) < 1e-8, (l, p, i)
+
+
+# ------------------------------------------------------------------ LoRA dropout
+def test_mix64_reproduces_published_splitmix64_outputs():
+    """The mask generator's mixing function is the output function of SplitMix64 (Steele, Lea, Flood: "Fast
+    splittable pseudorandom number generators", OOPSLA 2014; the public-domain reference implementation).  Its
+    first five outputs from state 1234567 are widely published test values."""
+    gamma, s0 = 0x9E3779B97F4A7C15, 1234567
+    got = [int(O._mix64(np.uint64((s0 + i * gamma) & (2 ** 64 - 1)))) for i in range(5)]
+    assert got == [6457827717110365317, 3203168211198807973, 9817491932198370423, 4593380528125082431,
+                   16408922859458223821]
+
+
+def test_dropout_factor_rate_values_keys_and_layout():
+    p, T, d = 0.05, 256, 512
+    D = O.dropout_factor(11, 3, 2, 1, T, d, p)
+    p32 = float(np.float32(p))
+    assert set(np.unique(D)) == {0.0, 1.0 / (1.0 - p32)}
+    drop = (D == 0).mean()
+    assert abs(drop - p) < 4 * math.sqrt(p * (1 - p) / (T * d))            # binomial, four sigma
+    assert abs(D.mean() - 1.0) < 4 * math.sqrt(p / (1 - p) / (T * d))      # the factor keeps the mean
+    assert np.array_equal(D, O.dropout_factor(11, 3, 2, 1, T, d, p))       # a pure function of its arguments
+    for other in ((12, 3, 2, 1), (11, 4, 2, 1), (11, 3, 3, 1), (11, 3, 2, 0)):   # seed, step, layer, group all matter
+        differ = ((O.dropout_factor(*other, T, d, p) == 0) != (D == 0)).mean()
+        assert abs(differ - 2 * p * (1 - p)) < 0.01
+    # element (t, c) has index t * d_in + c: the same stream cut into rows of another width
+    assert np.array_equal(O.dropout_factor(5, 0, 0, 0, 6, 4, 0.3).ravel(), O.dropout_factor(5, 0, 0, 0, 3, 8, 0.3).ravel())
+    assert np.all(O.dropout_factor(5, 0, 0, 0, 8, 8, 0.0) == 1.0)
+    # the threshold is floor(p 2^32) on the upper 32 bits: p = 0.5 keeps exactly the elements whose top bit is set
+    bits = O._mix64(O._mix64(np.uint64(5) ^ O._mix64(np.uint64(1 << 63))) + np.arange(64, dtype=np.uint64))
+    assert np.array_equal(O.dropout_factor(5, 0, 0, 0, 8, 8, 0.5).ravel() > 0, (bits >> np.uint64(63)) == 1)
+
+
+def test_lora_linear_with_dropout_elementwise_and_finite_differences():
+    X, W, A, B, dY = _lin()
+    s = 0.7
+    rng = np.random.default_rng(0)
+    D = (rng.random(X.shape) > 0.3) / 0.7
+    Y, _ = O.lora_linear_fwd(X, W, A, B, s, D)
+    for t in range(X.shape[0]):
+        for n in range(W.shape[0]):
+            acc = sum(X[t, c] * W[n, c] for c in range(X.shape[1]))
+            acc += s * sum(B[n, j] * sum(D[t, c] * X[t, c] * A[j, c] for c in range(X.shape[1]))
+                           for j in range(A.shape[0]))
+            assert abs(Y[t, n] - acc) < 1e-12
+    dX, dA, dB = O.lora_linear_bwd(dY, X, W, A, B, s, D)
+    f = lambda X_, A_, B_: float(np.sum(dY * O.lora_linear_fwd(X_, W, A_, B_, s, D)[0]))
+    h = 1e-6
+    for arr, grad, which in ((X, dX, 0), (A, dA, 1), (B, dB, 2)):
+        for idx in [(0, 0), (1, 2), (arr.shape[0] - 1, arr.shape[1] - 1)]:
+            ap, am = arr.copy(), arr.copy()
+            ap[idx] += h
+            am[idx] -= h
+            args_p = [X, A, B]; args_m = [X, A, B]
+            args_p[which], args_m[which] = ap, am
+            assert abs((f(*args_p) - f(*args_m)) / (2 * h) - grad[idx]) < 1e-6
+    # a dropped input element takes no part in the low-rank branch: dA has no contribution from it
+    t0, c0 = np.argwhere(D == 0)[0]
+    X2 = X.copy()
+    X2[t0, c0] += 1.0
+    assert np.allclose(O.lora_linear_bwd(dY, X2, W, A, B, s, D)[1], dA)
+
+
+def test_model_with_dropout_matches_autograd_graph_given_the_same_masks():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    drop = (0.25, 99, 5)
+    res = O.model_fwd_bwd(tok, 2, TINY, emb, head, gf, lambda l: Ws[l], lora, drop=drop)
+    D = [O.layer_dropout(drop, TINY, l, len(tok)) for l in range(TINY.n_layers)]
+    loss, params = _torch_model_loss(Ws, lora, emb, head, gf, tok, 2, TINY, D=D)
+    loss.backward()
+    assert abs(res["loss"] - float(loss.detach())) < 1e-10
+    it = iter(params)
+    for l in range(TINY.n_layers):
+        for p in PROJ:
+            A, B = next(it)
+            assert _rel(res["grads"][l][p][0], A.grad.numpy()) < 1e-9
+            assert _rel(res["grads"][l][p][1], B.grad.numpy()) < 1e-9
+    base = O.model_fwd_bwd(tok, 2, TINY, emb, head, gf, lambda l: Ws[l], lora)
+    assert abs(base["loss"] - res["loss"]) > 1e-6                          # the masks do act
+
+
+def test_dropout_zero_is_exactly_the_plain_update_and_steps_use_fresh_masks():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    get = lambda l: Ws[l]
+    r0, l0, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, O.new_opt_state(lora), lr=1e-3)
+    r1, l1, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, O.new_opt_state(lora), lr=1e-3, dropout=0.0, seed=5)
+    assert r0["loss"] == r1["loss"]
+    assert all(np.array_equal(l0[l][p][i], l1[l][p][i]) for l in range(TINY.n_layers) for p in PROJ for i in (0, 1))
+    # lr = 0 keeps the module fixed: the two losses differ only through the step index that keys the masks
+    opt = O.new_opt_state(lora)
+    ra, la, opt = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, opt, lr=0.0, dropout=0.3, seed=5)
+    rb, _, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, la, opt, lr=0.0, dropout=0.3, seed=5)
+    rc, _, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, O.new_opt_state(lora), lr=0.0, dropout=0.3, seed=5)
+    assert ra["loss"] != rb["loss"] and ra["loss"] == rc["loss"]
