@@ -64,6 +64,63 @@ def cpu_baseline(shape, T, seed):
                       f"final norm/lm_head/CE fwd+bwd timed once ({t_head:.2f} s); AdamW not included"}
 
 
+def decode_bench(args, torch, api, harness, synth):
+    """Greedy decoding with the module over the key/value cache (Algorithm 1's token loop): tokens/s, and the
+    matrix-vector kernel that streams the frozen weights against the HBM roofline."""
+    shape = synth.SHAPES["7b"].with_layers(args.layers)
+    seed, P, K = 3000, args.prompt, args.steps
+    model = harness.Model(shape, seed, max_tokens=P + K + args.warmup + 1, keep_host=False, device_random=True)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    # B = 0 would make the module a no-op numerically but not in work done: the kernels read A and B regardless
+    prompt = synth.uniform_tokens(seed, P, shape.vocab)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    nxt, _ = api.tl_prefill(lora, prompt)
+    t_prefill = time.perf_counter() - t0
+    for _ in range(args.warmup):
+        nxt, _ = api.tl_decode_step(lora, nxt)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        nxt, _ = api.tl_decode_step(lora, nxt)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    roof = None
+    if not args.no_events:
+        # a second window of the same length from the same start, with the weight-streaming launches bracketed
+        nxt, _ = api.tl_prefill(lora, prompt)
+        for _ in range(args.warmup):
+            nxt, _ = api.tl_decode_step(lora, nxt)
+        api.tl_profile_enable(lora, True)
+        for _ in range(K):
+            nxt, _ = api.tl_decode_step(lora, nxt)
+        ms, launches, flop = api.tl_profile_read(lora)
+        api.tl_profile_enable(lora, False)
+        gbs = flop / (ms * 1e-3) / 1e9 if ms > 0 else 0.0     # 2 flop per bf16 element of 2 bytes: bytes read = flop
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbs / 8000.0, 4),
+                "traffic": None, "kernel": "gemv_kernel (frozen matrix + LoRA B rows, one token)",
+                "launches_per_step": launches // max(K, 1), "avg_launch_us": round(ms * 1e3 / max(launches, 1), 2),
+                "bytes_per_launch": flop / max(launches, 1),
+                "share_of_step_time": round(ms * 1e-3 / dt, 4)}
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
+    d, f, V, L, r = shape.d_model, shape.d_ffn, shape.vocab, shape.n_layers, shape.rank
+    weight_bytes = 2.0 * (L * (4 * d * d + 3 * d * f) + d * V)
+    lora_bytes = 2.0 * r * L * (4 * 2 * d + 3 * (d + f))
+    kv_bytes = 2.0 * 2 * d * L * (P + args.warmup + K / 2.0)
+    print(json.dumps({
+        "metric": "greedy decode tokens/sec with the Temp-Lora module over a key/value cache (7B-shape, r=64)",
+        "value": round(K / dt, 1), "unit": "decoded tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": round(dt / K * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"generation side of configs[3] (not the headline metric): {args.layers} layers, window "
+                               f"{P} tokens at the start, {K} tokens decoded", "prefill_ms": round(t_prefill * 1e3, 2)},
+        "hbm_bytes_per_token": weight_bytes + lora_bytes + kv_bytes,
+        "hbm_frac_whole_step": round((weight_bytes + lora_bytes + kv_bytes) / (dt / K) / 8e12, 4),
+        "roofline": roof}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +130,10 @@ def main():
     ap.add_argument("--tokens", type=int, default=1024)
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="debug only: LoRA dropout rate (the benchmark configuration has none; marks the line)")
+    ap.add_argument("--decode", action="store_true",
+                    help="measure the generation side instead (the step either side of the update): one step = one "
+                         "greedily decoded token with the module applied, after a prefill of --prompt tokens")
+    ap.add_argument("--prompt", type=int, default=1024, help="--decode: tokens in the window when decoding starts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-events", action="store_true", help="do not bracket the GEMM launches with HIP events")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -99,6 +160,9 @@ def main():
         return
     from paper_2401_11504_amd import api, harness, synth
 
+    if args.decode:
+        decode_bench(args, torch, api, harness, synth)
+        return
     shape = synth.SHAPES["7b"].with_layers(args.layers)
     T, seed = args.tokens, 3000
     headline = args.layers == 32 and T == 1024 and args.dropout == 0.0

@@ -233,7 +233,9 @@ tl_status tl_get_dh(tl_lora* lora, int32_t boundary, float* host_out, size_t n);
  * dX backward, lm_head forward and backward) made by tl_chunk_update / tl_chunk_loss / tl_layer_step is bracketed
  * by two HIP events on the model's stream.  tl_profile_read synchronises, returns the summed elapsed time of
  * those launches in milliseconds, their number, and the floating-point operations they performed
- * (2 M N (K + K2) per launch), and clears the counters. */
+ * (2 M N (K + K2) per launch), and clears the counters.  On the generation side (tl_decode_step) the bracketed
+ * launches are the matrix-vector products that stream a frozen matrix (four per layer and the lm_head), with
+ * 2 N (K + r) operations each, i.e. N (K + r) bf16 elements = 2 N (K + r) bytes read per launch. */
 tl_status tl_profile_enable(tl_lora* lora, int32_t on);
 tl_status tl_profile_read(tl_lora* lora, double* ms_total, int64_t* launches, double* flop_total);
 
@@ -295,13 +297,17 @@ tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a,
  *   W, x, lora_b bf16; lora_h fp32 (already scaled); lora_b may be NULL.  y_f32 != 0: y and resid fp32, else y bf16
  *   and resid must be NULL.  K, ldw multiples of 8.
  * tl_k_attention_decode: o[n_heads * d_head] (bf16) = softmax(q K^T / sqrt(d_head)) V per head, q one row, K and V
- *   rows 0 .. n_keys-1 with row stride ld (elements), every key visible.
+ *   rows 0 .. n_keys-1 with row stride ld (elements), every key visible.  workspace: NULL, or device fp32 scratch of
+ *   workspace_elems floats: with it the keys are cut into up to 32 ranges of >= 128 keys, one workgroup per (head,
+ *   range) and a second launch that merges them (n_heads * ranges * (d_head + 2) floats are used); without it one
+ *   workgroup per head reads the whole cache.
  * tl_k_argmax: index of the largest of n fp32 values, lowest index among equals; out is a device int32. */
 tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x, int32_t N, int32_t K, const uint16_t* lora_b,
                     const float* lora_h, int32_t r, int32_t rows_per_group, float alpha, const float* resid, void* y,
                     int32_t y_f32, void* hip_stream);
 tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ld, int32_t n_keys,
-                                int32_t n_heads, int32_t d_head, uint16_t* o, void* hip_stream);
+                                int32_t n_heads, int32_t d_head, uint16_t* o, float* workspace, size_t workspace_elems,
+                                void* hip_stream);
 tl_status tl_k_argmax(const float* x, int32_t n, int32_t* out, void* hip_stream);
 /* dgu bf16 [T, 2f] from da bf16 [T, f] and gu. */
 tl_status tl_k_swiglu_bwd(const uint16_t* da, const uint16_t* gu, int32_t T, int32_t f, uint16_t* dgu,

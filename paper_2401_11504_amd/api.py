@@ -84,7 +84,7 @@ _SIGS = {
     "tl_k_swiglu_fwd": [_vp, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_bwd": [_vp, _vp, _i32, _i32, _vp, _vp],
     "tl_k_gemv": [_vp, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _vp],
-    "tl_k_attention_decode": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp],
+    "tl_k_attention_decode": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _sz, _vp],
     "tl_k_argmax": [_vp, _i32, _vp, _vp],
     "tl_k_attention_fwd": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _vp],
     "tl_k_attention_bwd": [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp],
@@ -329,8 +329,9 @@ def tl_k_gemv(W, x, y, lora_b=None, lora_h=None, rows_per_group=0, alpha=1.0, re
                         _dp(y), int(y.dtype == torch.float32), _s(stream)))
 
 
-def tl_k_attention_decode(q, k, v, n_heads, d_head, o, stream=None):
-    _chk(_lib.tl_k_attention_decode(_dp(q), _dp(k), _dp(v), k.stride(0), k.shape[0], n_heads, d_head, _dp(o), _s(stream)))
+def tl_k_attention_decode(q, k, v, n_heads, d_head, o, workspace=None, stream=None):
+    _chk(_lib.tl_k_attention_decode(_dp(q), _dp(k), _dp(v), k.stride(0), k.shape[0], n_heads, d_head, _dp(o),
+                                    _dp(workspace), workspace.numel() if workspace is not None else 0, _s(stream)))
 
 
 def tl_k_argmax(x, out, stream=None):

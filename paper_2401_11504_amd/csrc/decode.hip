@@ -123,17 +123,106 @@ __global__ __launch_bounds__(1024) void attn_decode_kernel(const bf16_t* __restr
     }
 }
 
+// Long windows: the keys are cut into n_split ranges, one workgroup per (head, range), so that the cache is read by
+// hundreds of workgroups instead of one per head.  Each writes its unnormalised output, its score maximum and its
+// sum of exponentials to ws[(head * n_split + range) * (d_head + 2)]; attn_decode_combine_kernel merges the ranges.
+__global__ __launch_bounds__(256) void attn_decode_split_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                                                const bf16_t* __restrict__ v, long ld, int n_keys,
+                                                                int d_head, float scale, int chunk,
+                                                                float* __restrict__ ws) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sp = (float*)smem;                     // [chunk] scores, then probabilities
+    float* part_buf = sp + ((chunk + 3) & ~3);    // [parts][d_head]
+    __shared__ float red[16];
+    const int head = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
+    const int k0 = blockIdx.y * chunk, nk = min(chunk, n_keys - k0);   // nk >= 1 by the launch geometry
+    const bf16_t* qh = q + (long)head * d_head;
+    const bf16_t* kh = k + (long)k0 * ld + (long)head * d_head;
+    const bf16_t* vh = v + (long)k0 * ld + (long)head * d_head;
+    const int lpk = d_head >> 3, sub = tid % lpk, kpp = nthr / lpk;
+    float qv[8];
+    unpack8(*(const uint4*)(qh + sub * 8), qv);
+    for (int u0 = 0; u0 < nk; u0 += kpp) {
+        const int u = u0 + tid / lpk;
+        float sdot = 0.f;
+        if (u < nk) {
+            float a[8];
+            unpack8(*(const uint4*)(kh + (long)u * ld + sub * 8), a);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sdot += a[e] * qv[e];
+        }
+        for (int off = lpk >> 1; off > 0; off >>= 1) sdot += __shfl_xor(sdot, off, 64);
+        if (u < nk && sub == 0) sp[u] = sdot * scale;
+    }
+    __syncthreads();
+    float mx = -1.0e30f;
+    for (int u = tid; u < nk; u += nthr) mx = fmaxf(mx, sp[u]);
+    mx = block_max(mx, red);
+    float sum = 0.f;
+    for (int u = tid; u < nk; u += nthr) {
+        const float pr = __expf(sp[u] - mx);
+        sp[u] = pr;
+        sum += pr;
+    }
+    sum = block_sum(sum, red);
+    __syncthreads();
+    const int parts = nthr / d_head, c = tid % d_head, part = tid / d_head;
+    float acc = 0.f;
+    for (int u = part; u < nk; u += parts) acc += sp[u] * bf16_to_f32(vh[(long)u * ld + c]);
+    part_buf[part * d_head + c] = acc;
+    __syncthreads();
+    float* out = ws + ((long)head * gridDim.y + blockIdx.y) * (d_head + 2);
+    if (tid < d_head) {
+        float t = 0.f;
+        for (int pp = 0; pp < parts; ++pp) t += part_buf[pp * d_head + tid];
+        out[tid] = t;
+    }
+    if (tid == 0) { out[d_head] = mx; out[d_head + 1] = sum; }
+}
+
+__global__ void attn_decode_combine_kernel(const float* __restrict__ ws, int n_split, int d_head, bf16_t* __restrict__ o) {
+    const int head = blockIdx.x, c = threadIdx.x;
+    const float* w = ws + (long)head * n_split * (d_head + 2);
+    float M = -1.0e30f;
+    for (int i = 0; i < n_split; ++i) M = fmaxf(M, w[i * (d_head + 2) + d_head]);
+    float L = 0.f, acc = 0.f;
+    for (int i = 0; i < n_split; ++i) {
+        const float e = __expf(w[i * (d_head + 2) + d_head] - M);
+        L += e * w[i * (d_head + 2) + d_head + 1];
+        acc += e * w[i * (d_head + 2) + c];
+    }
+    o[(long)head * d_head + c] = f32_to_bf16(acc / L);
+}
+
+// ws (may be null): scratch of ws_elems floats for the split path; n_heads * n_split * (d_head + 2) of them are used.
 hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
-                                   int d_head, bf16_t* o, hipStream_t s) {
+                                   int d_head, bf16_t* o, float* ws, size_t ws_elems, hipStream_t s) {
     if (n_keys <= 0 || n_heads <= 0) return hipErrorInvalidValue;
     if ((d_head != 64 && d_head != 128) || (ld & 7)) return hipErrorInvalidValue;
+    const float scale = 1.f / sqrtf((float)d_head);
+    // ranges of at least 128 keys, at most ATTN_DECODE_MAX_SPLIT of them, as many as the scratch holds
+    // (below about 400 keys one workgroup per head is as fast and saves the second launch)
+    int n_split = ws && n_keys >= 384 ? min(cdiv(n_keys, 128), ATTN_DECODE_MAX_SPLIT) : 1;
+    if (ws && (size_t)n_heads * n_split * (d_head + 2) > ws_elems) n_split = (int)(ws_elems / ((size_t)n_heads * (d_head + 2)));
+    if (n_split >= 2) {
+        const int chunk = cdiv(n_keys, n_split);
+        n_split = cdiv(n_keys, chunk);            // no empty range
+        const int parts = 256 / d_head;
+        const size_t lds = ((size_t)((chunk + 3) & ~3) + (size_t)parts * d_head) * sizeof(float);
+        if (lds > 60 * 1024) return hipErrorInvalidValue;
+        attn_decode_split_kernel<<<dim3(n_heads, n_split), 256, lds, s>>>(q, k, v, ld, n_keys, d_head, scale, chunk, ws);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        attn_decode_combine_kernel<<<n_heads, d_head, 0, s>>>(ws, n_split, d_head, o);
+        return hipGetLastError();
+    }
     const int nthr = n_keys > 128 ? 1024 : 256;
     const int parts = nthr / d_head;
     const size_t lds = ((size_t)((n_keys + 3) & ~3) + (size_t)parts * d_head) * sizeof(float);
     if (lds > 150 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)attn_decode_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attn_decode_kernel<<<n_heads, nthr, lds, s>>>(q, k, v, ld, n_keys, d_head, 1.f / sqrtf((float)d_head), o);
+    attn_decode_kernel<<<n_heads, nthr, lds, s>>>(q, k, v, ld, n_keys, d_head, scale, o);
     return hipGetLastError();
 }
 

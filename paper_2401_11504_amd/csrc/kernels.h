@@ -105,7 +105,8 @@ hipError_t launch_gemv(const bf16_t* W, long ldw, const bf16_t* x, int N, int K,
                        int r, int rows_per_group, float alpha, const float* resid, bf16_t* y_bf, float* y_f32,
                        hipStream_t s);
 // one query row against cache rows 0 .. n_keys-1 (row stride ld), per head
+constexpr int ATTN_DECODE_MAX_SPLIT = 32;   // key ranges per head in the split decode-attention path
 hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
-                                   int d_head, bf16_t* o, hipStream_t s);
+                                   int d_head, bf16_t* o, float* ws, size_t ws_elems, hipStream_t s);
 // index of the largest of n floats, lowest index among equals
 hipError_t launch_argmax(const float* x, int n, int* out, hipStream_t s);

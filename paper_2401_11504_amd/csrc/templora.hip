@@ -143,6 +143,8 @@ struct tl_lora {
     float* zdrop = nullptr;       // [max_tokens, max(d_model, d_ffn)] fp32: dH A before the mask is applied
     int kv_len = 0;
     float* lora_h = nullptr;      // [3 r] scaled low-rank activations of the projection group in flight
+    float* attn_ws = nullptr;     // partial results of the split decode attention
+    size_t attn_ws_elems = 0;
     int* next_dev = nullptr;
     int* next_host = nullptr;     // pinned
     // dA / dB of a layer (one grouped launch) are off the critical path of the backward pass: they run on a second
@@ -423,6 +425,8 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         HIPCHK(hipHostMalloc((void**)&L->loss_host, 4 * sizeof(float), hipHostMallocDefault));
         HIPCHK(hipHostMalloc((void**)&L->next_host, 4 * sizeof(int), hipHostMallocDefault));
         TLCHK(L->pool.alloc(&L->lora_h, (size_t)3 * r));
+        L->attn_ws_elems = (size_t)mc.n_heads * ATTN_DECODE_MAX_SPLIT * (mc.d_head + 2);
+        TLCHK(L->pool.alloc(&L->attn_ws, L->attn_ws_elems));
         TLCHK(L->pool.alloc(&L->next_dev, (size_t)4));
         HIPCHK(hipStreamSynchronize(s));
         return TL_OK;
@@ -766,8 +770,12 @@ static tl_status emit_next(tl_lora* L, const float* h_last, int32_t* next_token,
     const tl_model_cfg& c = m->cfg;
     hipStream_t s = m->stream;
     HIPCHK(launch_rmsnorm_fwd(h_last, m->gf, 1, c.d_model, c.rms_eps, L->hf, s));
-    HIPCHK(launch_gemv(m->head, c.d_model, L->hf, c.vocab, c.d_model, nullptr, nullptr, 0, 0, 1.f, nullptr, nullptr,
-                       L->logits, s));
+    prof_mark(L);
+    hipError_t e = launch_gemv(m->head, c.d_model, L->hf, c.vocab, c.d_model, nullptr, nullptr, 0, 0, 1.f, nullptr,
+                               nullptr, L->logits, s);
+    prof_mark(L);
+    if (L->prof_on) L->prof_flop += 2.0 * c.vocab * (double)c.d_model;
+    HIPCHK(e);
     HIPCHK(launch_argmax(L->logits, c.vocab, L->next_dev, s));
     HIPCHK(hipMemcpyAsync(L->next_host, L->next_dev, sizeof(int), hipMemcpyDeviceToHost, s));
     if (logits_out)
@@ -811,8 +819,12 @@ static tl_status group_decode(tl_lora* L, int l, int g, const bf16_t* x, bf16_t*
     const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
     const LayerOff& o = L->off[l];
     HIPCHK(launch_gemv(L->S + o.A[g], din, x, G * r, din, nullptr, nullptr, 0, 0, L->s, nullptr, nullptr, L->lora_h, s));
-    HIPCHK(launch_gemv(m->layers[l].w[g], din, x, G * dout, din, L->S + o.B[g], L->lora_h, r, dout, 1.f, resid, y_bf,
-                       y_f32, s));
+    prof_mark(L);   // timing (when on) brackets the launches that stream a frozen matrix
+    hipError_t e = launch_gemv(m->layers[l].w[g], din, x, G * dout, din, L->S + o.B[g], L->lora_h, r, dout, 1.f, resid,
+                               y_bf, y_f32, s);
+    prof_mark(L);
+    if (L->prof_on) L->prof_flop += 2.0 * G * dout * ((double)din + r);
+    HIPCHK(e);
     return TL_OK;
 }
 
@@ -838,7 +850,8 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
         HIPCHK(launch_rmsnorm_fwd(h_in, W.g1, 1, d, c.rms_eps, sv.x1, s));
         TLCHK(group_decode(L, l, G_QKV, sv.x1, row, nullptr, nullptr));
         HIPCHK(launch_rope(row, 3L * d, 1, 2 * c.n_heads, c.d_head, c.rope_base, p, +1, m->rope, s));
-        HIPCHK(launch_attention_decode(row, sv.qkv + d, sv.qkv + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o, s));
+        HIPCHK(launch_attention_decode(row, sv.qkv + d, sv.qkv + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o,
+                                       L->attn_ws, L->attn_ws_elems, s));
         TLCHK(group_decode(L, l, G_O, sv.o, nullptr, sv.hmid, h_in));
         HIPCHK(launch_rmsnorm_fwd(sv.hmid, W.g2, 1, d, c.rms_eps, sv.x2, s));
         TLCHK(group_decode(L, l, G_GU, sv.x2, sv.gu, nullptr, nullptr));
@@ -1103,10 +1116,11 @@ extern "C" tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x
 }
 extern "C" tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ld,
                                            int32_t n_keys, int32_t n_heads, int32_t d_head, uint16_t* o,
-                                           void* hip_stream) {
+                                           float* workspace, size_t workspace_elems, void* hip_stream) {
     KARGS_OK(q && k && v && o && n_keys > 0 && n_heads > 0 && (d_head == 64 || d_head == 128) && (ld & 7) == 0,
              "tl_k_attention_decode");
-    HIPCHK(launch_attention_decode(q, k, v, ld, n_keys, n_heads, d_head, o, (hipStream_t)hip_stream));
+    HIPCHK(launch_attention_decode(q, k, v, ld, n_keys, n_heads, d_head, o, workspace, workspace_elems,
+                                   (hipStream_t)hip_stream));
     return TL_OK;
 }
 extern "C" tl_status tl_k_argmax(const float* x, int32_t n, int32_t* out, void* hip_stream) {

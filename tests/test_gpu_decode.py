@@ -35,15 +35,18 @@ def test_gemv_with_lora_term(api, H, N, K, r, G):
     check(H.bf16_to_np(ybf), ref, BF16_TOL, "y bf16")
 
 
-@pytest.mark.parametrize("n_keys,nh,dh", [(1, 2, 64), (77, 3, 64), (1024, 2, 128), (2048, 1, 128)])
-def test_attention_decode_is_last_row_of_causal_attention(api, H, n_keys, nh, dh):
+@pytest.mark.parametrize("ws_splits", [0, 32, 3])      # no scratch (one workgroup per head); full scratch; a short one
+@pytest.mark.parametrize("n_keys,nh,dh", [(1, 2, 64), (77, 3, 64), (129, 2, 64), (384, 2, 64), (1000, 4, 64), (1024, 2, 128),
+                                          (2048, 1, 128), (3000, 2, 128)])
+def test_attention_decode_is_last_row_of_causal_attention(api, H, n_keys, nh, dh, ws_splits):
     d = nh * dh
     qkv = rnd(1, (n_keys, 3 * d), 1.0)
     q, k, v = (qkv[:, i * d:(i + 1) * d].reshape(n_keys, nh, dh) for i in range(3))
     ro, _ = O.attention_fwd(q, k, v)
     dev = H.to_dev_bf16(qkv)
     o = torch.zeros(d, dtype=torch.bfloat16, device="cuda")
-    api.tl_k_attention_decode(dev[n_keys - 1, :d], dev[:, d:2 * d], dev[:, 2 * d:], nh, dh, o)
+    ws = torch.zeros(nh * ws_splits * (dh + 2), device="cuda") if ws_splits else None
+    api.tl_k_attention_decode(dev[n_keys - 1, :d], dev[:, d:2 * d], dev[:, 2 * d:], nh, dh, o, ws)
     torch.cuda.synchronize()
     check(H.bf16_to_np(o), ro[-1].reshape(d), BF16_TOL, "o")
 
