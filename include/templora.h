@@ -305,6 +305,10 @@ tl_status tl_k_swiglu_fwd(const uint16_t* gu, int32_t T, int32_t f, uint16_t* a,
 tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x, int32_t N, int32_t K, const uint16_t* lora_b,
                     const float* lora_h, int32_t r, int32_t rows_per_group, float alpha, const float* resid, void* y,
                     int32_t y_f32, void* hip_stream);
+/* y fp32 [N] = W x with x formed inside the launch: mode 1, x = bf16(RMSNorm(h) * gain) of the fp32 row h[K];
+ * mode 2, x = bf16(silu(g) * u) of the bf16 row gu = g[K] | u[K].  x_out (bf16 [K]) receives x if not NULL. */
+tl_status tl_k_gemv_pre(const uint16_t* W, int32_t ldw, int32_t N, int32_t K, int32_t mode, const float* h,
+                        const float* gain, float eps, const uint16_t* gu, uint16_t* x_out, float* y, void* hip_stream);
 tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ld, int32_t n_keys,
                                 int32_t n_heads, int32_t d_head, uint16_t* o, float* workspace, size_t workspace_elems,
                                 void* hip_stream);

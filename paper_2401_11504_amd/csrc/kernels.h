@@ -101,9 +101,18 @@ hipError_t launch_copy2d_bf16(const bf16_t* src, long lds, int rows, int cols, b
 
 // ---------------------------------------------------------------- one-token decoding (decode.hip)
 // y[N] = alpha * (W[N, K] x[K] + sum_j lora_b[n, j] lora_h[(n / rows_per_group) r + j]) (+ resid, fp32 output only)
+// Where a matrix-vector product takes its input vector from (see gemv_kernel)
+struct GemvPre {
+    int mode = 0;                 // 0: x as given; 1: RMSNorm of h with gain; 2: SwiGLU of the gate|up row gu
+    const float* h = nullptr;
+    const float* gain = nullptr;
+    float eps = 0.f;
+    const bf16_t* gu = nullptr;
+    bf16_t* x_out = nullptr;      // if set, workgroup 0 stores the input vector it formed
+};
 hipError_t launch_gemv(const bf16_t* W, long ldw, const bf16_t* x, int N, int K, const bf16_t* lora_b, const float* lora_h,
                        int r, int rows_per_group, float alpha, const float* resid, bf16_t* y_bf, float* y_f32,
-                       hipStream_t s);
+                       hipStream_t s, const GemvPre* pre = nullptr);
 // one query row against cache rows 0 .. n_keys-1 (row stride ld), per head
 constexpr int ATTN_DECODE_MAX_SPLIT = 32;   // key ranges per head in the split decode-attention path
 hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,

@@ -769,10 +769,11 @@ static tl_status emit_next(tl_lora* L, const float* h_last, int32_t* next_token,
     tl_model* m = L->model;
     const tl_model_cfg& c = m->cfg;
     hipStream_t s = m->stream;
-    HIPCHK(launch_rmsnorm_fwd(h_last, m->gf, 1, c.d_model, c.rms_eps, L->hf, s));
+    GemvPre nf;    // the final norm is formed inside the lm_head product
+    nf.mode = 1; nf.h = h_last; nf.gain = m->gf; nf.eps = c.rms_eps;
     prof_mark(L);
-    hipError_t e = launch_gemv(m->head, c.d_model, L->hf, c.vocab, c.d_model, nullptr, nullptr, 0, 0, 1.f, nullptr,
-                               nullptr, L->logits, s);
+    hipError_t e = launch_gemv(m->head, c.d_model, nullptr, c.vocab, c.d_model, nullptr, nullptr, 0, 0, 1.f, nullptr,
+                               nullptr, L->logits, s, &nf);
     prof_mark(L);
     if (L->prof_on) L->prof_flop += 2.0 * c.vocab * (double)c.d_model;
     HIPCHK(e);
@@ -813,12 +814,15 @@ extern "C" tl_status tl_prefill(tl_lora* L, const int32_t* tokens, int32_t n_tok
 }
 
 // One LoRA-adapted projection group of a single token: h = s A x, then y = W x + B h (+ residual)
-static tl_status group_decode(tl_lora* L, int l, int g, const bf16_t* x, bf16_t* y_bf, float* y_f32, const float* resid) {
+// x: the group's input vector; with `pre` it is formed (norm / SwiGLU) inside the first launch, which stores it to x
+static tl_status group_decode(tl_lora* L, int l, int g, const bf16_t* x, bf16_t* y_bf, float* y_f32, const float* resid,
+                              const GemvPre* pre = nullptr) {
     tl_model* m = L->model;
     hipStream_t s = m->stream;
     const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
     const LayerOff& o = L->off[l];
-    HIPCHK(launch_gemv(L->S + o.A[g], din, x, G * r, din, nullptr, nullptr, 0, 0, L->s, nullptr, nullptr, L->lora_h, s));
+    HIPCHK(launch_gemv(L->S + o.A[g], din, x, G * r, din, nullptr, nullptr, 0, 0, L->s, nullptr, nullptr, L->lora_h, s,
+                       pre));
     prof_mark(L);   // timing (when on) brackets the launches that stream a frozen matrix
     hipError_t e = launch_gemv(m->layers[l].w[g], din, x, G * dout, din, L->S + o.B[g], L->lora_h, r, dout, 1.f, resid,
                                y_bf, y_f32, s);
@@ -837,7 +841,7 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
     if (L->kv_len >= c.max_tokens) return fail(TL_ERR_WINDOW, "the window is full (%d positions)", c.max_tokens);
     if (token < 0 || token >= c.vocab) return fail(TL_ERR_TOKEN_RANGE, "token = %d outside [0, %d)", token, c.vocab);
     hipStream_t s = m->stream;
-    const int d = c.d_model, f = c.d_ffn, p = L->kv_len;
+    const int d = c.d_model, p = L->kv_len;
     L->tok_host[0] = token;
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(launch_embed(m->emb, L->tok, 1, d, L->hs[0], s));
@@ -847,16 +851,17 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
         const float* h_in = L->hs[l];
         float* h_out = L->hs[l + 1];
         bf16_t* row = sv.qkv + (size_t)p * 3 * d;                 // the new cache row: q | k | v of position p
-        HIPCHK(launch_rmsnorm_fwd(h_in, W.g1, 1, d, c.rms_eps, sv.x1, s));
-        TLCHK(group_decode(L, l, G_QKV, sv.x1, row, nullptr, nullptr));
+        GemvPre n1, n2, sw;
+        n1.mode = 1; n1.h = h_in; n1.gain = W.g1; n1.eps = c.rms_eps; n1.x_out = sv.x1;
+        n2.mode = 1; n2.h = sv.hmid; n2.gain = W.g2; n2.eps = c.rms_eps; n2.x_out = sv.x2;
+        sw.mode = 2; sw.gu = sv.gu; sw.x_out = sv.act;
+        TLCHK(group_decode(L, l, G_QKV, sv.x1, row, nullptr, nullptr, &n1));
         HIPCHK(launch_rope(row, 3L * d, 1, 2 * c.n_heads, c.d_head, c.rope_base, p, +1, m->rope, s));
         HIPCHK(launch_attention_decode(row, sv.qkv + d, sv.qkv + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o,
                                        L->attn_ws, L->attn_ws_elems, s));
         TLCHK(group_decode(L, l, G_O, sv.o, nullptr, sv.hmid, h_in));
-        HIPCHK(launch_rmsnorm_fwd(sv.hmid, W.g2, 1, d, c.rms_eps, sv.x2, s));
-        TLCHK(group_decode(L, l, G_GU, sv.x2, sv.gu, nullptr, nullptr));
-        HIPCHK(launch_swiglu_fwd(sv.gu, 1, f, sv.act, s));
-        TLCHK(group_decode(L, l, G_DOWN, sv.act, nullptr, h_out, sv.hmid));
+        TLCHK(group_decode(L, l, G_GU, sv.x2, sv.gu, nullptr, nullptr, &n2));
+        TLCHK(group_decode(L, l, G_DOWN, sv.act, nullptr, h_out, sv.hmid, &sw));
     }
     TLCHK(emit_next(L, L->hs[c.n_layers], next_token, logits_out));
     L->kv_len = p + 1;
@@ -1112,6 +1117,17 @@ extern "C" tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x
                  (y_f32 || !resid), "tl_k_gemv");
     HIPCHK(launch_gemv(W, ldw, x, N, K, lora_b, lora_h, r, rows_per_group, alpha, resid, y_f32 ? nullptr : (bf16_t*)y,
                        y_f32 ? (float*)y : nullptr, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_gemv_pre(const uint16_t* W, int32_t ldw, int32_t N, int32_t K, int32_t mode, const float* h,
+                                   const float* gain, float eps, const uint16_t* gu, uint16_t* x_out, float* y,
+                                   void* hip_stream) {
+    KARGS_OK(W && y && N >= 0 && K > 0 && (K & 7) == 0 && (ldw & 7) == 0 &&
+                 ((mode == 1 && h && gain) || (mode == 2 && gu)), "tl_k_gemv_pre");
+    GemvPre pre;
+    pre.mode = mode; pre.h = h; pre.gain = gain; pre.eps = eps; pre.gu = gu; pre.x_out = x_out;
+    HIPCHK(launch_gemv(W, ldw, nullptr, N, K, nullptr, nullptr, 0, 0, 1.f, nullptr, nullptr, y, (hipStream_t)hip_stream,
+                       &pre));
     return TL_OK;
 }
 extern "C" tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int32_t ld,

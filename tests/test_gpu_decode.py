@@ -14,7 +14,8 @@ from test_gpu_kernels import BF16_TOL, H, api, check, rnd  # noqa: E402,F401
 
 
 # ------------------------------------------------------------------ kernels
-@pytest.mark.parametrize("N,K,r,G", [(64, 64, 0, 1), (1000, 4096, 16, 1), (3 * 256, 256, 8, 3), (776, 11008, 64, 1)])
+@pytest.mark.parametrize("N,K,r,G", [(64, 64, 0, 1), (1000, 4096, 16, 1), (3 * 256, 256, 8, 3), (776, 11008, 64, 1),
+                                     (192, 4096, 64, 3), (512, 11008, 16, 1), (516, 256, 8, 1), (1, 8, 0, 1)])
 def test_gemv_with_lora_term(api, H, N, K, r, G):
     W, x = rnd(1, (N, K), 0.05), rnd(2, (1, K))[0]
     ref = W.astype(np.float64) @ x.astype(np.float64)
@@ -33,6 +34,27 @@ def test_gemv_with_lora_term(api, H, N, K, r, G):
     torch.cuda.synchronize()
     check(y32.cpu().numpy(), 0.5 * ref + res, 1e-4, "y fp32 + resid")      # bf16 products are exact; fp32 sums
     check(H.bf16_to_np(ybf), ref, BF16_TOL, "y bf16")
+
+
+@pytest.mark.parametrize("N,K", [(64, 4096), (192, 264), (1000, 4096), (128, 11008)])
+def test_gemv_with_norm_and_swiglu_prologues(api, H, N, K):
+    """The input vector formed inside the launch: RMSNorm of an fp32 row, SwiGLU of a gate|up row."""
+    W = rnd(1, (N, K), 0.05)
+    h, gain = rnd(2, (1, K), 2.0, False), 1.0 + rnd(3, (1, K), 0.1, False)[0]
+    gu = rnd(4, (1, 2 * K), 1.5)
+    y = torch.empty(N, dtype=torch.float32, device="cuda")
+    xo = torch.empty(K, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_gemv_pre(H.to_dev_bf16(W), y, 1, h=H.to_dev_f32(h[0]), gain=H.to_dev_f32(gain), eps=1e-5, x_out=xo)
+    torch.cuda.synchronize()
+    x_ref = O.rmsnorm_fwd(h, gain, 1e-5)[0]
+    check(H.bf16_to_np(xo), x_ref, BF16_TOL, "x (norm)")
+    # the product is taken with the bf16-rounded vector the kernel stored, so that only the summation differs
+    check(y.cpu().numpy(), W.astype(np.float64) @ H.bf16_to_np(xo).astype(np.float64), 1e-4, "y (norm)")
+    api.tl_k_gemv_pre(H.to_dev_bf16(W), y, 2, gu=H.to_dev_bf16(gu[0]), x_out=xo)
+    torch.cuda.synchronize()
+    a_ref = O.swiglu_fwd(gu[:, :K], gu[:, K:])[0]
+    check(H.bf16_to_np(xo), a_ref, BF16_TOL, "x (swiglu)")
+    check(y.cpu().numpy(), W.astype(np.float64) @ H.bf16_to_np(xo).astype(np.float64), 1e-4, "y (swiglu)")
 
 
 @pytest.mark.parametrize("ws_splits", [0, 32, 3])      # no scratch (one workgroup per head); full scratch; a short one
@@ -68,7 +90,7 @@ def _oracle_args(model, facs):
     return (shape, model.emb, model.head, np.ones(shape.d_model), lambda l: model.host_layers[l], facs)
 
 
-@pytest.mark.parametrize("name,n_prompt,n_new", [("small", 37, 12), ("small128", 130, 8)])
+@pytest.mark.parametrize("name,n_prompt,n_new", [("small", 37, 12), ("small128", 130, 8), ("small", 420, 4)])
 def test_prefill_and_decode_follow_the_oracle(api, H, name, n_prompt, n_new):
     shape = synth.SHAPES[name]
     seed = 4100
