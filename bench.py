@@ -128,6 +128,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=32, help="debug only: fewer layers (marks the line invalid)")
     ap.add_argument("--tokens", type=int, default=1024)
+    ap.add_argument("--ctx", type=int, default=0,
+                    help="debug only: the first CTX of --tokens are conditioning (L_T prefix, no loss on them)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="debug only: LoRA dropout rate (the benchmark configuration has none; marks the line)")
     ap.add_argument("--decode", action="store_true",
@@ -165,7 +167,7 @@ def main():
         return
     shape = synth.SHAPES["7b"].with_layers(args.layers)
     T, seed = args.tokens, 3000
-    headline = args.layers == 32 and T == 1024 and args.dropout == 0.0
+    headline = args.layers == 32 and T == 1024 and args.dropout == 0.0 and args.ctx == 0
     model = harness.Model(shape, seed, max_tokens=T, keep_host=False, device_random=True)
     # config: A ~ N(0, 0.02^2), B = 0, AdamW lr 5e-5, betas (0.9, 0.999), wd 0
     lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed,
@@ -175,12 +177,12 @@ def main():
 
     loss = None
     for _ in range(args.warmup):
-        loss, n_targets = api.tl_chunk_update(lora, tok, 0, lr)
+        loss, n_targets = api.tl_chunk_update(lora, tok, args.ctx, lr)
     # timed region 1: exactly K steps, nothing but the update on the GPU -> `value`
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        loss, n_targets = api.tl_chunk_update(lora, tok, 0, lr)
+        loss, n_targets = api.tl_chunk_update(lora, tok, args.ctx, lr)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # timed region 2: K more steps with every launch of the dominant kernel bracketed by HIP events on the
@@ -192,7 +194,7 @@ def main():
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for _ in range(args.steps):
-            api.tl_chunk_update(lora, tok, 0, lr)
+            api.tl_chunk_update(lora, tok, args.ctx, lr)
         torch.cuda.synchronize()
         dt_ev = time.perf_counter() - t1
         ms, launches, flop = api.tl_profile_read(lora)
@@ -220,7 +222,7 @@ def main():
     total_flop = 2 * frozen + lora_fl + attn
     out = {
         "metric": "trained tokens/sec per Temp-Lora chunk update (7B-shape, r=64); MFMA util %",
-        "value": round(T / (ms_step * 1e-3), 1),
+        "value": round((T - args.ctx) / (ms_step * 1e-3), 1),   # chunk tokens; conditioning tokens are not trained on
         "unit": "trained tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 3),
@@ -229,7 +231,8 @@ def main():
         "config": {"workload": "configs[2]: full Temp-Lora chunk update, 7B-shaped decoder (32 layers, d 4096, 32x128 "
                                "heads, ffn 11008, vocab 32000), LoRA r=64 alpha=64 on q,k,v,o,gate,up,down, "
                                "one 1024-token chunk, AdamW lr 5e-5" if headline else
-                               f"DEBUG (not the benchmark): {args.layers} layers, {T} tokens, dropout {args.dropout}",
+                               f"DEBUG (not the benchmark): {args.layers} layers, {T} tokens of which {args.ctx} conditioning, "
+                               f"dropout {args.dropout}",
                    "n_tokens": T, "n_layers": args.layers, "rank": r, "loss": round(float(loss), 5),
                    "n_targets": n_targets},
         "mfma_util_whole_update": round(total_flop / (ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
