@@ -64,6 +64,41 @@ def cpu_baseline(shape, T, seed):
                       f"final norm/lm_head/CE fwd+bwd timed once ({t_head:.2f} s); AdamW not included"}
 
 
+def stream_probe(torch, api):
+    """The operand streams of the frozen-weight GEMM with no arithmetic (tl_probe_operand_stream), at the shapes of the
+    update's N = 4096 GEMMs with 128x128 tiles: what the loads alone cost, with the weights in the last-level cache
+    ("warm": the same matrix every launch) and coming from HBM ("cold": launches rotate over copies that together
+    exceed the 256 MB cache, as consecutive layers do in the update).  Prints one JSON line per case."""
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    A = torch.ones(1 << 26, dtype=torch.float32, device="cuda")     # 256 MiB of activations-to-be
+    B = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB of weight copies
+    tiles_m, tiles_n = 8, 32                                        # M = 1024, N = 4096
+    for name, K in (("o (K 4096)", 4096), ("down (K 11008)", 11008), ("dx_gate|up (K 22016)", 22016)):
+        ld = kb = 2 * K
+        bsz = tiles_n * 128 * ld
+        copies = (B.numel() * 4) // bsz
+        for mode in ("warm", "cold"):
+            for steps in (1, 2, 3, 4, 8):
+                sel = (lambda i: 0) if mode == "warm" else (lambda i: i % copies)
+                reps = 24
+                for i in range(3):
+                    api.tl_probe_operand_stream(A.data_ptr(), B.data_ptr() + sel(i) * bsz, ld, kb, tiles_m, tiles_n, steps, sink)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(reps):
+                    api.tl_probe_operand_stream(A.data_ptr(), B.data_ptr() + sel(i + 3) * bsz, ld, kb, tiles_m, tiles_n, steps, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                req = 256.0 * kb * tiles_m * tiles_n                # bytes requested by all workgroups per launch
+                print(json.dumps({"streams_of": name, "weights": mode, "weight_copies": copies if mode == "cold" else 1,
+                                  "steps_in_flight": steps, "us_per_launch": round(us, 1),
+                                  "requested_TB_per_s": round(req / us / 1e6, 2),
+                                  "GB_per_s_per_CU": round(req / us / 1e3 / 256, 1),
+                                  "weight_TB_per_s": round(bsz / us / 1e6, 2)}), flush=True)
+
+
 def decode_bench(args, torch, api, harness, synth):
     """Greedy decoding with the module over the key/value cache (Algorithm 1's token loop): tokens/s, and the
     matrix-vector kernel that streams the frozen weights against the HBM roofline."""
@@ -132,6 +167,8 @@ def main():
                     help="debug only: the first CTX of --tokens are conditioning (L_T prefix, no loss on them)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="debug only: LoRA dropout rate (the benchmark configuration has none; marks the line)")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="only run the GEMM operand-stream probe (loads without arithmetic) and exit")
     ap.add_argument("--decode", action="store_true",
                     help="measure the generation side instead (the step either side of the update): one step = one "
                          "greedily decoded token with the module applied, after a prefill of --prompt tokens")
@@ -162,6 +199,9 @@ def main():
         return
     from paper_2401_11504_amd import api, harness, synth
 
+    if args.stream_probe:
+        stream_probe(torch, api)
+        return
     if args.decode:
         decode_bench(args, torch, api, harness, synth)
         return

@@ -239,6 +239,15 @@ tl_status tl_get_dh(tl_lora* lora, int32_t boundary, float* host_out, size_t n);
 tl_status tl_profile_enable(tl_lora* lora, int32_t on);
 tl_status tl_profile_read(tl_lora* lora, double* ms_total, int64_t* launches, double* flop_total);
 
+/* The operand streams of the frozen-weight GEMM without its arithmetic (a ceiling for that kernel's loads): one
+ * workgroup per 128x128 output tile pulls 128 rows of A (device, tiles_m * 128 rows) and 128 rows of B (device,
+ * tiles_n * 128 rows), the first k_bytes (a multiple of 128) of every row, rows ld_bytes apart (a multiple of 16;
+ * each matrix below 4 GiB), 128 bytes per row and step, steps_in_flight (1, 2, 3, 4, 6 or 8) steps ahead, into LDS,
+ * and discards them.  sink: one device uint32 (never written in practice).  Nothing is synchronised: time it with
+ * events on hip_stream.  Errors: TL_ERR_ARG (null pointer, geometry), TL_ERR_DEVICE. */
+tl_status tl_probe_operand_stream(const void* A, const void* B, uint32_t ld_bytes, uint32_t k_bytes, int32_t tiles_m,
+                                  int32_t tiles_n, int32_t steps_in_flight, uint32_t* sink, void* hip_stream);
+
 /*
  * One decoder layer alone: forward from a given hidden state, backward from a
  * given upstream gradient, gradients of that layer's 7 LoRA pairs, and

@@ -84,6 +84,7 @@ _SIGS = {
     "tl_k_swiglu_fwd": [_vp, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_bwd": [_vp, _vp, _i32, _i32, _vp, _vp],
     "tl_k_gemv": [_vp, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _vp],
+    "tl_probe_operand_stream": [_vp, _vp, C.c_uint32, C.c_uint32, _i32, _i32, _i32, _vp, _vp],
     "tl_k_gemv_pre": [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _f32, _vp, _vp, _vp, _vp],
     "tl_k_attention_decode": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _sz, _vp],
     "tl_k_argmax": [_vp, _i32, _vp, _vp],
@@ -328,6 +329,12 @@ def tl_k_gemv(W, x, y, lora_b=None, lora_h=None, rows_per_group=0, alpha=1.0, re
     r = lora_b.shape[1] if lora_b is not None else 0
     _chk(_lib.tl_k_gemv(_dp(W), W.stride(0), _dp(x), N, K, _dp(lora_b), _dp(lora_h), r, rows_per_group, alpha, _dp(resid),
                         _dp(y), int(y.dtype == torch.float32), _s(stream)))
+
+
+def tl_probe_operand_stream(A_ptr, B_ptr, ld_bytes, k_bytes, tiles_m, tiles_n, steps_in_flight, sink, stream=None):
+    """A_ptr, B_ptr: device addresses (int); sink: device int32 tensor."""
+    _chk(_lib.tl_probe_operand_stream(A_ptr, B_ptr, ld_bytes, k_bytes, tiles_m, tiles_n, steps_in_flight, _dp(sink),
+                                      _s(stream)))
 
 
 def tl_k_gemv_pre(W, y, mode, h=None, gain=None, eps=0.0, gu=None, x_out=None, stream=None):

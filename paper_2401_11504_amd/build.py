@@ -15,7 +15,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libtemplora.so")
-SOURCES = ["templora.hip", "gemm_bf16.hip", "gemm_f32.hip", "attention.hip", "elementwise.hip", "decode.hip"]
+SOURCES = ["templora.hip", "gemm_bf16.hip", "gemm_f32.hip", "attention.hip", "elementwise.hip", "decode.hip", "stream_probe.hip"]
 # packed-fp32 VALU forms are switched off for device code on purpose ("Build flags")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]

@@ -165,7 +165,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, int PIPE = 0>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n, int xcd_split) {
     constexpr int NT = WM * WN * 64;
     constexpr int ROWS = BM + BN;
     constexpr int CPRW = BKT / 8;             // 16-byte chunks per tile row
@@ -186,9 +186,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, g = lane >> 5;
 
+    // Workgroup ids go round-robin over the 8 XCDs (x fastest, then y), each with its own L2: XCD c gets a contiguous
+    // range of tiles (m fastest), so that its CUs share weight rows.  With the contraction split 2, 4 or 8 ways the
+    // XCD also fixes the split: XCD c works on split c / (8 / n_split) only, so an XCD fetches just its share of the
+    // contraction range of the activations instead of all of it.
     const int ntiles = tiles_m * tiles_n;
-    int pid = blockIdx.x;
-    if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+    const int n_split = SPLITK ? (int)gridDim.y : 1;
+    int pid = blockIdx.x, split = SPLITK ? (int)blockIdx.y : 0;
+    const int xs = 8 / max(n_split, 1);   // XCDs per split
+    if (SPLITK && xcd_split && gridDim.z == 1 && (n_split == 2 || n_split == 4 || n_split == 8) && ntiles % xs == 0) {
+        const int id = blockIdx.y * gridDim.x + blockIdx.x, c = id & 7, j = id >> 3;
+        split = c / xs;
+        pid = (c % xs) * (ntiles / xs) + j;
+    } else if ((ntiles & 7) == 0) {
+        pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+    }
     const int tile_m = pid % tiles_m, tile_n = pid / tiles_m;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int z = blockIdx.z;
@@ -198,8 +210,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     const bf16_t* A2 = p.A2 ? p.A2 + (long)z * p.bA2 : nullptr;
     const bf16_t* B2 = p.B2 ? p.B2 + (long)z * p.bB2 : nullptr;
     const int nk1 = p.K / BKT, nk2 = p.K2 / BKT;
-    // with SPLITK, grid.y workgroups share one output tile: this one takes k-tiles [kt0, kt0 + nk)
-    const int n_split = SPLITK ? (int)gridDim.y : 1, split = SPLITK ? (int)blockIdx.y : 0;
+    // with SPLITK, n_split workgroups share one output tile: this one takes k-tiles [kt0, kt0 + nk)
     const int kt0 = (int)((long)(nk1 + nk2) * split / n_split);
     const int nk = (int)((long)(nk1 + nk2) * (split + 1) / n_split) - kt0;
 
@@ -526,7 +537,8 @@ static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     }
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n);
+    static const int xcd_split = getenv("TL_GEMM_XCD_SPLIT") ? atoi(getenv("TL_GEMM_XCD_SPLIT")) : 1;   // tuning aid
+    kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n, xcd_split);
     if (SPLITK) {
         const long n = (long)g.M * (g.N >> 2) * g.batch;
         splitk_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, n_split);

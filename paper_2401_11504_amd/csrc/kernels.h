@@ -85,6 +85,9 @@ hipError_t launch_labels(const int* tokens, int T, int* labels, hipStream_t s);
 hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float value, hipStream_t s);
 hipError_t launch_init_normal(float* p, size_t n, float std, uint64_t seed, uint64_t stream_id, hipStream_t s);
+// measurement aid: the GEMM's operand streams without arithmetic (stream_probe.hip)
+hipError_t launch_stream_probe(const void* A, const void* B, unsigned ld, unsigned kbytes, int tiles_m, int tiles_n,
+                               int steps_in_flight, unsigned* sink, hipStream_t s);
 // LoRA dropout: the mask is a function of (key, element index); key from (seed, optimizer step, layer, group)
 uint64_t dropout_key(uint64_t seed, int64_t step, int layer, int group);
 hipError_t launch_dropout_fwd(const bf16_t* x, bf16_t* y, size_t n, uint64_t key, float p, hipStream_t s);

@@ -1119,6 +1119,16 @@ extern "C" tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x
                        y_f32 ? (float*)y : nullptr, (hipStream_t)hip_stream));
     return TL_OK;
 }
+extern "C" tl_status tl_probe_operand_stream(const void* A, const void* B, uint32_t ld_bytes, uint32_t k_bytes,
+                                             int32_t tiles_m, int32_t tiles_n, int32_t steps_in_flight, uint32_t* sink,
+                                             void* hip_stream) {
+    KARGS_OK(A && B && sink, "tl_probe_operand_stream");
+    hipError_t e = launch_stream_probe(A, B, ld_bytes, k_bytes, tiles_m, tiles_n, steps_in_flight, sink,
+                                       (hipStream_t)hip_stream);
+    if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return fail(TL_ERR_ARG, "tl_probe_operand_stream: bad geometry"); }
+    HIPCHK(e);
+    return TL_OK;
+}
 extern "C" tl_status tl_k_gemv_pre(const uint16_t* W, int32_t ldw, int32_t N, int32_t K, int32_t mode, const float* h,
                                    const float* gain, float eps, const uint16_t* gu, uint16_t* x_out, float* y,
                                    void* hip_stream) {
