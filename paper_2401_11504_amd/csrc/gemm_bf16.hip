@@ -17,6 +17,14 @@
 #include <type_traits>
 
 // ======================================================================== NT
+// Workgroup ids go round-robin over the 8 XCDs (each with its own L2).  XCD c therefore runs ids c, c + 8, ..: give
+// it the contiguous tile range that starts after the ranges of XCDs 0 .. c-1 (the first n % 8 XCDs hold one tile
+// more), so that the CUs of one XCD work on neighbouring tiles and share operand rows in their L2.
+__device__ __forceinline__ int xcd_contiguous(int id, int n) {
+    const int c = id & 7, q = n >> 3, rem = n & 7;
+    return c * q + min(c, rem) + (id >> 3);
+}
+
 template <int BM, int BN, int WM, int WN, bool PARTIAL>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT p, int tiles_m, int tiles_n, int split_k) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -34,7 +42,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmNT p, int tiles_m, int
     // XCD x the contiguous tile range [x * n/8, (x+1) * n/8): its CUs then share W columns in its L2.
     const int ntiles = tiles_m * tiles_n;
     int pid = blockIdx.x;
-    if ((ntiles & 7) == 0) pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+    pid = xcd_contiguous(pid, ntiles);
     const int tile_m = pid % tiles_m, tile_n = pid / tiles_m;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int z = blockIdx.z, split = blockIdx.y;
@@ -198,8 +206,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         const int id = blockIdx.y * gridDim.x + blockIdx.x, c = id & 7, j = id >> 3;
         split = c / xs;
         pid = (c % xs) * (ntiles / xs) + j;
-    } else if ((ntiles & 7) == 0) {
-        pid = (pid & 7) * (ntiles >> 3) + (pid >> 3);
+    } else if (xcd_split != 2 || (ntiles & 7) == 0) {   // (2: tuning aid, plain round-robin for ragged tile counts)
+        pid = xcd_contiguous(pid, ntiles);
     }
     const int tile_m = pid % tiles_m, tile_n = pid / tiles_m;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
