@@ -191,7 +191,7 @@ tl_status tl_discard(tl_lora* lora);
  * rotated keys and the values of every layer for positions 0 .. kv_length-1 (positions count from the start of the
  * window handed to tl_prefill).  It is (re)built by tl_prefill and extended by tl_decode_step; every
  * tl_chunk_update / tl_chunk_loss / tl_layer_step invalidates it, which is the paper's default of recomputing the
- * cache with the updated module after each chunk (call tl_prefill on the last L_X tokens).
+ * cache with the updated module after each chunk (call tl_prefill on the last L_X tokens); tl_cache_reuse changes that.
  *
  * tl_prefill: tokens host int32[n_tokens], 1 <= n_tokens <= max_tokens.  Runs the LoRA-adapted forward pass over the
  * window, fills the cache, and returns in *next_token the greedy continuation (index of the largest last-position
@@ -202,6 +202,15 @@ tl_status tl_discard(tl_lora* lora);
 tl_status tl_prefill(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int32_t* next_token, float* logits_out);
 tl_status tl_decode_step(tl_lora* lora, int32_t token, int32_t* next_token, float* logits_out);
 tl_status tl_kv_length(tl_lora* lora, int32_t* n_out);
+
+/* Cache reuse (Section 2: after an update, keep the key/value states instead of recomputing them with the updated
+ * module).  on != 0: the cache moves to buffers of its own (allocated on the first call: n_layers * max_tokens *
+ * 3 d_model bf16) and survives tl_chunk_update / tl_chunk_train / tl_chunk_loss / tl_layer_step; tl_decode_step then
+ * attends over keys and values of the earlier module for the positions cached before the update and uses the updated
+ * module for everything it computes itself.  tl_prefill still rebuilds the whole cache with the current module (the
+ * paper's default, and what the caller does when the window is full).  on == 0 (the initial state): back to the
+ * default, the cache is dropped.  Errors: TL_ERR_ARG, TL_ERR_DISCARDED, TL_ERR_OOM, TL_ERR_DEVICE. */
+tl_status tl_cache_reuse(tl_lora* lora, int32_t on);
 
 /* Release the (discarded or not) handle itself. NULL is accepted. */
 tl_status tl_lora_free(tl_lora* lora);

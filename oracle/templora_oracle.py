@@ -21,6 +21,8 @@ independent autograd graph agree with every gradient; the loss is a valid NLL
 with its step-1 closed form and with a library optimizer over several steps;
 RoPE and RMSNorm invariants; causality; window_logits agrees with the autograd
 graph's logits and is causal (a longer window leaves earlier rows unchanged);
+window_logits_reuse with the same module on both sides is window_logits, and
+with different ones its old positions are untouched by the new module;
 chunk_train's samples cover every chunk position exactly once per epoch with at
 most L_T conditioning tokens, its warm-up is checked against hand-computed
 rates, and with one piece, one epoch and no warm-up it is chunk_update; the
@@ -384,6 +386,45 @@ def greedy_decode(prompt, n_new, shape, emb, head, g_final, get_layer, lora):
         nxt, _ = greedy_next(seq, shape, emb, head, g_final, get_layer, lora)
         seq.append(nxt)
     return seq[len(prompt):]
+
+
+def _layer_with_past(h, W, L, shape, past_k, past_v):
+    """One layer over new positions n_past .. n_past + T - 1 whose attention also sees the given keys and values of
+    positions 0 .. n_past - 1 (past_k rotated, both [n_past, n_heads, d_head]).  Returns (h_out, k, v) of the new rows.
+    Written from the definition: softmax over every visible key, no running statistics."""
+    T, n_past = h.shape[0], past_k.shape[0]
+    nh, dh, s = shape.n_heads, shape.d_head, shape.scale
+    x1 = rmsnorm_fwd(h, W["g1"], shape.rms_eps)
+    q = rope_fwd(lora_linear_fwd(x1, W["q"], *L["q"], s)[0].reshape(T, nh, dh), shape.rope_base, n_past)
+    k = rope_fwd(lora_linear_fwd(x1, W["k"], *L["k"], s)[0].reshape(T, nh, dh), shape.rope_base, n_past)
+    v = lora_linear_fwd(x1, W["v"], *L["v"], s)[0].reshape(T, nh, dh)
+    K = np.concatenate([_f(past_k), k], 0)
+    V = np.concatenate([_f(past_v), v], 0)
+    o = np.zeros((T, nh, dh), F64)
+    for i in range(T):
+        vis = n_past + i + 1                                   # query i sits at position n_past + i
+        sc = np.einsum("hd,uhd->hu", q[i], K[:vis]) / np.sqrt(dh)
+        sc = np.exp(sc - sc.max(1, keepdims=True))
+        o[i] = np.einsum("hu,uhd->hd", sc / sc.sum(1, keepdims=True), V[:vis])
+    h1 = h + lora_linear_fwd(o.reshape(T, nh * dh), W["o"], *L["o"], s)[0]
+    x2 = rmsnorm_fwd(h1, W["g2"], shape.rms_eps)
+    a = swiglu_fwd(lora_linear_fwd(x2, W["gate"], *L["gate"], s)[0], lora_linear_fwd(x2, W["up"], *L["up"], s)[0])
+    return h1 + lora_linear_fwd(a, W["down"], *L["down"], s)[0], k, v
+
+
+def window_logits_reuse(tokens, n_stale, shape, emb, head, g_final, get_layer, lora_old, lora_new):
+    """Cache reuse (Section 2): logits of positions n_stale .. under lora_new, attending over the keys and values that
+    lora_old computed for positions 0 .. n_stale - 1 (every layer's cache is the old module's forward pass over the old
+    positions; nothing of the old positions is recomputed)."""
+    tok = np.asarray(tokens, dtype=np.int64)
+    nh, dh = shape.n_heads, shape.d_head
+    empty = np.zeros((0, nh, dh), F64)
+    h_old, h_new = _f(emb)[tok[:n_stale]], _f(emb)[tok[n_stale:]]
+    for l in range(shape.n_layers):
+        W = get_layer(l)
+        h_old, k_old, v_old = _layer_with_past(h_old, W, lora_old[l], shape, empty, empty)
+        h_new, _, _ = _layer_with_past(h_new, W, lora_new[l], shape, k_old, v_old)
+    return rmsnorm_fwd(h_new, g_final, shape.rms_eps) @ _f(head).T
 
 
 def new_opt_state(lora):

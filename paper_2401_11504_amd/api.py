@@ -64,6 +64,7 @@ _SIGS = {
     "tl_prefill": [_vp, _vp, _i32, C.POINTER(_i32), _vp],
     "tl_decode_step": [_vp, _i32, C.POINTER(_i32), _vp],
     "tl_kv_length": [_vp, C.POINTER(_i32)],
+    "tl_cache_reuse": [_vp, _i32],
     "tl_discard": [_vp],
     "tl_lora_free": [_vp],
     "tl_get_factor": [_vp, _i32, _i32, _i32, _vp, _sz],
@@ -207,6 +208,10 @@ def tl_decode_step(lora, token, vocab=0):
     logits = np.empty(vocab, np.float32) if vocab else None
     _chk(_lib.tl_decode_step(lora, int(token), C.byref(nxt), logits.ctypes.data if vocab else None))
     return nxt.value, logits
+
+
+def tl_cache_reuse(lora, on=True):
+    _chk(_lib.tl_cache_reuse(lora, int(on)))
 
 
 def tl_kv_length(lora):

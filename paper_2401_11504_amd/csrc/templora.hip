@@ -142,6 +142,11 @@ struct tl_lora {
     bool drop_on = false;
     float* zdrop = nullptr;       // [max_tokens, max(d_model, d_ffn)] fp32: dH A before the mask is applied
     int kv_len = 0;
+    // cache reuse (Section 2): with kv_keep the cache lives in buffers of its own ([max_tokens, 3 d] per layer, same
+    // q|k|v row layout), so that a module update leaves it in place: decoding then goes on over keys and values that
+    // the previous module computed.
+    bool kv_keep = false;
+    std::vector<bf16_t*> kvbuf;
     float* lora_h = nullptr;      // [3 r] scaled low-rank activations of the projection group in flight
     float* attn_ws = nullptr;     // partial results of the split decode attention
     size_t attn_ws_elems = 0;
@@ -634,7 +639,7 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     const int first = (n_ctx > 1 ? n_ctx : 1) - 1;
     const int N = (T - 1) - first;
     *n_targets = N;
-    L->kv_len = 0;   // the forward pass below overwrites the buffers the key/value cache lives in
+    if (!L->kv_keep) L->kv_len = 0;   // the forward pass below overwrites the buffers the cache lives in by default
     L->drop_on = want_grad && L->cfg.dropout > 0.f;   // scoring (no gradient) runs the module without dropout
     memcpy(L->tok_host, tokens, (size_t)T * sizeof(int));
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
@@ -808,8 +813,35 @@ extern "C" tl_status tl_prefill(tl_lora* L, const int32_t* tokens, int32_t n_tok
     HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
     // the chunk path's forward: it leaves q|k|v (q, k rotated) of every position in save[l].qkv, which is the cache
     for (int l = 0; l < c.n_layers; ++l) TLCHK(layer_forward(L, l, L->hs[l], L->hs[l + 1], T));
+    if (L->kv_keep)
+        for (int l = 0; l < c.n_layers; ++l)
+            HIPCHK(hipMemcpyAsync(L->kvbuf[l], L->save[l].qkv, (size_t)T * 3 * d * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
     TLCHK(emit_next(L, L->hs[c.n_layers] + (size_t)(T - 1) * d, next_token, logits_out));
     L->kv_len = T;
+    return TL_OK;
+}
+
+extern "C" tl_status tl_cache_reuse(tl_lora* L, int32_t on) {
+    LIVE(L, "tl_cache_reuse");
+    tl_model* m = L->model;
+    const tl_model_cfg& c = m->cfg;
+    if (!on) {
+        if (L->kv_keep) L->kv_len = 0;    // the cache in the dedicated buffers is dropped
+        L->kv_keep = false;
+        return TL_OK;
+    }
+    if (L->kv_keep) return TL_OK;
+    if (L->kvbuf.empty()) {
+        std::vector<bf16_t*> bufs(c.n_layers, nullptr);
+        for (int l = 0; l < c.n_layers; ++l) TLCHK(L->pool.alloc(&bufs[l], (size_t)c.max_tokens * 3 * c.d_model));
+        L->kvbuf = bufs;
+    }
+    // a cache that exists already moves along
+    for (int l = 0; l < c.n_layers && L->kv_len > 0; ++l)
+        HIPCHK(hipMemcpyAsync(L->kvbuf[l], L->save[l].qkv, (size_t)L->kv_len * 3 * c.d_model * sizeof(bf16_t),
+                              hipMemcpyDeviceToDevice, m->stream));
+    HIPCHK(hipStreamSynchronize(m->stream));
+    L->kv_keep = true;
     return TL_OK;
 }
 
@@ -837,7 +869,9 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
     if (!next_token) return fail(TL_ERR_ARG, "next_token is null");
     tl_model* m = L->model;
     const tl_model_cfg& c = m->cfg;
-    if (L->kv_len <= 0) return fail(TL_ERR_ARG, "tl_decode_step: no key/value cache (call tl_prefill after every update)");
+    if (L->kv_len <= 0)
+        return fail(TL_ERR_ARG, "tl_decode_step: no key/value cache (call tl_prefill first, and again after every "
+                                "update unless tl_cache_reuse is on)");
     if (L->kv_len >= c.max_tokens) return fail(TL_ERR_WINDOW, "the window is full (%d positions)", c.max_tokens);
     if (token < 0 || token >= c.vocab) return fail(TL_ERR_TOKEN_RANGE, "token = %d outside [0, %d)", token, c.vocab);
     hipStream_t s = m->stream;
@@ -850,14 +884,15 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
         const LayerW& W = m->layers[l];
         const float* h_in = L->hs[l];
         float* h_out = L->hs[l + 1];
-        bf16_t* row = sv.qkv + (size_t)p * 3 * d;                 // the new cache row: q | k | v of position p
+        bf16_t* cache = L->kv_keep ? L->kvbuf[l] : sv.qkv;
+        bf16_t* row = cache + (size_t)p * 3 * d;                  // the new cache row: q | k | v of position p
         GemvPre n1, n2, sw;
         n1.mode = 1; n1.h = h_in; n1.gain = W.g1; n1.eps = c.rms_eps; n1.x_out = sv.x1;
         n2.mode = 1; n2.h = sv.hmid; n2.gain = W.g2; n2.eps = c.rms_eps; n2.x_out = sv.x2;
         sw.mode = 2; sw.gu = sv.gu; sw.x_out = sv.act;
         TLCHK(group_decode(L, l, G_QKV, sv.x1, row, nullptr, nullptr, &n1));
         HIPCHK(launch_rope(row, 3L * d, 1, 2 * c.n_heads, c.d_head, c.rope_base, p, +1, m->rope, s));
-        HIPCHK(launch_attention_decode(row, sv.qkv + d, sv.qkv + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o,
+        HIPCHK(launch_attention_decode(row, cache + d, cache + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o,
                                        L->attn_ws, L->attn_ws_elems, s));
         TLCHK(group_decode(L, l, G_O, sv.o, nullptr, sv.hmid, h_in));
         TLCHK(group_decode(L, l, G_GU, sv.x2, sv.gu, nullptr, nullptr, &n2));
@@ -884,7 +919,7 @@ extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in,
     if (n_tokens < 1 || n_tokens > c.max_tokens) return fail(TL_ERR_WINDOW, "n_tokens outside [1, max_tokens]");
     if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(TL_ERR_ARG, "lr must be finite and >= 0");
     hipStream_t s = L->model->stream;
-    L->kv_len = 0;
+    if (!L->kv_keep) L->kv_len = 0;
     L->drop_on = L->cfg.dropout > 0.f;
     TLCHK(layer_forward(L, layer, h_in, h_out, n_tokens));
     HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf[0], (size_t)n_tokens * c.d_model, s));

@@ -191,3 +191,61 @@ def test_algorithm1_stream_decode_then_update(api, H):
     api.tl_discard(lora)
     api.tl_lora_free(lora)
     model.close()
+
+
+def _gpu_factors(api, lora, shape):
+    return [{p: (api.tl_get_factor(lora, l, i, api.FACTOR_A, (shape.rank, shape.proj_dims(p)[1])).astype(np.float64),
+                 api.tl_get_factor(lora, l, i, api.FACTOR_B, (shape.proj_dims(p)[0], shape.rank)).astype(np.float64))
+             for i, p in enumerate(synth.PROJ)} for l in range(shape.n_layers)]
+
+
+def test_cache_reuse_decodes_over_the_old_modules_keys_and_values(api, H):
+    """Section 2's cache reuse: after an update the cached keys and values stay (computed by the module as it was),
+    new positions use the updated module.  The learning rate is large on purpose, so that the two modules differ by
+    far more than the tolerance and reuse is distinguishable from recomputing."""
+    shape = synth.SHAPES["small"]
+    seed, n_prompt, n_new = 4400, 40, 5
+    model = H.Model(shape, seed, max_tokens=n_prompt + n_new + 1)
+    lora, facs_old = H.new_lora(model, seed, b_std=0.01)
+    base = (shape, model.emb, model.head, np.ones(shape.d_model), lambda l: model.host_layers[l])
+    prompt = synth.zipf_tokens(seed, n_prompt, shape.vocab)
+    api.tl_cache_reuse(lora, True)
+    nxt, _ = api.tl_prefill(lora, prompt)
+    api.tl_chunk_update(lora, prompt, 0, 2e-2)
+    assert api.tl_kv_length(lora) == n_prompt                   # the cache survived the update
+    facs_new = _gpu_factors(api, lora, shape)                   # the module the GPU now holds, for like with like
+    seq = [int(t) for t in prompt]
+    for step in range(n_new):
+        seq.append(nxt)
+        nxt, logits = api.tl_decode_step(lora, seq[-1], shape.vocab)
+        ref = O.window_logits_reuse(seq, n_prompt, *base, facs_old, facs_new)[-1]
+        check(logits, ref, BF16_TOL, f"reuse logits at step {step}")
+        fresh = O.window_logits(seq, *base, facs_new)[-1]
+        assert np.linalg.norm(ref - fresh) > 10 * BF16_TOL * np.linalg.norm(ref)     # recomputing would be different
+    # the paper's default is one call away: a prefill rebuilds the cache with the current module
+    nxt2, logits2 = api.tl_prefill(lora, np.array(seq, np.int32), shape.vocab)
+    check(logits2, O.window_logits(seq, *base, facs_new)[-1], BF16_TOL, "prefill after reuse")
+    api.tl_cache_reuse(lora, False)
+    assert api.tl_kv_length(lora) == 0
+    api.tl_lora_free(lora)
+    model.close()
+
+
+def test_cache_reuse_switched_on_after_a_prefill_keeps_the_cache(api, H):
+    shape = synth.SHAPES["small"]
+    seed, n_prompt = 4500, 33
+    model = H.Model(shape, seed, max_tokens=n_prompt + 4)
+    la, _ = H.new_lora(model, seed, b_std=0.01)
+    lb, _ = H.new_lora(model, seed, b_std=0.01)
+    prompt = synth.zipf_tokens(seed, n_prompt, shape.vocab)
+    na, _ = api.tl_prefill(la, prompt)
+    nb, _ = api.tl_prefill(lb, prompt)
+    api.tl_cache_reuse(lb, True)                                # moves the existing cache into its own buffers
+    assert na == nb and api.tl_kv_length(lb) == n_prompt
+    for _ in range(3):
+        na, xa = api.tl_decode_step(la, na, shape.vocab)
+        nb, xb = api.tl_decode_step(lb, nb, shape.vocab)
+        assert na == nb and np.array_equal(xa, xb)              # same kernels on the same values: bit-identical
+    for h in (la, lb):
+        api.tl_lora_free(h)
+    model.close()

@@ -706,3 +706,30 @@ def test_dropout_zero_is_exactly_the_plain_update_and_steps_use_fresh_masks():
     rb, _, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, la, opt, lr=0.0, dropout=0.3, seed=5)
     rc, _, _ = O.chunk_update(tok, 0, TINY, emb, head, gf, get, lora, O.new_opt_state(lora), lr=0.0, dropout=0.3, seed=5)
     assert ra["loss"] != rb["loss"] and ra["loss"] == rc["loss"]
+
+
+# ------------------------------------------------------------------ cache reuse
+def test_window_logits_reuse_reduces_to_window_logits_and_keeps_old_positions_stale():
+    Ws, lora, emb, head, gf, tok = _tiny_model()
+    get = lambda l: Ws[l]
+    full = O.window_logits(tok, TINY, emb, head, gf, get, lora)
+    for n_stale in (0, 1, 4, len(tok) - 1):
+        got = O.window_logits_reuse(tok, n_stale, TINY, emb, head, gf, get, lora, lora)
+        assert np.allclose(got, full[n_stale:], rtol=0, atol=1e-10)        # same module on both sides: nothing is stale
+    # the autograd graph's logits too (an implementation that shares nothing with the oracle)
+    ref = _torch_model_loss(Ws, lora, emb, head, gf, tok, 0, TINY, want_logits=True)
+    assert np.allclose(O.window_logits_reuse(tok, 3, TINY, emb, head, gf, get, lora, lora), ref[3:], atol=1e-9)
+    # another module for the new positions: the result differs from both pure windows, and depends on the old module
+    # only through the cached keys and values (zeroing the old module's B changes it; the old module's q factors,
+    # which no later position ever reads, do not)
+    other = [{p: (a, 3.0 * b) for p, (a, b) in L.items()} for L in lora]
+    mixed = O.window_logits_reuse(tok, 5, TINY, emb, head, gf, get, lora, other)
+    assert not np.allclose(mixed, O.window_logits(tok, TINY, emb, head, gf, get, other)[5:], atol=1e-6)
+    assert not np.allclose(mixed, full[5:], atol=1e-6)
+    last = TINY.n_layers - 1
+    q_changed = [dict(L) for L in lora]
+    q_changed[last]["q"] = (lora[last]["q"][0], 0.0 * lora[last]["q"][1])     # the last layer's old queries are never cached
+    assert np.allclose(O.window_logits_reuse(tok, 5, TINY, emb, head, gf, get, q_changed, other), mixed, atol=1e-12)
+    k_changed = [dict(L) for L in lora]
+    k_changed[last]["k"] = (lora[last]["k"][0], 0.0 * lora[last]["k"][1])
+    assert not np.allclose(O.window_logits_reuse(tok, 5, TINY, emb, head, gf, get, k_changed, other), mixed, atol=1e-9)
