@@ -733,3 +733,13 @@ def test_window_logits_reuse_reduces_to_window_logits_and_keeps_old_positions_st
     k_changed = [dict(L) for L in lora]
     k_changed[last]["k"] = (lora[last]["k"][0], 0.0 * lora[last]["k"][1])
     assert not np.allclose(O.window_logits_reuse(tok, 5, TINY, emb, head, gf, get, k_changed, other), mixed, atol=1e-9)
+
+
+def test_training_steps_match_the_papers_worked_example():
+    """Table 5's caption works one case out: chunk size 2048, batch 1024, n = 2 epochs need 2 * (2048 / 1024) = 4
+    training steps.  The grid of the table follows the same rule."""
+    assert 2 * len(O.training_samples(1024, 2048, 1024, 1024)) == 4
+    for delta in (1024, 2048, 4096):
+        for batch in (256, 512, 1024, 2048, 4096):
+            if batch <= delta:
+                assert len(O.training_samples(1024, delta, 1024, batch)) == delta // batch
