@@ -303,9 +303,9 @@ hipError_t launch_labels(const int* tokens, int T, int* labels, hipStream_t s) {
 __global__ __launch_bounds__(512) void cross_entropy_kernel(const float* __restrict__ logits,
                                                             const int* __restrict__ labels, int T, int V,
                                                             int first_target, float inv_n, float* __restrict__ nll,
-                                                            bf16_t* __restrict__ dlogits) {
+                                                            bf16_t* __restrict__ dlogits, int row0) {
     __shared__ float red[16];
-    const int t = blockIdx.x;
+    const int t = blockIdx.x + row0;
     const float* z = logits + (long)t * V;
     bf16_t* dz = dlogits ? dlogits + (long)t * V : nullptr;
     const bool target = (t >= first_target) && (t < T - 1);
@@ -341,10 +341,18 @@ __global__ __launch_bounds__(256) void nll_sum_kernel(const float* __restrict__ 
     s = block_sum(s, red);
     if (threadIdx.x == 0) out[0] = s;
 }
+// row0: rows below it are conditioning positions the caller knows carry no loss: their nll is set to 0 and their
+// logits / dlogits rows are neither read nor written (the caller does not compute or use them).
 hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, int V, int first_target,
-                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s) {
+                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s, int row0) {
     if (T <= 0) return hipSuccess;
-    cross_entropy_kernel<<<T, 512, 0, s>>>(logits, labels, T, V, first_target, 1.f / (float)n_targets, nll, dlogits);
+    if (row0 < 0 || row0 > first_target || row0 >= T) return hipErrorInvalidValue;
+    if (row0 > 0) {
+        hipError_t e = launch_fill_f32(nll, (size_t)row0, 0.f, s);
+        if (e != hipSuccess) return e;
+    }
+    cross_entropy_kernel<<<T - row0, 512, 0, s>>>(logits, labels, T, V, first_target, 1.f / (float)n_targets, nll, dlogits,
+                                                  row0);
     if (loss_sum) nll_sum_kernel<<<1, 256, 0, s>>>(nll, T, loss_sum);
     return hipGetLastError();
 }

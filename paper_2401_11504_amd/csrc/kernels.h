@@ -77,7 +77,7 @@ hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, h
 hipError_t launch_swiglu_fwd(const bf16_t* gu, int T, int f, bf16_t* a, hipStream_t s);
 hipError_t launch_swiglu_bwd(const bf16_t* da, const bf16_t* gu, int T, int f, bf16_t* dgu, hipStream_t s);
 hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, int V, int first_target,
-                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s);
+                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s, int row0 = 0);
 hipError_t launch_adamw(float* p, const float* g, float* m, float* v, bf16_t* shadow, size_t n, long step, float lr,
                         float beta1, float beta2, float eps, float wd, hipStream_t s);
 hipError_t launch_embed(const bf16_t* E, const int* tokens, int T, int d, float* h, hipStream_t s);

@@ -141,6 +141,7 @@ struct tl_lora {
     // LoRA dropout (training-side forward / backward only): on for the pass in flight?
     bool drop_on = false;
     float* zdrop = nullptr;       // [max_tokens, max(d_model, d_ffn)] fp32: dH A before the mask is applied
+    int loss_row0 = 0;            // first row lm_head and the loss were computed for in the last forward pass
     int kv_len = 0;
     // cache reuse (Section 2): with kv_keep the cache lives in buffers of its own ([max_tokens, 3 d] per layer, same
     // q|k|v row layout), so that a module update leaves it in place: decoding then goes on over keys and values that
@@ -647,12 +648,17 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
     for (int l = 0; l < c.n_layers; ++l) TLCHK(layer_forward(L, l, L->hs[l], L->hs[l + 1], T));
     HIPCHK(launch_rmsnorm_fwd(L->hs[c.n_layers], m->gf, T, d, c.rms_eps, L->hf, s));
+    // conditioning positions carry no loss: their logits are not needed, so lm_head runs on the rows from the first
+    // target on only (with the paper's 1024 + 1024 sample that halves it; with Table 5's short pieces it is most of it)
+    static const bool all_rows = getenv("TL_LOSS_ALL_ROWS") && atoi(getenv("TL_LOSS_ALL_ROWS")) != 0;   // tuning aid
+    const int r0 = first >= 64 && !all_rows ? first : 0;
+    L->loss_row0 = r0;
     GemmNT lg;
-    lg.A = L->hf; lg.lda = d; lg.B = m->head; lg.ldb = d; lg.M = T; lg.N = V; lg.K = d;
-    lg.C = L->logits; lg.ldc = V; lg.c_f32 = 1;
+    lg.A = L->hf + (size_t)r0 * d; lg.lda = d; lg.B = m->head; lg.ldb = d; lg.M = T - r0; lg.N = V; lg.K = d;
+    lg.C = L->logits + (size_t)r0 * V; lg.ldc = V; lg.c_f32 = 1;
     HIPCHK(timed_gemm(L, lg));
     HIPCHK(launch_cross_entropy(L->logits, L->labels, T, V, first, N, L->nll, want_grad ? L->dlogits : nullptr,
-                                L->loss_sum, s));
+                                L->loss_sum, s, r0));
     HIPCHK(hipMemcpyAsync(L->loss_host, L->loss_sum, sizeof(float), hipMemcpyDeviceToHost, s));
     L->last_tokens = T;
     return TL_OK;
@@ -687,9 +693,11 @@ static tl_status update_step(tl_lora* L, const int32_t* tokens, int32_t n_tokens
     const float loss = L->loss_host[0] / (float)N;
     if (!std::isfinite(loss)) return fail(TL_ERR_NONFINITE, "loss is not finite; optimizer step skipped");
     // backward: lm_head, final norm, layers
+    const int r0 = L->loss_row0;          // rows below it have no loss and hence a zero gradient at the lm_head input
+    if (r0 > 0) HIPCHK(hipMemsetAsync(L->dhf, 0, (size_t)r0 * d * sizeof(bf16_t), s));
     GemmNT dh;
-    dh.A = L->dlogits; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T; dh.N = d; dh.K = V;
-    dh.C = L->dhf; dh.ldc = d;
+    dh.A = L->dlogits + (size_t)r0 * V; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T - r0; dh.N = d; dh.K = V;
+    dh.C = L->dhf + (size_t)r0 * d; dh.ldc = d;
     dh.partial = L->partial; dh.partial_elems = L->partial_elems;
     HIPCHK(timed_gemm(L, dh));
     HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf[nl & 1], s));
