@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak (vendor figure, 
 # (FETCH_SIZE, then WRITE_SIZE; summed over the kernel's launches of one update, divided by their number,
 # each counter scaled by what it reads for --copy-calibration's 1 GiB copy).  The passes and the scaling
 # factors are in profiles/chunk_update_7b_r64_T1024.md; counters cannot be read from inside this process.
-GEMM_NT_HBM_BYTES_PER_LAUNCH = 326e6
+GEMM_NT_HBM_BYTES_PER_LAUNCH = 248e6
 
 
 def cpu_baseline(shape, T, seed):
