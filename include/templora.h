@@ -203,6 +203,28 @@ tl_status tl_prefill(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int
 tl_status tl_decode_step(tl_lora* lora, int32_t token, int32_t* next_token, float* logits_out);
 tl_status tl_kv_length(tl_lora* lora, int32_t* n_out);
 
+/*
+ * Algorithm 1 as one call (the cascaded deployment of Section 3, "Efficiency": generation pauses while the module is
+ * updated).  Starting from `prompt` (host int32[n_prompt], n_prompt >= 1), repeat: take the most recent cfg->window
+ * tokens of the text so far as X (L_X), rebuild the cache with the current module, decode greedily until the chunk
+ * holds cfg->chunk tokens (Delta), then tl_chunk_train on that chunk with the up to cfg->train.n_ctx_max tokens
+ * before it (L_T) as conditioning.  Stops after n_new tokens; a last, incomplete chunk is not trained on.  The module
+ * stays alive afterwards (the caller discards it, Algorithm 1's last line).
+ *   tokens_out : host int32[n_new], the generated tokens.
+ *   losses_out : host fp32[(n_new / chunk) * epochs * ceil(chunk / batch)] or NULL: the loss of every training step.
+ *   n_steps_out: training steps made, or NULL.
+ * Needs window + chunk <= max_tokens and n_ctx_max + batch <= max_tokens (TL_ERR_WINDOW otherwise, before anything
+ * runs).  Other errors as tl_prefill / tl_decode_step / tl_chunk_train; what was generated and trained before an
+ * error stays.
+ */
+typedef struct {
+    int32_t window;      /* L_X */
+    int32_t chunk;       /* Delta */
+    tl_train_cfg train;  /* L_T, batch, epochs, warm-up, learning rate */
+} tl_generate_cfg;
+tl_status tl_generate(tl_lora* lora, const int32_t* prompt, int32_t n_prompt, int32_t n_new, const tl_generate_cfg* cfg,
+                      int32_t* tokens_out, float* losses_out, int32_t* n_steps_out);
+
 /* Cache reuse (Section 2: after an update, keep the key/value states instead of recomputing them with the updated
  * module).  on != 0: the cache moves to buffers of its own (allocated on the first call: n_layers * max_tokens *
  * 3 d_model bf16) and survives tl_chunk_update / tl_chunk_train / tl_chunk_loss / tl_layer_step; tl_decode_step then

@@ -53,6 +53,10 @@ class tl_train_cfg(C.Structure):
                 ("lr", C.c_float)]
 
 
+class tl_generate_cfg(C.Structure):
+    _fields_ = [("window", C.c_int32), ("chunk", C.c_int32), ("train", tl_train_cfg)]
+
+
 _vp, _i32, _i64, _f32, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
 _SIGS = {
     "tl_model_create": [C.POINTER(tl_model_cfg), C.POINTER(_vp), _vp, C.POINTER(_vp)],
@@ -64,6 +68,7 @@ _SIGS = {
     "tl_prefill": [_vp, _vp, _i32, C.POINTER(_i32), _vp],
     "tl_decode_step": [_vp, _i32, C.POINTER(_i32), _vp],
     "tl_kv_length": [_vp, C.POINTER(_i32)],
+    "tl_generate": [_vp, _vp, _i32, _i32, C.POINTER(tl_generate_cfg), _vp, _vp, C.POINTER(_i32)],
     "tl_cache_reuse": [_vp, _i32],
     "tl_discard": [_vp],
     "tl_lora_free": [_vp],
@@ -208,6 +213,19 @@ def tl_decode_step(lora, token, vocab=0):
     logits = np.empty(vocab, np.float32) if vocab else None
     _chk(_lib.tl_decode_step(lora, int(token), C.byref(nxt), logits.ctypes.data if vocab else None))
     return nxt.value, logits
+
+
+def tl_generate(lora, prompt, n_new, window, chunk, n_ctx_max=1024, batch=0, epochs=2, lr=5e-5, warmup_steps=0):
+    """-> (generated tokens int32[n_new], per-step training losses)"""
+    a, p = _tok(prompt)
+    cfg = tl_generate_cfg(window, chunk, tl_train_cfg(n_ctx_max, batch, epochs, warmup_steps, lr))
+    out = np.zeros(max(n_new, 1), np.int32)
+    b = batch if 0 < batch < chunk else max(chunk, 1)
+    losses = np.zeros(max(1, (n_new // max(chunk, 1)) * max(epochs, 1) * (-(-max(chunk, 1) // b))), np.float32)
+    n = _i32()
+    _chk(_lib.tl_generate(lora, p, a.size, n_new, C.byref(cfg), out.ctypes.data_as(_vp), losses.ctypes.data_as(_vp),
+                          C.byref(n)))
+    return out[:n_new], [float(x) for x in losses[:n.value]]
 
 
 def tl_cache_reuse(lora, on=True):

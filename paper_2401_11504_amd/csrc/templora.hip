@@ -911,6 +911,52 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
     return TL_OK;
 }
 
+// Algorithm 1, cascaded deployment: generate, and after every full chunk pause and train the module on it.
+extern "C" tl_status tl_generate(tl_lora* L, const int32_t* prompt, int32_t n_prompt, int32_t n_new,
+                                 const tl_generate_cfg* cfg, int32_t* tokens_out, float* losses_out,
+                                 int32_t* n_steps_out) {
+    LIVE(L, "tl_generate");
+    if (!prompt || !cfg || !tokens_out) return fail(TL_ERR_ARG, "tl_generate: null pointer");
+    const tl_model_cfg& c = L->model->cfg;
+    if (n_prompt < 1 || n_new < 0) return fail(TL_ERR_ARG, "tl_generate: n_prompt must be >= 1 and n_new >= 0");
+    if (cfg->window < 1 || cfg->chunk < 1) return fail(TL_ERR_ARG, "tl_generate: window and chunk must be >= 1");
+    if (cfg->window + cfg->chunk > c.max_tokens)
+        return fail(TL_ERR_WINDOW, "window %d + chunk %d exceed max_tokens = %d", cfg->window, cfg->chunk, c.max_tokens);
+    const int batch = cfg->train.batch > 0 && cfg->train.batch < cfg->chunk ? cfg->train.batch : cfg->chunk;
+    if (cfg->train.n_ctx_max < 0 || cfg->train.n_ctx_max + batch > c.max_tokens)
+        return fail(TL_ERR_WINDOW, "training sample of %d conditioning + %d chunk tokens exceeds max_tokens = %d",
+                    cfg->train.n_ctx_max, batch, c.max_tokens);
+    for (int i = 0; i < n_prompt; ++i)
+        if (prompt[i] < 0 || prompt[i] >= c.vocab)
+            return fail(TL_ERR_TOKEN_RANGE, "prompt[%d] = %d outside [0, %d)", i, prompt[i], c.vocab);
+    if (n_steps_out) *n_steps_out = 0;
+    std::vector<int32_t> text(prompt, prompt + n_prompt);     // Y of Algorithm 1: everything read or generated so far
+    int produced = 0, steps = 0;
+    while (produced < n_new) {
+        // X: the most recent `window` tokens; the cache is rebuilt with the current module
+        const int n_x = std::min<int>((int)text.size(), cfg->window);
+        int32_t next = 0;
+        TLCHK(tl_prefill(L, text.data() + text.size() - n_x, n_x, &next, nullptr));
+        int in_chunk = 0;
+        while (in_chunk < cfg->chunk && produced < n_new) {
+            text.push_back(next);
+            tokens_out[produced++] = next;
+            ++in_chunk;
+            if (in_chunk < cfg->chunk && produced < n_new) TLCHK(tl_decode_step(L, next, &next, nullptr));
+        }
+        if (in_chunk < cfg->chunk) break;                     // generation ended inside a chunk: nothing to train on
+        // train on the chunk just generated, conditioned on what precedes it
+        const int n_before = std::min<int>((int)text.size() - cfg->chunk, cfg->train.n_ctx_max);
+        int made = 0;
+        tl_status st = tl_chunk_train(L, text.data() + text.size() - cfg->chunk - n_before, n_before + cfg->chunk, cfg->chunk,
+                                      &cfg->train, losses_out ? losses_out + steps : nullptr, &made);
+        steps += made;
+        if (n_steps_out) *n_steps_out = steps;
+        TLCHK(st);
+    }
+    return TL_OK;
+}
+
 extern "C" tl_status tl_kv_length(tl_lora* L, int32_t* n_out) {
     LIVE(L, "tl_kv_length");
     if (!n_out) return fail(TL_ERR_ARG, "n_out is null");

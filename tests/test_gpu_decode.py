@@ -249,3 +249,42 @@ def test_cache_reuse_switched_on_after_a_prefill_keeps_the_cache(api, H):
     for h in (la, lb):
         api.tl_lora_free(h)
     model.close()
+
+
+def test_generate_is_algorithm1_made_of_the_same_calls(api, H):
+    """tl_generate against the same loop written out with tl_prefill / tl_decode_step / tl_chunk_train on a second
+    module: identical kernels on identical values, so tokens and losses must agree bit for bit (the loop itself is
+    checked against the oracle in test_algorithm1_stream_decode_then_update)."""
+    shape = synth.SHAPES["small"]
+    seed, L_X, L_T, DELTA, n_new, lr = 4600, 20, 12, 8, 21, 2e-3        # two full chunks and a tail of five tokens
+    model = H.Model(shape, seed, max_tokens=L_X + DELTA)
+    la, _ = H.new_lora(model, seed, b_std=0.01)
+    lb, _ = H.new_lora(model, seed, b_std=0.01)
+    prompt = [int(t) for t in synth.zipf_tokens(seed, 30, shape.vocab)]
+    toks, losses = api.tl_generate(la, prompt, n_new, L_X, DELTA, n_ctx_max=L_T, batch=4, epochs=2, lr=lr, warmup_steps=3)
+    text, want_tok, want_loss = list(prompt), [], []
+    while len(want_tok) < n_new:
+        nxt, _ = api.tl_prefill(lb, np.array(text[-L_X:], np.int32))
+        got = 0
+        while got < DELTA and len(want_tok) < n_new:
+            text.append(nxt)
+            want_tok.append(nxt)
+            got += 1
+            if got < DELTA and len(want_tok) < n_new:
+                nxt, _ = api.tl_decode_step(lb, nxt)
+        if got < DELTA:
+            break
+        want_loss += api.tl_chunk_train(lb, np.array(text[-(L_T + DELTA):], np.int32), DELTA, L_T, 4, 2, lr, 3)
+    assert list(toks) == want_tok
+    assert losses == want_loss and len(losses) == 2 * 2 * 2            # two chunks x two epochs x two pieces
+    assert api.tl_get_step(la) == api.tl_get_step(lb) == 8
+    # geometry errors come before anything runs
+    for kwargs, code in ((dict(window=L_X + 1, chunk=DELTA), -4), (dict(window=L_X, chunk=DELTA, n_ctx_max=L_X + DELTA), -4),
+                         (dict(window=0, chunk=DELTA), -1)):
+        with pytest.raises(api.TlError) as e:
+            api.tl_generate(la, prompt, 4, **kwargs)
+        assert e.value.status == code
+    assert api.tl_get_step(la) == 8
+    for h in (la, lb):
+        api.tl_lora_free(h)
+    model.close()
