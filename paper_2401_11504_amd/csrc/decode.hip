@@ -4,6 +4,15 @@
 // the 13.5 GB of frozen weights, not by arithmetic.
 #include "kernels.h"
 
+typedef unsigned gemv_vu4 __attribute__((ext_vector_type(4)));
+// 16 bytes of a weight row.  Every byte of the matrix is read exactly once per token, so the loads are marked
+// non-temporal: measured 5 % faster per token than ordinary loads (eight loads in flight instead of four, two or four
+// rows per wave, or two waves per row were all slower or equal).
+__device__ __forceinline__ uint4 load_w16(const bf16_t* p) {
+    const gemv_vu4 v = __builtin_nontemporal_load((const gemv_vu4*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // ---------------------------------------------------------------- y = W x (+ s-scaled LoRA term) (+ residual)
 // One wave per output row n: the row W[n, :] is read with 16-byte loads, 64 lanes wide; x sits in LDS.
 // lora_h (fp32 [G * r], already scaled by s) and lora_b (bf16 [N, r]) add  sum_j B[n, j] h[(n / rows_per_group) r + j].
@@ -83,7 +92,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ W,
     for (; k + 3 * 512 < K; k += 4 * 512) {          // four 16-byte loads of the row in flight per lane
         uint4 wv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) wv[u] = *(const uint4*)(w + k + u * 512);
+        for (int u = 0; u < 4; ++u) wv[u] = load_w16(w + k + u * 512);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             float a[8], b[8];
@@ -95,7 +104,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ W,
     }
     for (; k < K; k += 512) {
         float a[8], b[8];
-        unpack8(*(const uint4*)(w + k), a);
+        unpack8(load_w16(w + k), a);
         unpack8(*(const uint4*)(sx + k), b);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc += a[e] * b[e];
