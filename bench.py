@@ -25,6 +25,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak (vendor figure, 
 # each counter scaled by what it reads for --copy-calibration's 1 GiB copy).  The passes and the scaling
 # factors are in profiles/chunk_update_7b_r64_T1024.md; counters cannot be read from inside this process.
 GEMM_NT_HBM_BYTES_PER_LAUNCH = 248e6
+# the same for the weight-streaming matrix-vector launches of the generation side (profiles/decode_7b_r64_window1024.md):
+# 50 839 KiB of FETCH_SIZE per launch x 2.000 = 104.1 MB against 103.8 MB of algorithmic bytes; writes are negligible
+GEMV_HBM_BYTES_PER_LAUNCH = 104.1e6
 
 
 def cpu_baseline(shape, T, seed):
@@ -163,7 +166,8 @@ def decode_bench(args, torch, api, harness, synth):
         api.tl_profile_enable(lora, False)
         gbs = flop / (ms * 1e-3) / 1e9 if ms > 0 else 0.0     # 2 flop per bf16 element of 2 bytes: bytes read = flop
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbs / 8000.0, 4),
-                "traffic": None, "kernel": "gemv_kernel (frozen matrix + LoRA B rows, one token)",
+                "traffic": GEMV_HBM_BYTES_PER_LAUNCH if args.layers == 32 else None,
+                "kernel": "gemv_kernel (frozen matrix + LoRA B rows, one token)",
                 "launches_per_step": launches // max(K, 1), "avg_launch_us": round(ms * 1e3 / max(launches, 1), 2),
                 "bytes_per_launch": flop / max(launches, 1),
                 "share_of_step_time": round(ms * 1e-3 / dt, 4)}
