@@ -150,13 +150,38 @@ hipError_t launch_gemv(const bf16_t* W, long ldw, const bf16_t* x, int N, int K,
 // blockDim / (d_head / 8) keys per pass; four passes of loads are issued before the first is consumed (the loop is
 // bound by load latency, not by bytes).  Returns the score maximum and the sum of exponentials; the unnormalised
 // output sum_u exp(s_u - max) v_u is left in out_acc[0 .. d_head).
-__device__ __forceinline__ void attend_range(const bf16_t* __restrict__ qh, const bf16_t* __restrict__ kh,
+//
+// rope_row != null: the query row and key row `new_key` of the range (the token being decoded; -1 if it lies in another
+// range) are still unrotated.  They are rotated here with the (cos, sin) pairs of the token's position (RoPE pairs
+// elements i and i + d_head / 2; both halves of a row are held by lanes of the same wave), rounded to bf16 as the
+// separate kernel would have stored them, and the rotated key is written back to the cache for the tokens to come.
+__device__ __forceinline__ void rope8(const float* mine, const float* other, const float2* __restrict__ rope_row,
+                                      int sub, int lpk, float* out) {
+    const bool first = sub < (lpk >> 1);
+    const int i0 = (sub % (lpk >> 1)) * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float2 cs = rope_row[i0 + e];
+        const float a = first ? mine[e] : other[e], b = first ? other[e] : mine[e];   // a: first-half element of the pair
+        out[e] = bf16_to_f32(f32_to_bf16(first ? a * cs.x - b * cs.y : b * cs.x + a * cs.y));
+    }
+}
+__device__ __forceinline__ void attend_range(const bf16_t* __restrict__ qh, bf16_t* __restrict__ kh,
                                              const bf16_t* __restrict__ vh, long ld, int nk, int d_head, float scale,
-                                             float* sp, float* part_buf, float* red, float& mx_out, float& sum_out) {
+                                             float* sp, float* part_buf, float* red, float& mx_out, float& sum_out,
+                                             const float2* __restrict__ rope_row, int new_key) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int lpk = d_head >> 3, sub = tid % lpk, kk = tid / lpk, kpp = nthr / lpk;   // lanes per key, keys per pass
+    const int psub = sub ^ (lpk >> 1);                                                 // the lane holding the pair partners
     float qv[8];
     unpack8(*(const uint4*)(qh + sub * 8), qv);
+    if (rope_row) {
+        float other[8], rot[8];
+        unpack8(*(const uint4*)(qh + psub * 8), other);
+        rope8(qv, other, rope_row, sub, lpk, rot);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[e] = rot[e];
+    }
     for (int u0 = 0; u0 < nk; u0 += 4 * kpp) {
         uint4 kr[4];
 #pragma unroll
@@ -169,6 +194,14 @@ __device__ __forceinline__ void attend_range(const bf16_t* __restrict__ qh, cons
             const int u = u0 + b * kpp + kk;
             float a[8], sdot = 0.f;
             unpack8(kr[b], a);
+            if (rope_row && u == new_key) {      // taken by the d_head / 8 lanes of one key, all in one wave
+                float other[8], rot[8];
+                unpack8(*(const uint4*)(kh + (long)u * ld + psub * 8), other);
+                rope8(a, other, rope_row, sub, lpk, rot);
+                *(uint4*)(kh + (long)u * ld + sub * 8) = pack8(rot);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[e] = rot[e];
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) sdot += a[e] * qv[e];
             for (int off = lpk >> 1; off > 0; off >>= 1) sdot += __shfl_xor(sdot, off, 64);
@@ -224,9 +257,10 @@ static size_t attend_lds_floats(int nk, int nthr, int d_head) {
 }
 
 // One workgroup per head over the whole cache.
-__global__ __launch_bounds__(1024) void attn_decode_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(1024) void attn_decode_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ k,
                                                            const bf16_t* __restrict__ v, long ld, int n_keys, int d_head,
-                                                           float scale, bf16_t* __restrict__ o) {
+                                                           float scale, bf16_t* __restrict__ o,
+                                                           const float2* __restrict__ rope_row) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sp = (float*)smem;
     float* part_buf = sp + ((n_keys + 3) & ~3);
@@ -234,17 +268,18 @@ __global__ __launch_bounds__(1024) void attn_decode_kernel(const bf16_t* __restr
     const int head = blockIdx.x;
     float mx, sum;
     attend_range(q + (long)head * d_head, k + (long)head * d_head, v + (long)head * d_head, ld, n_keys, d_head, scale, sp,
-                 part_buf, red, mx, sum);
+                 part_buf, red, mx, sum, rope_row, n_keys - 1);
     if ((int)threadIdx.x < d_head) o[(long)head * d_head + threadIdx.x] = f32_to_bf16(part_buf[threadIdx.x] / sum);
 }
 
 // Long windows: the keys are cut into n_split ranges, one workgroup per (head, range), so that the cache is read by
 // hundreds of workgroups instead of one per head.  Each writes its unnormalised output, its score maximum and its
 // sum of exponentials to ws[(head * n_split + range) * (d_head + 2)]; attn_decode_combine_kernel merges the ranges.
-__global__ __launch_bounds__(256) void attn_decode_split_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+__global__ __launch_bounds__(256) void attn_decode_split_kernel(const bf16_t* __restrict__ q, bf16_t* __restrict__ k,
                                                                 const bf16_t* __restrict__ v, long ld, int n_keys,
                                                                 int d_head, float scale, int chunk,
-                                                                float* __restrict__ ws) {
+                                                                float* __restrict__ ws,
+                                                                const float2* __restrict__ rope_row) {
     extern __shared__ __align__(16) unsigned char smem[];
     float* sp = (float*)smem;
     float* part_buf = sp + ((chunk + 3) & ~3);
@@ -252,8 +287,9 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const bf16_t* __
     const int head = blockIdx.x;
     const int k0 = blockIdx.y * chunk, nk = min(chunk, n_keys - k0);   // nk >= 1 by the launch geometry
     float mx, sum;
+    const int new_key = n_keys - 1 - k0;                             // inside this range only for the last one
     attend_range(q + (long)head * d_head, k + (long)k0 * ld + (long)head * d_head, v + (long)k0 * ld + (long)head * d_head,
-                 ld, nk, d_head, scale, sp, part_buf, red, mx, sum);
+                 ld, nk, d_head, scale, sp, part_buf, red, mx, sum, rope_row, new_key < nk ? new_key : -1);
     float* out = ws + ((long)head * gridDim.y + blockIdx.y) * (d_head + 2);
     if ((int)threadIdx.x < d_head) out[threadIdx.x] = part_buf[threadIdx.x];
     if (threadIdx.x == 0) { out[d_head] = mx; out[d_head + 1] = sum; }
@@ -274,8 +310,11 @@ __global__ void attn_decode_combine_kernel(const float* __restrict__ ws, int n_s
 }
 
 // ws (may be null): scratch of ws_elems floats for the split path; n_heads * n_split * (d_head + 2) of them are used.
-hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
-                                   int d_head, bf16_t* o, float* ws, size_t ws_elems, hipStream_t s) {
+// rope_row (may be null): (cos, sin) of the newest position for i = 0 .. d_head / 2 - 1.  With it q and key row
+// n_keys - 1 are taken as unrotated, and the rotated key row is written back into k (k is then written, not only read).
+hipError_t launch_attention_decode(const bf16_t* q, bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
+                                   int d_head, bf16_t* o, float* ws, size_t ws_elems, hipStream_t s,
+                                   const float2* rope_row) {
     if (n_keys <= 0 || n_heads <= 0) return hipErrorInvalidValue;
     if ((d_head != 64 && d_head != 128) || (ld & 7)) return hipErrorInvalidValue;
     const float scale = 1.f / sqrtf((float)d_head);
@@ -288,7 +327,8 @@ hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_
         n_split = cdiv(n_keys, chunk);            // no empty range
         const size_t lds = attend_lds_floats(chunk, 256, d_head) * sizeof(float);
         if (lds > 60 * 1024) return hipErrorInvalidValue;
-        attn_decode_split_kernel<<<dim3(n_heads, n_split), 256, lds, s>>>(q, k, v, ld, n_keys, d_head, scale, chunk, ws);
+        attn_decode_split_kernel<<<dim3(n_heads, n_split), 256, lds, s>>>(q, k, v, ld, n_keys, d_head, scale, chunk, ws,
+                                                                          rope_row);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         attn_decode_combine_kernel<<<n_heads, d_head, 0, s>>>(ws, n_split, d_head, o);
@@ -299,7 +339,7 @@ hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_
     if (lds > 150 * 1024) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)attn_decode_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attn_decode_kernel<<<n_heads, nthr, lds, s>>>(q, k, v, ld, n_keys, d_head, scale, o);
+    attn_decode_kernel<<<n_heads, nthr, lds, s>>>(q, k, v, ld, n_keys, d_head, scale, o, rope_row);
     return hipGetLastError();
 }
 

@@ -118,7 +118,8 @@ hipError_t launch_gemv(const bf16_t* W, long ldw, const bf16_t* x, int N, int K,
                        hipStream_t s, const GemvPre* pre = nullptr);
 // one query row against cache rows 0 .. n_keys-1 (row stride ld), per head
 constexpr int ATTN_DECODE_MAX_SPLIT = 32;   // key ranges per head in the split decode-attention path
-hipError_t launch_attention_decode(const bf16_t* q, const bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
-                                   int d_head, bf16_t* o, float* ws, size_t ws_elems, hipStream_t s);
+hipError_t launch_attention_decode(const bf16_t* q, bf16_t* k, const bf16_t* v, long ld, int n_keys, int n_heads,
+                                   int d_head, bf16_t* o, float* ws, size_t ws_elems, hipStream_t s,
+                                   const float2* rope_row = nullptr);
 // index of the largest of n floats, lowest index among equals
 hipError_t launch_argmax(const float* x, int n, int* out, hipStream_t s);

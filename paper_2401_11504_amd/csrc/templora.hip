@@ -899,9 +899,9 @@ extern "C" tl_status tl_decode_step(tl_lora* L, int32_t token, int32_t* next_tok
         n2.mode = 1; n2.h = sv.hmid; n2.gain = W.g2; n2.eps = c.rms_eps; n2.x_out = sv.x2;
         sw.mode = 2; sw.gu = sv.gu; sw.x_out = sv.act;
         TLCHK(group_decode(L, l, G_QKV, sv.x1, row, nullptr, nullptr, &n1));
-        HIPCHK(launch_rope(row, 3L * d, 1, 2 * c.n_heads, c.d_head, c.rope_base, p, +1, m->rope, s));
+        // q and k of the new row are rotated inside the attention launch (the rotated k goes back into the cache)
         HIPCHK(launch_attention_decode(row, cache + d, cache + 2 * d, 3L * d, p + 1, c.n_heads, c.d_head, sv.o,
-                                       L->attn_ws, L->attn_ws_elems, s));
+                                       L->attn_ws, L->attn_ws_elems, s, m->rope + (size_t)p * (c.d_head / 2)));
         TLCHK(group_decode(L, l, G_O, sv.o, nullptr, sv.hmid, h_in));
         TLCHK(group_decode(L, l, G_GU, sv.x2, sv.gu, nullptr, nullptr, &n2));
         TLCHK(group_decode(L, l, G_DOWN, sv.act, nullptr, h_out, sv.hmid, &sw));
@@ -1234,8 +1234,8 @@ extern "C" tl_status tl_k_attention_decode(const uint16_t* q, const uint16_t* k,
                                            float* workspace, size_t workspace_elems, void* hip_stream) {
     KARGS_OK(q && k && v && o && n_keys > 0 && n_heads > 0 && (d_head == 64 || d_head == 128) && (ld & 7) == 0,
              "tl_k_attention_decode");
-    HIPCHK(launch_attention_decode(q, k, v, ld, n_keys, n_heads, d_head, o, workspace, workspace_elems,
-                                   (hipStream_t)hip_stream));
+    HIPCHK(launch_attention_decode(q, (bf16_t*)k, v, ld, n_keys, n_heads, d_head, o, workspace, workspace_elems,
+                                   (hipStream_t)hip_stream));   // without a RoPE row nothing is written to k
     return TL_OK;
 }
 extern "C" tl_status tl_k_argmax(const float* x, int32_t n, int32_t* out, void* hip_stream) {
