@@ -656,9 +656,15 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
                     if (c < 0.97 * best) { best = c; cfg = 43 + sp; }   // 45, 46, 47 = split 2, 3, 4
                 }
             }
-            else if (fill(t256) >= 0.9) cfg = 6;
-            else if (fill(t256x128) >= 0.85) cfg = 28;
-            else cfg = g.batch > 1 ? 22 : 6;
+            else {
+                // Many tiles: the same byte count decides between 256x256 tiles (fewest bytes per flop, but only two
+                // full-depth or four half-depth stages fit in LDS and the loop reaches about 42 GB/s per CU) and
+                // 256x128 tiles (55 GB/s per CU); rounds of tiles x rows per tile / rate.
+                auto rounds = [](long t) { return (double)((t + 255) / 256); };
+                const double c256 = rounds(t256) * 512.0 / 42.0, c128 = rounds(t256x128) * 384.0 / 55.0;
+                if (c128 < c256) cfg = 28;
+                else cfg = fill(t256) < 0.9 && g.batch > 1 ? 22 : 6;   // half-depth four-stage loop for batched launches
+            }
         }
         switch (cfg) {
             case 1: return run_nt_dl<128, 128, 2, 2, 3>(g, s);
