@@ -59,12 +59,26 @@ template <int NV>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restrict__ dy, const float* __restrict__ h,
                                                           const float* __restrict__ g, const float* __restrict__ dres,
                                                           int d, float eps, float* __restrict__ dh_out,
-                                                          bf16_t* __restrict__ dh_bf) {
+                                                          bf16_t* __restrict__ dh_bf, const float* __restrict__ dy_part,
+                                                          int n_part, long part_stride) {
     __shared__ float red[32];
     const long row = blockIdx.x;
+    // chunk i (four elements) of this row of dy: the bf16 array, or the sum of the fp32 partial arrays
+    auto dy4 = [&](int i) {
+        if (dy_part) {
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < n_part; ++k) {
+                const float4 q = *(const float4*)(dy_part + (long)k * part_stride + row * d + 4 * (long)i);
+                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+            }
+            return t;
+        }
+        const uint2 r = ((const uint2*)(dy + row * d))[i];
+        return make_float4(bf16_to_f32(r.x & 0xffff), bf16_to_f32(r.x >> 16), bf16_to_f32(r.y & 0xffff),
+                           bf16_to_f32(r.y >> 16));
+    };
     const float4* hp = (const float4*)(h + row * d);
     const float4* gp = (const float4*)g;
-    const uint2* dp = (const uint2*)(dy + row * d);
     const float4* rp = dres ? (const float4*)(dres + row * d) : nullptr;
     float4* op = (float4*)(dh_out + row * d);
     uint2* bp = dh_bf ? (uint2*)(dh_bf + row * d) : nullptr;
@@ -79,23 +93,18 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
             xs[j] = make_float4(0.f, 0.f, 0.f, 0.f);
             gd[j] = xs[j];
             if (i < n4) {
-                const float4 x = hp[i], w = gp[i];
-                const uint2 r = dp[i];
+                const float4 x = hp[i], w = gp[i], dv = dy4(i);
                 xs[j] = x;
-                gd[j] = make_float4(w.x * bf16_to_f32(r.x & 0xffff), w.y * bf16_to_f32(r.x >> 16),
-                                    w.z * bf16_to_f32(r.y & 0xffff), w.w * bf16_to_f32(r.y >> 16));
+                gd[j] = make_float4(w.x * dv.x, w.y * dv.y, w.z * dv.z, w.w * dv.w);
                 ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
                 dot += x.x * gd[j].x + x.y * gd[j].y + x.z * gd[j].z + x.w * gd[j].w;
             }
         }
     } else {
         for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-            const float4 x = hp[i], w = gp[i];
-            const uint2 r = dp[i];
-            const float d0 = bf16_to_f32(r.x & 0xffff), d1 = bf16_to_f32(r.x >> 16);
-            const float d2 = bf16_to_f32(r.y & 0xffff), d3 = bf16_to_f32(r.y >> 16);
+            const float4 x = hp[i], w = gp[i], dv = dy4(i);
             ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
-            dot += x.x * w.x * d0 + x.y * w.y * d1 + x.z * w.z * d2 + x.w * w.w * d3;
+            dot += x.x * w.x * dv.x + x.y * w.y * dv.y + x.z * w.z * dv.z + x.w * w.w * dv.w;
         }
     }
     // both sums through one pair of barriers
@@ -130,10 +139,8 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
         }
     } else {
         for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-            const float4 x = hp[i], w = gp[i];
-            const uint2 r = dp[i];
-            emit(i, x, make_float4(w.x * bf16_to_f32(r.x & 0xffff), w.y * bf16_to_f32(r.x >> 16),
-                                   w.z * bf16_to_f32(r.y & 0xffff), w.w * bf16_to_f32(r.y >> 16)));
+            const float4 x = hp[i], w = gp[i], dv = dy4(i);
+            emit(i, x, make_float4(w.x * dv.x, w.y * dv.y, w.z * dv.z, w.w * dv.w));
         }
     }
 }
@@ -146,11 +153,13 @@ hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, floa
     return hipGetLastError();
 }
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
-                              float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s) {
+                              float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s, const float* dy_part, int n_part,
+                              long part_stride) {
     if (T <= 0) return hipSuccess;
-    if (d <= 4096) rmsnorm_bwd_kernel<4><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
-    else if (d <= 8192) rmsnorm_bwd_kernel<8><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
-    else rmsnorm_bwd_kernel<0><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf);
+    if (dy_part ? (n_part < 1 || (part_stride & 3)) : !dy) return hipErrorInvalidValue;
+    if (d <= 4096) rmsnorm_bwd_kernel<4><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride);
+    else if (d <= 8192) rmsnorm_bwd_kernel<8><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride);
+    else rmsnorm_bwd_kernel<0><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride);
     return hipGetLastError();
 }
 

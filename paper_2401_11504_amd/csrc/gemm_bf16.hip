@@ -548,6 +548,10 @@ static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     static const int xcd_split = getenv("TL_GEMM_XCD_SPLIT") ? atoi(getenv("TL_GEMM_XCD_SPLIT")) : 1;   // tuning aid
     kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n, xcd_split);
     if (SPLITK) {
+        if (g.deferred && BM >= 256) {    // wide-output instance: the consumer adds the partial tiles up
+            *g.deferred = n_split;
+            return hipGetLastError();
+        }
         const long n = (long)g.M * (g.N >> 2) * g.batch;
         splitk_reduce_kernel<<<cdiv(n, 256), 256, 0, s>>>(g, n_split);
     }
@@ -613,6 +617,10 @@ static hipError_t run_nt(const GemmNT& g, int split_k, hipStream_t s) {
 }
 
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
+    if (g.deferred) {
+        *g.deferred = 0;
+        if (g.batch != 1 || g.alpha != 1.f || g.c_f32 || g.R) return hipErrorInvalidValue;
+    }
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
     if ((g.K & 7) || (g.K2 & 7) || (g.lda & 7) || (g.ldb & 7) || (g.lda2 & 7) || (g.ldb2 & 7)) return hipErrorInvalidValue;
     if ((g.bA & 7) || (g.bB & 7) || (g.bA2 & 7) || (g.bB2 & 7)) return hipErrorInvalidValue;

@@ -20,6 +20,10 @@ struct GemmNT {
     int split_k = 0;                            // 0 = choose; >1 needs `partial`
     float* partial = nullptr;                   // fp32 scratch, >= batch*split*M*N elements
     size_t partial_elems = 0;
+    // If set (batch must be 1, alpha 1, bf16 C, no R): when the launcher splits the contraction of a wide-output GEMM
+    // it leaves the fp32 partial tiles in `partial` ([n_split][M][N]), does not write C, and stores n_split here, so
+    // that the consumer can add them up itself instead of a reduce pass; otherwise 0 is stored and C is written.
+    int* deferred = nullptr;
 };
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s);
 
@@ -69,8 +73,11 @@ hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
 
 // ---------------------------------------------------------------- elementwise / reductions (elementwise.hip)
 hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s);
+// dy_part != null: dy is the sum of n_part fp32 arrays [T, d] that lie part_stride elements apart (the partial tiles a
+// split GEMM left behind, see GemmNT::deferred); the bf16 dy is then not read.
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
-                              float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s);
+                              float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s, const float* dy_part = nullptr,
+                              int n_part = 0, long part_stride = 0);
 hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float base, int pos0, int sign,
                        const float2* table, hipStream_t s);
 hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, hipStream_t s);

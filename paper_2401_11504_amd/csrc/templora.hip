@@ -506,8 +506,10 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
 // backward: dH = s dY B;  dX = dY W + D o (dH A)  (D = 1 without dropout: then one GEMM with the contraction extended
 // by dH | A);  the products dA = dH^T X and dB = dY^T Hs are appended to `tn`, which
 // the caller launches once per layer (dY, dH, X and Hs must stay untouched until then).
+// deferred (may be null): where the dX GEMM may report that it left split partial tiles in L->partial instead of
+// writing dX (see GemmNT::deferred); the caller's next kernel then adds them up.
 static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf16_t* X, int T, bf16_t* dX,
-                           GemmTNGroup& tn) {
+                           GemmTNGroup& tn, int* deferred = nullptr) {
     tl_model* m = L->model;
     hipStream_t s = m->stream;
     const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
@@ -527,6 +529,8 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         if (!L->drop_on) { x.A2 = dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r; }
         x.C = dX; x.ldc = din;
         x.partial = L->partial; x.partial_elems = L->partial_elems;
+        static const bool defer_ok = !(getenv("TL_GEMM_DEFER") && atoi(getenv("TL_GEMM_DEFER")) == 0);   // tuning aid
+        if (deferred && defer_ok && !L->drop_on) x.deferred = deferred;   // with dropout dX is needed as a whole below
         HIPCHK(timed_gemm(L, x));
         if (L->drop_on) {
             GemmNT z;
@@ -591,12 +595,17 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     // below this point overwrites them
     TLCHK(wait_tn(L, par ^ 1));
     HIPCHK(launch_swiglu_bwd(L->d_act, sv.gu, T, f, L->dgu, s));
-    TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx, tn));
-    HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s));
+    // the two dX GEMMs that feed an RMSNorm backward have a long contraction and may be split: the norm kernel then
+    // adds the partial tiles up itself (no reduce launch, no bf16 round trip of dX)
+    int nsp = 0;
+    TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx, tn, &nsp));
+    HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s,
+                              nsp ? L->partial : nullptr, nsp, (long)T * d));
     TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o, tn));
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
                                 c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s));   // dq, dk rotated back inside
-    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx, tn));
+    nsp = 0;
+    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx, tn, &nsp));
     // all eleven dA / dB products of the layer in one launch on the side stream
     if (tn.n > TN_GROUP_MAX) return fail(TL_ERR_ARG, "too many products for one grouped launch");
     HIPCHK(hipEventRecord(L->ev_ready[par], s));
@@ -605,7 +614,8 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     HIPCHK(hipEventRecord(L->ev_done[par], L->side));
     L->tn_pending[par] = true;
     // dh_in_bf must not be the buffer dh_out_bf (dB of the down projection is still reading it): callers alternate
-    HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s));
+    HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s,
+                              nsp ? L->partial : nullptr, nsp, (long)T * d));
     return TL_OK;
 }
 
