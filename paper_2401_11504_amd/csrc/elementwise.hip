@@ -8,10 +8,25 @@
 // With d <= 256 * 4 * NV the row stays in registers between the reduction and the output pass (NV float4 per
 // thread); wider rows are read twice (NV = 0).
 template <int NV>
-__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ h, const float* __restrict__ g,
-                                                          int d, float eps, bf16_t* __restrict__ y) {
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const float* __restrict__ g,
+                                                          int d, float eps, bf16_t* __restrict__ y,
+                                                          const float* __restrict__ part, int n_part, long part_stride,
+                                                          const float* resid, float* h_write) {
     __shared__ float red[16];
     const long row = blockIdx.x;
+    if (part) {
+        // assemble the row first: sum of the partial tiles a split GEMM left behind, plus the residual; it becomes
+        // the residual stream (h_write) and the input of the norm.  Each thread re-reads only what it wrote itself.
+        for (int i = threadIdx.x; i < (d >> 2); i += blockDim.x) {
+            float4 t = resid ? *(const float4*)(resid + row * d + 4 * (long)i) : make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int k = 0; k < n_part; ++k) {
+                const float4 q = *(const float4*)(part + (long)k * part_stride + row * d + 4 * (long)i);
+                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+            }
+            *(float4*)(h_write + row * d + 4 * (long)i) = t;
+        }
+        h = h_write;
+    }
     const float4* hp = (const float4*)(h + row * d);
     const float4* gp = (const float4*)g;
     uint2* yp = (uint2*)(y + row * d);
@@ -145,11 +160,13 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
     }
 }
 
-hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s) {
+hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s,
+                              const float* part, int n_part, long part_stride, const float* resid, float* h_write) {
     if (T <= 0) return hipSuccess;
-    if (d <= 4096) rmsnorm_fwd_kernel<4><<<T, 256, 0, s>>>(h, g, d, eps, y);
-    else if (d <= 8192) rmsnorm_fwd_kernel<8><<<T, 256, 0, s>>>(h, g, d, eps, y);
-    else rmsnorm_fwd_kernel<0><<<T, 256, 0, s>>>(h, g, d, eps, y);
+    if (part ? (n_part < 1 || (part_stride & 3) || !h_write) : !h) return hipErrorInvalidValue;
+    if (d <= 4096) rmsnorm_fwd_kernel<4><<<T, 256, 0, s>>>(h, g, d, eps, y, part, n_part, part_stride, resid, h_write);
+    else if (d <= 8192) rmsnorm_fwd_kernel<8><<<T, 256, 0, s>>>(h, g, d, eps, y, part, n_part, part_stride, resid, h_write);
+    else rmsnorm_fwd_kernel<0><<<T, 256, 0, s>>>(h, g, d, eps, y, part, n_part, part_stride, resid, h_write);
     return hipGetLastError();
 }
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,

@@ -619,7 +619,7 @@ static hipError_t run_nt(const GemmNT& g, int split_k, hipStream_t s) {
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     if (g.deferred) {
         *g.deferred = 0;
-        if (g.batch != 1 || g.alpha != 1.f || g.c_f32 || g.R) return hipErrorInvalidValue;
+        if (g.batch != 1 || g.alpha != 1.f) return hipErrorInvalidValue;
     }
     if (g.M <= 0 || g.N <= 0 || g.batch <= 0) return hipSuccess;
     if ((g.K & 7) || (g.K2 & 7) || (g.lda & 7) || (g.ldb & 7) || (g.lda2 & 7) || (g.ldb2 & 7)) return hipErrorInvalidValue;

@@ -20,9 +20,9 @@ struct GemmNT {
     int split_k = 0;                            // 0 = choose; >1 needs `partial`
     float* partial = nullptr;                   // fp32 scratch, >= batch*split*M*N elements
     size_t partial_elems = 0;
-    // If set (batch must be 1, alpha 1, bf16 C, no R): when the launcher splits the contraction of a wide-output GEMM
-    // it leaves the fp32 partial tiles in `partial` ([n_split][M][N]), does not write C, and stores n_split here, so
-    // that the consumer can add them up itself instead of a reduce pass; otherwise 0 is stored and C is written.
+    // If set (batch must be 1, alpha 1): when the launcher splits the contraction of a wide-output GEMM it leaves the
+    // fp32 partial tiles in `partial` ([n_split][M][N]), does not write C (nor add R), and stores n_split here, so that
+    // the consumer can add them up itself instead of a reduce pass; otherwise 0 is stored and C is written.
     int* deferred = nullptr;
 };
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s);
@@ -72,7 +72,11 @@ hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
                                 bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise / reductions (elementwise.hip)
-hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s);
+// part != null: the input row is not read from h but formed as the sum of n_part fp32 arrays [T, d] lying part_stride
+// elements apart plus resid (may be null), and written to h_write (the residual stream) on the way.
+hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, float eps, bf16_t* y, hipStream_t s,
+                              const float* part = nullptr, int n_part = 0, long part_stride = 0,
+                              const float* resid = nullptr, float* h_write = nullptr);
 // dy_part != null: dy is the sum of n_part fp32 arrays [T, d] that lie part_stride elements apart (the partial tiles a
 // split GEMM left behind, see GemmNT::deferred); the bf16 dy is then not read.
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,

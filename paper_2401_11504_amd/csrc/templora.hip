@@ -141,6 +141,12 @@ struct tl_lora {
     // LoRA dropout (training-side forward / backward only): on for the pass in flight?
     bool drop_on = false;
     float* zdrop = nullptr;       // [max_tokens, max(d_model, d_ffn)] fp32: dH A before the mask is applied
+    // A split down-projection GEMM may leave its partial tiles in `partial` for the next RMSNorm, which then also writes
+    // the residual stream row (pend_h = pend_resid + sum of pend_n tiles); until then pend_h does not hold its values.
+    int pend_n = 0;
+    float* pend_h = nullptr;
+    const float* pend_resid = nullptr;
+    int pend_T = 0;
     int loss_row0 = 0;            // first row lm_head and the loss were computed for in the last forward pass
     int kv_len = 0;
     // cache reuse (Section 2): with kv_keep the cache lives in buffers of its own ([max_tokens, 3 d] per layer, same
@@ -475,7 +481,7 @@ extern "C" tl_status tl_lora_free(tl_lora* L) {
 // ---------------------------------------------------------------- one LoRA-adapted projection group
 // forward:  Hs = s X A^T  (kept),  Y = X W^T + Hs B^T (+ residual)
 static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf16_t* Y_bf, float* Y_f32,
-                           const float* resid) {
+                           const float* resid, int* deferred = nullptr) {
     tl_model* m = L->model;
     hipStream_t s = m->stream;
     const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g), r = L->cfg.rank;
@@ -499,7 +505,34 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     y.ldc = (long)G * dout;
     if (Y_f32) { y.C = Y_f32; y.c_f32 = 1; y.R = resid; } else { y.C = Y_bf; }
     y.partial = L->partial; y.partial_elems = L->partial_elems;
+    static const bool defer_ok = !(getenv("TL_GEMM_DEFER") && atoi(getenv("TL_GEMM_DEFER")) == 0);   // tuning aid
+    if (deferred && defer_ok && G == 1) y.deferred = deferred;
     HIPCHK(timed_gemm(L, y));
+    return TL_OK;
+}
+
+// RMSNorm of a residual-stream row block that may still be pending as partial tiles (see tl_lora::pend_n)
+static tl_status norm_fwd(tl_lora* L, const float* h, const float* gain, int T, bf16_t* y) {
+    tl_model* m = L->model;
+    const int d = m->cfg.d_model;
+    if (L->pend_n > 0 && L->pend_h == h && L->pend_T == T) {
+        HIPCHK(launch_rmsnorm_fwd(nullptr, gain, T, d, m->cfg.rms_eps, y, m->stream, L->partial, L->pend_n, (long)T * d,
+                                  L->pend_resid, L->pend_h));
+        L->pend_n = 0;
+        return TL_OK;
+    }
+    if (L->pend_n > 0) return fail(TL_ERR_DEVICE, "internal: pending partial tiles were not consumed");
+    HIPCHK(launch_rmsnorm_fwd(h, gain, T, d, m->cfg.rms_eps, y, m->stream));
+    return TL_OK;
+}
+// write a pending residual-stream block out without a norm (single-layer entry point, generation side)
+static tl_status flush_pending(tl_lora* L) {
+    if (L->pend_n == 0) return TL_OK;
+    tl_model* m = L->model;
+    // the norm kernel is the one that knows how to add the tiles up: run it into a scratch output
+    HIPCHK(launch_rmsnorm_fwd(nullptr, m->layers[0].g1, L->pend_T, m->cfg.d_model, m->cfg.rms_eps, L->dhmid_bf, m->stream,
+                              L->partial, L->pend_n, (long)L->pend_T * m->cfg.d_model, L->pend_resid, L->pend_h));
+    L->pend_n = 0;
     return TL_OK;
 }
 
@@ -557,7 +590,7 @@ static tl_status layer_forward(tl_lora* L, int l, const float* h_in, float* h_ou
     const int d = c.d_model, f = c.d_ffn;
     LayerSave& sv = L->save[l];
     const LayerW& W = m->layers[l];
-    HIPCHK(launch_rmsnorm_fwd(h_in, W.g1, T, d, c.rms_eps, sv.x1, s));
+    TLCHK(norm_fwd(L, h_in, W.g1, T, sv.x1));
     TLCHK(group_fwd(L, l, G_QKV, sv.x1, T, sv.qkv, nullptr, nullptr));
     HIPCHK(launch_rope(sv.qkv, 3L * d, T, 2 * c.n_heads, c.d_head, c.rope_base, 0, +1, m->rope, s));  // q and k
     HIPCHK(launch_attention_fwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, 3L * d, T, c.n_heads, c.d_head, sv.o, d, sv.lse, s));
@@ -565,7 +598,9 @@ static tl_status layer_forward(tl_lora* L, int l, const float* h_in, float* h_ou
     HIPCHK(launch_rmsnorm_fwd(sv.hmid, W.g2, T, d, c.rms_eps, sv.x2, s));
     TLCHK(group_fwd(L, l, G_GU, sv.x2, T, sv.gu, nullptr, nullptr));
     HIPCHK(launch_swiglu_fwd(sv.gu, T, f, sv.act, s));
-    TLCHK(group_fwd(L, l, G_DOWN, sv.act, T, nullptr, h_out, sv.hmid));
+    int nsp = 0;
+    TLCHK(group_fwd(L, l, G_DOWN, sv.act, T, nullptr, h_out, sv.hmid, &nsp));
+    if (nsp > 0) { L->pend_n = nsp; L->pend_h = h_out; L->pend_resid = sv.hmid; L->pend_T = T; }
     return TL_OK;
 }
 
@@ -656,8 +691,9 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(launch_labels(L->tok, T, L->labels, s));
     HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
+    L->pend_n = 0;
     for (int l = 0; l < c.n_layers; ++l) TLCHK(layer_forward(L, l, L->hs[l], L->hs[l + 1], T));
-    HIPCHK(launch_rmsnorm_fwd(L->hs[c.n_layers], m->gf, T, d, c.rms_eps, L->hf, s));
+    TLCHK(norm_fwd(L, L->hs[c.n_layers], m->gf, T, L->hf));
     // conditioning positions carry no loss: their logits are not needed, so lm_head runs on the rows from the first
     // target on only (with the paper's 1024 + 1024 sample that halves it; with Table 5's short pieces it is most of it)
     static const bool all_rows = getenv("TL_LOSS_ALL_ROWS") && atoi(getenv("TL_LOSS_ALL_ROWS")) != 0;   // tuning aid
@@ -830,7 +866,9 @@ extern "C" tl_status tl_prefill(tl_lora* L, const int32_t* tokens, int32_t n_tok
     HIPCHK(hipMemcpyAsync(L->tok, L->tok_host, (size_t)T * sizeof(int), hipMemcpyHostToDevice, s));
     HIPCHK(launch_embed(m->emb, L->tok, T, d, L->hs[0], s));
     // the chunk path's forward: it leaves q|k|v (q, k rotated) of every position in save[l].qkv, which is the cache
+    L->pend_n = 0;
     for (int l = 0; l < c.n_layers; ++l) TLCHK(layer_forward(L, l, L->hs[l], L->hs[l + 1], T));
+    TLCHK(flush_pending(L));      // the last layer's output rows are read directly below
     if (L->kv_keep)
         for (int l = 0; l < c.n_layers; ++l)
             HIPCHK(hipMemcpyAsync(L->kvbuf[l], L->save[l].qkv, (size_t)T * 3 * d * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
@@ -985,7 +1023,9 @@ extern "C" tl_status tl_layer_step(tl_lora* L, int32_t layer, const float* h_in,
     hipStream_t s = L->model->stream;
     if (!L->kv_keep) L->kv_len = 0;
     L->drop_on = L->cfg.dropout > 0.f;
+    L->pend_n = 0;
     TLCHK(layer_forward(L, layer, h_in, h_out, n_tokens));
+    TLCHK(flush_pending(L));      // the caller reads h_out
     HIPCHK(launch_f32_to_bf16(dh_out, L->dh_bf[0], (size_t)n_tokens * c.d_model, s));
     TLCHK(layer_backward(L, layer, h_in, dh_out, L->dh_bf[0], dh_in, nullptr, n_tokens));
     TLCHK(wait_tn(L, 0));
