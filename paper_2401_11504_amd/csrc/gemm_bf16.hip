@@ -659,8 +659,10 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
                 for (int sp = 2; sp <= 4; ++sp) {
                     const size_t need = (size_t)sp * g.M * g.N * g.batch;
                     if (!g.partial || need > g.partial_elems || (g.N & 3) || nk / sp < 8) continue;
-                    const double c = rounds(t256x128 * sp) * 384.0 * (ktot / sp) * 2.0 / per_us +
-                                     (double)need * 8.0 / 5e6 + 5.0;
+                    // the pass over the partials: a reduce launch that reads them and writes C, or, when the consumer
+                    // adds them up itself (g.deferred), only the extra bytes written here and read there
+                    const double pass = g.deferred ? (double)need * 4.0 / 5e6 : (double)need * 8.0 / 5e6 + 5.0;
+                    const double c = rounds(t256x128 * sp) * 384.0 * (ktot / sp) * 2.0 / per_us + pass;
                     if (c < 0.97 * best) { best = c; cfg = 43 + sp; }   // 45, 46, 47 = split 2, 3, 4
                 }
             }

@@ -594,8 +594,10 @@ static tl_status layer_forward(tl_lora* L, int l, const float* h_in, float* h_ou
     TLCHK(group_fwd(L, l, G_QKV, sv.x1, T, sv.qkv, nullptr, nullptr));
     HIPCHK(launch_rope(sv.qkv, 3L * d, T, 2 * c.n_heads, c.d_head, c.rope_base, 0, +1, m->rope, s));  // q and k
     HIPCHK(launch_attention_fwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, 3L * d, T, c.n_heads, c.d_head, sv.o, d, sv.lse, s));
-    TLCHK(group_fwd(L, l, G_O, sv.o, T, nullptr, sv.hmid, h_in));
-    HIPCHK(launch_rmsnorm_fwd(sv.hmid, W.g2, T, d, c.rms_eps, sv.x2, s));
+    int nsp_o = 0;
+    TLCHK(group_fwd(L, l, G_O, sv.o, T, nullptr, sv.hmid, h_in, &nsp_o));
+    if (nsp_o > 0) { L->pend_n = nsp_o; L->pend_h = sv.hmid; L->pend_resid = h_in; L->pend_T = T; }
+    TLCHK(norm_fwd(L, sv.hmid, W.g2, T, sv.x2));
     TLCHK(group_fwd(L, l, G_GU, sv.x2, T, sv.gu, nullptr, nullptr));
     HIPCHK(launch_swiglu_fwd(sv.gu, T, f, sv.act, s));
     int nsp = 0;
