@@ -86,7 +86,7 @@ def test_gemm_nt_skinny(api, H, M, N, K):
     check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")
 
 
-@pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5", "6", "7", "8", "10", "11", "12", "13", "14", "15", "16", "21", "22", "23", "24", "25", "26", "27", "28", "29", "30", "31", "32", "33", "34", "35", "36", "37", "41", "42", "45", "46", "47"])
+@pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5", "6", "7", "8", "10", "11", "12", "13", "14", "15", "16", "21", "22", "23", "24", "25", "26", "27", "28", "29", "30", "31", "32", "33", "34", "35", "36", "37", "41", "42", "45", "46", "47", "50"])
 @pytest.mark.parametrize("M,N,K,K2", [(1024, 2048, 256, 64), (1000, 2056, 128, 0), (520, 4104, 192, 128)])
 def test_gemm_nt_pipelined_tiles(api, H, monkeypatch, tile, M, N, K, K2):
     """The direct-to-LDS kernel in each of its tile configurations (K, K2 multiples of 64; ragged M and N)."""
