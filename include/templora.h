@@ -136,8 +136,10 @@ tl_status tl_lora_init(tl_model* model, const tl_lora_cfg* cfg, tl_lora** out);
  *              positions (so perplexity = exp(loss)).
  *   lr       : AdamW learning rate of this step.
  * On success the step counter advances and A, B, moments are updated.  On any
- * error (bad token id, window violation, non-finite loss) the module state is
- * left exactly as it was.
+ * error found before the backward pass (bad token id, window violation,
+ * non-finite loss) the module state is left exactly as it was; a device error
+ * during the backward pass (TL_ERR_DEVICE) leaves it undefined, because the
+ * optimizer step of a layer is applied as soon as its gradients are complete.
  */
 tl_status tl_chunk_update(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float lr,
                           float* loss_out, int32_t* n_targets_out);

@@ -593,11 +593,12 @@ hipError_t launch_transpose_bf16(const bf16_t* src, long lds, int rows, int cols
 }
 __global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __restrict__ src_base,
                                                               bf16_t* __restrict__ dst_base,
-                                                              const TransposeDesc* __restrict__ tab, int n_desc) {
+                                                              const TransposeDesc* __restrict__ tab, int n_desc,
+                                                              int tile_begin) {
     __shared__ bf16_t tile[64 * 66];
     // binary search for the descriptor whose tile range holds this block
     int lo = 0, hi = n_desc - 1;
-    const int b = blockIdx.x;
+    const int b = blockIdx.x + tile_begin;
     while (lo < hi) {
         int mid = (lo + hi + 1) >> 1;
         if (tab[mid].tile0 <= b) lo = mid; else hi = mid - 1;
@@ -608,10 +609,11 @@ __global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __re
     transpose_tile(src_base + d.src_off, d.lds, d.rows, d.cols, dst_base + d.dst_off, d.ldd, local / tiles_c,
                    local % tiles_c, tile);
 }
+// tiles [tile_begin, tile_begin + n_tiles) of the table's tile numbering
 hipError_t launch_transpose_table(const bf16_t* src_base, bf16_t* dst_base, const TransposeDesc* table_dev,
-                                  int n_desc, int total_tiles, hipStream_t s) {
-    if (n_desc <= 0 || total_tiles <= 0) return hipSuccess;
-    transpose_table_kernel<<<total_tiles, 256, 0, s>>>(src_base, dst_base, table_dev, n_desc);
+                                  int n_desc, int n_tiles, hipStream_t s, int tile_begin) {
+    if (n_desc <= 0 || n_tiles <= 0) return hipSuccess;
+    transpose_table_kernel<<<n_tiles, 256, 0, s>>>(src_base, dst_base, table_dev, n_desc, tile_begin);
     return hipGetLastError();
 }
 __global__ void copy2d_kernel(const bf16_t* __restrict__ src, long lds, int rows, int cols8, bf16_t* __restrict__ dst,

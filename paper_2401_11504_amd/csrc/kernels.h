@@ -109,7 +109,7 @@ hipError_t launch_transpose_bf16(const bf16_t* src, long lds, int rows, int cols
 // many transposes in one launch: descriptors live in device memory
 struct TransposeDesc { long src_off, dst_off; int rows, cols, lds, ldd, tile0, pad; };
 hipError_t launch_transpose_table(const bf16_t* src_base, bf16_t* dst_base, const TransposeDesc* table_dev,
-                                  int n_desc, int total_tiles, hipStream_t s);
+                                  int n_desc, int n_tiles, hipStream_t s, int tile_begin = 0);
 // copy rows [rows, cols] bf16 from src (stride lds) to dst (stride ldd)
 hipError_t launch_copy2d_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd, hipStream_t s);
 

@@ -124,6 +124,12 @@ struct tl_lora {
     std::vector<LayerOff> off;
     TransposeDesc* ttable = nullptr;
     int n_desc = 0, total_tiles = 0;
+    std::vector<int> layer_tile0;     // first tile of each layer in the table's numbering (and the total at [n_layers])
+    // During tl_chunk_update the AdamW step of a layer (and the refresh of its transposed shadows) is issued on the side
+    // stream right after that layer's dA / dB launch, so it runs under the backward pass of the layers below.
+    bool opt_inline = false;
+    float opt_lr = 0.f;
+    hipEvent_t ev_opt = nullptr;      // side: every optimizer launch of the update has finished
     std::vector<LayerSave> save;
     std::vector<float*> hs, dhs;   // residual stream / its gradient at the L+1 layer boundaries
     // shared temporaries
@@ -288,6 +294,7 @@ static void lora_release(tl_lora* L) {
         L->ev_ready[k] = L->ev_done[k] = nullptr;
         L->tn_pending[k] = false;
     }
+    if (L->ev_opt) { (void)hipEventDestroy(L->ev_opt); L->ev_opt = nullptr; }
     for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
     L->prof_ev.clear();
     L->prof_used = 0;
@@ -330,8 +337,10 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         size_t n = 0, nt = 0;
         std::vector<TransposeDesc> desc;
         int tiles = 0;
+        L->layer_tile0.assign(nl + 1, 0);
         for (int l = 0; l < nl; ++l)
             for (int g = 0; g < N_GROUPS; ++g) {
+                if (g == 0) L->layer_tile0[l] = tiles;
                 const int G = kGroupCount[g], din = m->d_in(g), dout = m->d_out(g);
                 L->off[l].A[g] = n;  n += (size_t)G * r * din;
                 L->off[l].B[g] = n;  n += (size_t)G * dout * r;
@@ -349,6 +358,7 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
                     tiles += cdiv(dout, 64) * cdiv(r, 64);
                 }
             }
+        L->layer_tile0[nl] = tiles;
         L->n_params = n;
         L->n_t = nt;
         L->n_desc = (int)desc.size();
@@ -413,6 +423,7 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
             HIPCHK(hipEventCreateWithFlags(&L->ev_done[k], hipEventDisableTiming));
         }
         HIPCHK(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
+        HIPCHK(hipEventCreateWithFlags(&L->ev_opt, hipEventDisableTiming));
         TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
         // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r]) or four of a
         // [T, d_model] output (long-K GEMMs with few output tiles)
@@ -650,6 +661,16 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     HIPCHK(launch_gemm_tn_grouped(tn, L->side));
     HIPCHK(hipEventRecord(L->ev_done[par], L->side));
     L->tn_pending[par] = true;
+    if (L->opt_inline) {
+        // this layer's gradients are complete once that launch is: its AdamW step and the transposed shadows follow on
+        // the side stream (every main-stream kernel that reads the layer's factors was enqueued before ev_ready)
+        const size_t off = L->off[l].A[0];
+        const size_t end = (l + 1 < c.n_layers) ? L->off[l + 1].A[0] : L->n_params;
+        HIPCHK(launch_adamw(L->P + off, L->G + off, L->M + off, L->V + off, L->S + off, end - off, (long)(L->step + 1),
+                            L->opt_lr, L->cfg.beta1, L->cfg.beta2, L->cfg.eps, L->cfg.weight_decay, L->side));
+        HIPCHK(launch_transpose_table(L->S, L->ST, L->ttable, L->n_desc, L->layer_tile0[l + 1] - L->layer_tile0[l],
+                                      L->side, L->layer_tile0[l]));
+    }
     // dh_in_bf must not be the buffer dh_out_bf (dB of the down projection is still reading it): callers alternate
     HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s,
                               nsp ? L->partial : nullptr, nsp, (long)T * d));
@@ -749,12 +770,23 @@ static tl_status update_step(tl_lora* L, const int32_t* tokens, int32_t n_tokens
     dh.partial = L->partial; dh.partial_elems = L->partial_elems;
     HIPCHK(timed_gemm(L, dh));
     HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf[nl & 1], s));
-    for (int l = nl - 1; l >= 0; --l)
-        TLCHK(layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf[(l + 1) & 1], L->dhs[l], L->dh_bf[l & 1], T));
+    static const bool opt_inline = !(getenv("TL_OPT_INLINE") && atoi(getenv("TL_OPT_INLINE")) == 0);   // tuning aid
+    L->opt_inline = opt_inline;
+    L->opt_lr = lr;
+    tl_status bst = TL_OK;
+    for (int l = nl - 1; l >= 0 && bst == TL_OK; --l)
+        bst = layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf[(l + 1) & 1], L->dhs[l], L->dh_bf[l & 1], T);
+    L->opt_inline = false;
+    TLCHK(bst);
     TLCHK(wait_tn(L, 0));
     TLCHK(wait_tn(L, 1));
     L->have_grads = true;
-    TLCHK(optimizer_step(L, lr, 0, L->n_params));
+    if (opt_inline) {
+        HIPCHK(hipEventRecord(L->ev_opt, L->side));
+        HIPCHK(hipStreamWaitEvent(s, L->ev_opt, 0));
+    } else {
+        TLCHK(optimizer_step(L, lr, 0, L->n_params));
+    }
     HIPCHK(hipStreamSynchronize(s));
     L->step += 1;
     *loss_out = loss;
