@@ -303,7 +303,7 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
             dlt += bf16_to_f32(aw[e] & 0xffff) * bf16_to_f32(bw[e] & 0xffff) + bf16_to_f32(aw[e] >> 16) * bf16_to_f32(bw[e] >> 16);
     }
     dlt += __shfl_xor(dlt, 32, 64);   // the partner lane holds the other eight of every sixteen columns
-    if (kg == 0 && g == 0 && t_abs < T) delta[(long)head * T + t_abs] = dlt;
+    if (delta && kg == 0 && g == 0 && t_abs < T) delta[(long)head * T + t_abs] = dlt;
     const float lse2 = (t_abs < T) ? lse[(long)head * T + t_abs] * 1.4426950408889634f : 1.0e30f;
     f32x16_t acc[C::ND];
 #pragma unroll
@@ -540,14 +540,47 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
     return hipErrorInvalidValue;
 }
 
+// delta[head][t] = dO[t, head, :] . O[t, head, :] on its own (used when the dQ and dK/dV kernels run side by side and
+// the dK/dV kernel cannot wait for the dQ kernel to produce it): DH / 8 lanes per (t, head), 16 bytes each.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
+                                                         long ldo, int T, int n_heads, float* __restrict__ delta) {
+    constexpr int LPR = DH / 8;
+    const long item = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
+    const int sub = threadIdx.x % LPR;
+    const bool live = item < (long)T * n_heads;
+    const int t = live ? (int)(item / n_heads) : 0, head = live ? (int)(item % n_heads) : 0;
+    float a[8], b[8], dot = 0.f;
+    unpack8(*(const uint4*)(o + (long)t * ldo + (long)head * DH + sub * 8), a);
+    unpack8(*(const uint4*)(d_o + (long)t * ldo + (long)head * DH + sub * 8), b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dot += a[e] * b[e];
+    for (int off = LPR >> 1; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
+    if (live && sub == 0) delta[(long)head * T + t] = dot;
+}
+
+// s2 == null: dQ kernel (which also writes delta), then dK/dV kernel, on s.  s2 != null: delta from its own small
+// kernel, then the dQ kernel on s and the dK/dV kernel on s2 at the same time (neither fills the chip: one workgroup
+// per CU with an 8:1 causal imbalance between workgroups); s waits for s2 before it returns to the caller's work.
 template <int DH>
 static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                           const float* lse, float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
-                          bf16_t* dv, const float2* rope, hipStream_t s) {
+                          bf16_t* dv, const float2* rope, hipStream_t s, hipStream_t s2, hipEvent_t ev_fork,
+                          hipEvent_t ev_join) {
     using C = AttnCfg<DH>;
     constexpr int NW = ATTN_NW, KG = ATTN_KG;
     const float scale = 1.f / sqrtf((float)DH);
     dim3 grid(cdiv(T, NW * 32), n_heads);
+    hipStream_t skv = s;
+    if (s2) {
+        const long items = (long)T * n_heads * (DH / 8);
+        attn_delta_kernel<DH><<<cdiv(items, 256), 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if ((e = hipEventRecord(ev_fork, s)) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(s2, ev_fork, 0)) != hipSuccess) return e;
+        skv = s2;
+    }
     {
         size_t lds = (size_t)KG * (2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
         const size_t merge = KG > 1 ? (size_t)NW * 64 * (C::ND * 16) * sizeof(float) : 0;
@@ -555,14 +588,17 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
         auto kern = attn_bwd_dq_kernel<DH, NW, KG>;
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, scale, rope);
+        kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, o, d_o, lse, s2 ? nullptr : delta, ldq, ldo, T, dq, scale, rope);
     }
     const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
     auto kern = attn_bwd_dkv_kernel<DH, NW>;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, NW * 64, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope);
-    return hipGetLastError();
+    kern<<<grid, NW * 64, lds, skv>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope);
+    e = hipGetLastError();
+    if (e != hipSuccess || !s2) return e;
+    if ((e = hipEventRecord(ev_join, s2)) != hipSuccess) return e;
+    return hipStreamWaitEvent(s, ev_join, 0);
 }
 
 // delta (fp32 [n_heads, T]) is written by the dQ kernel and read by the dK/dV kernel.  rope != null: q and k were
@@ -570,10 +606,13 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
 // come out as gradients with respect to the UNROTATED projections.
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
-                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s) {
+                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s, hipStream_t s2,
+                                hipEvent_t ev_fork, hipEvent_t ev_join) {
     if (T <= 0 || n_heads <= 0) return hipSuccess;
-    if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
-    if (d_head == 128) return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s);
-    if (d_head == 64) return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s);
+    if ((ldq & 7) || (ldo & 7) || (s2 && (!ev_fork || !ev_join))) return hipErrorInvalidValue;
+    if (d_head == 128)
+        return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, s2, ev_fork, ev_join);
+    if (d_head == 64)
+        return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, s2, ev_fork, ev_join);
     return hipErrorInvalidValue;
 }
