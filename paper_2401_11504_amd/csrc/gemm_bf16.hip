@@ -780,7 +780,8 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
         split = 1;
         if (g.partial && t64 < 256) {
             split = (int)(512 / t64);
-            if (split > nk / 4) split = nk / 4;
+            static const int kdiv = getenv("TL_SKINNY_KDIV") ? atoi(getenv("TL_SKINNY_KDIV")) : 4;   // tuning aid
+            if (split > nk / kdiv) split = nk / kdiv;   // at least kdiv k-tiles per split
             if (split < 1) split = 1;
             while (split > 1 && (size_t)split * g.M * g.N * g.batch > g.partial_elems) --split;
         }
