@@ -1,5 +1,6 @@
 #!/usr/bin/env python3
-"""Writes tests/golden/prefix_7bwidth_L4_seed2048.npz: the CPU oracle's results for one update on the paper's actual
+"""Writes tests/golden/prefix_7bwidth_L4_seed2048.npz (default) or, with the argument "piece", tests/golden/
+prefix_7bwidth_L2_seed1357.npz.  The first holds the CPU oracle's results for one update on the paper's actual
 training sample layout -- L_T = 1024 conditioning tokens followed by a chunk of 1024 (Section 2, "use the preceding
 L_T tokens as the input and the chunk as the output"), i.e. 2048 tokens with n_ctx = 1024 so that only the chunk
 positions carry loss -- on a decoder of the 7B width (d 4096, 32x128 heads, ffn 11008, vocab 32000, r = 64) cut to
@@ -9,7 +10,10 @@ Calls only oracle/ and the seeded input generator.  Zipf(1.1) token ids, A ~ N(0
 dA != 0).  Stored: loss, n_targets, per-position nll, samples of the hidden-state gradient at every layer boundary and
 of dA / dB of every projection of every layer, with full-tensor norms.
 
-    python tests/golden/make_prefix_golden.py
+The "piece" file is the layout of one of Table 5's smaller batches: the same 1024 conditioning tokens followed by a
+ragged piece of 333 tokens (1357 in all, no multiple of any tile), on two layers of the same width.
+
+    python tests/golden/make_prefix_golden.py [piece]
 """
 import os
 import sys
@@ -22,8 +26,12 @@ sys.path.insert(0, ROOT)
 from oracle import templora_oracle as O  # noqa: E402
 from paper_2401_11504_amd import synth  # noqa: E402
 
-SEED, T, N_CTX, N_LAYERS, B_STD = 2048, 2048, 1024, 4, 0.01
-OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "prefix_7bwidth_L4_seed2048.npz")
+B_STD = 0.01
+if sys.argv[1:] == ["piece"]:
+    SEED, T, N_CTX, N_LAYERS = 1357, 1357, 1024, 2
+else:
+    SEED, T, N_CTX, N_LAYERS = 2048, 2048, 1024, 4
+OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), f"prefix_7bwidth_L{N_LAYERS}_seed{SEED}.npz")
 ROWS, COLS = 2, 256
 
 
@@ -48,7 +56,11 @@ def main():
     out = {"loss": np.float64(res["loss"]), "n_targets": np.int64(res["n_targets"]), "nll": f32(res["nll"]),
            "n_layers": np.int64(shape.n_layers), "seed": np.int64(SEED), "n_ctx": np.int64(N_CTX), "b_std": np.float64(B_STD),
            "tokens": tok}
-    rows_t = np.sort(rs.choice(T, 4, replace=False))
+    if N_LAYERS == 4:
+        rows_t = np.sort(rs.choice(T, 4, replace=False))
+    else:       # two conditioning rows (their gradient arrives through dK / dV alone) and two rows of the piece
+        rows_t = np.concatenate([np.sort(rs.choice(N_CTX - 1, 2, replace=False)),
+                                 np.sort(N_CTX - 1 + rs.choice(T - N_CTX + 1, 2, replace=False))])
     cols_d = np.sort(rs.choice(shape.d_model, COLS, replace=False))
     out["dh_rows"], out["dh_cols"] = rows_t, cols_d
     out["dh_final"] = f32(res["dh"]["final"][np.ix_(rows_t, cols_d)])
