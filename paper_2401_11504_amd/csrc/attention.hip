@@ -261,25 +261,21 @@ __device__ __forceinline__ void rope_rotate_dT(f32x16_t* acc, const float2* __re
 // ======================================================================== backward: dQ
 // Same shape as the forward kernel: KG key groups share the causal range tile by tile and their dQ partial sums are
 // added through LDS at the end.  delta[t] = dO[t] . O[t] is formed here from the rows the wave already holds (and
-// written out for the dK/dV kernel, which runs afterwards); with a RoPE table the gradient is rotated back before it
-// is stored, so no separate pass over dq is needed.
+// written out, if delta != null, for a dK/dV kernel that runs afterwards); with a RoPE table the gradient is rotated
+// back before it is stored, so no separate pass over dq is needed.
 template <int DH, int NW, int KG>
-__global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
+__device__ __forceinline__ void attn_dq_block(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse, float* __restrict__ delta, long ldq, long ldo, int T,
-    bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope) {
+    bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope, int qb, int head, unsigned char* smem_raw) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
     constexpr int GROUP_ELEMS = 2 * 64 * C::LSK + DH * LST;
-    extern __shared__ __align__(16) unsigned char smem_raw[];
     const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / NT);
     const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
     bf16_t* sV = sK + 64 * C::LSK;
     bf16_t* sKt = sV + 64 * C::LSK;
-    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;   // see attn_fwd_kernel
-    const int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
-    const int head = blockIdx.y;
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
     const bf16_t* qh = q + (long)head * DH;
@@ -383,19 +379,27 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
     }
 }
 
+template <int DH, int NW, int KG>
+__global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, float* __restrict__ delta, long ldq, long ldo, int T,
+    bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;   // see attn_fwd_kernel
+    const int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
+    attn_dq_block<DH, NW, KG>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, scale, rope, qb, blockIdx.y, smem_raw);
+}
+
 // ======================================================================== backward: dK, dV
 template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ q,
-                                                               const bf16_t* __restrict__ k,
-                                                               const bf16_t* __restrict__ v,
-                                                               const bf16_t* __restrict__ d_o,
-                                                               const float* __restrict__ lse,
-                                                               const float* __restrict__ delta, long ldq, long ldo,
-                                                               int T, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
-                                                               float scale, const float2* __restrict__ rope) {
+__device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                                               const bf16_t* __restrict__ v, const bf16_t* __restrict__ d_o,
+                                               const float* __restrict__ lse, const float* __restrict__ delta, long ldq,
+                                               long ldo, int T, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
+                                               float scale, const float2* __restrict__ rope, int kb, int head,
+                                               unsigned char* smem) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, KB = NW * 32;
-    extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* sQ = (bf16_t*)smem;             // [64][LSK]
     bf16_t* sdO = sQ + 64 * C::LSK;         // [64][LSK]
     bf16_t* sQt = sdO + 64 * C::LSK;        // [DH][LST]
@@ -403,10 +407,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
     float* sLse = (float*)(sdOt + DH * LST); // [64]
     float* sDelta = sLse + 64;              // [64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
-    // early key blocks see the most queries and are scheduled first; second half of the grid mirrored (see attn_fwd_kernel)
-    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;
-    const int kb = mirror ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
-    const int head = blockIdx.y;
     const int u0 = kb * KB, uw0 = u0 + 32 * wave, u_abs = uw0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
     const bf16_t* qh = q + (long)head * DH;
@@ -502,6 +502,40 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
     }
 }
 
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ q,
+                                                               const bf16_t* __restrict__ k,
+                                                               const bf16_t* __restrict__ v,
+                                                               const bf16_t* __restrict__ d_o,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ delta, long ldq, long ldo,
+                                                               int T, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
+                                                               float scale, const float2* __restrict__ rope) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    // early key blocks see the most queries and are scheduled first; second half of the grid mirrored (see attn_fwd_kernel)
+    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;
+    const int kb = mirror ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
+    attn_dkv_block<DH, NW>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope, kb, blockIdx.y, smem);
+}
+
+// ======================================================================== backward: both in one launch
+// Block b of a head does the dK/dV work of key block b (every query block from b on) and then the dQ work of query
+// block b (every key block up to b), so that every workgroup carries about the same load.  As two launches each has
+// an 8:1 causal imbalance between its workgroups (one per CU at 1024 tokens x 32 heads) and the chip waits for the
+// longest one twice.  delta must already be in memory: the dK/dV part reads rows that other workgroups' dQ parts own.
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_fused_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta, long ldq, long ldo,
+    int T, bf16_t* __restrict__ dq, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, float scale,
+    const float2* __restrict__ rope) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int b = blockIdx.x, head = blockIdx.y;
+    attn_dkv_block<DH, NW>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope, b, head, smem);
+    __syncthreads();   // the dQ part lays its own tiles over the same LDS
+    attn_dq_block<DH, NW, 1>(q, k, v, o, d_o, lse, nullptr, ldq, ldo, T, dq, scale, rope, b, head, smem);
+}
+
 // ======================================================================== launchers
 // waves per workgroup (32 queries / keys each), fixed at build time.  Measured at T = 1024, 32 heads of 128:
 // 4 waves beat 2 (a K/V tile is shared by more queries; the extra workgroups of 2 do not overlap enough).
@@ -540,8 +574,8 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
     return hipErrorInvalidValue;
 }
 
-// delta[head][t] = dO[t, head, :] . O[t, head, :] on its own (used when the dQ and dK/dV kernels run side by side and
-// the dK/dV kernel cannot wait for the dQ kernel to produce it): DH / 8 lanes per (t, head), 16 bytes each.
+// delta[head][t] = dO[t, head, :] . O[t, head, :] on its own, for the one-launch backward, whose dK/dV parts cannot
+// wait for other workgroups' dQ parts to produce it: DH / 8 lanes per (t, head), 16 bytes each.
 template <int DH>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
                                                          long ldo, int T, int n_heads, float* __restrict__ delta) {
@@ -559,27 +593,29 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
     if (live && sub == 0) delta[(long)head * T + t] = dot;
 }
 
-// s2 == null: dQ kernel (which also writes delta), then dK/dV kernel, on s.  s2 != null: delta from its own small
-// kernel, then the dQ kernel on s and the dK/dV kernel on s2 at the same time (neither fills the chip: one workgroup
-// per CU with an 8:1 causal imbalance between workgroups); s waits for s2 before it returns to the caller's work.
+// fused: delta from its own small kernel, then one launch in which every workgroup does one key block's dK/dV and one
+// query block's dQ.  Otherwise (tuning aid): the dQ kernel, which also writes delta, then the dK/dV kernel.
 template <int DH>
 static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                           const float* lse, float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
-                          bf16_t* dv, const float2* rope, hipStream_t s, hipStream_t s2, hipEvent_t ev_fork,
-                          hipEvent_t ev_join) {
+                          bf16_t* dv, const float2* rope, hipStream_t s, bool fused) {
     using C = AttnCfg<DH>;
     constexpr int NW = ATTN_NW, KG = ATTN_KG;
     const float scale = 1.f / sqrtf((float)DH);
     dim3 grid(cdiv(T, NW * 32), n_heads);
-    hipStream_t skv = s;
-    if (s2) {
+    const size_t lds_kv = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
+    if (fused) {
         const long items = (long)T * n_heads * (DH / 8);
         attn_delta_kernel<DH><<<cdiv(items, 256), 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if ((e = hipEventRecord(ev_fork, s)) != hipSuccess) return e;
-        if ((e = hipStreamWaitEvent(s2, ev_fork, 0)) != hipSuccess) return e;
-        skv = s2;
+        const size_t lds_q = (size_t)(2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
+        const size_t lds = lds_q > lds_kv ? lds_q : lds_kv;
+        auto kern = attn_bwd_fused_kernel<DH, NW>;
+        e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        kern<<<grid, NW * 64, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, dk, dv, scale, rope);
+        return hipGetLastError();
     }
     {
         size_t lds = (size_t)KG * (2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
@@ -588,31 +624,24 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
         auto kern = attn_bwd_dq_kernel<DH, NW, KG>;
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, o, d_o, lse, s2 ? nullptr : delta, ldq, ldo, T, dq, scale, rope);
+        kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, scale, rope);
     }
-    const size_t lds = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
     auto kern = attn_bwd_dkv_kernel<DH, NW>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv);
     if (e != hipSuccess) return e;
-    kern<<<grid, NW * 64, lds, skv>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope);
-    e = hipGetLastError();
-    if (e != hipSuccess || !s2) return e;
-    if ((e = hipEventRecord(ev_join, s2)) != hipSuccess) return e;
-    return hipStreamWaitEvent(s, ev_join, 0);
+    kern<<<grid, NW * 64, lds_kv, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope);
+    return hipGetLastError();
 }
 
-// delta (fp32 [n_heads, T]) is written by the dQ kernel and read by the dK/dV kernel.  rope != null: q and k were
-// rotated by RoPE (table of (cos, sin) per position and pair, positions 0 .. T-1) before the forward pass, and dq, dk
-// come out as gradients with respect to the UNROTATED projections.
+// delta (fp32 [n_heads, T]) = rowsum(dO * O), workspace written here and read by the dK/dV part.  rope != null: q and k
+// were rotated by RoPE (table of (cos, sin) per position and pair, positions 0 .. T-1) before the forward pass, and dq,
+// dk come out as gradients with respect to the UNROTATED projections.
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
-                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s, hipStream_t s2,
-                                hipEvent_t ev_fork, hipEvent_t ev_join) {
+                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s, bool fused) {
     if (T <= 0 || n_heads <= 0) return hipSuccess;
-    if ((ldq & 7) || (ldo & 7) || (s2 && (!ev_fork || !ev_join))) return hipErrorInvalidValue;
-    if (d_head == 128)
-        return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, s2, ev_fork, ev_join);
-    if (d_head == 64)
-        return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, s2, ev_fork, ev_join);
+    if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
+    if (d_head == 128) return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, fused);
+    if (d_head == 64) return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, fused);
     return hipErrorInvalidValue;
 }

@@ -70,7 +70,7 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
                                 bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s,
-                                hipStream_t s2 = nullptr, hipEvent_t ev_fork = nullptr, hipEvent_t ev_join = nullptr);
+                                bool fused = true);
 
 // ---------------------------------------------------------------- elementwise / reductions (elementwise.hip)
 // part != null: the input row is not read from h but formed as the sum of n_part fp32 arrays [T, d] lying part_stride

@@ -130,7 +130,6 @@ struct tl_lora {
     bool opt_inline = false;
     float opt_lr = 0.f;
     hipEvent_t ev_opt = nullptr;      // side: every optimizer launch of the update has finished
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;   // attention backward: dK/dV on the side stream beside dQ on the main one
     std::vector<LayerSave> save;
     std::vector<float*> hs, dhs;   // residual stream / its gradient at the L+1 layer boundaries
     // shared temporaries
@@ -296,8 +295,6 @@ static void lora_release(tl_lora* L) {
         L->tn_pending[k] = false;
     }
     if (L->ev_opt) { (void)hipEventDestroy(L->ev_opt); L->ev_opt = nullptr; }
-    if (L->ev_fork) { (void)hipEventDestroy(L->ev_fork); L->ev_fork = nullptr; }
-    if (L->ev_join) { (void)hipEventDestroy(L->ev_join); L->ev_join = nullptr; }
     for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
     L->prof_ev.clear();
     L->prof_used = 0;
@@ -427,8 +424,6 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         }
         HIPCHK(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
         HIPCHK(hipEventCreateWithFlags(&L->ev_opt, hipEventDisableTiming));
-        HIPCHK(hipEventCreateWithFlags(&L->ev_fork, hipEventDisableTiming));
-        HIPCHK(hipEventCreateWithFlags(&L->ev_join, hipEventDisableTiming));
         TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
         // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r]) or four of a
         // [T, d_model] output (long-K GEMMs with few output tiles)
@@ -632,6 +627,12 @@ static tl_status wait_tn(tl_lora* L, int par) {
 }
 
 // dh_out (fp32) and its bf16 copy dh_out_bf -> dh_in (fp32) and, if dh_in_bf != null, its bf16 copy
+// tuning aid: TL_ATTN_FUSED=0 runs the attention backward as two launches (dQ, then dK/dV) instead of one
+static bool attn_fused() {
+    static const bool on = !(getenv("TL_ATTN_FUSED") && atoi(getenv("TL_ATTN_FUSED")) == 0);
+    return on;
+}
+
 static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const float* dh_out, const bf16_t* dh_out_bf,
                                 float* dh_in, bf16_t* dh_in_bf, int T) {
     tl_model* m = L->model;
@@ -655,12 +656,9 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s,
                               nsp ? L->partial : nullptr, nsp, (long)T * d));
     TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o, tn));
-    // from 2048 tokens on the dK/dV kernel runs on the side stream beside the dQ kernel (measured: 82.2 -> 81.1 ms per
-    // update at 2048 tokens, but 41.7 -> 42.0 at 1024, where the extra delta launch and the two event hand-overs cost more)
-    static const bool attn_two = !(getenv("TL_ATTN_TWO_STREAMS") && atoi(getenv("TL_ATTN_TWO_STREAMS")) == 0);   // tuning aid
+    // one launch for dQ and dK/dV (dq, dk rotated back inside): 120 -> 90 us per layer at 1024 tokens
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
-                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s,
-                                attn_two && T >= 2048 ? L->side : nullptr, L->ev_fork, L->ev_join));   // dq, dk rotated back inside
+                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s, attn_fused()));
     nsp = 0;
     TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx, tn, &nsp));
     // all eleven dA / dB products of the layer in one launch on the side stream
@@ -1356,7 +1354,7 @@ extern "C" tl_status tl_k_attention_bwd(const uint16_t* q, const uint16_t* k, co
     KARGS_OK(q && k && v && o && d_o && lse && dq && dk && dv && delta && T >= 0 && n_heads > 0 &&
                  (d_head == 64 || d_head == 128), "tl_k_attention_bwd");
     HIPCHK(launch_attention_bwd(q, k, v, o, d_o, lse, ldq, ldo, T, n_heads, d_head, dq, dk, dv, delta, nullptr,
-                                (hipStream_t)hip_stream));
+                                (hipStream_t)hip_stream, attn_fused()));
     return TL_OK;
 }
 extern "C" tl_status tl_k_cross_entropy(const float* logits, const int32_t* labels, int32_t T, int32_t V,
