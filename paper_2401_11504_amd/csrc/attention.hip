@@ -10,6 +10,8 @@
 // P is never stored: the backward kernels rebuild it from the saved log-sum-exp.
 // The two backward kernels write disjoint outputs, so no atomics are needed and results are
 // bit-reproducible.
+#include <type_traits>
+
 #include "kernels.h"
 #include "tiles.h"
 
@@ -333,17 +335,20 @@ __device__ __forceinline__ void attn_dq_block(
             dp1 = mfma32(*(const bf16x8_t*)(sV + o1), dof[ks], dp1);
         }
         float ds[32];
-        const bool diag = u0 + 63 > tq0;
+        // only a tile on the diagonal needs the causal mask (wave-uniform); the others skip its compares
+        auto probs = [&](auto masked) {
 #pragma unroll
-        for (int vv = 0; vv < 16; ++vv) {
-            const int u = u0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
-            const float pe0 = fast_exp2(s0[vv] * scale_log2e - lse2);
-            const float pe1 = fast_exp2(s1[vv] * scale_log2e - lse2);
-            const float p0 = (diag && u > t_abs) ? 0.f : pe0;
-            const float p1 = (diag && u + 32 > t_abs) ? 0.f : pe1;
-            ds[vv] = p0 * (dp0[vv] - dlt);
-            ds[16 + vv] = p1 * (dp1[vv] - dlt);
-        }
+            for (int vv = 0; vv < 16; ++vv) {
+                const int u = u0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
+                const float pe0 = fast_exp2(s0[vv] * scale_log2e - lse2);
+                const float pe1 = fast_exp2(s1[vv] * scale_log2e - lse2);
+                const float p0 = (decltype(masked)::value && u > t_abs) ? 0.f : pe0;
+                const float p1 = (decltype(masked)::value && u + 32 > t_abs) ? 0.f : pe1;
+                ds[vv] = p0 * (dp0[vv] - dlt);
+                ds[16 + vv] = p1 * (dp1[vv] - dlt);
+            }
+        };
+        if (u0 + 63 > tq0) probs(std::true_type{}); else probs(std::false_type{});
 #pragma unroll
         for (int us = 0; us < 2; ++us)
 #pragma unroll
@@ -464,23 +469,26 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
                 dpacc = mfma32(b, vf[ks], dpacc);
             }
             float p[16], ds[16];
-            const bool diag = tsub0 < uw0 + 32;
+            // only a sub-tile on the diagonal needs the causal mask (wave-uniform); the others skip its compares
+            auto probs = [&](auto masked) {
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int tl = ts * 32 + 8 * vq + 4 * g;
-                const float4 l4 = *(const float4*)(sLse + tl);
-                const float4 d4 = *(const float4*)(sDelta + tl);
-                const float ll[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int tl = ts * 32 + 8 * vq + 4 * g;
+                    const float4 l4 = *(const float4*)(sLse + tl);
+                    const float4 d4 = *(const float4*)(sDelta + tl);
+                    const float ll[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int vv = 4 * vq + e;
-                    const int t = t0 + tl + e;
-                    const float pe = fast_exp2(sacc[vv] * scale_log2e - ll[e]);
-                    const float pv = (diag && u_abs > t) ? 0.f : pe;
-                    p[vv] = pv;
-                    ds[vv] = pv * (dpacc[vv] - dd[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        const int vv = 4 * vq + e;
+                        const int t = t0 + tl + e;
+                        const float pe = fast_exp2(sacc[vv] * scale_log2e - ll[e]);
+                        const float pv = (decltype(masked)::value && u_abs > t) ? 0.f : pe;
+                        p[vv] = pv;
+                        ds[vv] = pv * (dpacc[vv] - dd[e]);
+                    }
                 }
-            }
+            };
+            if (tsub0 < uw0 + 32) probs(std::true_type{}); else probs(std::false_type{});
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const bf16x8_t bp = pack_b_from_d(p, h);
