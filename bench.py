@@ -298,7 +298,9 @@ def main():
     frozen = 2.0 * T * (L * (4 * d * d + 3 * d * f) + d * V)
     lora_fl = 6.0 * T * r * L * (4 * 2 * d + 3 * (d + f))
     attn = 3.5 * 2.0 * T * T * d * L
-    total_flop = 2 * frozen + lora_fl + attn
+    # the gradient at the embedding output feeds nothing trainable: dX of layer 0's q|k|v (frozen part and its low-rank
+    # extension) is not computed and not counted
+    total_flop = 2 * frozen + lora_fl + attn - 2.0 * T * 3 * d * (d + r)
     out = {
         "metric": "trained tokens/sec per Temp-Lora chunk update (7B-shape, r=64); MFMA util %",
         "value": round((T - args.ctx) / (ms_step * 1e-3), 1),   # chunk tokens; conditioning tokens are not trained on

@@ -260,6 +260,12 @@ tl_status tl_get_nll(tl_lora* lora, float* host_out, size_t n);
 /* Gradient of the last update's loss w.r.t. the hidden state entering layer `boundary`
  * (boundary = n_layers: the state entering the final RMSNorm): host fp32[n_tokens * d_model]. */
 tl_status tl_get_dh(tl_lora* lora, int32_t boundary, float* host_out, size_t n);
+/* The gradient at boundary 0 (the embedding output) reaches no trainable parameter: the embedding is frozen
+ * (Section 2: only the module is trained) and dA, dB of layer 0 do not need it.  By default an update therefore
+ * leaves out dX of layer 0's q|k|v projections and the backward of its first RMSNorm, and tl_get_dh(.., 0, ..)
+ * returns TL_ERR_ARG.  on != 0 makes the following updates compute it (parity checks); every other output of the
+ * update is bit-identical either way. */
+tl_status tl_keep_input_grad(tl_lora* lora, int32_t on);
 
 /* ---- measurement hooks (not part of the paper's method) ----
  * While enabled, every launch of the frozen-weight GEMM kernel (the LoRA-adapted projections forward and their

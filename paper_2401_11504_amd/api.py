@@ -77,6 +77,7 @@ _SIGS = {
     "tl_get_step": [_vp, C.POINTER(_i64)],
     "tl_get_nll": [_vp, _vp, _sz],
     "tl_get_dh": [_vp, _i32, _vp, _sz],
+    "tl_keep_input_grad": [_vp, _i32],
     "tl_profile_enable": [_vp, _i32],
     "tl_profile_read": [_vp, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)],
     "tl_layer_step": [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _i32],
@@ -274,6 +275,10 @@ def tl_get_dh(lora, boundary, n_tokens, d_model):
     out = np.empty((n_tokens, d_model), dtype=np.float32)
     _chk(_lib.tl_get_dh(lora, boundary, out.ctypes.data_as(_vp), out.size))
     return out
+
+
+def tl_keep_input_grad(lora, on=True):
+    _chk(_lib.tl_keep_input_grad(lora, int(on)))
 
 
 def tl_profile_enable(lora, on=True):

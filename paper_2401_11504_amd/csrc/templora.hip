@@ -130,6 +130,9 @@ struct tl_lora {
     bool opt_inline = false;
     float opt_lr = 0.f;
     hipEvent_t ev_opt = nullptr;      // side: every optimizer launch of the update has finished
+    // The gradient at the embedding output feeds nothing trainable; an update computes it only on request
+    // (tl_keep_input_grad), for tl_get_dh(boundary 0).
+    bool keep_input_grad = false, have_dh0 = false;
     std::vector<LayerSave> save;
     std::vector<float*> hs, dhs;   // residual stream / its gradient at the L+1 layer boundaries
     // shared temporaries
@@ -660,7 +663,9 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
                                 c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s, attn_fused()));
     nsp = 0;
-    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, L->dx, tn, &nsp));
+    // dh_in == null: the caller does not want the gradient of the layer's input (the bottom layer of an update: it would
+    // feed only the frozen embedding), so dX of q|k|v and the first RMSNorm's backward are left out; dA / dB are not
+    TLCHK(group_bwd(L, l, G_QKV, L->dqkv, sv.x1, T, dh_in ? L->dx : nullptr, tn, &nsp));
     // all eleven dA / dB products of the layer in one launch on the side stream
     if (tn.n > TN_GROUP_MAX) return fail(TL_ERR_ARG, "too many products for one grouped launch");
     HIPCHK(hipEventRecord(L->ev_ready[par], s));
@@ -679,8 +684,9 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
                                       L->side, L->layer_tile0[l]));
     }
     // dh_in_bf must not be the buffer dh_out_bf (dB of the down projection is still reading it): callers alternate
-    HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s,
-                              nsp ? L->partial : nullptr, nsp, (long)T * d));
+    if (dh_in)
+        HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s,
+                                  nsp ? L->partial : nullptr, nsp, (long)T * d));
     return TL_OK;
 }
 
@@ -781,8 +787,12 @@ static tl_status update_step(tl_lora* L, const int32_t* tokens, int32_t n_tokens
     L->opt_inline = opt_inline;
     L->opt_lr = lr;
     tl_status bst = TL_OK;
-    for (int l = nl - 1; l >= 0 && bst == TL_OK; --l)
-        bst = layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf[(l + 1) & 1], L->dhs[l], L->dh_bf[l & 1], T);
+    for (int l = nl - 1; l >= 0 && bst == TL_OK; --l) {
+        const bool want_in = l > 0 || L->keep_input_grad;
+        bst = layer_backward(L, l, L->hs[l], L->dhs[l + 1], L->dh_bf[(l + 1) & 1], want_in ? L->dhs[l] : nullptr,
+                             L->dh_bf[l & 1], T);
+        if (l == 0) L->have_dh0 = want_in;
+    }
     L->opt_inline = false;
     TLCHK(bst);
     TLCHK(wait_tn(L, 0));
@@ -1139,12 +1149,20 @@ extern "C" tl_status tl_get_nll(tl_lora* L, float* host_out, size_t n) {
     return TL_OK;
 }
 
+extern "C" tl_status tl_keep_input_grad(tl_lora* L, int32_t on) {
+    LIVE(L, "tl_keep_input_grad");
+    L->keep_input_grad = on != 0;
+    return TL_OK;
+}
+
 extern "C" tl_status tl_get_dh(tl_lora* L, int32_t boundary, float* host_out, size_t n) {
     LIVE(L, "tl_get_dh");
     if (!host_out) return fail(TL_ERR_ARG, "host_out is null");
     const tl_model_cfg& c = L->model->cfg;
     if (boundary < 0 || boundary > c.n_layers) return fail(TL_ERR_ARG, "boundary out of range");
     if (!L->have_grads || n != (size_t)L->last_tokens * c.d_model) return fail(TL_ERR_ARG, "n must be n_tokens * d_model of the last update");
+    if (boundary == 0 && !L->have_dh0)
+        return fail(TL_ERR_ARG, "the gradient at the embedding output was not computed: call tl_keep_input_grad(lora, 1) before the update");
     HIPCHK(hipStreamSynchronize(L->model->stream));
     HIPCHK(hipMemcpy(host_out, L->dhs[boundary], n * sizeof(float), hipMemcpyDeviceToHost));
     return TL_OK;

@@ -79,11 +79,15 @@ class Model:
             self.handle = None
 
 
-def new_lora(model: Model, seed: int, b_std: float = 0.0, set_from_synth: bool = True, **hyper):
+def new_lora(model: Model, seed: int, b_std: float = 0.0, set_from_synth: bool = True, keep_input_grad: bool = True,
+             **hyper):
     """tl_lora_init + (optionally) overwrite A, B with the synth draws the oracle also uses.
-    Returns (handle, host factors [{proj: (A, B)}] or None)."""
+    Returns (handle, host factors [{proj: (A, B)}] or None).  keep_input_grad: updates also compute the gradient at
+    the embedding output (off by default in the library), so that tl_get_dh(.., 0, ..) can be compared."""
     shape = model.shape
     h = api.tl_lora_init(model.handle, shape.rank, shape.alpha, seed=seed, **hyper)
+    if keep_input_grad:
+        api.tl_keep_input_grad(h, True)
     if not set_from_synth:
         return h, None
     facs = [synth.lora_factors(seed, shape, l, b_std=b_std) for l in range(shape.n_layers)]

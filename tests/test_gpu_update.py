@@ -267,3 +267,35 @@ def test_update_is_bit_reproducible(api, H):
     assert outs[0][0] == outs[1][0]
     assert np.array_equal(outs[0][1], outs[1][1]) and np.array_equal(outs[0][2], outs[1][2])
     model.close()
+
+
+@pytest.mark.parametrize("name,T,p", [("small", 160, 0.0), ("small128", 130, 0.0), ("small", 96, 0.1)])
+def test_input_gradient_is_left_out_by_default_and_nothing_else_changes(api, H, name, T, p):
+    """The gradient at the embedding output feeds no trainable parameter (the embedding is frozen): by default an
+    update leaves out dX of layer 0's q|k|v and its first RMSNorm backward.  Everything else must be bit-identical
+    to an update that computes it, and tl_get_dh(.., 0, ..) must say that it has nothing to give."""
+    shape = synth.SHAPES[name]
+    model = H.Model(shape, 8100, max_tokens=T)
+    tok = synth.uniform_tokens(8100, T, shape.vocab)
+    la, _ = H.new_lora(model, 8100, b_std=0.01, keep_input_grad=False, dropout=p)
+    lb, _ = H.new_lora(model, 8100, b_std=0.01, keep_input_grad=True, dropout=p)
+    for step in range(2):
+        assert api.tl_chunk_update(la, tok, 0, 1e-3) == api.tl_chunk_update(lb, tok, 0, 1e-3)
+        for l in range(shape.n_layers):
+            for i, pj in enumerate(synth.PROJ):
+                dout, din = shape.proj_dims(pj)
+                for sel, shp in ((api.GRAD_A, (shape.rank, din)), (api.GRAD_B, (dout, shape.rank)),
+                                 (api.FACTOR_A, (shape.rank, din)), (api.FACTOR_B, (dout, shape.rank))):
+                    assert np.array_equal(api.tl_get_factor(la, l, i, sel, shp), api.tl_get_factor(lb, l, i, sel, shp))
+        for b in range(1, shape.n_layers + 1):
+            assert np.array_equal(api.tl_get_dh(la, b, T, shape.d_model), api.tl_get_dh(lb, b, T, shape.d_model))
+        with pytest.raises(api.TlError) as e:
+            api.tl_get_dh(la, 0, T, shape.d_model)
+        assert e.value.status == -1
+        assert np.isfinite(api.tl_get_dh(lb, 0, T, shape.d_model)).all()
+    api.tl_keep_input_grad(la, True)                       # switching it on takes effect from the next update
+    assert api.tl_chunk_update(la, tok, 0, 1e-3) == api.tl_chunk_update(lb, tok, 0, 1e-3)
+    assert np.array_equal(api.tl_get_dh(la, 0, T, shape.d_model), api.tl_get_dh(lb, 0, T, shape.d_model))
+    for h in (la, lb):
+        api.tl_lora_free(h)
+    model.close()
