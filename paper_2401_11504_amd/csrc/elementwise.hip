@@ -75,16 +75,22 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
                                                           const float* __restrict__ g, const float* __restrict__ dres,
                                                           int d, float eps, float* __restrict__ dh_out,
                                                           bf16_t* __restrict__ dh_bf, const float* __restrict__ dy_part,
-                                                          int n_part, long part_stride) {
+                                                          int n_part, long part_stride, int part_bf16) {
     __shared__ float red[32];
     const long row = blockIdx.x;
-    // chunk i (four elements) of this row of dy: the bf16 array, or the sum of the fp32 partial arrays
+    // chunk i (four elements) of this row of dy: the bf16 array, or the sum of the partial arrays (fp32 or bf16)
     auto dy4 = [&](int i) {
         if (dy_part) {
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int k = 0; k < n_part; ++k) {
-                const float4 q = *(const float4*)(dy_part + (long)k * part_stride + row * d + 4 * (long)i);
-                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                if (part_bf16) {
+                    const uint2 r = *(const uint2*)((const bf16_t*)dy_part + (long)k * part_stride + row * d + 4 * (long)i);
+                    t.x += bf16_to_f32(r.x & 0xffff); t.y += bf16_to_f32(r.x >> 16);
+                    t.z += bf16_to_f32(r.y & 0xffff); t.w += bf16_to_f32(r.y >> 16);
+                } else {
+                    const float4 q = *(const float4*)(dy_part + (long)k * part_stride + row * d + 4 * (long)i);
+                    t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+                }
             }
             return t;
         }
@@ -171,12 +177,12 @@ hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, floa
 }
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
                               float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s, const float* dy_part, int n_part,
-                              long part_stride) {
+                              long part_stride, int part_bf16) {
     if (T <= 0) return hipSuccess;
     if (dy_part ? (n_part < 1 || (part_stride & 3)) : !dy) return hipErrorInvalidValue;
-    if (d <= 4096) rmsnorm_bwd_kernel<4><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride);
-    else if (d <= 8192) rmsnorm_bwd_kernel<8><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride);
-    else rmsnorm_bwd_kernel<0><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride);
+    if (d <= 4096) rmsnorm_bwd_kernel<4><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride, part_bf16);
+    else if (d <= 8192) rmsnorm_bwd_kernel<8><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride, part_bf16);
+    else rmsnorm_bwd_kernel<0><<<T, 256, 0, s>>>(dy, h, g, dres, d, eps, dh_out, dh_bf, dy_part, n_part, part_stride, part_bf16);
     return hipGetLastError();
 }
 

@@ -457,7 +457,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         }
     }
 
-    if constexpr (SPLITK) {
+    bool bf16_partials = false;
+    if constexpr (SPLITK) bf16_partials = p.partial_bf16 != 0;
+    if (SPLITK && !bf16_partials) {
         // each split stores its fp32 tile; splitk_reduce_kernel adds the splits in index order afterwards
         // (a second launch: device-wide fences inside a kernel cost a full L2 write-back on this chip)
         float* part = p.partial + ((long)z * n_split + split) * (long)p.M * p.N;
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             }
         return;
     }
-    if (p.c_f32) {
+    if (p.c_f32 && !bf16_partials) {
         // fp32 output (+ fp32 residual): half a wave already writes 128 contiguous bytes per row
 #pragma unroll
         for (int i = 0; i < FM; ++i)
@@ -501,15 +503,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
         __builtin_amdgcn_s_barrier();  // every wave is done reading operand tiles
         asm volatile("" ::: "memory");
         bf16_t* slab = (bf16_t*)smem + wave * 32 * SLD;
-        bf16_t* Cb = (bf16_t*)p.C + (long)z * p.bC;
-        const bool vec_ok = ((p.ldc & 7) == 0) && ((p.bC & 7) == 0) && (((size_t)p.C & 15) == 0);
+        // a split whose consumer adds the tiles up itself and asked for bf16 ones: the split's tile leaves the same
+        // way, unscaled, into its [M, N] slice of the scratch
+        bf16_t* Cb = bf16_partials ? (bf16_t*)p.partial + ((long)z * n_split + split) * (long)p.M * p.N
+                                   : (bf16_t*)p.C + (long)z * p.bC;
+        const long ldc = bf16_partials ? (long)p.N : p.ldc;
+        const float alpha = bf16_partials ? 1.f : p.alpha;
+        const bool vec_ok = bf16_partials ? ((p.N & 7) == 0 && (((size_t)p.partial & 15) == 0) && (((long)p.M * p.N) & 7) == 0)
+                                          : ((p.ldc & 7) == 0) && ((p.bC & 7) == 0) && (((size_t)p.C & 15) == 0);
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    slab[(8 * (v >> 2) + 4 * g + (v & 3)) * SLD + j * 32 + l32] = f32_to_bf16(p.alpha * acc[i][j][v]);
+                    slab[(8 * (v >> 2) + 4 * g + (v & 3)) * SLD + j * 32 + l32] = f32_to_bf16(alpha * acc[i][j][v]);
             __builtin_amdgcn_wave_barrier();
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             constexpr int CPR = TN / 8;  // 16-byte chunks per slab row
@@ -519,7 +527,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
                 const int row = m0 + wm * TM + i * 32 + r, col = n0 + wn * TN + cc;
                 if (row >= p.M || col >= p.N) continue;
                 const uint4 val = *(const uint4*)(slab + r * SLD + cc);
-                bf16_t* dst = Cb + (long)row * p.ldc + col;
+                bf16_t* dst = Cb + (long)row * ldc + col;
                 if (vec_ok && col + 8 <= p.N) {
                     *(uint4*)dst = val;
                 } else {
@@ -546,7 +554,9 @@ static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     static const int xcd_split = getenv("TL_GEMM_XCD_SPLIT") ? atoi(getenv("TL_GEMM_XCD_SPLIT")) : 1;   // tuning aid
-    kern<<<grid, WM * WN * 64, lds, s>>>(g, tiles_m, tiles_n, xcd_split);
+    GemmNT gk = g;
+    if (!(SPLITK && g.deferred && BM >= 256)) gk.partial_bf16 = 0;   // bf16 partial tiles only where the reduce is left to the consumer
+    kern<<<grid, WM * WN * 64, lds, s>>>(gk, tiles_m, tiles_n, xcd_split);
     if (SPLITK) {
         if (g.deferred && BM >= 256) {    // wide-output instance: the consumer adds the partial tiles up
             *g.deferred = n_split;
@@ -661,7 +671,7 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
                     if (!g.partial || need > g.partial_elems || (g.N & 3) || nk / sp < 8) continue;
                     // the pass over the partials: a reduce launch that reads them and writes C, or, when the consumer
                     // adds them up itself (g.deferred), only the extra bytes written here and read there
-                    const double pass = g.deferred ? (double)need * 4.0 / 5e6 : (double)need * 8.0 / 5e6 + 5.0;
+                    const double pass = g.deferred ? (double)need * (g.partial_bf16 ? 2.0 : 4.0) / 5e6 : (double)need * 8.0 / 5e6 + 5.0;
                     const double c = rounds(t256x128 * sp) * 384.0 * (ktot / sp) * 2.0 / per_us + pass;
                     if (c < 0.97 * best) { best = c; cfg = 43 + sp; }   // 45, 46, 47 = split 2, 3, 4
                 }

@@ -24,6 +24,9 @@ struct GemmNT {
     // fp32 partial tiles in `partial` ([n_split][M][N]), does not write C (nor add R), and stores n_split here, so that
     // the consumer can add them up itself instead of a reduce pass; otherwise 0 is stored and C is written.
     int* deferred = nullptr;
+    // With `deferred`: the partial tiles left for the consumer are bf16 (the same [n_split][M][N] layout over the same
+    // scratch, half the bytes written here and read there; each partial is rounded once) instead of fp32.
+    int partial_bf16 = 0;
 };
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s);
 
@@ -82,7 +85,7 @@ hipError_t launch_rmsnorm_fwd(const float* h, const float* g, int T, int d, floa
 // split GEMM left behind, see GemmNT::deferred); the bf16 dy is then not read.
 hipError_t launch_rmsnorm_bwd(const bf16_t* dy, const float* h, const float* g, const float* dres, int T, int d,
                               float eps, float* dh_out, bf16_t* dh_bf, hipStream_t s, const float* dy_part = nullptr,
-                              int n_part = 0, long part_stride = 0);
+                              int n_part = 0, long part_stride = 0, int part_bf16 = 0);
 hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float base, int pos0, int sign,
                        const float2* table, hipStream_t s);
 hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, hipStream_t s);

@@ -550,6 +550,14 @@ static tl_status flush_pending(tl_lora* L) {
     return TL_OK;
 }
 
+// The partial tiles a split dX GEMM leaves to the RMSNorm backward are bf16: dX was a bf16 tensor before the reduce
+// pass was folded into the norm, so the gradient loses nothing it had, and the tiles cost half the bytes on both sides.
+// tuning aid: TL_DEFER_BF16=0 keeps them fp32
+static bool defer_bf16() {
+    static const bool on = !(getenv("TL_DEFER_BF16") && atoi(getenv("TL_DEFER_BF16")) == 0);
+    return on;
+}
+
 // backward: dH = s dY B;  dX = dY W + D o (dH A)  (D = 1 without dropout: then one GEMM with the contraction extended
 // by dH | A);  the products dA = dH^T X and dB = dY^T Hs are appended to `tn`, which
 // the caller launches once per layer (dY, dH, X and Hs must stay untouched until then).
@@ -577,7 +585,10 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         x.C = dX; x.ldc = din;
         x.partial = L->partial; x.partial_elems = L->partial_elems;
         static const bool defer_ok = !(getenv("TL_GEMM_DEFER") && atoi(getenv("TL_GEMM_DEFER")) == 0);   // tuning aid
-        if (deferred && defer_ok && !L->drop_on) x.deferred = deferred;   // with dropout dX is needed as a whole below
+        if (deferred && defer_ok && !L->drop_on) {   // with dropout dX is needed as a whole below
+            x.deferred = deferred;
+            x.partial_bf16 = defer_bf16() ? 1 : 0;
+        }
         HIPCHK(timed_gemm(L, x));
         if (L->drop_on) {
             GemmNT z;
@@ -657,7 +668,7 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     int nsp = 0;
     TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx, tn, &nsp));
     HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s,
-                              nsp ? L->partial : nullptr, nsp, (long)T * d));
+                              nsp ? L->partial : nullptr, nsp, (long)T * d, defer_bf16()));
     TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o, tn));
     // one launch for dQ and dK/dV (dq, dk rotated back inside): 120 -> 90 us per layer at 1024 tokens
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
@@ -686,7 +697,7 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     // dh_in_bf must not be the buffer dh_out_bf (dB of the down projection is still reading it): callers alternate
     if (dh_in)
         HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s,
-                                  nsp ? L->partial : nullptr, nsp, (long)T * d));
+                                  nsp ? L->partial : nullptr, nsp, (long)T * d, defer_bf16()));
     return TL_OK;
 }
 
