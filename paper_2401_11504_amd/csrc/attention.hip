@@ -117,9 +117,16 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
     // Heaviest (latest) query blocks first; the second half of the heads takes the mirrored block, so that two
     // workgroups placed on one CU by round-robin dispatch (ids i and i + n/2 in dispatch order, x fastest) carry the
     // same total number of key tiles whichever CU they land on.
+    // With more workgroups than CUs (several rounds) the order of dispatch decides the tail instead: every head's
+    // heaviest block first, then every head's second heaviest, and so on (longest job first).
     const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;
-    const int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
-    const int head = blockIdx.y;
+    int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
+    int head = blockIdx.y;
+    if (gridDim.x * gridDim.y > 256) {
+        const int idx = blockIdx.y * gridDim.x + blockIdx.x;   // position in dispatch order (x fastest)
+        qb = (int)gridDim.x - 1 - idx / (int)gridDim.y;
+        head = idx % (int)gridDim.y;
+    }
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const bf16_t* qh = q + (long)head * DH;
     const bf16_t* kh = k + (long)head * DH;
@@ -527,10 +534,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __r
 }
 
 // ======================================================================== backward: both in one launch
-// Block b of a head does the dK/dV work of key block b (every query block from b on) and then the dQ work of query
-// block b (every key block up to b), so that every workgroup carries about the same load.  As two launches each has
-// an 8:1 causal imbalance between its workgroups (one per CU at 1024 tokens x 32 heads) and the chip waits for the
-// longest one twice.  delta must already be in memory: the dK/dV part reads rows that other workgroups' dQ parts own.
+// Every workgroup does ONE part -- the dK/dV of a key block (all query blocks from it on) or the dQ of a query block (all
+// key blocks up to it) -- and the parts are handed out longest first: level j of the grid holds the dK/dV part of key
+// block j and the dQ part of query block n - 1 - j of every head, which cost about the same, and levels run from the
+// heaviest down.  As two launches each part list has an 8:1 causal imbalance between its workgroups and, at 1024
+// tokens x 32 heads, exactly one workgroup per CU, so the chip waits for the longest one twice; in one launch a CU that
+// finishes a light part picks up the next.  delta must already be in memory (the dK/dV parts read rows that other
+// workgroups' dQ parts own).  grid = (n blocks, heads, 2).
 template <int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_fused_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
@@ -538,10 +548,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_fused_kernel(
     int T, bf16_t* __restrict__ dq, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, float scale,
     const float2* __restrict__ rope) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int b = blockIdx.x, head = blockIdx.y;
-    attn_dkv_block<DH, NW>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope, b, head, smem);
-    __syncthreads();   // the dQ part lays its own tiles over the same LDS
-    attn_dq_block<DH, NW, 1>(q, k, v, o, d_o, lse, nullptr, ldq, ldo, T, dq, scale, rope, b, head, smem);
+    const int n = gridDim.x, heads = gridDim.y;
+    const int idx = (blockIdx.z * heads + blockIdx.y) * n + blockIdx.x;   // position in dispatch order (x fastest)
+    const int level = idx / (2 * heads), r = idx % (2 * heads), head = r % heads;
+    if (r < heads) attn_dkv_block<DH, NW>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope, level, head, smem);
+    else attn_dq_block<DH, NW, 1>(q, k, v, o, d_o, lse, nullptr, ldq, ldo, T, dq, scale, rope, n - 1 - level, head, smem);
 }
 
 // ======================================================================== launchers
@@ -583,7 +594,7 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
 }
 
 // delta[head][t] = dO[t, head, :] . O[t, head, :] on its own, for the one-launch backward, whose dK/dV parts cannot
-// wait for other workgroups' dQ parts to produce it: DH / 8 lanes per (t, head), 16 bytes each.
+// wait for the dQ parts of other workgroups to produce it: DH / 8 lanes per (t, head), 16 bytes each.
 template <int DH>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
                                                          long ldo, int T, int n_heads, float* __restrict__ delta) {
@@ -601,8 +612,8 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
     if (live && sub == 0) delta[(long)head * T + t] = dot;
 }
 
-// fused: delta from its own small kernel, then one launch in which every workgroup does one key block's dK/dV and one
-// query block's dQ.  Otherwise (tuning aid): the dQ kernel, which also writes delta, then the dK/dV kernel.
+// fused: delta from its own small kernel, then one launch that holds every dK/dV and every dQ part, longest first.
+// Otherwise (tuning aid): the dQ kernel, which also writes delta, then the dK/dV kernel.
 template <int DH>
 static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                           const float* lse, float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
@@ -622,6 +633,7 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
         auto kern = attn_bwd_fused_kernel<DH, NW>;
         e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
+        grid.z = 2;
         kern<<<grid, NW * 64, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, dk, dv, scale, rope);
         return hipGetLastError();
     }
