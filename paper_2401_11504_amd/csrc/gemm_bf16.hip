@@ -626,6 +626,34 @@ static hipError_t run_nt(const GemmNT& g, int split_k, hipStream_t s) {
     return hipGetLastError();
 }
 
+// A many-tile GEMM whose tile count leaves the last round of workgroups poorly filled can be cheaper as two launches:
+// columns [0, N1) (of every batch) as whole rounds of 256x256 tiles, the rest on its own with whatever tile suits it
+// (gate|up at 1024 tokens: 688 tiles of 256x128 are 2.7 rounds and cost three; 256 tiles of 256x256 plus 176 of 256x128
+// cost 12.2 + 7.0 instead of 3 x 7.0 in the units of the tile model below).  Returns N1, or 0 for one launch.
+int gemm_nt_column_split(const GemmNT& g) {
+    static const bool off = getenv("TL_GEMM_TILE") || (getenv("TL_GEMM_NSPLIT") && atoi(getenv("TL_GEMM_NSPLIT")) == 0);   // tuning aids
+    if (off || g.deferred || g.split_k > 1 || g.M <= 0 || g.N < 512 || g.batch <= 0) return 0;
+    if ((g.K % BK) || (g.K2 % BK) || g.K <= 0) return 0;
+    const long tm = (long)cdiv(g.M, 256) * g.batch;
+    if (tm > 256 || 256 % tm) return 0;                       // a round of 256x256 tiles must be whole tile columns
+    const long cols_round = 256 / tm * 256;
+    if (tm * cdiv(g.N, 256) < 160) return 0;                  // few tiles: launch_gemm_nt has other choices there
+    auto rounds = [](long t) { return (double)((t + 255) / 256); };
+    auto one_launch = [&](long n) {                           // the many-tile model of launch_gemm_nt, per unit of K
+        const double c256 = rounds(tm * cdiv(n, 256)) * 512.0 / 42.0, c128 = rounds(tm * cdiv(n, 128)) * 384.0 / 55.0;
+        const double c192 = rounds(tm * cdiv(n, 192)) * 448.0 / 42.0;
+        return c256 < c128 ? (c256 < c192 ? c256 : c192) : (c128 < c192 ? c128 : c192);
+    };
+    const double k_us = ((double)g.K + g.K2) * 2.0 / 1e3, second_launch_us = 6.0;
+    double best = one_launch(g.N) * k_us;
+    int n1 = 0;
+    for (long c = cols_round; c + 128 <= g.N; c += cols_round) {
+        const double cost = ((double)(c / cols_round) * 512.0 / 42.0 + one_launch(g.N - c)) * k_us + second_launch_us;
+        if (cost < 0.97 * best) { best = cost; n1 = (int)c; }
+    }
+    return n1;
+}
+
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     if (g.deferred) {
         *g.deferred = 0;
@@ -689,7 +717,7 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
                 static const bool no192 = getenv("TL_GEMM_NO192") != nullptr;   // tuning aid
                 if (!no192 && c192 < c256 && c192 < c128) cfg = 50;
                 else if (c128 < c256) cfg = 28;
-                else cfg = fill(t256) < 0.9 && g.batch > 1 ? 22 : 6;   // half-depth four-stage loop for batched launches
+                else cfg = 22;   // 256x256: the half-depth four-stage loop (faster than two full-depth stages on every shape measured)
             }
         }
         switch (cfg) {

@@ -194,12 +194,26 @@ static void prof_mark(tl_lora* L) {
     (void)hipEventRecord(L->prof_ev[L->prof_used++], L->model->stream);
 }
 // run one frozen-weight GEMM, bracketed by events when timing is on
-static hipError_t timed_gemm(tl_lora* L, const GemmNT& g) {
+static hipError_t timed_gemm_one(tl_lora* L, const GemmNT& g) {
     prof_mark(L);
     hipError_t e = launch_gemm_nt(g, L->model->stream);
     prof_mark(L);
     if (L->prof_on) L->prof_flop += 2.0 * g.M * (double)g.N * ((double)g.K + g.K2) * g.batch;
     return e;
+}
+// as two launches over two column ranges where the tile model finds that cheaper (each is timed as a launch of its own)
+static hipError_t timed_gemm(tl_lora* L, const GemmNT& g) {
+    const int n1 = gemm_nt_column_split(g);
+    if (n1 <= 0) return timed_gemm_one(L, g);
+    GemmNT a = g, b = g;
+    a.N = n1;
+    b.N = g.N - n1;
+    b.B = g.B + (long)n1 * g.ldb;
+    if (g.K2 > 0) b.B2 = g.B2 + (long)n1 * g.ldb2;
+    b.C = (char*)g.C + (size_t)n1 * (g.c_f32 ? sizeof(float) : sizeof(bf16_t));
+    if (g.R) b.R = g.R + n1;
+    hipError_t e = timed_gemm_one(L, a);
+    return e != hipSuccess ? e : timed_gemm_one(L, b);
 }
 
 // ---------------------------------------------------------------- model
