@@ -631,8 +631,8 @@ static hipError_t run_nt(const GemmNT& g, int split_k, hipStream_t s) {
 // (gate|up at 1024 tokens: 688 tiles of 256x128 are 2.7 rounds and cost three; 256 tiles of 256x256 plus 176 of 256x128
 // cost 12.2 + 7.0 instead of 3 x 7.0 in the units of the tile model below).  Returns N1, or 0 for one launch.
 int gemm_nt_column_split(const GemmNT& g) {
-    static const bool off = getenv("TL_GEMM_TILE") || (getenv("TL_GEMM_NSPLIT") && atoi(getenv("TL_GEMM_NSPLIT")) == 0);   // tuning aids
-    if (off || g.deferred || g.split_k > 1 || g.M <= 0 || g.N < 512 || g.batch <= 0) return 0;
+    static const bool off = getenv("TL_GEMM_NSPLIT") && atoi(getenv("TL_GEMM_NSPLIT")) == 0;   // tuning aid
+    if (off || getenv("TL_GEMM_TILE") || g.deferred || g.split_k > 1 || g.M <= 0 || g.N < 512 || g.batch <= 0) return 0;
     if ((g.K % BK) || (g.K2 % BK) || g.K <= 0) return 0;
     const long tm = (long)cdiv(g.M, 256) * g.batch;
     if (tm > 256 || 256 % tm) return 0;                       // a round of 256x256 tiles must be whole tile columns
