@@ -569,25 +569,48 @@ hipError_t launch_dropout_add(bf16_t* dx, const float* z, size_t n, uint64_t key
 }
 
 // ---------------------------------------------------------------- transposes / copies
-// 64x64 bf16 tiles through LDS (row stride 66 elements keeps both phases spread over the banks)
+// 64x64 bf16 tiles through LDS.  With everything a multiple of 8 elements (every LoRA factor is) a thread moves 16-byte
+// pieces on both sides of the turn; otherwise element by element.  tile: TR_TILE_ELEMS elements, 16-byte aligned.
+constexpr int TR_LD = 72;                    // LDS row stride: 144 bytes, so that a row starts on a 16-byte boundary
+constexpr int TR_TILE_ELEMS = 64 * TR_LD;
 __device__ __forceinline__ void transpose_tile(const bf16_t* __restrict__ src, long lds, int rows, int cols,
                                                bf16_t* __restrict__ dst, long ldd, int tr, int tc, bf16_t* tile) {
     const int r0 = tr * 64, c0 = tc * 64;
+    const bool vec = !((lds | ldd | rows | cols) & 7) && !(((size_t)src | (size_t)dst) & 15);
+    if (vec) {
+        for (int i = threadIdx.x; i < 64 * 8; i += blockDim.x) {
+            const int r = i >> 3, c8 = (i & 7) * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (r0 + r < rows && c0 + c8 < cols) v = *(const uint4*)(src + (long)(r0 + r) * lds + c0 + c8);
+            *(uint4*)(tile + r * TR_LD + c8) = v;
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < 64 * 8; i += blockDim.x) {
+            const int c = i >> 3, r8 = (i & 7) * 8;
+            if (c0 + c >= cols || r0 + r8 >= rows) continue;
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w[e] = (uint32_t)tile[(r8 + 2 * e) * TR_LD + c] | ((uint32_t)tile[(r8 + 2 * e + 1) * TR_LD + c] << 16);
+            *(uint4*)(dst + (long)(c0 + c) * ldd + r0 + r8) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        return;
+    }
     for (int i = threadIdx.x; i < 64 * 64; i += blockDim.x) {
         const int r = i >> 6, c = i & 63;
         bf16_t v = 0;
         if (r0 + r < rows && c0 + c < cols) v = src[(long)(r0 + r) * lds + c0 + c];
-        tile[r * 66 + c] = v;
+        tile[r * TR_LD + c] = v;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < 64 * 64; i += blockDim.x) {
         const int c = i >> 6, r = i & 63;
-        if (r0 + r < rows && c0 + c < cols) dst[(long)(c0 + c) * ldd + r0 + r] = tile[r * 66 + c];
+        if (r0 + r < rows && c0 + c < cols) dst[(long)(c0 + c) * ldd + r0 + r] = tile[r * TR_LD + c];
     }
 }
 __global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ src, long lds, int rows, int cols,
                                                         bf16_t* __restrict__ dst, long ldd) {
-    __shared__ bf16_t tile[64 * 66];
+    __shared__ __align__(16) bf16_t tile[TR_TILE_ELEMS];
     transpose_tile(src, lds, rows, cols, dst, ldd, blockIdx.y, blockIdx.x, tile);
 }
 hipError_t launch_transpose_bf16(const bf16_t* src, long lds, int rows, int cols, bf16_t* dst, long ldd,
@@ -601,7 +624,7 @@ __global__ __launch_bounds__(256) void transpose_table_kernel(const bf16_t* __re
                                                               bf16_t* __restrict__ dst_base,
                                                               const TransposeDesc* __restrict__ tab, int n_desc,
                                                               int tile_begin) {
-    __shared__ bf16_t tile[64 * 66];
+    __shared__ __align__(16) bf16_t tile[TR_TILE_ELEMS];
     // binary search for the descriptor whose tile range holds this block
     int lo = 0, hi = n_desc - 1;
     const int b = blockIdx.x + tile_begin;
