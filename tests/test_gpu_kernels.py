@@ -181,7 +181,10 @@ def test_swiglu(api, H, T, f):
 
 
 # ------------------------------------------------------------------ attention
-@pytest.mark.parametrize("T,nh,dh", [(64, 1, 64), (200, 2, 64), (333, 2, 128), (1024, 2, 128), (1, 1, 64), (129, 1, 128)])
+# the last case has more workgroups than the chip has CUs (9 query blocks x 30 heads, ragged): the forward kernel then
+# hands its blocks out heaviest first, a different block-to-workgroup mapping from the one-round cases
+@pytest.mark.parametrize("T,nh,dh", [(64, 1, 64), (200, 2, 64), (333, 2, 128), (1024, 2, 128), (1, 1, 64), (129, 1, 128),
+                                     (1100, 30, 64)])
 def test_attention_fwd_bwd(api, H, T, nh, dh):
     qkv = rnd(1, (T, 3 * nh * dh), 1.0)
     do = rnd(2, (T, nh * dh))
