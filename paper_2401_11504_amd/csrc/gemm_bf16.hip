@@ -654,6 +654,21 @@ int gemm_nt_column_split(const GemmNT& g) {
     return n1;
 }
 
+// the two launches of a column split: a = columns [0, N1), b = the rest; false (and nothing written) for one launch
+bool gemm_nt_split_columns(const GemmNT& g, GemmNT* a, GemmNT* b) {
+    const int n1 = gemm_nt_column_split(g);
+    if (n1 <= 0) return false;
+    *a = g;
+    *b = g;
+    a->N = n1;
+    b->N = g.N - n1;
+    b->B = g.B + (long)n1 * g.ldb;
+    if (g.K2 > 0) b->B2 = g.B2 + (long)n1 * g.ldb2;
+    b->C = (char*)g.C + (size_t)n1 * (g.c_f32 ? sizeof(float) : sizeof(bf16_t));
+    if (g.R) b->R = g.R + n1;
+    return true;
+}
+
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     if (g.deferred) {
         *g.deferred = 0;

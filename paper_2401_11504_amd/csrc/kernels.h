@@ -31,6 +31,7 @@ struct GemmNT {
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s);
 // N1 > 0: cheaper as two launches, columns [0, N1) and [N1, N) of every batch (see gemm_bf16.hip); 0: one launch
 int gemm_nt_column_split(const GemmNT& g);
+bool gemm_nt_split_columns(const GemmNT& g, GemmNT* a, GemmNT* b);   // the two launches, if N1 > 0
 
 // C[Mo, No] (fp32) = alpha * P[T, Mo]^T Q[T, No]
 struct GemmTN {

@@ -203,15 +203,8 @@ static hipError_t timed_gemm_one(tl_lora* L, const GemmNT& g) {
 }
 // as two launches over two column ranges where the tile model finds that cheaper (each is timed as a launch of its own)
 static hipError_t timed_gemm(tl_lora* L, const GemmNT& g) {
-    const int n1 = gemm_nt_column_split(g);
-    if (n1 <= 0) return timed_gemm_one(L, g);
-    GemmNT a = g, b = g;
-    a.N = n1;
-    b.N = g.N - n1;
-    b.B = g.B + (long)n1 * g.ldb;
-    if (g.K2 > 0) b.B2 = g.B2 + (long)n1 * g.ldb2;
-    b.C = (char*)g.C + (size_t)n1 * (g.c_f32 ? sizeof(float) : sizeof(bf16_t));
-    if (g.R) b.R = g.R + n1;
+    GemmNT a, b;
+    if (!gemm_nt_split_columns(g, &a, &b)) return timed_gemm_one(L, g);
     hipError_t e = timed_gemm_one(L, a);
     return e != hipSuccess ? e : timed_gemm_one(L, b);
 }
@@ -1288,6 +1281,12 @@ extern "C" tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t
             scratch_elems = want;
         }
         g.partial = scratch; g.partial_elems = scratch_elems;
+    }
+    GemmNT ga, gb;   // the same column split as the update path makes
+    if (gemm_nt_split_columns(g, &ga, &gb)) {
+        HIPCHK(launch_gemm_nt(ga, (hipStream_t)hip_stream));
+        HIPCHK(launch_gemm_nt(gb, (hipStream_t)hip_stream));
+        return TL_OK;
     }
     HIPCHK(launch_gemm_nt(g, (hipStream_t)hip_stream));
     return TL_OK;

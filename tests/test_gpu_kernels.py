@@ -105,6 +105,27 @@ def test_gemm_nt_pipelined_tiles(api, H, monkeypatch, tile, M, N, K, K2):
     check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")
 
 
+def test_gemm_nt_two_column_ranges(api, H):
+    """The gate|up shape at 1024 tokens: the launcher sends it out as two launches over two column ranges (whole rounds
+    of 256x256 tiles, then the rest).  Checked on sampled columns, among them those on both sides of the seam."""
+    M, N, K, K2 = 1024, 22016, 4096, 128
+    A, B = rnd(1, (M, K)), rnd(2, (N, K), 0.05)
+    A2, B2 = rnd(3, (M, K2)), rnd(4, (N, K2), 0.05)
+    rs = np.random.default_rng(7)
+    cols = np.unique(np.concatenate([rs.choice(N, 384, replace=False), np.arange(16384 - 40, 16384 + 40),
+                                     np.arange(8192 - 8, 8192 + 8), [0, N - 1]]))
+    ref = A.astype(np.float64) @ B[cols].T.astype(np.float64) + A2.astype(np.float64) @ B2[cols].T.astype(np.float64)
+    Cd = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cd, H.to_dev_bf16(A2), H.to_dev_bf16(B2))
+    torch.cuda.synchronize()
+    check(H.bf16_to_np(Cd)[:, cols], ref, BF16_TOL, "C bf16")
+    R = rnd(5, (M, N), 1.0, False)
+    Cf = torch.zeros(M, N, dtype=torch.float32, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cf, H.to_dev_bf16(A2), H.to_dev_bf16(B2), alpha=1.0, R=H.to_dev_f32(R))
+    torch.cuda.synchronize()
+    check(Cf.cpu().numpy()[:, cols], ref + R[:, cols], 1e-3, "C f32 + R")
+
+
 def test_gemm_nt_strided_operands(api, H):
     # operands that are column blocks of wider buffers (as q|k|v and gate|up are)
     M, N, K = 200, 96, 128
