@@ -317,7 +317,9 @@ tl_status tl_linear_step(const float* X, const float* W, const float* A, const f
 
 /* C[M,N] = alpha * (A[M,K] B[N,K]^T + A2[M,K2] B2[N,K2]^T) (+ R[M,N] if R != NULL), bf16 MFMA, fp32 accumulate.
  * A2/B2 may be NULL (K2 = 0).  c_f32 != 0: C and R are fp32, else C is bf16 and R must be NULL.
- * lda/ldb/lda2/ldb2/ldc are row strides in elements; K, K2, lda, ldb, lda2, ldb2 multiples of 8. */
+ * lda/ldb/lda2/ldb2/ldc are row strides in elements; K, K2, lda, ldb, lda2, ldb2 multiples of 8.
+ * Tile shape, contraction split and (for many-tile shapes whose last round of workgroups would be poorly filled)
+ * a split into two launches over two column ranges are chosen as in the update path. */
 tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t* B, int32_t ldb, int32_t M, int32_t N,
                        int32_t K, const uint16_t* A2, int32_t lda2, const uint16_t* B2, int32_t ldb2, int32_t K2,
                        float alpha, const float* R, void* C, int32_t ldc, int32_t c_f32, void* hip_stream);
