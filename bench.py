@@ -31,9 +31,10 @@ GEMV_HBM_BYTES_PER_LAUNCH = 104.1e6
 
 
 def cpu_baseline(shape, T, seed):
-    """The fp64 oracle as it stands, timed on this host: layer 0 of the 7B shape (forward + backward of one
-    layer, all 32 are identical in cost) and the embedding / final norm / lm_head / cross-entropy part, each
-    once.  Reported as trained tokens/s of the whole update = T / (n_layers * t_layer + t_head)."""
+    """The fp64 oracle as it stands, timed on this host on a bounded sample of the same update: the embedding gather,
+    layer 0 of the 7B shape (forward + backward + the AdamW step of its 14 factors; all 32 layers cost the same), and
+    the final norm / lm_head / cross-entropy part, each once.  Reported as trained tokens/s of the whole update
+    = T / (t_gather + n_layers * (t_layer + t_adamw) + t_head)."""
     import numpy as np
     from oracle import templora_oracle as O
     from paper_2401_11504_amd import synth
@@ -44,15 +45,26 @@ def cpu_baseline(shape, T, seed):
         cores = os.cpu_count() or 1
     W = synth.layer_weights(seed, shape, 0)
     facs = synth.lora_factors(seed, shape, 0)
-    h = synth.hidden(seed, T, shape.d_model)
+    emb = synth.embedding(seed, shape)
+    tok = synth.uniform_tokens(seed, T, shape.vocab)
+    t0 = time.perf_counter()
+    h = np.asarray(emb, dtype=np.float64)[tok]                     # the oracle's gather (model_fwd_bwd, first line)
+    t_gather = time.perf_counter() - t0
+    del emb
     dy = synth.upstream_grad(seed, T, shape.d_model)
     t0 = time.perf_counter()
     _, cache = O.layer_fwd(h, W, facs, shape)
-    O.layer_bwd(dy, cache, W, facs, shape)
+    _, G = O.layer_bwd(dy, cache, W, facs, shape)
     t_layer = time.perf_counter() - t0
     del cache, W
+    t0 = time.perf_counter()
+    for p in O.PROJ:
+        for i in range(2):
+            z = np.zeros_like(np.asarray(facs[p][i], dtype=np.float64))
+            O.adamw_step(facs[p][i], G[p][i], z, z, 1, 5e-5)
+    t_adamw = time.perf_counter() - t0
+    del G
     head = synth.lm_head(seed, shape)
-    tok = synth.uniform_tokens(seed, T, shape.vocab)
     t0 = time.perf_counter()
     labels, mask, _ = O.labels_and_mask(tok, 0)
     hf = O.rmsnorm_fwd(h, np.ones(shape.d_model), shape.rms_eps)
@@ -61,45 +73,53 @@ def cpu_baseline(shape, T, seed):
     dhf = dlogits @ head.astype(np.float64)
     O.rmsnorm_bwd(dhf, h, np.ones(shape.d_model), shape.rms_eps)
     t_head = time.perf_counter() - t0
-    total = shape.n_layers * t_layer + t_head
+    total = t_gather + shape.n_layers * (t_layer + t_adamw) + t_head
     return {"value": T / total, "unit": "trained tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 oracle: layer 0 fwd+bwd timed once ({t_layer:.2f} s, x{shape.n_layers} layers) + "
-                      f"final norm/lm_head/CE fwd+bwd timed once ({t_head:.2f} s); AdamW not included"}
+            "sample": f"fp64 oracle: embedding gather ({t_gather:.3f} s) + layer 0 fwd+bwd ({t_layer:.2f} s) and its AdamW "
+                      f"step ({t_adamw:.2f} s), each timed once and counted x{shape.n_layers} layers + final "
+                      f"norm/lm_head/CE fwd+bwd timed once ({t_head:.2f} s)"}
 
 
-def stream_probe(torch, api):
-    """The operand streams of the frozen-weight GEMM with no arithmetic (tl_probe_operand_stream), at the shapes of the
-    update's N = 4096 GEMMs with 128x128 tiles: what the loads alone cost, with the weights in the last-level cache
-    ("warm": the same matrix every launch) and coming from HBM ("cold": launches rotate over copies that together
-    exceed the 256 MB cache, as consecutive layers do in the update).  Prints one JSON line per case."""
-    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    A = torch.ones(1 << 26, dtype=torch.float32, device="cuda")     # 256 MiB of activations-to-be
-    B = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB of weight copies
-    tiles_m, tiles_n = 8, 32                                        # M = 1024, N = 4096
-    for name, K in (("o (K 4096)", 4096), ("down (K 11008)", 11008), ("dx_gate|up (K 22016)", 22016)):
-        ld = kb = 2 * K
-        bsz = tiles_n * 128 * ld
-        copies = (B.numel() * 4) // bsz
-        for mode in ("warm", "cold"):
-            for steps in (1, 2, 3, 4, 8):
-                sel = (lambda i: 0) if mode == "warm" else (lambda i: i % copies)
-                reps = 24
-                for i in range(3):
-                    api.tl_probe_operand_stream(A.data_ptr(), B.data_ptr() + sel(i) * bsz, ld, kb, tiles_m, tiles_n, steps, sink)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for i in range(reps):
-                    api.tl_probe_operand_stream(A.data_ptr(), B.data_ptr() + sel(i + 3) * bsz, ld, kb, tiles_m, tiles_n, steps, sink)
-                e1.record()
-                torch.cuda.synchronize()
-                us = e0.elapsed_time(e1) * 1e3 / reps
-                req = 256.0 * kb * tiles_m * tiles_n                # bytes requested by all workgroups per launch
-                print(json.dumps({"streams_of": name, "weights": mode, "weight_copies": copies if mode == "cold" else 1,
-                                  "steps_in_flight": steps, "us_per_launch": round(us, 1),
-                                  "requested_TB_per_s": round(req / us / 1e6, 2),
-                                  "GB_per_s_per_CU": round(req / us / 1e3 / 256, 1),
-                                  "weight_TB_per_s": round(bsz / us / 1e6, 2)}), flush=True)
+def stream_bench(args, torch, api, harness, synth):
+    """configs[4]: a long synthetic input consumed as sequential 1024-token chunks, two epochs of updates per chunk,
+    the module (and its AdamW state) carried from chunk to chunk and discarded at the end.  Sustained trained
+    tokens/s = epochs * chunks * 1024 / total time, host-side token hand-over included."""
+    shape = synth.SHAPES["7b"].with_layers(args.layers)
+    seed, T, chunks, epochs, lr = 5000, 1024, args.stream, 2, 5e-5
+    model = harness.Model(shape, seed, max_tokens=T, keep_host=False, device_random=True)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    stream = synth.zipf_tokens(seed, chunks * T, shape.vocab)
+    warm = synth.zipf_tokens(seed + 1, T, shape.vocab)
+    for _ in range(2):
+        api.tl_chunk_update(lora, warm, 0, lr)
+    api.tl_discard(lora)                               # the warm-up module is thrown away: the stream starts from k = 0
+    api.tl_lora_free(lora)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    torch.cuda.synchronize()
+    losses = []
+    t0 = time.perf_counter()
+    for c in range(chunks):
+        tok = stream[c * T:(c + 1) * T]
+        for _ in range(epochs):
+            loss, _ = api.tl_chunk_update(lora, tok, 0, lr)
+            losses.append(loss)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    steps = int(api.tl_get_step(lora))
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
+    n = chunks * epochs
+    second_lower = sum(1 for c in range(chunks) if losses[2 * c + 1] < losses[2 * c])
+    print(json.dumps({
+        "metric": "sustained trained tokens/sec over a stream of Temp-Lora chunk updates (7B-shape, r=64)",
+        "value": round(n * T / dt, 1), "unit": "trained tokens/s", "n_gpus": 1, "steps": n, "warmup": 2,
+        "ms_per_step": round(dt / n * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"DEBUG (not the headline metric): configs[4] shape, {chunks} sequential 1024-token chunks of a "
+                               f"Zipf(1.1) stream x {epochs} epochs, state carried, discarded at the end",
+                   "n_layers": args.layers, "optimizer_steps": steps, "first_loss": round(float(losses[0]), 5),
+                   "last_loss": round(float(losses[-1]), 5), "chunks_whose_second_epoch_loss_is_lower": second_lower}}))
 
 
 def generate_bench(args, torch, api, harness, synth):
@@ -201,8 +221,9 @@ def main():
                     help="debug only: the first CTX of --tokens are conditioning (L_T prefix, no loss on them)")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="debug only: LoRA dropout rate (the benchmark configuration has none; marks the line)")
-    ap.add_argument("--stream-probe", action="store_true",
-                    help="only run the GEMM operand-stream probe (loads without arithmetic) and exit")
+    ap.add_argument("--stream", type=int, default=0, metavar="CHUNKS",
+                    help="measure the long-input workload instead (configs[4]): CHUNKS sequential 1024-token chunks of a "
+                         "Zipf(1.1) token stream, two epochs each, module state carried, discarded at the end")
     ap.add_argument("--generate", type=int, default=0, metavar="CHUNKS",
                     help="measure Algorithm 1 end to end instead: generate CHUNKS chunks of 1024 tokens with tl_generate")
     ap.add_argument("--decode", action="store_true",
@@ -235,8 +256,8 @@ def main():
         return
     from paper_2401_11504_amd import api, harness, synth
 
-    if args.stream_probe:
-        stream_probe(torch, api)
+    if args.stream > 0:
+        stream_bench(args, torch, api, harness, synth)
         return
     if args.generate > 0:
         generate_bench(args, torch, api, harness, synth)
@@ -254,14 +275,18 @@ def main():
     tok = synth.uniform_tokens(seed, T, shape.vocab)
     lr = 5e-5
 
-    loss = None
+    loss = first_loss = None
     for _ in range(args.warmup):
         loss, n_targets = api.tl_chunk_update(lora, tok, args.ctx, lr)
+        if first_loss is None:
+            first_loss = loss                    # the module's very first step: B = 0, so this is the base model's loss
     # timed region 1: exactly K steps, nothing but the update on the GPU -> `value`
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         loss, n_targets = api.tl_chunk_update(lora, tok, args.ctx, lr)
+        if first_loss is None:
+            first_loss = loss
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # timed region 2: K more steps with every launch of the dominant kernel bracketed by HIP events on the
@@ -282,6 +307,7 @@ def main():
         roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": GEMM_NT_HBM_BYTES_PER_LAUNCH if headline else None,
+                "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes recorded in profiles/ (not measured in this run)",
                 "kernel": "gemm_nt_dl_kernel (frozen W GEMM + low-rank K-extension; all tile shapes)",
                 "launches_per_step": launches // max(args.steps, 1),
                 "avg_launch_us": round(ms * 1e3 / max(launches, 1), 2),
@@ -314,8 +340,8 @@ def main():
                                "one 1024-token chunk, AdamW lr 5e-5" if headline else
                                f"DEBUG (not the benchmark): {args.layers} layers, {T} tokens of which {args.ctx} conditioning, "
                                f"dropout {args.dropout}",
-                   "n_tokens": T, "n_layers": args.layers, "rank": r, "loss": round(float(loss), 5),
-                   "n_targets": n_targets},
+                   "n_tokens": T, "n_layers": args.layers, "rank": r, "first_step_loss": round(float(first_loss), 5),
+                   "loss_after_all_steps_on_the_same_chunk": round(float(loss), 5), "n_targets": n_targets},
         "mfma_util_whole_update": round(total_flop / (ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
         "algorithmic_tflop_per_step": round(total_flop / 1e12, 3),
         "roofline": roof,

@@ -2,8 +2,9 @@
  * templora.h -- C ABI of the MI355X (gfx950) Temp-Lora chunk-update library.
  *
  * The library implements the inference-time training step of Temp-Lora
- * (arXiv 2401.11504): Algorithm 1's "Train Theta_k: In X_T -> Out Chunk_k"
- * line, i.e. one forward + backward pass of a chunk of tokens through a frozen
+ * (arXiv 2401.11504): the training line of Algorithm 1 (the module Theta_k is
+ * trained to produce the newest chunk from the tokens before it), i.e. one
+ * forward + backward pass of a chunk of tokens through a frozen
  * Llama2-style decoder (Section 3, "Baselines") whose q, k, v, o, gate, up and
  * down projections carry a temporary LoRA module (Section 2; rank / alpha from
  * Section 3, "Setup"), followed by one AdamW step on the LoRA factors only.
@@ -46,7 +47,7 @@ typedef enum {
     TL_ERR_SHAPE = -2,       /* unsupported dimensions (see tl_model_cfg) */
     TL_ERR_TOKEN_RANGE = -3, /* a token id is < 0 or >= vocab */
     TL_ERR_WINDOW = -4,      /* n_tokens > max_tokens, n_tokens < 2 or n_ctx >= n_tokens */
-    TL_ERR_NONFINITE = -5,   /* the loss came out NaN/Inf; the optimizer step was skipped */
+    TL_ERR_NONFINITE = -5,   /* the loss (or a LoRA gradient) came out NaN/Inf; see tl_chunk_update */
     TL_ERR_DEVICE = -6,      /* HIP error, or no gfx950 device */
     TL_ERR_DISCARDED = -7,   /* the module was already discarded */
     TL_ERR_OOM = -8          /* device allocation failed */
@@ -118,7 +119,7 @@ tl_status tl_model_create(const tl_model_cfg* cfg, const void* const* weight_ptr
 tl_status tl_model_destroy(tl_model* model);
 
 /*
- * Create the temporary module (Algorithm 1: "Temp-Lora ID k <- 0").  Allocates
+ * Create the temporary module (Algorithm 1's initialisation: the module counter k starts at 0).  Allocates
  * A, B, gradients, moments, bf16 shadows and all activation workspaces for
  * max_tokens tokens.  A is drawn N(0, a_init_std^2), B = 0, moments 0, step 0.
  * Errors: TL_ERR_ARG, TL_ERR_SHAPE (rank), TL_ERR_OOM, TL_ERR_DEVICE.
@@ -135,11 +136,16 @@ tl_status tl_lora_init(tl_model* model, const tl_lora_cfg* cfg, tl_lora** out);
  *   loss_out : host, mean negative log-likelihood over the *n_targets_out target
  *              positions (so perplexity = exp(loss)).
  *   lr       : AdamW learning rate of this step.
- * On success the step counter advances and A, B, moments are updated.  On any
- * error found before the backward pass (bad token id, window violation,
- * non-finite loss) the module state is left exactly as it was; a device error
- * during the backward pass (TL_ERR_DEVICE) leaves it undefined, because the
- * optimizer step of a layer is applied as soon as its gradients are complete.
+ * On success the step counter advances and A, B, moments are updated.  A bad
+ * token id, a window violation or a non-finite loss (TL_ERR_NONFINITE) leave the
+ * module state exactly as it was: the loss kernel leaves its verdict in device
+ * memory and every optimizer launch of the call reads it before it writes.  The
+ * optimizer step of a layer is applied as soon as that layer's gradients are
+ * complete, while the layers below are still in their backward pass; so a
+ * gradient entry that is not finite although the loss was (TL_ERR_NONFINITE as
+ * well: the step of the layer it appeared in and of every layer below is
+ * skipped, the step counter does not advance) and a device error during the
+ * backward pass (TL_ERR_DEVICE) leave the layers above already stepped.
  */
 tl_status tl_chunk_update(tl_lora* lora, const int32_t* tokens, int32_t n_tokens, int32_t n_ctx, float lr,
                           float* loss_out, int32_t* n_targets_out);
@@ -278,15 +284,6 @@ tl_status tl_keep_input_grad(tl_lora* lora, int32_t on);
 tl_status tl_profile_enable(tl_lora* lora, int32_t on);
 tl_status tl_profile_read(tl_lora* lora, double* ms_total, int64_t* launches, double* flop_total);
 
-/* The operand streams of the frozen-weight GEMM without its arithmetic (a ceiling for that kernel's loads): one
- * workgroup per 128x128 output tile pulls 128 rows of A (device, tiles_m * 128 rows) and 128 rows of B (device,
- * tiles_n * 128 rows), the first k_bytes (a multiple of 128) of every row, rows ld_bytes apart (a multiple of 16;
- * each matrix below 4 GiB), 128 bytes per row and step, steps_in_flight (1, 2, 3, 4, 6 or 8) steps ahead, into LDS,
- * and discards them.  sink: one device uint32 (never written in practice).  Nothing is synchronised: time it with
- * events on hip_stream.  Errors: TL_ERR_ARG (null pointer, geometry), TL_ERR_DEVICE. */
-tl_status tl_probe_operand_stream(const void* A, const void* B, uint32_t ld_bytes, uint32_t k_bytes, int32_t tiles_m,
-                                  int32_t tiles_n, int32_t steps_in_flight, uint32_t* sink, void* hip_stream);
-
 /*
  * One decoder layer alone: forward from a given hidden state, backward from a
  * given upstream gradient, gradients of that layer's 7 LoRA pairs, and
@@ -319,10 +316,20 @@ tl_status tl_linear_step(const float* X, const float* W, const float* A, const f
  * A2/B2 may be NULL (K2 = 0).  c_f32 != 0: C and R are fp32, else C is bf16 and R must be NULL.
  * lda/ldb/lda2/ldb2/ldc are row strides in elements; K, K2, lda, ldb, lda2, ldb2 multiples of 8.
  * Tile shape, contraction split and (for many-tile shapes whose last round of workgroups would be poorly filled)
- * a split into two launches over two column ranges are chosen as in the update path. */
+ * a split into two launches over two column ranges are chosen as in the update path.
+ * workspace: NULL, or device fp32 scratch of workspace_elems floats for the partial results of a split contraction
+ * (without it no shape is split; a split of s ways uses s * M * N floats; contents are undefined afterwards). */
 tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t* B, int32_t ldb, int32_t M, int32_t N,
                        int32_t K, const uint16_t* A2, int32_t lda2, const uint16_t* B2, int32_t ldb2, int32_t K2,
-                       float alpha, const float* R, void* C, int32_t ldc, int32_t c_f32, void* hip_stream);
+                       float alpha, const float* R, void* C, int32_t ldc, int32_t c_f32, float* workspace,
+                       size_t workspace_elems, void* hip_stream);
+/* Which tile configuration tl_k_gemm_nt uses for dense operands of these sizes with a workspace of workspace_elems
+ * floats (0 = none): its name ("128x128", "256x128", "256x128-split", "256x192", "256x256", "reg-128x128",
+ * "reg-128x64", "64x64", "64x64-split", "reg-64x64", "reg-64x64-split") into name_out (host, name_cap bytes), the
+ * contraction split and the number of launches (2 = two column ranges; the name is then the first range's).  Host
+ * only, nothing is launched: the kernel tests use it to show that their shapes reach every configuration. */
+tl_status tl_k_gemm_nt_plan(int32_t M, int32_t N, int32_t K, int32_t K2, size_t workspace_elems, char* name_out,
+                            size_t name_cap, int32_t* n_split_out, int32_t* n_launches_out);
 
 /* C[Mo,No] (fp32) = alpha * P[T,Mo]^T Q[T,No]  (contraction over the token dimension; dA and dB). */
 tl_status tl_k_gemm_tn(const uint16_t* P, int32_t ldp, const uint16_t* Q, int32_t ldq, int32_t T, int32_t Mo,

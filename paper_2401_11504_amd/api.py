@@ -82,7 +82,9 @@ _SIGS = {
     "tl_profile_read": [_vp, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)],
     "tl_layer_step": [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _i32],
     "tl_linear_step": [_vp] * 5 + [_i32] * 4 + [_f32] * 6 + [_i32] + [_vp] * 6 + [_vp],
-    "tl_k_gemm_nt": [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _i32, _vp],
+    "tl_k_gemm_nt": [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _i32, _vp,
+                     _sz, _vp],
+    "tl_k_gemm_nt_plan": [_i32, _i32, _i32, _i32, _sz, C.c_char_p, _sz, C.POINTER(_i32), C.POINTER(_i32)],
     "tl_k_gemm_tn": [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _f32, _vp, _i32, _vp],
     "tl_k_rmsnorm_fwd": [_vp, _vp, _i32, _i32, _f32, _vp, _vp],
     "tl_k_rmsnorm_bwd": [_vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp],
@@ -91,7 +93,6 @@ _SIGS = {
     "tl_k_swiglu_fwd": [_vp, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_bwd": [_vp, _vp, _i32, _i32, _vp, _vp],
     "tl_k_gemv": [_vp, _i32, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _vp],
-    "tl_probe_operand_stream": [_vp, _vp, C.c_uint32, C.c_uint32, _i32, _i32, _i32, _vp, _vp],
     "tl_k_gemv_pre": [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _f32, _vp, _vp, _vp, _vp],
     "tl_k_attention_decode": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _sz, _vp],
     "tl_k_argmax": [_vp, _i32, _vp, _vp],
@@ -311,13 +312,22 @@ def _s(stream):
     return stream if stream is not None else current_stream_handle()
 
 
-def tl_k_gemm_nt(A, B, C_out, A2=None, B2=None, alpha=1.0, R=None, stream=None):
+def tl_k_gemm_nt(A, B, C_out, A2=None, B2=None, alpha=1.0, R=None, workspace=None, stream=None):
     M, K = A.shape
     N = B.shape[0]
     K2 = A2.shape[1] if A2 is not None else 0
     _chk(_lib.tl_k_gemm_nt(_dp(A), A.stride(0), _dp(B), B.stride(0), M, N, K, _dp(A2),
                            A2.stride(0) if A2 is not None else 0, _dp(B2), B2.stride(0) if B2 is not None else 0, K2,
-                           alpha, _dp(R), _dp(C_out), C_out.stride(0), int(C_out.dtype == torch.float32), _s(stream)))
+                           alpha, _dp(R), _dp(C_out), C_out.stride(0), int(C_out.dtype == torch.float32),
+                           _dp(workspace), workspace.numel() if workspace is not None else 0, _s(stream)))
+
+
+def tl_k_gemm_nt_plan(M, N, K, K2=0, workspace_elems=0):
+    """-> (configuration name, contraction split, launches)"""
+    buf = C.create_string_buffer(32)
+    sp, nl = _i32(0), _i32(0)
+    _chk(_lib.tl_k_gemm_nt_plan(M, N, K, K2, workspace_elems, buf, 32, C.byref(sp), C.byref(nl)))
+    return buf.value.decode(), sp.value, nl.value
 
 
 def tl_k_gemm_tn(P, Q, C_out, alpha=1.0, stream=None):
@@ -357,12 +367,6 @@ def tl_k_gemv(W, x, y, lora_b=None, lora_h=None, rows_per_group=0, alpha=1.0, re
     r = lora_b.shape[1] if lora_b is not None else 0
     _chk(_lib.tl_k_gemv(_dp(W), W.stride(0), _dp(x), N, K, _dp(lora_b), _dp(lora_h), r, rows_per_group, alpha, _dp(resid),
                         _dp(y), int(y.dtype == torch.float32), _s(stream)))
-
-
-def tl_probe_operand_stream(A_ptr, B_ptr, ld_bytes, k_bytes, tiles_m, tiles_n, steps_in_flight, sink, stream=None):
-    """A_ptr, B_ptr: device addresses (int); sink: device int32 tensor."""
-    _chk(_lib.tl_probe_operand_stream(A_ptr, B_ptr, ld_bytes, k_bytes, tiles_m, tiles_n, steps_in_flight, _dp(sink),
-                                      _s(stream)))
 
 
 def tl_k_gemv_pre(W, y, mode, h=None, gain=None, eps=0.0, gu=None, x_out=None, stream=None):

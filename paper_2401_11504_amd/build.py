@@ -15,14 +15,11 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libtemplora.so")
-SOURCES = ["templora.hip", "gemm_bf16.hip", "gemm_f32.hip", "attention.hip", "elementwise.hip", "decode.hip", "stream_probe.hip"]
+SOURCES = ["templora.hip", "gemm_bf16.hip", "gemm_f32.hip", "attention.hip", "elementwise.hip", "decode.hip"]
 # packed-fp32 VALU forms are switched off for device code on purpose: the compiler otherwise emits v_pk_*_f32
 # forms that have been seen to give wrong results on these machines
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option"]
-FLAGS += os.environ.get("TL_EXTRA_HIPCC_FLAGS", "").split()  # tuning builds, e.g. -DATTN_NW=4
-if os.environ.get("TL_GEMM_ABLATE"):  # tuning builds only: kernels with loads / MFMAs / LDS reads removed
-    FLAGS.append("-DTL_GEMM_ABLATE")
 
 
 def _hipcc() -> str:

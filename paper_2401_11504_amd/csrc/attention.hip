@@ -391,17 +391,6 @@ __device__ __forceinline__ void attn_dq_block(
     }
 }
 
-template <int DH, int NW, int KG>
-__global__ __launch_bounds__(NW * 64 * KG) void attn_bwd_dq_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
-    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, float* __restrict__ delta, long ldq, long ldo, int T,
-    bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope) {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;   // see attn_fwd_kernel
-    const int qb = mirror ? (int)blockIdx.x : (int)(gridDim.x - 1 - blockIdx.x);
-    attn_dq_block<DH, NW, KG>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, scale, rope, qb, blockIdx.y, smem_raw);
-}
-
 // ======================================================================== backward: dK, dV
 template <int DH, int NW>
 __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
@@ -517,22 +506,6 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
     }
 }
 
-template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ q,
-                                                               const bf16_t* __restrict__ k,
-                                                               const bf16_t* __restrict__ v,
-                                                               const bf16_t* __restrict__ d_o,
-                                                               const float* __restrict__ lse,
-                                                               const float* __restrict__ delta, long ldq, long ldo,
-                                                               int T, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv,
-                                                               float scale, const float2* __restrict__ rope) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    // early key blocks see the most queries and are scheduled first; second half of the grid mirrored (see attn_fwd_kernel)
-    const bool mirror = 2 * blockIdx.y >= gridDim.y + 1;
-    const int kb = mirror ? (int)(gridDim.x - 1 - blockIdx.x) : (int)blockIdx.x;
-    attn_dkv_block<DH, NW>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope, kb, blockIdx.y, smem);
-}
-
 // ======================================================================== backward: both in one launch
 // Every workgroup does ONE part -- the dK/dV of a key block (all query blocks from it on) or the dQ of a query block (all
 // key blocks up to it) -- and the parts are handed out longest first: level j of the grid holds the dK/dV part of key
@@ -612,44 +585,26 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restric
     if (live && sub == 0) delta[(long)head * T + t] = dot;
 }
 
-// fused: delta from its own small kernel, then one launch that holds every dK/dV and every dQ part, longest first.
-// Otherwise (tuning aid): the dQ kernel, which also writes delta, then the dK/dV kernel.
+// delta from its own small kernel, then one launch that holds every dK/dV and every dQ part, longest first.
 template <int DH>
 static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                           const float* lse, float* delta, long ldq, long ldo, int T, int n_heads, bf16_t* dq, bf16_t* dk,
-                          bf16_t* dv, const float2* rope, hipStream_t s, bool fused) {
+                          bf16_t* dv, const float2* rope, hipStream_t s) {
     using C = AttnCfg<DH>;
-    constexpr int NW = ATTN_NW, KG = ATTN_KG;
+    constexpr int NW = ATTN_NW;
     const float scale = 1.f / sqrtf((float)DH);
-    dim3 grid(cdiv(T, NW * 32), n_heads);
+    dim3 grid(cdiv(T, NW * 32), n_heads, 2);
     const size_t lds_kv = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
-    if (fused) {
-        const long items = (long)T * n_heads * (DH / 8);
-        attn_delta_kernel<DH><<<cdiv(items, 256), 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        const size_t lds_q = (size_t)(2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
-        const size_t lds = lds_q > lds_kv ? lds_q : lds_kv;
-        auto kern = attn_bwd_fused_kernel<DH, NW>;
-        e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        grid.z = 2;
-        kern<<<grid, NW * 64, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, dk, dv, scale, rope);
-        return hipGetLastError();
-    }
-    {
-        size_t lds = (size_t)KG * (2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
-        const size_t merge = KG > 1 ? (size_t)NW * 64 * (C::ND * 16) * sizeof(float) : 0;
-        if (merge > lds) lds = merge;
-        auto kern = attn_bwd_dq_kernel<DH, NW, KG>;
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        kern<<<grid, NW * 64 * KG, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, scale, rope);
-    }
-    auto kern = attn_bwd_dkv_kernel<DH, NW>;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_kv);
+    const long items = (long)T * n_heads * (DH / 8);
+    attn_delta_kernel<DH><<<cdiv(items, 256), 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    kern<<<grid, NW * 64, lds_kv, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope);
+    const size_t lds_q = (size_t)(2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
+    const size_t lds = lds_q > lds_kv ? lds_q : lds_kv;
+    auto kern = attn_bwd_fused_kernel<DH, NW>;
+    e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, NW * 64, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, dk, dv, scale, rope);
     return hipGetLastError();
 }
 
@@ -658,10 +613,10 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
 // dk come out as gradients with respect to the UNROTATED projections.
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
-                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s, bool fused) {
+                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s) {
     if (T <= 0 || n_heads <= 0) return hipSuccess;
     if ((ldq & 7) || (ldo & 7)) return hipErrorInvalidValue;
-    if (d_head == 128) return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, fused);
-    if (d_head == 64) return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s, fused);
+    if (d_head == 128) return run_bwd<128>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s);
+    if (d_head == 64) return run_bwd<64>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, n_heads, dq, dk, dv, rope, s);
     return hipErrorInvalidValue;
 }

@@ -365,18 +365,24 @@ __global__ __launch_bounds__(512) void cross_entropy_kernel(const float* __restr
         }
     }
 }
-// deterministic sum of nll over the call's positions (one block)
-__global__ __launch_bounds__(256) void nll_sum_kernel(const float* __restrict__ nll, int T, float* __restrict__ out) {
+// deterministic sum of nll over the call's positions (one block); flag (may be null) receives 0 if the sum is finite,
+// 1 otherwise: the optimizer launches of the same update read it and leave the module untouched when it is set
+__global__ __launch_bounds__(256) void nll_sum_kernel(const float* __restrict__ nll, int T, float* __restrict__ out,
+                                                      int* __restrict__ flag) {
     __shared__ float red[16];
     float s = 0.f;
     for (int i = threadIdx.x; i < T; i += blockDim.x) s += nll[i];
     s = block_sum(s, red);
-    if (threadIdx.x == 0) out[0] = s;
+    if (threadIdx.x == 0) {
+        out[0] = s;
+        if (flag) flag[0] = isfinite(s) ? 0 : 1;
+    }
 }
 // row0: rows below it are conditioning positions the caller knows carry no loss: their nll is set to 0 and their
 // logits / dlogits rows are neither read nor written (the caller does not compute or use them).
 hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, int V, int first_target,
-                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s, int row0) {
+                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s, int row0,
+                                int* flag) {
     if (T <= 0) return hipSuccess;
     if (row0 < 0 || row0 > first_target || row0 >= T) return hipErrorInvalidValue;
     if (row0 > 0) {
@@ -385,7 +391,7 @@ hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, i
     }
     cross_entropy_kernel<<<T - row0, 512, 0, s>>>(logits, labels, T, V, first_target, 1.f / (float)n_targets, nll, dlogits,
                                                   row0);
-    if (loss_sum) nll_sum_kernel<<<1, 256, 0, s>>>(nll, T, loss_sum);
+    if (loss_sum) nll_sum_kernel<<<1, 256, 0, s>>>(nll, T, loss_sum, flag);
     return hipGetLastError();
 }
 
@@ -395,7 +401,8 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ p, const
                                                     float* __restrict__ m, float* __restrict__ v,
                                                     bf16_t* __restrict__ shadow, size_t n4, size_t n, float lr,
                                                     float b1, float b2, float eps, float decay, float inv_bc1,
-                                                    float inv_bc2) {
+                                                    float inv_bc2, const int* __restrict__ skip_flag) {
+    if (skip_flag && *skip_flag != 0) return;   // the update was found invalid (non-finite loss or gradient): change nothing
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     // two independent groups of four per trip: eight 16-byte loads are in flight before the first one is used
     for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < n4; i0 += 2 * stride) {
@@ -445,7 +452,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ p, const
     }
 }
 hipError_t launch_adamw(float* p, const float* g, float* m, float* v, bf16_t* shadow, size_t n, long step, float lr,
-                        float beta1, float beta2, float eps, float wd, hipStream_t s) {
+                        float beta1, float beta2, float eps, float wd, hipStream_t s, const int* skip_flag) {
     if (n == 0) return hipSuccess;
     const double bc1 = 1.0 - pow((double)beta1, (double)step);
     const double bc2 = 1.0 - pow((double)beta2, (double)step);
@@ -454,7 +461,7 @@ hipError_t launch_adamw(float* p, const float* g, float* m, float* v, bf16_t* sh
     if (blocks > 256 * 16) blocks = 256 * 16;
     if (blocks < 1) blocks = 1;
     adamw_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, g, m, v, shadow, n4, n, lr, beta1, beta2, eps, 1.f - lr * wd,
-                                                  (float)(1.0 / bc1), (float)(1.0 / bc2));
+                                                  (float)(1.0 / bc1), (float)(1.0 / bc2), skip_flag);
     return hipGetLastError();
 }
 
@@ -473,6 +480,20 @@ hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream
 __global__ void fill_f32_kernel(float* __restrict__ p, size_t n, float v) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+// n bf16 zeros (n a multiple of 2, p 4-byte aligned): a fill kernel rather than a memset node, so that the path stays
+// capturable in a HIP graph
+__global__ void zero_u32_kernel(uint32_t* __restrict__ p, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+hipError_t launch_fill_bf16_zero(bf16_t* p, size_t n, hipStream_t s) {
+    if (n == 0) return hipSuccess;
+    if ((n & 1) || ((size_t)p & 3)) return hipErrorInvalidValue;
+    size_t blocks = (n / 2 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    zero_u32_kernel<<<(unsigned)blocks, 256, 0, s>>>((uint32_t*)p, n / 2);
+    return hipGetLastError();
 }
 hipError_t launch_fill_f32(float* p, size_t n, float value, hipStream_t s) {
     if (n == 0) return hipSuccess;

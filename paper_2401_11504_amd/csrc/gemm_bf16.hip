@@ -13,7 +13,6 @@
 // reads of 8 consecutive rows fall into distinct banks.
 #include "kernels.h"
 #include "tiles.h"
-#include <cstdlib>
 #include <type_traits>
 
 // ======================================================================== NT
@@ -165,15 +164,16 @@ __global__ void splitk_reduce_kernel(GemmNT p, int split_k);
 // positions in the even rows and 8 in the odd rows: that is what the (r / 2) term gives.
 // Rows beyond M / N are clamped to the last valid row: they only feed outputs that are never stored.
 __device__ __forceinline__ void load_lds16(unsigned voff, const void* sbase, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr) : "memory");
+    // M0 carries the LDS destination: bound as a physical-register operand, so the compiler sets it and knows it is used
+    asm volatile("global_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "{m0}"(lds_addr) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, int PIPE = 0>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n, int xcd_split) {
+template <int BM, int BN, int WM, int WN, int STAGES, int BKT = 64, bool SPLITK = false, int PIPE = 0>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
     constexpr int NT = WM * WN * 64;
     constexpr int ROWS = BM + BN;
     constexpr int CPRW = BKT / 8;             // 16-byte chunks per tile row
@@ -202,11 +202,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     const int n_split = SPLITK ? (int)gridDim.y : 1;
     int pid = blockIdx.x, split = SPLITK ? (int)blockIdx.y : 0;
     const int xs = 8 / max(n_split, 1);   // XCDs per split
-    if (SPLITK && xcd_split && gridDim.z == 1 && (n_split == 2 || n_split == 4 || n_split == 8) && ntiles % xs == 0) {
+    if (SPLITK && gridDim.z == 1 && (n_split == 2 || n_split == 4 || n_split == 8) && ntiles % xs == 0) {
         const int id = blockIdx.y * gridDim.x + blockIdx.x, c = id & 7, j = id >> 3;
         split = c / xs;
         pid = (c % xs) * (ntiles / xs) + j;
-    } else if (xcd_split != 2 || (ntiles & 7) == 0) {   // (2: tuning aid, plain round-robin for ragged tile counts)
+    } else {
         pid = xcd_contiguous(pid, ntiles);
     }
     const int tile_m = pid % tiles_m, tile_n = pid / tiles_m;
@@ -291,9 +291,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             const int cur = ks % NSETS, nxt = (ks + PD) % NSETS;
 #pragma unroll
             for (int e = 0; e < NMF; ++e) {
-                if constexpr (!(DBG & 2)) acc[e / FN][e % FN] = mfma32(fa[cur][e / FN], fb[cur][e % FN], acc[e / FN][e % FN]);
-                else asm volatile("" ::"v"(fa[cur][e / FN]), "v"(fb[cur][e % FN]));
-                if constexpr (READS && !(DBG & 4)) {
+                acc[e / FN][e % FN] = mfma32(fa[cur][e / FN], fb[cur][e % FN], acc[e / FN][e % FN]);
+                if constexpr (READS) {
                     // RPS reads per slot, in the order A0, B0..B(FN-1), A1..: what that k-step's first MFMAs need first
 #pragma unroll
                     for (int r = e * RPS; r < (e + 1) * RPS && r < NRD; ++r) {
@@ -302,7 +301,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
                         else fa[nxt][r - FN] = *(const bf16x8_t*)(a_ptr + rd_stage + (r - FN) * 32 * ROWB + coff[rd_ks]);
                     }
                 }
-                if constexpr (LOADS && !(DBG & 1)) {
+                if constexpr (LOADS) {
                     const int gs = ks * NMF + e;          // slot number within the tile
                     const int j = (gs * L + NSLOT - 1) / NSLOT;   // first load with j * NSLOT / L >= gs
                     if (j < L && j * NSLOT / L == gs) {
@@ -402,17 +401,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             for (int ks = 0; ks < KS; ++ks) {
                 const int cur = ks & 1, nxt = cur ^ 1;
                 if (ks < KS - 1) {
-                    if (!(DBG & 4)) read_frags(stg, ks + 1, fa[nxt], fb[nxt]);
+                    read_frags(stg, ks + 1, fa[nxt], fb[nxt]);
                 } else if (kt + 1 < nk) {
                     if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 3) * L>(); else wait_vmcnt<0>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
-                    if (kt + STAGES - 1 < nk && !(DBG & 1)) issue(kt + STAGES - 1);
-                    if (!(DBG & 4)) read_frags((kt + 1) % STAGES, 0, fa[nxt], fb[nxt]);
-                }
-                if (DBG & 2) {
-                    asm volatile("" ::"v"(fa[cur][0]), "v"(fb[cur][0]), "v"(fa[cur][FM - 1]), "v"(fb[cur][FN - 1]));
-                    continue;
+                    if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);
+                    read_frags((kt + 1) % STAGES, 0, fa[nxt], fb[nxt]);
                 }
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
@@ -429,26 +424,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
             if (kt + STAGES - 2 < nk) wait_vmcnt<(STAGES - 2) * L>(); else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            if (kt + STAGES - 1 < nk && !(DBG & 1)) issue(kt + STAGES - 1);   // into the buffer every wave finished reading last iteration
+            if (kt + STAGES - 1 < nk) issue(kt + STAGES - 1);   // into the buffer every wave finished reading last iteration
             const unsigned char* st = smem + (kt % STAGES) * STAGE_BYTES;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 bf16x8_t fa[FM], fb[FN];
-                if (!(DBG & 4)) {
 #pragma unroll
-                    for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * ROWB + coff[ks]);
+                for (int i = 0; i < FM; ++i) fa[i] = *(const bf16x8_t*)(st + a_row + i * 32 * ROWB + coff[ks]);
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * ROWB + coff[ks]);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < FM; ++i) for (int e = 0; e < 8; ++e) fa[i][e] = (__bf16)(float)(lane + ks);
-#pragma unroll
-                    for (int j = 0; j < FN; ++j) for (int e = 0; e < 8; ++e) fb[j][e] = (__bf16)(float)(lane - ks);
-                }
-                if (DBG & 2) {
-                    asm volatile("" ::"v"(fa[0]), "v"(fb[0]), "v"(fa[FM - 1]), "v"(fb[FN - 1]));
-                    continue;
-                }
+                for (int j = 0; j < FN; ++j) fb[j] = *(const bf16x8_t*)(st + b_row + j * 32 * ROWB + coff[ks]);
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -541,22 +525,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     }
 }
 
-template <int BM, int BN, int WM, int WN, int STAGES, int DBG = 0, int BKT = 64, bool SPLITK = false, int PIPE = 0>
+template <int BM, int BN, int WM, int WN, int STAGES, int BKT = 64, bool SPLITK = false, int PIPE = 0>
 static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     const int tiles_m = cdiv(g.M, BM), tiles_n = cdiv(g.N, BN);
     const size_t lds = (size_t)STAGES * (BM + BN) * BKT * 2;
     dim3 grid(tiles_m * tiles_n, SPLITK ? n_split : 1, g.batch);
-    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, PIPE>;
+    auto kern = gemm_nt_dl_kernel<BM, BN, WM, WN, STAGES, BKT, SPLITK, PIPE>;
     if constexpr (PIPE != 0) {  // the branch-free steady-state loop assumes every split has at least STAGES k-tiles
         const int nkt = g.K / BKT + g.K2 / BKT;
-        if (nkt / n_split < STAGES) return run_nt_dl<BM, BN, WM, WN, STAGES, DBG, BKT, SPLITK, 0>(g, s, n_split);
+        if (nkt / n_split < STAGES) return run_nt_dl<BM, BN, WM, WN, STAGES, BKT, SPLITK, 0>(g, s, n_split);
     }
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    static const int xcd_split = getenv("TL_GEMM_XCD_SPLIT") ? atoi(getenv("TL_GEMM_XCD_SPLIT")) : 1;   // tuning aid
     GemmNT gk = g;
     if (!(SPLITK && g.deferred && BM >= 256)) gk.partial_bf16 = 0;   // bf16 partial tiles only where the reduce is left to the consumer
-    kern<<<grid, WM * WN * 64, lds, s>>>(gk, tiles_m, tiles_n, xcd_split);
+    kern<<<grid, WM * WN * 64, lds, s>>>(gk, tiles_m, tiles_n);
     if (SPLITK) {
         if (g.deferred && BM >= 256) {    // wide-output instance: the consumer adds the partial tiles up
             *g.deferred = n_split;
@@ -631,8 +614,7 @@ static hipError_t run_nt(const GemmNT& g, int split_k, hipStream_t s) {
 // (gate|up at 1024 tokens: 688 tiles of 256x128 are 2.7 rounds and cost three; 256 tiles of 256x256 plus 176 of 256x128
 // cost 12.2 + 7.0 instead of 3 x 7.0 in the units of the tile model below).  Returns N1, or 0 for one launch.
 int gemm_nt_column_split(const GemmNT& g) {
-    static const bool off = getenv("TL_GEMM_NSPLIT") && atoi(getenv("TL_GEMM_NSPLIT")) == 0;   // tuning aid
-    if (off || getenv("TL_GEMM_TILE") || g.deferred || g.split_k > 1 || g.M <= 0 || g.N < 512 || g.batch <= 0) return 0;
+    if (g.deferred || g.split_k > 1 || g.M <= 0 || g.N < 512 || g.batch <= 0) return 0;
     if ((g.K % BK) || (g.K2 % BK) || g.K <= 0) return 0;
     const long tm = (long)cdiv(g.M, 256) * g.batch;
     if (tm > 256 || 256 % tm) return 0;                       // a round of 256x256 tiles must be whole tile columns
@@ -669,6 +651,106 @@ bool gemm_nt_split_columns(const GemmNT& g, GemmNT* a, GemmNT* b) {
     return true;
 }
 
+// The tile configurations the launcher can pick (every one is reachable from launch_gemm_nt; the kernel tests name the
+// shape that lands on each).
+enum NtConfig {
+    NT_128x128,         // 128x128 tiles, BK 64, four-stage ring, interleaved loop: a few hundred tiles in all
+    NT_256x128,         // 256x128 tiles, BK 64, three stages
+    NT_256x128_SPLIT,   // the same with the contraction split 2..4 ways (partials reduced afterwards or by the consumer)
+    NT_256x192,         // 256x192 tiles, BK 64, two stages: tile counts that 256x256 leaves a third of the CUs idle on
+    NT_256x256,         // 256x256 tiles, BK 32, four stages
+    NT_REG_128x128,     // register-staged fallbacks for contractions that are no multiple of 64 or operands beyond 1 Gi elements
+    NT_REG_128x64,
+    NT_SKINNY           // N <= 64 per batch or few tiles: 64x64 tiles, contraction split over up to 16 workgroups
+};
+
+// Measured on MI355X at M = 1024.  Every tile shape is limited by how fast a CU can pull operand bytes out of L2, so
+// the largest tile that still gives every CU work wins.
+static NtConfig choose_nt(const GemmNT& g, int* n_split) {
+    *n_split = 1;
+    const int nk = cdiv(g.K, BK) + cdiv(g.K2, BK);
+    const long t128 = (long)cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch;
+    const long t64n = (long)cdiv(g.M, 128) * cdiv(g.N, 64) * g.batch;
+    const bool dl_ok = (g.K % BK) == 0 && (g.K2 % BK) == 0 && g.K > 0 && g.N > 64 &&
+                       (long)g.M * g.lda < (1L << 30) && (long)g.N * g.ldb < (1L << 30) &&
+                       (long)g.M * g.lda2 < (1L << 30) && (long)g.N * g.ldb2 < (1L << 30);
+    auto rounds = [](long t) { return (double)((t + 255) / 256); };
+    if (dl_ok && t128 >= 128) {
+        const long t256 = (long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
+        const long t256x128 = (long)cdiv(g.M, 256) * cdiv(g.N, 128) * g.batch;
+        if (t256 < 160) {
+            // Few 256x256 tiles: pick among 128x128 tiles, 256x128 tiles, and 256x128 tiles with the contraction split
+            // 2..4 ways, by the operand bytes the busiest CU has to pull in (the loop is bound by that rate, about
+            // 53 GB/s per CU, not by the matrix pipe): rounds of tiles x (BM + BN) x K x 2 bytes.  A split adds one
+            // pass over its partials (written and read back at about 5 TB/s, plus a launch).  At M = 1024 this
+            // picks the two-way split from K of about 10k on (measured: K 11008 -7 %, 12288 -13 %, 22016 -17 %,
+            // 32000 -15 % against 128x128) and 128x128 below; at M = 2048 plain 256x128 tiles fill the chip.
+            const double ktot = (double)g.K + g.K2, per_us = 53e3;
+            double best = rounds(t128) * 256.0 * ktot * 2.0 / per_us;
+            NtConfig cfg = NT_128x128;
+            const double c28 = rounds(t256x128) * 384.0 * ktot * 2.0 / per_us;
+            if (c28 < best) { best = c28; cfg = NT_256x128; }
+            for (int sp = 2; sp <= 4; ++sp) {
+                const size_t need = (size_t)sp * g.M * g.N * g.batch;
+                if (!g.partial || need > g.partial_elems || (g.N & 3) || nk / sp < 8) continue;
+                // the pass over the partials: a reduce launch that reads them and writes C, or, when the consumer
+                // adds them up itself (g.deferred), only the extra bytes written here and read there
+                const double pass = g.deferred ? (double)need * (g.partial_bf16 ? 2.0 : 4.0) / 5e6 : (double)need * 8.0 / 5e6 + 5.0;
+                const double c = rounds(t256x128 * sp) * 384.0 * (ktot / sp) * 2.0 / per_us + pass;
+                if (c < 0.97 * best) { best = c; cfg = NT_256x128_SPLIT; *n_split = sp; }
+            }
+            return cfg;
+        }
+        // Many tiles: the same byte count decides between 256x256 tiles (fewest bytes per flop, but only four
+        // half-depth stages fit in LDS and the loop reaches about 42 GB/s per CU) and 256x128 tiles (55 GB/s per CU);
+        // rounds of tiles x rows per tile / rate.  256x192 tiles when they land in fewer rounds (dx of the down
+        // projection at 1024 tokens: 232 tiles, one round, against 172 of 256x256 that leave a third of the CUs
+        // idle; measured -9 %).
+        const double c256 = rounds(t256) * 512.0 / 42.0, c128 = rounds(t256x128) * 384.0 / 55.0;
+        const long t256x192 = (long)cdiv(g.M, 256) * cdiv(g.N, 192) * g.batch;
+        const double c192 = rounds(t256x192) * 448.0 / 42.0;
+        if (c192 < c256 && c192 < c128) return NT_256x192;
+        return c128 < c256 ? NT_256x128 : NT_256x256;
+    }
+    if (g.N > 64 && t128 >= 200) return NT_REG_128x128;
+    if (g.N > 64 && t64n >= 200) return NT_REG_128x64;
+    // few output tiles: 64x64 tiles, and split the contraction when scratch is available
+    const long t64 = (long)cdiv(g.M, 64) * cdiv(g.N, 64) * g.batch;
+    int split = g.split_k;
+    if (split == 0) {
+        split = 1;
+        if (g.partial && t64 < 256) {
+            split = (int)(512 / t64);
+            if (split > nk / 4) split = nk / 4;   // at least four k-tiles per split
+            if (split < 1) split = 1;
+            while (split > 1 && (size_t)split * g.M * g.N * g.batch > g.partial_elems) --split;
+        }
+    }
+    if (split > nk) split = nk > 0 ? nk : 1;
+    if (g.N & 3) split = 1;   // the reduce kernel works on groups of four columns
+    *n_split = split;
+    return NT_SKINNY;
+}
+
+const char* gemm_nt_plan(const GemmNT& g, int* n_split) {
+    int sp = 1;
+    const NtConfig c = choose_nt(g, &sp);
+    if (n_split) *n_split = sp;
+    switch (c) {
+        case NT_128x128: return "128x128";
+        case NT_256x128: return "256x128";
+        case NT_256x128_SPLIT: return "256x128-split";
+        case NT_256x192: return "256x192";
+        case NT_256x256: return "256x256";
+        case NT_REG_128x128: return "reg-128x128";
+        case NT_REG_128x64: return "reg-128x64";
+        case NT_SKINNY: break;
+    }
+    const bool dl_small = (g.K % BK) == 0 && g.K2 == 0 && g.K > 0 && (long)g.M * g.lda < (1L << 30) &&
+                          (long)g.N * g.ldb < (1L << 30);
+    return dl_small ? (sp > 1 ? "64x64-split" : "64x64") : (sp > 1 ? "reg-64x64-split" : "reg-64x64");
+}
+
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     if (g.deferred) {
         *g.deferred = 0;
@@ -678,173 +760,23 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
     if ((g.K & 7) || (g.K2 & 7) || (g.lda & 7) || (g.ldb & 7) || (g.lda2 & 7) || (g.ldb2 & 7)) return hipErrorInvalidValue;
     if ((g.bA & 7) || (g.bB & 7) || (g.bA2 & 7) || (g.bB2 & 7)) return hipErrorInvalidValue;
     if (!g.c_f32 && g.R) return hipErrorInvalidValue;
-    const int nk = cdiv(g.K, BK) + cdiv(g.K2, BK);
-    const long t128 = (long)cdiv(g.M, 128) * cdiv(g.N, 128) * g.batch;
-    const long t64n = (long)cdiv(g.M, 128) * cdiv(g.N, 64) * g.batch;
-    int split = g.split_k;
-    const bool dl_ok = (g.K % BK) == 0 && (g.K2 % BK) == 0 && g.K > 0 && g.N > 64 &&
-                       (long)g.M * g.lda < (1L << 30) && (long)g.N * g.ldb < (1L << 30) &&
-                       (long)g.M * g.lda2 < (1L << 30) && (long)g.N * g.ldb2 < (1L << 30);
-    if (dl_ok && t128 >= 128) {
-        const char* env = getenv("TL_GEMM_TILE");  // tuning aid: force one tile configuration
-        int cfg = env ? atoi(env) : 0;
-        if (cfg == 0) {
-            // Measured on MI355X at M = 1024.  Every tile shape is limited by how fast a CU can pull operand
-            // bytes out of L2 (about 64 bytes per clock at best), so the largest tile that still gives every CU
-            // work wins: 256x256 when its tiles fill the 256 CUs well, 256x128 when that quantises better, and
-            // 128x128 with the interleaved four-stage loop when there are only a few hundred tiles in all.
-            const long t256 = (long)cdiv(g.M, 256) * cdiv(g.N, 256) * g.batch;
-            const long t256x128 = (long)cdiv(g.M, 256) * cdiv(g.N, 128) * g.batch;
-            auto fill = [](long t) { return (double)t / (double)(((t + 255) / 256) * 256); };
-            // Few 256x256 tiles: pick among 128x128 tiles, 256x128 tiles, and 256x128 tiles with the contraction split
-            // 2..4 ways, by the operand bytes the busiest CU has to pull in (the loop is bound by that rate, about
-            // 53 GB/s per CU, not by the matrix pipe): rounds of tiles x (BM + BN) x K x 2 bytes.  A split adds one
-            // pass over its fp32 partials (written and read back at about 5 TB/s, plus a launch).  At M = 1024 this
-            // picks the two-way split from K of about 10k on (measured: K 11008 -7 %, 12288 -13 %, 22016 -17 %,
-            // 32000 -15 % against 128x128) and 128x128 below; at M = 2048 plain 256x128 tiles fill the chip.
-            if (t256 < 160) {
-                const double ktot = (double)g.K + g.K2, per_us = 53e3;
-                auto rounds = [](long t) { return (double)((t + 255) / 256); };
-                double best = rounds(t128) * 256.0 * ktot * 2.0 / per_us;
-                cfg = 25;
-                const double c28 = rounds(t256x128) * 384.0 * ktot * 2.0 / per_us;
-                if (c28 < best) { best = c28; cfg = 28; }
-                for (int sp = 2; sp <= 4; ++sp) {
-                    const size_t need = (size_t)sp * g.M * g.N * g.batch;
-                    if (!g.partial || need > g.partial_elems || (g.N & 3) || nk / sp < 8) continue;
-                    // the pass over the partials: a reduce launch that reads them and writes C, or, when the consumer
-                    // adds them up itself (g.deferred), only the extra bytes written here and read there
-                    const double pass = g.deferred ? (double)need * (g.partial_bf16 ? 2.0 : 4.0) / 5e6 : (double)need * 8.0 / 5e6 + 5.0;
-                    const double c = rounds(t256x128 * sp) * 384.0 * (ktot / sp) * 2.0 / per_us + pass;
-                    if (c < 0.97 * best) { best = c; cfg = 43 + sp; }   // 45, 46, 47 = split 2, 3, 4
-                }
-            }
-            else {
-                // Many tiles: the same byte count decides between 256x256 tiles (fewest bytes per flop, but only two
-                // full-depth or four half-depth stages fit in LDS and the loop reaches about 42 GB/s per CU) and
-                // 256x128 tiles (55 GB/s per CU); rounds of tiles x rows per tile / rate.
-                auto rounds = [](long t) { return (double)((t + 255) / 256); };
-                const double c256 = rounds(t256) * 512.0 / 42.0, c128 = rounds(t256x128) * 384.0 / 55.0;
-                // 256x192 tiles when they land in fewer rounds (dx of the down projection at 1024 tokens: 232 tiles, one
-                // round, against 172 of 256x256 that leave a third of the CUs idle; measured -9 %)
-                const long t256x192 = (long)cdiv(g.M, 256) * cdiv(g.N, 192) * g.batch;
-                const double c192 = rounds(t256x192) * 448.0 / 42.0;
-                static const bool no192 = getenv("TL_GEMM_NO192") != nullptr;   // tuning aid
-                if (!no192 && c192 < c256 && c192 < c128) cfg = 50;
-                else if (c128 < c256) cfg = 28;
-                else cfg = 22;   // 256x256: the half-depth four-stage loop (faster than two full-depth stages on every shape measured)
-            }
-        }
-        switch (cfg) {
-            case 1: return run_nt_dl<128, 128, 2, 2, 3>(g, s);
-            case 2: return run_nt_dl<256, 128, 4, 2, 3>(g, s);
-            case 3: return run_nt_dl<256, 128, 2, 2, 3>(g, s);
-            case 4: return run_nt_dl<128, 256, 2, 2, 3>(g, s);
-            case 5: return run_nt_dl<256, 256, 2, 2, 2>(g, s);
-            case 6: return run_nt_dl<256, 256, 4, 2, 2>(g, s);
-            case 50: return run_nt_dl<256, 192, 4, 2, 2>(g, s);
-            case 7: return run_nt_dl<128, 128, 2, 2, 2>(g, s);
-            case 8: return run_nt_dl<128, 256, 2, 4, 3>(g, s);
-            case 9: return run_nt<128, 128, 2, 2>(g, 1, s);
-            case 11: return run_nt_dl<256, 256, 2, 2, 4, 0, 32>(g, s);
-            case 12: return run_nt_dl<256, 256, 2, 2, 3, 0, 32>(g, s);
-            case 13: return run_nt_dl<256, 256, 4, 2, 4, 0, 32>(g, s);
-            case 14: return run_nt_dl<256, 128, 2, 2, 4, 0, 32>(g, s);
-            case 15: return run_nt_dl<128, 128, 2, 2, 6, 0, 32>(g, s);
-            case 16: return run_nt_dl<256, 128, 4, 2, 4, 0, 32>(g, s);
-            case 21: return run_nt_dl<256, 256, 2, 2, 4, 0, 32, false, 1>(g, s);
-            case 22: return run_nt_dl<256, 256, 4, 2, 4, 0, 32, false, 1>(g, s);
-            case 23: return run_nt_dl<256, 256, 2, 2, 3, 0, 32, false, 1>(g, s);
-            case 24: return run_nt_dl<256, 128, 2, 2, 4, 0, 32, false, 1>(g, s);
-            case 25: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, 1>(g, s);
-            case 26: return run_nt_dl<128, 128, 2, 2, 3, 0, 64, false, 1>(g, s);
-            case 27: return run_nt_dl<256, 128, 2, 2, 3, 0, 64, false, 1>(g, s);
-            case 28: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, 1>(g, s);
-            case 29: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, 1>(g, s);
-            case 30: return run_nt_dl<128, 256, 2, 2, 3, 0, 64, false, 1>(g, s);
-            case 41: case 42: case 43: case 44: {
-                const int sp = cfg == 41 ? 4 : (cfg == 42 ? 2 : (cfg == 43 ? 3 : 8));
-                if (!g.partial || (size_t)sp * g.M * g.N * g.batch > g.partial_elems || (g.N & 3)) return hipErrorInvalidValue;
-                return run_nt_dl<256, 256, 4, 2, 4, 0, 32, true, 1>(g, s, sp);
-            }
-            case 45: case 46: case 47: {
-                const int sp = cfg - 43;
-                if (!g.partial || (size_t)sp * g.M * g.N * g.batch > g.partial_elems || (g.N & 3)) return hipErrorInvalidValue;
-                return run_nt_dl<256, 128, 4, 2, 3, 0, 64, true, 1>(g, s, sp);
-            }
-            case 35: return run_nt_dl<128, 128, 4, 2, 4, 0, 64, false, 1>(g, s);
-            case 36: return run_nt_dl<128, 128, 2, 4, 4, 0, 64, false, 1>(g, s);
-            case 37: return run_nt_dl<128, 128, 4, 2, 4, 0, 64, false, 2>(g, s);
-            case 31: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, 2>(g, s);
-            case 32: return run_nt_dl<128, 128, 2, 2, 5, 0, 64, false, 2>(g, s);
-            case 33: return run_nt_dl<256, 128, 4, 2, 3, 0, 64, false, 2>(g, s);
-            case 34: return run_nt_dl<256, 128, 2, 2, 3, 0, 64, false, 2>(g, s);
-#ifdef TL_GEMM_ABLATE
-            case 101: return run_nt_dl<128, 128, 2, 2, 4, 1>(g, s);
-            case 102: return run_nt_dl<128, 128, 2, 2, 4, 2>(g, s);
-            case 103: return run_nt_dl<128, 128, 2, 2, 4, 3>(g, s);
-            case 104: return run_nt_dl<128, 128, 2, 2, 4, 4>(g, s);
-            case 105: return run_nt_dl<128, 128, 2, 2, 4, 5>(g, s);
-            case 106: return run_nt_dl<128, 128, 2, 2, 4, 6>(g, s);
-            case 107: return run_nt_dl<128, 128, 2, 2, 4, 7>(g, s);
-            case 500: return run_nt_dl<256, 256, 2, 2, 5, 0, 32, false, 1>(g, s);
-            case 506: return run_nt_dl<256, 256, 2, 2, 5, 6, 32, false, 1>(g, s);
-            case 600: return run_nt_dl<256, 256, 4, 2, 5, 0, 32, false, 1>(g, s);
-            case 606: return run_nt_dl<256, 256, 4, 2, 5, 6, 32, false, 1>(g, s);
-            case 700: return run_nt_dl<256, 256, 2, 2, 3, 0, 32, false, 1>(g, s);
-            case 706: return run_nt_dl<256, 256, 2, 2, 3, 6, 32, false, 1>(g, s);
-            case 301: return run_nt_dl<256, 256, 2, 2, 4, 1, 32, false, 1>(g, s);
-            case 302: return run_nt_dl<256, 256, 2, 2, 4, 2, 32, false, 1>(g, s);
-            case 303: return run_nt_dl<256, 256, 2, 2, 4, 3, 32, false, 1>(g, s);
-            case 304: return run_nt_dl<256, 256, 2, 2, 4, 4, 32, false, 1>(g, s);
-            case 305: return run_nt_dl<256, 256, 2, 2, 4, 5, 32, false, 1>(g, s);
-            case 306: return run_nt_dl<256, 256, 2, 2, 4, 6, 32, false, 1>(g, s);
-            case 307: return run_nt_dl<256, 256, 2, 2, 4, 7, 32, false, 1>(g, s);
-            case 401: return run_nt_dl<256, 256, 4, 2, 4, 1, 32, false, 1>(g, s);
-            case 402: return run_nt_dl<256, 256, 4, 2, 4, 2, 32, false, 1>(g, s);
-            case 403: return run_nt_dl<256, 256, 4, 2, 4, 3, 32, false, 1>(g, s);
-            case 404: return run_nt_dl<256, 256, 4, 2, 4, 4, 32, false, 1>(g, s);
-            case 405: return run_nt_dl<256, 256, 4, 2, 4, 5, 32, false, 1>(g, s);
-            case 406: return run_nt_dl<256, 256, 4, 2, 4, 6, 32, false, 1>(g, s);
-            case 407: return run_nt_dl<256, 256, 4, 2, 4, 7, 32, false, 1>(g, s);
-            case 201: return run_nt_dl<256, 256, 4, 2, 2, 1>(g, s);
-            case 202: return run_nt_dl<256, 256, 4, 2, 2, 2>(g, s);
-            case 203: return run_nt_dl<256, 256, 4, 2, 2, 3>(g, s);
-            case 204: return run_nt_dl<256, 256, 4, 2, 2, 4>(g, s);
-            case 205: return run_nt_dl<256, 256, 4, 2, 2, 5>(g, s);
-            case 206: return run_nt_dl<256, 256, 4, 2, 2, 6>(g, s);
-            case 207: return run_nt_dl<256, 256, 4, 2, 2, 7>(g, s);
-#endif
-            case 10: return run_nt_dl<128, 128, 2, 2, 4>(g, s);
-            default: return run_nt_dl<128, 128, 2, 2, 4, 0, 64, false, 1>(g, s);
-        }
-    }
-    if (g.N > 64 && t128 >= 200) {
-        return run_nt<128, 128, 2, 2>(g, 1, s);
-    }
-    if (g.N > 64 && t64n >= 200) {
-        return run_nt<128, 64, 2, 2>(g, 1, s);
-    }
-    // few output tiles: 64x64 tiles, and split the contraction when scratch is available
-    const long t64 = (long)cdiv(g.M, 64) * cdiv(g.N, 64) * g.batch;
-    const bool dl_small = (g.K % BK) == 0 && g.K2 == 0 && g.K > 0 && (long)g.M * g.lda < (1L << 30) &&
-                          (long)g.N * g.ldb < (1L << 30);
-    if (split == 0) {
-        split = 1;
-        if (g.partial && t64 < 256) {
-            split = (int)(512 / t64);
-            static const int kdiv = getenv("TL_SKINNY_KDIV") ? atoi(getenv("TL_SKINNY_KDIV")) : 4;   // tuning aid
-            if (split > nk / kdiv) split = nk / kdiv;   // at least kdiv k-tiles per split
-            if (split < 1) split = 1;
-            while (split > 1 && (size_t)split * g.M * g.N * g.batch > g.partial_elems) --split;
-        }
+    int split = 1;
+    switch (choose_nt(g, &split)) {
+        case NT_128x128: return run_nt_dl<128, 128, 2, 2, 4, 64, false, 1>(g, s);
+        case NT_256x128: return run_nt_dl<256, 128, 4, 2, 3, 64, false, 1>(g, s);
+        case NT_256x128_SPLIT: return run_nt_dl<256, 128, 4, 2, 3, 64, true, 1>(g, s, split);
+        case NT_256x192: return run_nt_dl<256, 192, 4, 2, 2>(g, s);
+        case NT_256x256: return run_nt_dl<256, 256, 4, 2, 4, 32, false, 1>(g, s);
+        case NT_REG_128x128: return run_nt<128, 128, 2, 2>(g, 1, s);
+        case NT_REG_128x64: return run_nt<128, 64, 2, 2>(g, 1, s);
+        case NT_SKINNY: break;
     }
     if (split > 1 && (!g.partial || (size_t)split * g.M * g.N * g.batch > g.partial_elems)) return hipErrorInvalidValue;
-    if (split > nk) split = nk > 0 ? nk : 1;
-    if (g.N & 3) split = 1;   // the reduce kernel works on groups of four columns
+    const bool dl_small = (g.K % BK) == 0 && g.K2 == 0 && g.K > 0 && (long)g.M * g.lda < (1L << 30) &&
+                          (long)g.N * g.ldb < (1L << 30);
     if (dl_small) {
-        if (split > 1) return run_nt_dl<64, 64, 2, 2, 4, 0, 64, true>(g, s, split);
-        if (split == 1) return run_nt_dl<64, 64, 2, 2, 4>(g, s);
+        if (split > 1) return run_nt_dl<64, 64, 2, 2, 4, 64, true>(g, s, split);
+        return run_nt_dl<64, 64, 2, 2, 4>(g, s);
     }
     return run_nt<64, 64, 2, 2>(g, split, s);
 }
@@ -946,13 +878,20 @@ __global__ __launch_bounds__(256) void gemm_tn_grouped_kernel(GemmTNGroup grp) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
     const int col = j0 + wj * 32 + l32;
+    bool bad = false;
     if (col < q.No) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = i0 + wi * 32 + 8 * (v >> 2) + 4 * g + (v & 3);
-            if (row < q.Mo) q.C[(long)row * q.ldc + col] = acc[v];
+            if (row < q.Mo) {
+                q.C[(long)row * q.ldc + col] = acc[v];
+                bad |= !isfinite(acc[v]);
+            }
         }
     }
+    // a gradient that is not finite must not reach the optimizer: raise bit 1 of the update's flag (one vector atomic
+    // per wave that saw one; never in a healthy update)
+    if (grp.flag && __builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) atomicOr(grp.flag, 2);
 }
 
 // adds the token splits of gemm_tn_kernel in index order

@@ -29,6 +29,8 @@ struct GemmNT {
     int partial_bf16 = 0;
 };
 hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s);
+// name of the tile configuration launch_gemm_nt picks for g (a static string) and the contraction split it uses
+const char* gemm_nt_plan(const GemmNT& g, int* n_split);
 // N1 > 0: cheaper as two launches, columns [0, N1) and [N1, N) of every batch (see gemm_bf16.hip); 0: one launch
 int gemm_nt_column_split(const GemmNT& g);
 bool gemm_nt_split_columns(const GemmNT& g, GemmNT* a, GemmNT* b);   // the two launches, if N1 > 0
@@ -58,6 +60,7 @@ struct TnProblem {
 struct GemmTNGroup {
     TnProblem p[TN_GROUP_MAX];
     int n = 0, T = 0;
+    int* flag = nullptr;   // if set: bit 1 of *flag is raised when any product entry is not finite
     void add(const bf16_t* P, long ldp, int Mo, const bf16_t* Q, long ldq, int No, float* C, long ldc) {
         if (n < TN_GROUP_MAX) { TnProblem& q = p[n]; q.P = P; q.ldp = ldp; q.Mo = Mo; q.Q = Q; q.ldq = ldq; q.No = No; q.C = C; q.ldc = ldc; }
         ++n;
@@ -75,8 +78,7 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
                                 int d_head, bf16_t* o, long ldo, float* lse, hipStream_t s);
 hipError_t launch_attention_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, const bf16_t* o, const bf16_t* d_o,
                                 const float* lse, long ldq, long ldo, int T, int n_heads, int d_head, bf16_t* dq,
-                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s,
-                                bool fused = true);
+                                bf16_t* dk, bf16_t* dv, float* delta, const float2* rope, hipStream_t s);
 
 // ---------------------------------------------------------------- elementwise / reductions (elementwise.hip)
 // part != null: the input row is not read from h but formed as the sum of n_part fp32 arrays [T, d] lying part_stride
@@ -95,17 +97,16 @@ hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, h
 hipError_t launch_swiglu_fwd(const bf16_t* gu, int T, int f, bf16_t* a, hipStream_t s);
 hipError_t launch_swiglu_bwd(const bf16_t* da, const bf16_t* gu, int T, int f, bf16_t* dgu, hipStream_t s);
 hipError_t launch_cross_entropy(const float* logits, const int* labels, int T, int V, int first_target,
-                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s, int row0 = 0);
+                                int n_targets, float* nll, bf16_t* dlogits, float* loss_sum, hipStream_t s, int row0 = 0,
+                                int* flag = nullptr);
 hipError_t launch_adamw(float* p, const float* g, float* m, float* v, bf16_t* shadow, size_t n, long step, float lr,
-                        float beta1, float beta2, float eps, float wd, hipStream_t s);
+                        float beta1, float beta2, float eps, float wd, hipStream_t s, const int* skip_flag = nullptr);
 hipError_t launch_embed(const bf16_t* E, const int* tokens, int T, int d, float* h, hipStream_t s);
 hipError_t launch_labels(const int* tokens, int T, int* labels, hipStream_t s);
 hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float value, hipStream_t s);
+hipError_t launch_fill_bf16_zero(bf16_t* p, size_t n, hipStream_t s);
 hipError_t launch_init_normal(float* p, size_t n, float std, uint64_t seed, uint64_t stream_id, hipStream_t s);
-// measurement aid: the GEMM's operand streams without arithmetic (stream_probe.hip)
-hipError_t launch_stream_probe(const void* A, const void* B, unsigned ld, unsigned kbytes, int tiles_m, int tiles_n,
-                               int steps_in_flight, unsigned* sink, hipStream_t s);
 // LoRA dropout: the mask is a function of (key, element index); key from (seed, optimizer step, layer, group)
 uint64_t dropout_key(uint64_t seed, int64_t step, int layer, int group);
 hipError_t launch_dropout_fwd(const bf16_t* x, bf16_t* y, size_t n, uint64_t key, float p, hipStream_t s);

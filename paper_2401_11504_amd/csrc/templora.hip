@@ -144,6 +144,11 @@ struct tl_lora {
     int *tok = nullptr, *labels = nullptr;
     int* tok_host = nullptr;      // pinned
     float* loss_host = nullptr;   // pinned
+    // Device-side verdict on the update in flight: bit 0 = the loss is not finite, bit 1 = a dA / dB entry is not finite.
+    // The AdamW launches read it and leave the module alone when it is set, so the host can enqueue the whole backward
+    // pass without waiting for the loss and still promise that a failed update changes nothing.
+    int* flag = nullptr;
+    int* flag_host = nullptr;     // pinned
     // generation side: the key/value cache is the q|k|v buffer the forward pass keeps per layer (rows = positions);
     // kv_len rows are valid.  Any training-side forward overwrites it, which matches the method (the cache is
     // recomputed with the updated module after every chunk update).
@@ -312,6 +317,8 @@ static void lora_release(tl_lora* L) {
     L->pool.release();
     if (L->tok_host) (void)hipHostFree(L->tok_host);
     if (L->loss_host) (void)hipHostFree(L->loss_host);
+    if (L->flag_host) (void)hipHostFree(L->flag_host);
+    L->flag_host = nullptr;
     if (L->next_host) (void)hipHostFree(L->next_host);
     L->tok_host = nullptr;
     L->loss_host = nullptr;
@@ -448,6 +455,9 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         TLCHK(L->pool.alloc(&L->labels, (size_t)Tm));
         TLCHK(L->pool.alloc(&L->nll, (size_t)Tm));
         TLCHK(L->pool.alloc(&L->loss_sum, (size_t)4));
+        TLCHK(L->pool.alloc(&L->flag, (size_t)4));
+        HIPCHK(hipMemsetAsync(L->flag, 0, 4 * sizeof(int), s));
+        HIPCHK(hipHostMalloc((void**)&L->flag_host, 4 * sizeof(int), hipHostMallocDefault));
         if (V > 0) {
             TLCHK(L->pool.alloc(&L->hf, Td));
             TLCHK(L->pool.alloc(&L->dhf, Td));
@@ -526,8 +536,7 @@ static tl_status group_fwd(tl_lora* L, int l, int g, const bf16_t* X, int T, bf1
     y.ldc = (long)G * dout;
     if (Y_f32) { y.C = Y_f32; y.c_f32 = 1; y.R = resid; } else { y.C = Y_bf; }
     y.partial = L->partial; y.partial_elems = L->partial_elems;
-    static const bool defer_ok = !(getenv("TL_GEMM_DEFER") && atoi(getenv("TL_GEMM_DEFER")) == 0);   // tuning aid
-    if (deferred && defer_ok && G == 1) y.deferred = deferred;
+    if (deferred && G == 1) y.deferred = deferred;
     HIPCHK(timed_gemm(L, y));
     return TL_OK;
 }
@@ -559,11 +568,7 @@ static tl_status flush_pending(tl_lora* L) {
 
 // The partial tiles a split dX GEMM leaves to the RMSNorm backward are bf16: dX was a bf16 tensor before the reduce
 // pass was folded into the norm, so the gradient loses nothing it had, and the tiles cost half the bytes on both sides.
-// tuning aid: TL_DEFER_BF16=0 keeps them fp32
-static bool defer_bf16() {
-    static const bool on = !(getenv("TL_DEFER_BF16") && atoi(getenv("TL_DEFER_BF16")) == 0);
-    return on;
-}
+constexpr int kDeferBf16 = 1;
 
 // backward: dH = s dY B;  dX = dY W + D o (dH A)  (D = 1 without dropout: then one GEMM with the contraction extended
 // by dH | A);  the products dA = dH^T X and dB = dY^T Hs are appended to `tn`, which
@@ -591,10 +596,9 @@ static tl_status group_bwd(tl_lora* L, int l, int g, const bf16_t* dY, const bf1
         if (!L->drop_on) { x.A2 = dH; x.lda2 = G * r; x.B2 = L->ST + o.AT[g]; x.ldb2 = G * r; x.K2 = G * r; }
         x.C = dX; x.ldc = din;
         x.partial = L->partial; x.partial_elems = L->partial_elems;
-        static const bool defer_ok = !(getenv("TL_GEMM_DEFER") && atoi(getenv("TL_GEMM_DEFER")) == 0);   // tuning aid
-        if (deferred && defer_ok && !L->drop_on) {   // with dropout dX is needed as a whole below
+        if (deferred && !L->drop_on) {   // with dropout dX is needed as a whole below
             x.deferred = deferred;
-            x.partial_bf16 = defer_bf16() ? 1 : 0;
+            x.partial_bf16 = kDeferBf16;
         }
         HIPCHK(timed_gemm(L, x));
         if (L->drop_on) {
@@ -648,12 +652,6 @@ static tl_status wait_tn(tl_lora* L, int par) {
 }
 
 // dh_out (fp32) and its bf16 copy dh_out_bf -> dh_in (fp32) and, if dh_in_bf != null, its bf16 copy
-// tuning aid: TL_ATTN_FUSED=0 runs the attention backward as two launches (dQ, then dK/dV) instead of one
-static bool attn_fused() {
-    static const bool on = !(getenv("TL_ATTN_FUSED") && atoi(getenv("TL_ATTN_FUSED")) == 0);
-    return on;
-}
-
 static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const float* dh_out, const bf16_t* dh_out_bf,
                                 float* dh_in, bf16_t* dh_in_bf, int T) {
     tl_model* m = L->model;
@@ -664,6 +662,7 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     const LayerW& W = m->layers[l];
     GemmTNGroup tn;
     tn.T = T;
+    tn.flag = L->opt_inline ? L->flag : nullptr;
     const int par = l & 1;
     TLCHK(group_bwd(L, l, G_DOWN, dh_out_bf, sv.act, T, L->d_act, tn));
     // the dA / dB launch of the layer above still reads dgu, dhmid_bf, dqkv (and the other parity's dH): everything
@@ -675,11 +674,11 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
     int nsp = 0;
     TLCHK(group_bwd(L, l, G_GU, L->dgu, sv.x2, T, L->dx, tn, &nsp));
     HIPCHK(launch_rmsnorm_bwd(L->dx, sv.hmid, W.g2, dh_out, T, d, c.rms_eps, L->dhmid, L->dhmid_bf, s,
-                              nsp ? L->partial : nullptr, nsp, (long)T * d, defer_bf16()));
+                              nsp ? L->partial : nullptr, nsp, (long)T * d, kDeferBf16));
     TLCHK(group_bwd(L, l, G_O, L->dhmid_bf, sv.o, T, L->d_o, tn));
     // one launch for every dQ and dK/dV part, longest first (dq, dk rotated back inside): 120 -> 84 us per layer at 1024 tokens
     HIPCHK(launch_attention_bwd(sv.qkv, sv.qkv + d, sv.qkv + 2 * d, sv.o, L->d_o, sv.lse, 3L * d, d, T, c.n_heads,
-                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s, attn_fused()));
+                                c.d_head, L->dqkv, L->dqkv + d, L->dqkv + 2 * d, L->delta, m->rope, s));
     nsp = 0;
     // dh_in == null: the caller does not want the gradient of the layer's input (the bottom layer of an update: it would
     // feed only the frozen embedding), so dX of q|k|v and the first RMSNorm's backward are left out; dA / dB are not
@@ -697,14 +696,14 @@ static tl_status layer_backward(tl_lora* L, int l, const float* h_in, const floa
         const size_t off = L->off[l].A[0];
         const size_t end = (l + 1 < c.n_layers) ? L->off[l + 1].A[0] : L->n_params;
         HIPCHK(launch_adamw(L->P + off, L->G + off, L->M + off, L->V + off, L->S + off, end - off, (long)(L->step + 1),
-                            L->opt_lr, L->cfg.beta1, L->cfg.beta2, L->cfg.eps, L->cfg.weight_decay, L->side));
+                            L->opt_lr, L->cfg.beta1, L->cfg.beta2, L->cfg.eps, L->cfg.weight_decay, L->side, L->flag));
         HIPCHK(launch_transpose_table(L->S, L->ST, L->ttable, L->n_desc, L->layer_tile0[l + 1] - L->layer_tile0[l],
                                       L->side, L->layer_tile0[l]));
     }
     // dh_in_bf must not be the buffer dh_out_bf (dB of the down projection is still reading it): callers alternate
     if (dh_in)
         HIPCHK(launch_rmsnorm_bwd(L->dx, h_in, W.g1, L->dhmid, T, d, c.rms_eps, dh_in, dh_in_bf, s,
-                                  nsp ? L->partial : nullptr, nsp, (long)T * d, defer_bf16()));
+                                  nsp ? L->partial : nullptr, nsp, (long)T * d, kDeferBf16));
     return TL_OK;
 }
 
@@ -750,15 +749,14 @@ static tl_status forward_loss(tl_lora* L, const int32_t* tokens, int T, int n_ct
     TLCHK(norm_fwd(L, L->hs[c.n_layers], m->gf, T, L->hf));
     // conditioning positions carry no loss: their logits are not needed, so lm_head runs on the rows from the first
     // target on only (with the paper's 1024 + 1024 sample that halves it; with Table 5's short pieces it is most of it)
-    static const bool all_rows = getenv("TL_LOSS_ALL_ROWS") && atoi(getenv("TL_LOSS_ALL_ROWS")) != 0;   // tuning aid
-    const int r0 = first >= 64 && !all_rows ? first : 0;
+    const int r0 = first >= 64 ? first : 0;
     L->loss_row0 = r0;
     GemmNT lg;
     lg.A = L->hf + (size_t)r0 * d; lg.lda = d; lg.B = m->head; lg.ldb = d; lg.M = T - r0; lg.N = V; lg.K = d;
     lg.C = L->logits + (size_t)r0 * V; lg.ldc = V; lg.c_f32 = 1;
     HIPCHK(timed_gemm(L, lg));
     HIPCHK(launch_cross_entropy(L->logits, L->labels, T, V, first, N, L->nll, want_grad ? L->dlogits : nullptr,
-                                L->loss_sum, s, r0));
+                                L->loss_sum, s, r0, L->flag));
     HIPCHK(hipMemcpyAsync(L->loss_host, L->loss_sum, sizeof(float), hipMemcpyDeviceToHost, s));
     L->last_tokens = T;
     return TL_OK;
@@ -788,21 +786,20 @@ static tl_status update_step(tl_lora* L, const int32_t* tokens, int32_t n_tokens
     const int T = n_tokens, d = c.d_model, V = c.vocab, nl = c.n_layers;
     int N = 0;
     TLCHK(forward_loss(L, tokens, T, n_ctx, true, &N));
-    // the loss decides whether anything is updated: read it before touching the module
-    HIPCHK(hipStreamSynchronize(s));
-    const float loss = L->loss_host[0] / (float)N;
-    if (!std::isfinite(loss)) return fail(TL_ERR_NONFINITE, "loss is not finite; optimizer step skipped");
+    // The loss decides whether anything is updated, but the host does not wait for it: the loss kernel leaves its
+    // verdict in L->flag, which every AdamW launch below reads before it writes, and the host looks at it once, after
+    // the backward pass.
     // backward: lm_head, final norm, layers
     const int r0 = L->loss_row0;          // rows below it have no loss and hence a zero gradient at the lm_head input
-    if (r0 > 0) HIPCHK(hipMemsetAsync(L->dhf, 0, (size_t)r0 * d * sizeof(bf16_t), s));
+    if (r0 > 0) HIPCHK(launch_fill_bf16_zero(L->dhf, (size_t)r0 * d, s));
     GemmNT dh;
     dh.A = L->dlogits + (size_t)r0 * V; dh.lda = V; dh.B = m->head_t; dh.ldb = V; dh.M = T - r0; dh.N = d; dh.K = V;
     dh.C = L->dhf + (size_t)r0 * d; dh.ldc = d;
     dh.partial = L->partial; dh.partial_elems = L->partial_elems;
     HIPCHK(timed_gemm(L, dh));
     HIPCHK(launch_rmsnorm_bwd(L->dhf, L->hs[nl], m->gf, nullptr, T, d, c.rms_eps, L->dhs[nl], L->dh_bf[nl & 1], s));
-    static const bool opt_inline = !(getenv("TL_OPT_INLINE") && atoi(getenv("TL_OPT_INLINE")) == 0);   // tuning aid
-    L->opt_inline = opt_inline;
+    // a layer's AdamW step follows its dA / dB launch on the side stream (see layer_backward)
+    L->opt_inline = true;
     L->opt_lr = lr;
     tl_status bst = TL_OK;
     for (int l = nl - 1; l >= 0 && bst == TL_OK; --l) {
@@ -816,13 +813,16 @@ static tl_status update_step(tl_lora* L, const int32_t* tokens, int32_t n_tokens
     TLCHK(wait_tn(L, 0));
     TLCHK(wait_tn(L, 1));
     L->have_grads = true;
-    if (opt_inline) {
-        HIPCHK(hipEventRecord(L->ev_opt, L->side));
-        HIPCHK(hipStreamWaitEvent(s, L->ev_opt, 0));
-    } else {
-        TLCHK(optimizer_step(L, lr, 0, L->n_params));
-    }
+    HIPCHK(hipEventRecord(L->ev_opt, L->side));
+    HIPCHK(hipStreamWaitEvent(s, L->ev_opt, 0));
+    HIPCHK(hipMemcpyAsync(L->flag_host, L->flag, sizeof(int), hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
+    const float loss = L->loss_host[0] / (float)N;
+    if ((L->flag_host[0] & 1) || !std::isfinite(loss))
+        return fail(TL_ERR_NONFINITE, "loss is not finite; optimizer step skipped");
+    if (L->flag_host[0] & 2)
+        return fail(TL_ERR_NONFINITE, "a LoRA gradient is not finite; the optimizer step of the layer it appeared in and "
+                                      "of every layer below was skipped");
     L->step += 1;
     *loss_out = loss;
     if (n_targets_out) *n_targets_out = N;
@@ -1263,25 +1263,13 @@ extern "C" tl_status tl_linear_step(const float* X, const float* W, const float*
 extern "C" tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t* B, int32_t ldb, int32_t M, int32_t N,
                                   int32_t K, const uint16_t* A2, int32_t lda2, const uint16_t* B2, int32_t ldb2,
                                   int32_t K2, float alpha, const float* R, void* C, int32_t ldc, int32_t c_f32,
-                                  void* hip_stream) {
+                                  float* workspace, size_t workspace_elems, void* hip_stream) {
     KARGS_OK(A && B && C && M >= 0 && N >= 0 && K >= 0 && K2 >= 0 && (K2 == 0 || (A2 && B2)), "tl_k_gemm_nt");
     GemmNT g;
     g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.M = M; g.N = N; g.K = K;
     g.A2 = K2 ? A2 : nullptr; g.lda2 = lda2; g.B2 = K2 ? B2 : nullptr; g.ldb2 = ldb2; g.K2 = K2;
     g.alpha = alpha; g.R = R; g.C = C; g.ldc = ldc; g.c_f32 = c_f32;
-    if (getenv("TL_GEMM_TILE") && M > 0 && N > 0) {
-        // tuning aid only: forced split-contraction configurations need scratch, kept for the life of the process
-        static float* scratch = nullptr;
-        static size_t scratch_elems = 0;
-        const size_t want = (size_t)8 * M * N;
-        if (want > scratch_elems) {
-            if (scratch) (void)hipFree(scratch);
-            scratch = nullptr; scratch_elems = 0;
-            HIPCHK(hipMalloc((void**)&scratch, want * sizeof(float)));
-            scratch_elems = want;
-        }
-        g.partial = scratch; g.partial_elems = scratch_elems;
-    }
+    if (workspace && workspace_elems > 0) { g.partial = workspace; g.partial_elems = workspace_elems; }
     GemmNT ga, gb;   // the same column split as the update path makes
     if (gemm_nt_split_columns(g, &ga, &gb)) {
         HIPCHK(launch_gemm_nt(ga, (hipStream_t)hip_stream));
@@ -1289,6 +1277,22 @@ extern "C" tl_status tl_k_gemm_nt(const uint16_t* A, int32_t lda, const uint16_t
         return TL_OK;
     }
     HIPCHK(launch_gemm_nt(g, (hipStream_t)hip_stream));
+    return TL_OK;
+}
+extern "C" tl_status tl_k_gemm_nt_plan(int32_t M, int32_t N, int32_t K, int32_t K2, size_t workspace_elems, char* name_out,
+                                       size_t name_cap, int32_t* n_split_out, int32_t* n_launches_out) {
+    KARGS_OK(name_out && name_cap > 0 && M > 0 && N > 0 && K >= 0 && K2 >= 0, "tl_k_gemm_nt_plan");
+    GemmNT g;     // dense operands, as tl_k_gemm_nt is called by the tests; only sizes matter to the choice
+    g.M = M; g.N = N; g.K = K; g.K2 = K2; g.lda = K; g.ldb = K; g.lda2 = K2; g.ldb2 = K2; g.ldc = N;
+    static float dummy;
+    if (workspace_elems > 0) { g.partial = &dummy; g.partial_elems = workspace_elems; }
+    GemmNT ga, gb;
+    int sp = 1;
+    const bool two = gemm_nt_split_columns(g, &ga, &gb);
+    const char* name = gemm_nt_plan(two ? ga : g, &sp);
+    snprintf(name_out, name_cap, "%s", name);
+    if (n_split_out) *n_split_out = sp;
+    if (n_launches_out) *n_launches_out = two ? 2 : 1;
     return TL_OK;
 }
 extern "C" tl_status tl_k_gemm_tn(const uint16_t* P, int32_t ldp, const uint16_t* Q, int32_t ldq, int32_t T, int32_t Mo,
@@ -1341,16 +1345,6 @@ extern "C" tl_status tl_k_gemv(const uint16_t* W, int32_t ldw, const uint16_t* x
                        y_f32 ? (float*)y : nullptr, (hipStream_t)hip_stream));
     return TL_OK;
 }
-extern "C" tl_status tl_probe_operand_stream(const void* A, const void* B, uint32_t ld_bytes, uint32_t k_bytes,
-                                             int32_t tiles_m, int32_t tiles_n, int32_t steps_in_flight, uint32_t* sink,
-                                             void* hip_stream) {
-    KARGS_OK(A && B && sink, "tl_probe_operand_stream");
-    hipError_t e = launch_stream_probe(A, B, ld_bytes, k_bytes, tiles_m, tiles_n, steps_in_flight, sink,
-                                       (hipStream_t)hip_stream);
-    if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return fail(TL_ERR_ARG, "tl_probe_operand_stream: bad geometry"); }
-    HIPCHK(e);
-    return TL_OK;
-}
 extern "C" tl_status tl_k_gemv_pre(const uint16_t* W, int32_t ldw, int32_t N, int32_t K, int32_t mode, const float* h,
                                    const float* gain, float eps, const uint16_t* gu, uint16_t* x_out, float* y,
                                    void* hip_stream) {
@@ -1396,7 +1390,7 @@ extern "C" tl_status tl_k_attention_bwd(const uint16_t* q, const uint16_t* k, co
     KARGS_OK(q && k && v && o && d_o && lse && dq && dk && dv && delta && T >= 0 && n_heads > 0 &&
                  (d_head == 64 || d_head == 128), "tl_k_attention_bwd");
     HIPCHK(launch_attention_bwd(q, k, v, o, d_o, lse, ldq, ldo, T, n_heads, d_head, dq, dk, dv, delta, nullptr,
-                                (hipStream_t)hip_stream, attn_fused()));
+                                (hipStream_t)hip_stream));
     return TL_OK;
 }
 extern "C" tl_status tl_k_cross_entropy(const float* logits, const int32_t* labels, int32_t T, int32_t V,

@@ -1,14 +1,22 @@
 #!/usr/bin/env python3
-"""Writes tests/golden/config3_7b_seed3000.npz: the CPU oracle's results for the full 7B-shaped chunk update.
+"""Writes the stored oracle values for the full-depth 7B-shaped chunk update, and the bf16 storage floor beside them.
 
-Calls only oracle/ and the seeded input generator.  The paper prints no numbers for one update, so these
-are the pinned oracle's values on the synthetic workload (32 layers, d 4096, 32x128 heads, ffn 11008,
-vocab 32000, LoRA r=64 alpha=64 with A ~ N(0, 0.02^2), B = 0, 1024 uniform token ids, seed 3000):
-loss, n_targets, per-position nll, and samples of dB (whose sign decides the first AdamW step) and of the
-hidden-state gradients at the layer boundaries 0, 16, 31 and at the final norm.
+    python tests/golden/make_config3_golden.py            -> config3_7b_seed3000.npz     (about 35 minutes, ~32 GB peak)
+    python tests/golden/make_config3_golden.py bne0       -> depth_7b_T256_seed3300.npz  (about 8 minutes)
 
-    python tests/golden/make_config3_golden.py          (about 64 GB of host memory is NOT needed: layers are
-                                                          generated on demand and caches are fp64, ~30 GB peak)
+Calls only oracle/, the seeded input generator and tests/bf16_floor.py (itself built from oracle functions only).  The
+paper prints no numbers for one update, so these are the pinned oracle's values on the synthetic workload (32 layers,
+d 4096, 32x128 heads, ffn 11008, vocab 32000, LoRA r = 64, alpha = 64, A ~ N(0, 0.02^2)):
+
+  config3  1024 uniform token ids, B = 0 (the benchmark configuration; dA is exactly 0)
+  bne0     256 uniform token ids, B ~ N(0, 0.01^2), so that dA is non-trivial at every depth
+
+Stored per file: loss, n_targets, per-position nll; a sample (16 rows x 256 columns) of the hidden-state gradient at
+EVERY layer boundary and at the final norm; a sample of dB (8 rows) and, for bne0, of dA (4 rows x 256 columns) of every
+projection of every layer; full-tensor norms.  Next to every sampled tensor two numbers `floor_*`: the error of the
+bf16-boundary replay of the oracle (tests/bf16_floor.py: the oracle's arithmetic in fp64, rounded to bf16 / fp32 exactly
+where the storage format of Section 3 "Setup" requires it) against the fp64 oracle ON THAT SAMPLE, as relative L2 error
+and as max-abs error over 10 RMS -- the two quantities the GPU tests bound.  No kernel is involved in either number.
 """
 import os
 import sys
@@ -16,59 +24,108 @@ import time
 
 import numpy as np
 
-ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
 sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.dirname(HERE))
+import bf16_floor as F  # noqa: E402
 from oracle import templora_oracle as O  # noqa: E402
 from paper_2401_11504_amd import synth  # noqa: E402
 
-SEED, T = 3000, 1024
-OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "config3_7b_seed3000.npz")
-SAMPLE_ROWS = 8      # rows of each sampled dB
-SAMPLE_DH_ROWS = 4   # rows and
-SAMPLE_DH_COLS = 256  # columns of each sampled hidden-state gradient
+DH_ROWS, DH_COLS, DB_ROWS, DA_ROWS, DA_COLS = 16, 256, 8, 4, 256
 
 
-def main(n_layers=32):
+def sample_err(x, ref):
+    """(relative L2 error, max-abs error / (10 RMS of ref)) of a sample: a tolerance tol passes iff both are <= tol."""
+    x, ref = np.asarray(x, np.float64), np.asarray(ref, np.float64)
+    rms = np.sqrt(np.mean(ref * ref))
+    return np.array([np.linalg.norm(x - ref) / np.linalg.norm(ref), np.max(np.abs(x - ref)) / (10.0 * rms)])
+
+
+def main(case="config3", n_layers=32):
+    if case == "config3":
+        seed, T, b_std, out_name = 3000, 1024, 0.0, "config3_7b_seed3000.npz"
+    else:
+        seed, T, b_std, out_name = 3300, 256, 0.01, "depth_7b_T256_seed3300.npz"
     shape = synth.SHAPES["7b"].with_layers(n_layers)
-    tok = synth.uniform_tokens(SEED, T, shape.vocab)
-    emb, head = synth.embedding(SEED, shape), synth.lm_head(SEED, shape)
-    lora = [synth.lora_factors(SEED, shape, l) for l in range(shape.n_layers)]
+    tok = synth.uniform_tokens(seed, T, shape.vocab)
+    emb, head = synth.embedding(seed, shape), synth.lm_head(seed, shape)
+    lora = [synth.lora_factors(seed, shape, l, b_std=b_std) for l in range(shape.n_layers)]
     cache = {}
 
     def get_layer(l):
         # forward visits 0..L-1 then backward L-1..0: keep only the layer in use
         if l not in cache:
             cache.clear()
-            cache[l] = synth.layer_weights(SEED, shape, l)
+            cache[l] = synth.layer_weights(seed, shape, l)
         return cache[l]
 
+    layers = list(range(shape.n_layers))
     t0 = time.time()
-    keep = sorted({0, shape.n_layers // 2, shape.n_layers - 1})
-    res = O.model_fwd_bwd(tok, 0, shape, emb, head, np.ones(shape.d_model), get_layer, lora, keep=keep)
+    res = O.model_fwd_bwd(tok, 0, shape, emb, head, np.ones(shape.d_model), get_layer, lora, keep=layers)
     print(f"oracle forward+backward: {time.time() - t0:.1f} s, loss {res['loss']:.6f}", flush=True)
-    rs = np.random.default_rng(SEED)
+    rs = np.random.default_rng(seed)
     f32 = lambda x: np.asarray(x, dtype=np.float32)
     out = {"loss": np.float64(res["loss"]), "n_targets": np.int64(res["n_targets"]), "nll": f32(res["nll"]),
-           "n_layers": np.int64(shape.n_layers), "seed": np.int64(SEED), "keep": np.array(keep)}
-    rows_t = np.sort(rs.choice(T, SAMPLE_DH_ROWS, replace=False))
-    cols_d = np.sort(rs.choice(shape.d_model, SAMPLE_DH_COLS, replace=False))
+           "n_layers": np.int64(shape.n_layers), "seed": np.int64(seed), "n_tokens": np.int64(T),
+           "b_std": np.float64(b_std), "tokens": tok}
+    rows_t = np.sort(rs.choice(T, DH_ROWS, replace=False))
+    cols_d = np.sort(rs.choice(shape.d_model, DH_COLS, replace=False))
     out["dh_rows"], out["dh_cols"] = rows_t, cols_d
     out["dh_final"] = f32(res["dh"]["final"][np.ix_(rows_t, cols_d)])
     out["dh_final_norm"] = np.float64(np.linalg.norm(res["dh"]["final"]))
-    for l in keep:
-        out[f"dh_{l}"] = f32(res["dh"][l][np.ix_(rows_t, cols_d)])
+    ref_dh = {"final": res["dh"]["final"][np.ix_(rows_t, cols_d)].copy()}
+    ref_full_norm = {}
+    for l in layers:
+        ref_dh[l] = res["dh"][l][np.ix_(rows_t, cols_d)].copy()
+        out[f"dh_{l}"] = f32(ref_dh[l])
         out[f"dh_norm_{l}"] = np.float64(np.linalg.norm(res["dh"][l]))
-    for l in keep:
+    ref_g = {}
+    for l in layers:
         for i, p in enumerate(synth.PROJ):
             dA, dB = res["grads"][l][p]
-            assert np.all(dA == 0.0)     # B = 0  =>  dA = 0 exactly
-            rows = np.sort(rs.choice(dB.shape[0], SAMPLE_ROWS, replace=False))
-            out[f"dB_rows_{l}_{i}"] = rows
-            out[f"dB_{l}_{i}"] = f32(dB[rows])
+            d_out, d_in = shape.proj_dims(p)
+            rb = np.sort(rs.choice(d_out, DB_ROWS, replace=False))
+            out[f"dB_rows_{l}_{i}"] = rb
+            out[f"dB_{l}_{i}"] = f32(dB[rb])
             out[f"dB_norm_{l}_{i}"] = np.float64(np.linalg.norm(dB))
-    np.savez_compressed(OUT if n_layers == 32 else OUT.replace(".npz", f"_L{n_layers}.npz"), **out)
-    print("wrote", OUT, flush=True)
+            ref_g[(l, i, 1)] = dB[rb].copy()
+            if b_std > 0:
+                ra = np.sort(rs.choice(shape.rank, DA_ROWS, replace=False))
+                ca = np.sort(rs.choice(d_in, DA_COLS, replace=False))
+                out[f"dA_rows_{l}_{i}"], out[f"dA_cols_{l}_{i}"] = ra, ca
+                out[f"dA_{l}_{i}"] = f32(dA[np.ix_(ra, ca)])
+                out[f"dA_norm_{l}_{i}"] = np.float64(np.linalg.norm(dA))
+                ref_g[(l, i, 0)] = dA[np.ix_(ra, ca)].copy()
+            else:
+                assert np.all(dA == 0.0)     # B = 0  =>  dA = 0 exactly
+    ref_loss, ref_nll = res["loss"], res["nll"].copy()
+    del res
+    cache.clear()
+
+    # ---- the bf16-boundary replay of the same update: what the storage format alone costs against the oracle
+    def on_layer(l, dh_in, G):
+        out[f"floor_dh_{l}"] = sample_err(dh_in[np.ix_(rows_t, cols_d)], ref_dh[l])
+        for i, p in enumerate(synth.PROJ):
+            out[f"floor_dB_{l}_{i}"] = sample_err(G[p][1][out[f"dB_rows_{l}_{i}"]], ref_g[(l, i, 1)])
+            if b_std > 0:
+                out[f"floor_dA_{l}_{i}"] = sample_err(G[p][0][np.ix_(out[f"dA_rows_{l}_{i}"], out[f"dA_cols_{l}_{i}"])],
+                                                      ref_g[(l, i, 0)])
+        print(f"  replay layer {l}: dh floor {out[f'floor_dh_{l}'][0]:.4f}, dB floors "
+              + " ".join(f"{out[f'floor_dB_{l}_{i}'][0]:.3f}" for i in range(7)), flush=True)
+
+    t0 = time.time()
+    rep = F.model_fwd_bwd(tok, 0, shape, emb, head, np.ones(shape.d_model), get_layer, lora, on_layer=on_layer)
+    out["floor_dh_final"] = sample_err(rep["dh"]["final"][np.ix_(rows_t, cols_d)], ref_dh["final"])
+    out["floor_loss"] = np.float64(abs(rep["loss"] - ref_loss) / abs(ref_loss))
+    out["floor_nll"] = sample_err(rep["nll"], ref_nll)
+    print(f"bf16-boundary replay: {time.time() - t0:.1f} s, loss {rep['loss']:.6f} (floor {out['floor_loss']:.2e}), "
+          f"dh_final floor {out['floor_dh_final'][0]:.4f}", flush=True)
+    path = os.path.join(HERE, out_name if n_layers == 32 else out_name.replace(".npz", f"_L{n_layers}.npz"))
+    np.savez_compressed(path, **out)
+    print("wrote", path, flush=True)
 
 
 if __name__ == "__main__":
-    main(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
+    a = sys.argv[1:]
+    main(a[0] if a else "config3", int(a[1]) if len(a) > 1 else 32)

@@ -86,11 +86,41 @@ def test_gemm_nt_skinny(api, H, M, N, K):
     check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")
 
 
-@pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5", "6", "7", "8", "10", "11", "12", "13", "14", "15", "16", "21", "22", "23", "24", "25", "26", "27", "28", "29", "30", "31", "32", "33", "34", "35", "36", "37", "41", "42", "45", "46", "47", "50"])
-@pytest.mark.parametrize("M,N,K,K2", [(1024, 2048, 256, 64), (1000, 2056, 128, 0), (520, 4104, 192, 128)])
-def test_gemm_nt_pipelined_tiles(api, H, monkeypatch, tile, M, N, K, K2):
-    """The direct-to-LDS kernel in each of its tile configurations (K, K2 multiples of 64; ragged M and N)."""
-    monkeypatch.setenv("TL_GEMM_TILE", tile)
+# One shape (ragged where the instance allows it) for every tile configuration the launcher can pick, with and without
+# scratch for a split contraction; `plan` is what tl_k_gemm_nt_plan must report for it, so that a change of the
+# selection rules cannot silently leave an instance untested.  K >= 512 runs the interleaved steady-state loop of the
+# direct-to-LDS instances, K = 128 their short-contraction fallback.
+NT_CASES = [
+    # M, N, K, K2, workspace, plan
+    (1024, 2048, 512, 64, False, ("128x128", 1)),
+    (1000, 2056, 128, 0, False, ("128x128", 1)),
+    (520, 4104, 576, 128, False, ("128x128", 1)),
+    (2048, 4096, 512, 64, False, ("256x128", 1)),
+    (1000, 8184, 128, 64, False, ("256x128", 1)),
+    (1000, 4072, 11008, 64, True, ("256x128-split", 2)),
+    (1000, 11008, 576, 64, False, ("256x192", 1)),
+    (1024, 12288, 128, 0, False, ("256x192", 1)),
+    (1000, 16200, 512, 64, False, ("256x256", 1)),
+    (1024, 16384, 64, 64, False, ("256x256", 1)),
+    (1000, 4104, 72, 8, False, ("reg-128x128", 1)),
+    (1024, 1600, 72, 0, False, ("reg-128x64", 1)),
+    (1000, 192, 1024, 0, True, ("64x64-split", 4)),
+    (1000, 192, 1024, 0, False, ("64x64", 1)),
+    (1000, 72, 1032, 0, True, ("reg-64x64-split", 4)),
+    (300, 200, 136, 8, False, ("reg-64x64", 1)),
+]
+
+
+def test_gemm_nt_cases_cover_every_configuration(api):
+    names = {api.tl_k_gemm_nt_plan(M, N, K, K2, (1 << 26) if ws else 0)[0] for M, N, K, K2, ws, _ in NT_CASES}
+    assert names == {"128x128", "256x128", "256x128-split", "256x192", "256x256", "reg-128x128", "reg-128x64", "64x64",
+                     "64x64-split", "reg-64x64", "reg-64x64-split"}
+
+
+@pytest.mark.parametrize("M,N,K,K2,ws,plan", NT_CASES)
+def test_gemm_nt_every_configuration(api, H, M, N, K, K2, ws, plan):
+    """Each tile configuration of the frozen-weight GEMM on a shape the launcher sends to it."""
+    assert api.tl_k_gemm_nt_plan(M, N, K, K2, (1 << 26) if ws else 0)[:2] == plan
     A, B = rnd(1, (M, K)), rnd(2, (N, K), 0.05)
     A2 = rnd(3, (M, K2)) if K2 else None
     B2 = rnd(4, (N, K2), 0.05) if K2 else None
@@ -98,11 +128,16 @@ def test_gemm_nt_pipelined_tiles(api, H, monkeypatch, tile, M, N, K, K2):
     if K2:
         ref = ref + A2.astype(np.float64) @ B2.T.astype(np.float64)
     R = rnd(5, (M, N), 1.0, False)
+    scratch = torch.empty(1 << 26, dtype=torch.float32, device="cuda") if ws else None
     Cf = torch.empty(M, N, dtype=torch.float32, device="cuda")
     api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cf, H.to_dev_bf16(A2) if K2 else None,
-                     H.to_dev_bf16(B2) if K2 else None, alpha=1.0, R=H.to_dev_f32(R))
+                     H.to_dev_bf16(B2) if K2 else None, alpha=1.0, R=H.to_dev_f32(R), workspace=scratch)
+    Cb = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    api.tl_k_gemm_nt(H.to_dev_bf16(A), H.to_dev_bf16(B), Cb, H.to_dev_bf16(A2) if K2 else None,
+                     H.to_dev_bf16(B2) if K2 else None, alpha=0.5, workspace=scratch)
     torch.cuda.synchronize()
-    check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")
+    check(Cf.cpu().numpy(), ref + R, 1e-3, "C f32 + R")   # bf16 products are exact; only fp32 summation order differs
+    check(H.bf16_to_np(Cb), 0.5 * ref, BF16_TOL, "C bf16")
 
 
 def test_gemm_nt_two_column_ranges(api, H):
