@@ -238,6 +238,50 @@ def test_lifecycle_and_error_paths(api, H):
     model.close()
 
 
+def test_non_finite_loss_leaves_the_module_bit_identical(api, H):
+    """A factor entry set to infinity makes the loss NaN.  The host no longer waits for the loss before it enqueues the
+    backward pass: the loss kernel leaves its verdict in device memory and every AdamW launch reads it.  The call must
+    return TL_ERR_NONFINITE with A, B, both moments and the step counter exactly as they were; every kernel of the
+    failed call runs to its normal end (NaNs are ordinary values to them)."""
+    shape = synth.SHAPES["small"]
+    T = 96
+    model = H.Model(shape, 5105, max_tokens=T)
+    tok = synth.uniform_tokens(5105, T, shape.vocab)
+    lora, facs = H.new_lora(model, 5105, b_std=0.01)
+    api.tl_chunk_update(lora, tok, 0, 1e-3)                 # a healthy step first, so that the moments are not zero
+    poisoned = np.array(facs[1]["o"][1], dtype=np.float32)
+    poisoned[3, 2] = np.inf
+    api.tl_set_factor(lora, 1, 3, api.FACTOR_B, poisoned)
+
+    def state():
+        out = []
+        for l in range(shape.n_layers):
+            for i, p in enumerate(synth.PROJ):
+                dout, din = shape.proj_dims(p)
+                for sel, shp in ((api.FACTOR_A, (shape.rank, din)), (api.FACTOR_B, (dout, shape.rank)),
+                                 (api.M_A, (shape.rank, din)), (api.M_B, (dout, shape.rank)),
+                                 (api.V_A, (shape.rank, din)), (api.V_B, (dout, shape.rank))):
+                    out.append(api.tl_get_factor(lora, l, i, sel, shp))
+        return out
+
+    before = state()
+    with pytest.raises(api.TlError) as e:
+        api.tl_chunk_update(lora, tok, 0, 1e-3)
+    assert e.value.status == -5
+    assert api.tl_get_step(lora) == 1
+    for a, b in zip(before, state()):
+        assert np.array_equal(a, b, equal_nan=True)
+    with pytest.raises(api.TlError) as e:
+        api.tl_chunk_loss(lora, tok)
+    assert e.value.status == -5
+    # repaired, the module goes on from where it was
+    api.tl_set_factor(lora, 1, 3, api.FACTOR_B, np.asarray(before[(1 * 7 + 3) * 6 + 1]))
+    loss, _ = api.tl_chunk_update(lora, tok, 0, 1e-3)
+    assert np.isfinite(loss) and api.tl_get_step(lora) == 2
+    api.tl_lora_free(lora)
+    model.close()
+
+
 def test_unsupported_shapes_are_rejected(api, H):
     with pytest.raises(api.TlError) as e:
         api.tl_model_create(1, 96, 2, 48, 64, 0, 16, [torch.zeros(1, device="cuda")] * 12)
