@@ -308,6 +308,21 @@ tl_status tl_linear_step(const float* X, const float* W, const float* A, const f
                          float beta2, float eps, float weight_decay, int32_t apply_adamw, float* Y, float* dX,
                          float* dA, float* dB, float* A_new, float* B_new, void* hip_stream);
 
+/*
+ * tl_linear_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results and errors as tl_linear_step, but the scratch that call
+ * takes from hipMalloc (H = X A^T and dH, fp32 [T, r] each, and with apply_adamw the 2 r (d_in + d_out) moments) lives
+ * in a buffer of 2^20 floats (4 MiB) that is part of the library's image: every GPU the library runs on holds one
+ * until the process ends, and this call performs no allocation or release of any kind.
+ * TL_ERR_SHAPE if 2 T r (+ 2 r (d_in + d_out)), each part rounded up to 64 floats, exceeds 2^20 floats.
+ * All calls on one GPU share that buffer: it holds the previous call's values on entry (the call clears what it needs
+ * zeroed), and two calls that overlap in time on one GPU race -- the caller serialises them.
+ */
+tl_status tl_linear_step_static(const float* X, const float* W, const float* A, const float* B, const float* dY,
+                                int32_t T, int32_t d_in, int32_t d_out, int32_t r, float s, float lr, float beta1,
+                                float beta2, float eps, float weight_decay, int32_t apply_adamw, float* Y, float* dX,
+                                float* dA, float* dB, float* A_new, float* B_new, void* hip_stream);
+
 /* ---- single kernels, exposed for per-kernel parity tests and timing ----
  * All pointers are device memory; work is enqueued on hip_stream and NOT synchronised.
  * bf16 buffers are passed as uint16_t*. */

@@ -82,6 +82,7 @@ _SIGS = {
     "tl_profile_read": [_vp, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)],
     "tl_layer_step": [_vp, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _i32],
     "tl_linear_step": [_vp] * 5 + [_i32] * 4 + [_f32] * 6 + [_i32] + [_vp] * 6 + [_vp],
+    "tl_linear_step_static": [_vp] * 5 + [_i32] * 4 + [_f32] * 6 + [_i32] + [_vp] * 6 + [_vp],
     "tl_k_gemm_nt": [_vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _i32, _f32, _vp, _vp, _i32, _i32, _vp,
                      _sz, _vp],
     "tl_k_gemm_nt_plan": [_i32, _i32, _i32, _i32, _sz, C.c_char_p, _sz, C.POINTER(_i32), C.POINTER(_i32)],
@@ -305,6 +306,15 @@ def tl_linear_step(X, W, A, B, dY, s, lr, beta1, beta2, eps, weight_decay, apply
     _chk(_lib.tl_linear_step(_dp(X), _dp(W), _dp(A), _dp(B), _dp(dY), T, d_in, d_out, r, s, lr, beta1, beta2, eps,
                              weight_decay, int(apply_adamw), _dp(Y), _dp(dX), _dp(dA), _dp(dB), _dp(A_new),
                              _dp(B_new), stream if stream is not None else current_stream_handle()))
+
+
+def tl_linear_step_static(X, W, A, B, dY, s, lr, beta1, beta2, eps, weight_decay, apply_adamw, Y, dX, dA, dB, A_new,
+                          B_new, stream=None):
+    T, d_in = X.shape
+    d_out, r = B.shape
+    _chk(_lib.tl_linear_step_static(_dp(X), _dp(W), _dp(A), _dp(B), _dp(dY), T, d_in, d_out, r, s, lr, beta1, beta2, eps,
+                                    weight_decay, int(apply_adamw), _dp(Y), _dp(dX), _dp(dA), _dp(dB), _dp(A_new),
+                                    _dp(B_new), stream if stream is not None else current_stream_handle()))
 
 
 # ------------------------------------------------------------------ single kernels (not synchronised)

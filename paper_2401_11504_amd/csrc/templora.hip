@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1214,45 +1215,109 @@ extern "C" tl_status tl_profile_read(tl_lora* L, double* ms_total, int64_t* laun
 }
 
 // ---------------------------------------------------------------- single fp32 LoRA-adapted linear layer
+// H, dH: [T, r] scratch; mom: 2 (r d_in + d_out r) floats of optimizer moments (only with apply_adamw).
+static tl_status linear_step_run(const float* X, const float* W, const float* A, const float* B, const float* dY, int T,
+                                 int d_in, int d_out, int r, float s, float lr, float beta1, float beta2, float eps,
+                                 float wd, int apply_adamw, float* Y, float* dX, float* dA, float* dB, float* A_new,
+                                 float* B_new, float* H, float* dH, float* mom, hipStream_t st) {
+    // H = X A^T;  Y = X W^T + s H B^T
+    HIPCHK(launch_sgemm(0, 1, T, r, d_in, 1.f, X, d_in, A, d_in, 0.f, H, r, st));
+    HIPCHK(launch_sgemm(0, 1, T, d_out, d_in, 1.f, X, d_in, W, d_in, 0.f, Y, d_out, st));
+    HIPCHK(launch_sgemm(0, 1, T, d_out, r, s, H, r, B, r, 1.f, Y, d_out, st));
+    // dH = s dY B;  dX = dY W + dH A;  dA = dH^T X;  dB = s dY^T H
+    HIPCHK(launch_sgemm(0, 0, T, r, d_out, s, dY, d_out, B, r, 0.f, dH, r, st));
+    HIPCHK(launch_sgemm(0, 0, T, d_in, d_out, 1.f, dY, d_out, W, d_in, 0.f, dX, d_in, st));
+    HIPCHK(launch_sgemm(0, 0, T, d_in, r, 1.f, dH, r, A, d_in, 1.f, dX, d_in, st));
+    HIPCHK(launch_sgemm(1, 0, r, d_in, T, 1.f, dH, r, X, d_in, 0.f, dA, d_in, st));
+    HIPCHK(launch_sgemm(1, 0, d_out, r, T, s, dY, d_out, H, r, 0.f, dB, r, st));
+    if (apply_adamw) {
+        const size_t na = (size_t)r * d_in, nb = (size_t)d_out * r;
+        HIPCHK(launch_fill_f32(mom, 2 * (na + nb), 0.f, st));     // first step: zero moments (a kernel, not a memset node)
+        HIPCHK(hipMemcpyAsync(A_new, A, na * sizeof(float), hipMemcpyDeviceToDevice, st));
+        HIPCHK(hipMemcpyAsync(B_new, B, nb * sizeof(float), hipMemcpyDeviceToDevice, st));
+        HIPCHK(launch_adamw(A_new, dA, mom, mom + na, nullptr, na, 1, lr, beta1, beta2, eps, wd, st));
+        HIPCHK(launch_adamw(B_new, dB, mom + 2 * na, mom + 2 * na + nb, nullptr, nb, 1, lr, beta1, beta2, eps, wd, st));
+    }
+    HIPCHK(hipStreamSynchronize(st));
+    return TL_OK;
+}
+
+static tl_status linear_step_args(const float* X, const float* W, const float* A, const float* B, const float* dY, int T,
+                                  int d_in, int d_out, int r, int apply_adamw, float* Y, float* dX, float* dA,
+                                  float* dB, float* A_new, float* B_new) {
+    if (!X || !W || !A || !B || !dY || !Y || !dX || !dA || !dB) return fail(TL_ERR_ARG, "tl_linear_step: null pointer");
+    if (apply_adamw && (!A_new || !B_new)) return fail(TL_ERR_ARG, "tl_linear_step: A_new/B_new required");
+    if (T < 1 || d_in < 1 || d_out < 1 || r < 1) return fail(TL_ERR_SHAPE, "tl_linear_step: non-positive dimension");
+    return require_gfx950();
+}
+
 extern "C" tl_status tl_linear_step(const float* X, const float* W, const float* A, const float* B, const float* dY,
                                     int32_t T, int32_t d_in, int32_t d_out, int32_t r, float s, float lr, float beta1,
                                     float beta2, float eps, float wd, int32_t apply_adamw, float* Y, float* dX,
                                     float* dA, float* dB, float* A_new, float* B_new, void* hip_stream) {
-    if (!X || !W || !A || !B || !dY || !Y || !dX || !dA || !dB) return fail(TL_ERR_ARG, "tl_linear_step: null pointer");
-    if (apply_adamw && (!A_new || !B_new)) return fail(TL_ERR_ARG, "tl_linear_step: A_new/B_new required");
-    if (T < 1 || d_in < 1 || d_out < 1 || r < 1) return fail(TL_ERR_SHAPE, "tl_linear_step: non-positive dimension");
-    TLCHK(require_gfx950());
+    TLCHK(linear_step_args(X, W, A, B, dY, T, d_in, d_out, r, apply_adamw, Y, dX, dA, dB, A_new, B_new));
     hipStream_t st = (hipStream_t)hip_stream;
     Pool pool;
     float *H = nullptr, *dH = nullptr, *mom = nullptr;
     auto body = [&]() -> tl_status {
         TLCHK(pool.alloc(&H, (size_t)T * r));
         TLCHK(pool.alloc(&dH, (size_t)T * r));
-        // H = X A^T;  Y = X W^T + s H B^T
-        HIPCHK(launch_sgemm(0, 1, T, r, d_in, 1.f, X, d_in, A, d_in, 0.f, H, r, st));
-        HIPCHK(launch_sgemm(0, 1, T, d_out, d_in, 1.f, X, d_in, W, d_in, 0.f, Y, d_out, st));
-        HIPCHK(launch_sgemm(0, 1, T, d_out, r, s, H, r, B, r, 1.f, Y, d_out, st));
-        // dH = s dY B;  dX = dY W + dH A;  dA = dH^T X;  dB = s dY^T H
-        HIPCHK(launch_sgemm(0, 0, T, r, d_out, s, dY, d_out, B, r, 0.f, dH, r, st));
-        HIPCHK(launch_sgemm(0, 0, T, d_in, d_out, 1.f, dY, d_out, W, d_in, 0.f, dX, d_in, st));
-        HIPCHK(launch_sgemm(0, 0, T, d_in, r, 1.f, dH, r, A, d_in, 1.f, dX, d_in, st));
-        HIPCHK(launch_sgemm(1, 0, r, d_in, T, 1.f, dH, r, X, d_in, 0.f, dA, d_in, st));
-        HIPCHK(launch_sgemm(1, 0, d_out, r, T, s, dY, d_out, H, r, 0.f, dB, r, st));
-        if (apply_adamw) {
-            const size_t na = (size_t)r * d_in, nb = (size_t)d_out * r;
-            TLCHK(pool.alloc(&mom, 2 * (na + nb)));
-            HIPCHK(launch_fill_f32(mom, 2 * (na + nb), 0.f, st));
-            HIPCHK(hipMemcpyAsync(A_new, A, na * sizeof(float), hipMemcpyDeviceToDevice, st));
-            HIPCHK(hipMemcpyAsync(B_new, B, nb * sizeof(float), hipMemcpyDeviceToDevice, st));
-            HIPCHK(launch_adamw(A_new, dA, mom, mom + na, nullptr, na, 1, lr, beta1, beta2, eps, wd, st));
-            HIPCHK(launch_adamw(B_new, dB, mom + 2 * na, mom + 2 * na + nb, nullptr, nb, 1, lr, beta1, beta2, eps, wd, st));
-        }
-        HIPCHK(hipStreamSynchronize(st));
-        return TL_OK;
+        if (apply_adamw) TLCHK(pool.alloc(&mom, 2 * ((size_t)r * d_in + (size_t)d_out * r)));
+        return linear_step_run(X, W, A, B, dY, T, d_in, d_out, r, s, lr, beta1, beta2, eps, wd, apply_adamw, Y, dX, dA, dB,
+                               A_new, B_new, H, dH, mom, st);
     };
     tl_status rc = body();
     if (rc != TL_OK) (void)hipStreamSynchronize(st);
     pool.release();
+    return rc;
+}
+
+// ---------------------------------------------------------------- tl_linear_step without allocation
+// For callers that cannot allocate (HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+// scratch tl_linear_step takes from hipMalloc (H, dH and, with AdamW, the moments) lives in one file-scope device
+// array instead.  Every GPU the library runs on holds its own copy for the life of the process; the array's name is
+// only a host-side handle, so its device address is looked up once per device (with that device current) and kept.
+constexpr size_t kStaticScratchFloats = (size_t)1 << 20;    // 4 MiB
+static __device__ __align__(256) float tl_static_scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+static float* g_static_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_static_scratch_mutex;
+
+static tl_status static_scratch(float** out) {
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TL_ERR_DEVICE, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch_ptr[dev]) {
+        float* p = nullptr;
+        HIPCHK(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(tl_static_scratch)));
+        if (!p) return fail(TL_ERR_DEVICE, "hipGetSymbolAddress returned a null address for the static scratch");
+        g_static_scratch_ptr[dev] = p;
+    }
+    *out = g_static_scratch_ptr[dev];
+    return TL_OK;
+}
+
+extern "C" tl_status tl_linear_step_static(const float* X, const float* W, const float* A, const float* B,
+                                           const float* dY, int32_t T, int32_t d_in, int32_t d_out, int32_t r, float s,
+                                           float lr, float beta1, float beta2, float eps, float wd, int32_t apply_adamw,
+                                           float* Y, float* dX, float* dA, float* dB, float* A_new, float* B_new,
+                                           void* hip_stream) {
+    TLCHK(linear_step_args(X, W, A, B, dY, T, d_in, d_out, r, apply_adamw, Y, dX, dA, dB, A_new, B_new));
+    // sub-buffers start on 256-byte boundaries
+    auto up = [](size_t n) { return (n + 63) & ~(size_t)63; };
+    const size_t n_h = up((size_t)T * r);
+    const size_t n_mom = apply_adamw ? up(2 * ((size_t)r * d_in + (size_t)d_out * r)) : 0;
+    const size_t need = 2 * n_h + n_mom;
+    if (need > kStaticScratchFloats)
+        return fail(TL_ERR_SHAPE, "tl_linear_step_static: needs %zu floats of scratch (2 T r%s), the static buffer holds %zu; "
+                                  "use tl_linear_step", need, apply_adamw ? " + 2 r (d_in + d_out)" : "", kStaticScratchFloats);
+    float* base = nullptr;
+    TLCHK(static_scratch(&base));
+    hipStream_t st = (hipStream_t)hip_stream;
+    tl_status rc = linear_step_run(X, W, A, B, dY, T, d_in, d_out, r, s, lr, beta1, beta2, eps, wd, apply_adamw, Y, dX, dA,
+                                   dB, A_new, B_new, base, base + n_h, apply_adamw ? base + 2 * n_h : nullptr, st);
+    if (rc != TL_OK) (void)hipStreamSynchronize(st);
     return rc;
 }
 
