@@ -101,12 +101,17 @@ def _oracle_update(model, facs, opt, tok, n_ctx, lr, keep=()):
                           lambda l: model.host_layers[l], facs, opt, lr, keep=keep)
 
 
-def _compare_update(api, lora, shape, res, old_facs, new_facs, lr):
+def _compare_update(api, lora, shape, res, old_facs, new_facs, lr, cancel_zero=False):
     """Gradients against the oracle; the step against the oracle's AdamW fed the GPU's own gradient (tight);
     the new factors against the oracle's new factors.  The first AdamW step is -lr * g / (|g| + eps), a sign
     function of g: where a factor starts at zero (B = 0) an entry whose gradient lies within the bf16 error of
-    zero may land on either side, so there the comparison is the closed form plus sign agreement."""
+    zero may land on either side, so there the comparison is the closed form plus sign agreement.
+    cancel_zero: the two-token case.  Its only target row attends to one key, so the oracle's dS = P (dP - rowsum(dP P))
+    is x - x = 0 in fp64 and the q / k gradients vanish identically; in fp32 the two sums are taken in different orders
+    and cancel to rounding (measured 2e-9 of the v gradient), so there the bound is 1e-6 of the largest gradient entry
+    of the same layer instead of exact zero."""
     for l in range(shape.n_layers):
+        scale = max(np.abs(np.asarray(res["grads"][l][p][w])).max() for p in PROJ for w in (0, 1))
         for i, p in enumerate(PROJ):
             dout, din = shape.proj_dims(p)
             for w, (gsel, fsel, shp) in enumerate(((api.GRAD_A, api.FACTOR_A, (shape.rank, din)),
@@ -115,7 +120,9 @@ def _compare_update(api, lora, shape, res, old_facs, new_facs, lr):
                 g = api.tl_get_factor(lora, l, i, gsel, shp)
                 new = api.tl_get_factor(lora, l, i, fsel, shp)
                 old = old_facs[l][p][w]
-                check(g, res["grads"][l][p][w], BF16_TOL, "d" + tag)
+                check(g, res["grads"][l][p][w], BF16_TOL, "d" + tag, zero_atol=1e-6 * scale if cancel_zero else 0.0)
+                if cancel_zero and not np.any(res["grads"][l][p][w]):
+                    continue      # AdamW's first step is a sign function: on rounding noise around zero it says nothing
                 own, _, _ = O.adamw_step(old, g, 0, 0, 1, lr)
                 check(new - old, own - old, 1e-3, "step of " + tag)
                 if np.any(old != 0):
@@ -142,7 +149,7 @@ def test_chunk_update_matches_oracle(api, H, name, T, n_ctx, b_std):
     check(api.tl_get_dh(lora, shape.n_layers, T, shape.d_model), res["dh"]["final"], BF16_TOL, "dh final")
     for l in range(shape.n_layers):
         check(api.tl_get_dh(lora, l, T, shape.d_model), res["dh"][l], BF16_TOL, f"dh layer {l}")
-    _compare_update(api, lora, shape, res, facs, new_facs, LR)
+    _compare_update(api, lora, shape, res, facs, new_facs, LR, cancel_zero=(T == 2))
     if b_std == 0.0:
         # B = 0: dA is exactly zero and A is untouched; every B entry moved by ~lr (AdamW step-1 closed form)
         for l in range(shape.n_layers):
