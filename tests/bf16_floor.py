@@ -202,6 +202,18 @@ def chunk_update(tokens, n_ctx, shape, emb, head, g_final, get_layer, lora, opt,
     return res, new_lora, {"tau": tau, "m": new_m, "v": new_v}
 
 
+def chunk_train(tokens, n_chunk, L_T, batch, epochs, lr, warmup_steps, shape, emb, head, g_final, get_layer, lora, opt):
+    """The replay of oracle.chunk_train: same samples, same warm-up, steps made by chunk_update above."""
+    tok = np.asarray(tokens, dtype=np.int64)
+    losses = []
+    for _ in range(epochs):
+        for first, n_ctx, end in O.training_samples(tok.size - n_chunk, n_chunk, L_T, batch):
+            rate = O.warmup_lr(lr, opt["tau"], warmup_steps)
+            res, lora, opt = chunk_update(tok[first:end], n_ctx, shape, emb, head, g_final, get_layer, lora, opt, rate)
+            losses.append(res["loss"])
+    return losses, lora, opt
+
+
 def rel_err(x, ref):
     x, ref = np.asarray(x, dtype=F64), np.asarray(ref, dtype=F64)
     n = np.linalg.norm(ref)

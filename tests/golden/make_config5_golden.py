@@ -12,6 +12,14 @@ Stored: loss and per-position nll of every step; for layers 0, 16, 31 and every 
 every step and of A and B after the last step (two rows each, 256 columns of the wide ones), with full-tensor norms.
 
     python tests/golden/make_config5_golden.py [n_layers]      (about an hour on 8 cores, ~35 GB peak)
+    python tests/golden/make_config5_golden.py floor            (another hour; adds the floor_* entries to the file)
+
+`floor` replays the same four steps with tests/bf16_floor.py (the oracle's arithmetic in fp64, rounded to bf16 / fp32
+exactly where the storage format of Section 3 "Setup" stores a tensor; AdamW state in fp32; no kernel involved) and
+stores, next to every sample already in the file, that replay's error against it as (relative L2, max-abs / 10 RMS):
+what ANY bf16 implementation of the stream differs from the fp64 oracle by, step by step.  From the second step on the
+replay's own B = -lr sign(dB) differs from the oracle's wherever a dB entry lies inside the storage noise, which is why
+the dA floors of steps 1-3 are tens of per cent.
 """
 import os
 import sys
@@ -21,6 +29,8 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import bf16_floor as F  # noqa: E402
 from oracle import templora_oracle as O  # noqa: E402
 from paper_2401_11504_amd import synth  # noqa: E402
 
@@ -86,5 +96,63 @@ def main(n_layers=32):
     print("wrote", OUT, flush=True)
 
 
+def floor():
+    gold = dict(np.load(OUT))
+    shape = synth.SHAPES["7b"].with_layers(int(gold["n_layers"]))
+    stream = synth.zipf_tokens(SEED, N_CHUNKS * T, shape.vocab)
+    assert np.array_equal(stream, gold["tokens"])
+    emb, head = synth.embedding(SEED, shape), synth.lm_head(SEED, shape)
+    lora = [synth.lora_factors(SEED, shape, l) for l in range(shape.n_layers)]
+    opt = O.new_opt_state(lora)
+    cache = {}
+
+    def get_layer(l):
+        if l not in cache:
+            cache.clear()
+            cache[l] = synth.layer_weights(SEED, shape, l)
+        return cache[l]
+
+    def sample_err(x, ref):
+        x, ref = np.asarray(x, np.float64), np.asarray(ref, np.float64)
+        nr = np.linalg.norm(ref)
+        if nr == 0:
+            return np.array([float(np.linalg.norm(x)), float(np.max(np.abs(x)))])
+        rms = nr / np.sqrt(ref.size)
+        return np.array([np.linalg.norm(x - ref) / nr, np.max(np.abs(x - ref)) / (10.0 * rms)])
+
+    keep = [int(x) for x in gold["keep"]]
+    for step in range(int(gold["n_steps"])):
+        tok = stream[(step // N_EPOCHS) * T:(step // N_EPOCHS + 1) * T]
+        t0 = time.time()
+        res, lora, opt = F.chunk_update(tok, 0, shape, emb, head, np.ones(shape.d_model), get_layer, lora, opt, LR)
+        ref_loss = float(gold[f"loss_{step}"])
+        gold[f"floor_loss_{step}"] = np.float64(abs(res["loss"] - ref_loss) / ref_loss)
+        gold[f"floor_nll_{step}"] = sample_err(res["nll"], gold[f"nll_{step}"])
+        for l in keep:
+            for i, p in enumerate(synth.PROJ):
+                dA, dB = res["grads"][l][p]
+                ra, ca, rb = gold[f"rowsA_{l}_{i}"], gold[f"colsA_{l}_{i}"], gold[f"rowsB_{l}_{i}"]
+                gold[f"floor_dA_{step}_{l}_{i}"] = sample_err(dA[np.ix_(ra, ca)], gold[f"dA_{step}_{l}_{i}"])
+                gold[f"floor_dB_{step}_{l}_{i}"] = sample_err(dB[rb], gold[f"dB_{step}_{l}_{i}"])
+                gold[f"floor_dA_norm_{step}_{l}_{i}"] = np.float64(
+                    abs(np.linalg.norm(dA) - float(gold[f"dA_norm_{step}_{l}_{i}"])) / max(float(gold[f"dA_norm_{step}_{l}_{i}"]), 1e-300))
+        print(f"replay step {step}: {time.time() - t0:.1f} s, loss floor {gold[f'floor_loss_{step}']:.2e}, largest dA / dB floor "
+              f"{max(gold[f'floor_dA_{step}_{l}_{i}'][0] for l in keep for i in range(7)):.3f} / "
+              f"{max(gold[f'floor_dB_{step}_{l}_{i}'][0] for l in keep for i in range(7)):.3f}", flush=True)
+        del res
+    for l in keep:
+        for i, p in enumerate(synth.PROJ):
+            A, B = lora[l][p]
+            ra, ca, rb = gold[f"rowsA_{l}_{i}"], gold[f"colsA_{l}_{i}"], gold[f"rowsB_{l}_{i}"]
+            gold[f"floor_A_final_{l}_{i}"] = np.float64(np.max(np.abs(np.asarray(A)[np.ix_(ra, ca)] - gold[f"A_final_{l}_{i}"])))
+            b, rb_ = np.asarray(B)[rb].ravel(), np.asarray(gold[f"B_final_{l}_{i}"], np.float64).ravel()
+            gold[f"floor_B_final_cos_{l}_{i}"] = np.float64(b @ rb_ / (np.linalg.norm(b) * np.linalg.norm(rb_)))
+    np.savez_compressed(OUT, **gold)
+    print("wrote", OUT, flush=True)
+
+
 if __name__ == "__main__":
-    main(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
+    if sys.argv[1:] == ["floor"]:
+        floor()
+    else:
+        main(int(sys.argv[1]) if len(sys.argv) > 1 else 32)

@@ -6,9 +6,11 @@ L_T tokens as the input and the chunk as the output"), i.e. 2048 tokens with n_c
 positions carry loss -- on a decoder of the 7B width (d 4096, 32x128 heads, ffn 11008, vocab 32000, r = 64) cut to
 four layers so that the oracle finishes in minutes and every tensor can be held to the bf16 tolerance.
 
-Calls only oracle/ and the seeded input generator.  Zipf(1.1) token ids, A ~ N(0, 0.02^2), B ~ N(0, 0.01^2) (so that
+Calls only oracle/, the seeded input generator and tests/bf16_floor.py (built from oracle functions only).  Zipf(1.1) token ids, A ~ N(0, 0.02^2), B ~ N(0, 0.01^2) (so that
 dA != 0).  Stored: loss, n_targets, per-position nll, samples of the hidden-state gradient at every layer boundary and
-of dA / dB of every projection of every layer, with full-tensor norms.
+of dA / dB of every projection of every layer, with full-tensor norms; and next to every sample `floor_*`: the error
+of the bf16-boundary replay of the oracle (tests/bf16_floor.py) against the fp64 oracle on that sample, as (relative L2,
+max-abs / 10 RMS) -- what the storage format of Section 3 "Setup" alone costs, no kernel involved.
 
 The "piece" file is the layout of one of Table 5's smaller batches: the same 1024 conditioning tokens followed by a
 ragged piece of 333 tokens (1357 in all, no multiple of any tile), on two layers of the same width.
@@ -23,6 +25,8 @@ import numpy as np
 
 ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+import bf16_floor as F  # noqa: E402
 from oracle import templora_oracle as O  # noqa: E402
 from paper_2401_11504_amd import synth  # noqa: E402
 
@@ -79,6 +83,39 @@ def main():
             out[f"dB_{l}_{i}"] = f32(dB[rb])
             out[f"dA_norm_{l}_{i}"] = np.float64(np.linalg.norm(dA))
             out[f"dB_norm_{l}_{i}"] = np.float64(np.linalg.norm(dB))
+
+    def sample_err(x, ref):
+        x, ref = np.asarray(x, np.float64), np.asarray(ref, np.float64)
+        rms = np.sqrt(np.mean(ref * ref))
+        return np.array([np.linalg.norm(x - ref) / np.linalg.norm(ref), np.max(np.abs(x - ref)) / (10.0 * rms)])
+
+    t0 = time.time()
+    rep = F.model_fwd_bwd(tok, N_CTX, shape, emb, head, np.ones(shape.d_model), get_layer, lora, keep=keep)
+    out["floor_loss"] = np.float64(abs(rep["loss"] - res["loss"]) / abs(res["loss"]))
+    out["floor_nll"] = sample_err(rep["nll"], res["nll"])
+    out["floor_dh_final"] = sample_err(rep["dh"]["final"][np.ix_(rows_t, cols_d)], out["dh_final"])
+    for l in keep:
+        out[f"floor_dh_{l}"] = sample_err(rep["dh"][l][np.ix_(rows_t, cols_d)], res["dh"][l][np.ix_(rows_t, cols_d)])
+        if N_LAYERS != 4:     # conditioning rows and piece rows are bounded separately in the test
+            pre = rows_t < N_CTX - 1
+            for tag, sel in (("cond", pre), ("piece", ~pre)):
+                out[f"floor_dh_{tag}_{l}"] = sample_err(rep["dh"][l][np.ix_(rows_t[sel], cols_d)],
+                                                        res["dh"][l][np.ix_(rows_t[sel], cols_d)])
+        for i, p in enumerate(synth.PROJ):
+            dA, dB = rep["grads"][l][p]
+            rA, rB = res["grads"][l][p]
+            ra, ca, rb = out[f"rowsA_{l}_{i}"], out[f"colsA_{l}_{i}"], out[f"rowsB_{l}_{i}"]
+            out[f"floor_dA_{l}_{i}"] = sample_err(dA[np.ix_(ra, ca)], rA[np.ix_(ra, ca)])
+            out[f"floor_dB_{l}_{i}"] = sample_err(dB[rb], rB[rb])
+    if N_LAYERS != 4:
+        pre = rows_t < N_CTX - 1
+        for tag, sel in (("cond", pre), ("piece", ~pre)):
+            out[f"floor_dh_{tag}_final"] = sample_err(rep["dh"]["final"][np.ix_(rows_t[sel], cols_d)],
+                                                      res["dh"]["final"][np.ix_(rows_t[sel], cols_d)])
+    print(f"bf16-boundary replay: {time.time() - t0:.1f} s, loss floor {out['floor_loss']:.2e}; dh floors "
+          + " ".join(f"{out[f'floor_dh_{l}'][0]:.4f}" for l in keep) + "; largest dA / dB floor "
+          + f"{max(out[f'floor_dA_{l}_{i}'][0] for l in keep for i in range(7)):.4f} / "
+          + f"{max(out[f'floor_dB_{l}_{i}'][0] for l in keep for i in range(7)):.4f}", flush=True)
     np.savez_compressed(OUT, **out)
     print("wrote", OUT, flush=True)
 

@@ -2,17 +2,18 @@
 bench.py times, against values the CPU oracle computed once for the same seeded inputs
 (tests/golden/config3_7b_seed3000.npz, written by tests/golden/make_config3_golden.py, which calls only the
 oracle).  The oracle needs ~14 minutes and ~30 GB for this size, so its loss, per-position nll and samples of
-the gradients are stored; everything else is checked through properties that hold at any size
+the gradients -- the hidden-state gradient at EVERY layer boundary, dB of every projection of every layer --
+are stored; everything else is checked through properties that hold at any size
 (B = 0  =>  dA == 0 exactly and A untouched; first AdamW step moves every B entry by lr).
 
 Tolerances.  Loss, per-position nll, the gradient at the final norm and every tensor norm meet the bf16 bar
-(2e-2).  Tensors that sit behind many layers cannot: a random-init N(0, 0.02^2) decoder of this width is in
-the regime where a perturbation of the hidden state grows from layer to layer, so the ~2e-3 relative noise
-of bf16 storage is amplified with depth (measured: dX 0.2 % at the final norm, 1.6 % one layer down, 6.6 %
-at layer 16, 8.8 % at layer 0; dB 6-12 % at every depth because Hs at layer l carries the forward noise of l
-layers).  A single 7B-shaped layer from exact inputs meets 2e-2 on every output
-(test_config3_single_layer_full_shape), so the deep bound below (DEEP_TOL) is a statement about the
-conditioning of the synthetic workload, not about a kernel."""
+(2e-2).  Tensors that sit behind many layers cannot, whatever the kernels do: the same file stores, next to every
+sample, the error that a bf16-boundary replay of the ORACLE (its fp64 arithmetic, rounded to bf16 / fp32 only where
+the storage format of Section 3 "Setup" stores a tensor -- tests/bf16_floor.py, no kernel involved) has against
+the fp64 oracle on that sample: 0.2 % at the final norm, 1.6 % one layer down, 6 % at layer 16, 8 % at layer 0 for dX
+and 7-14 % for dB at every depth (Hs at layer l carries the forward rounding of l layers).  Each deep tensor is
+therefore held to max(2e-2, 1.5 x its own stored floor).  A single 7B-shaped layer from exact inputs meets 2e-2 on
+every output (test_config3_single_layer_full_shape)."""
 import os
 
 import numpy as np
@@ -23,10 +24,10 @@ pytestmark = pytest.mark.gpu
 
 from paper_2401_11504_amd import synth  # noqa: E402
 from test_gpu_kernels import BF16_TOL, check  # noqa: E402
+from test_gpu_depth import floor_tol  # noqa: E402
 
 GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_7b_seed3000.npz")
 LR = 5e-5
-DEEP_TOL = 0.15   # see the module docstring
 
 
 def _cos(a, b):
@@ -39,11 +40,12 @@ def test_config3_full_update_matches_stored_oracle():
     gold = np.load(GOLD)
     seed, T = int(gold["seed"]), 1024
     shape = synth.SHAPES["7b"]
-    assert int(gold["n_layers"]) == shape.n_layers
+    assert int(gold["n_layers"]) == shape.n_layers and int(gold["n_tokens"]) == T
     print("building the 7B-shaped synthetic model ...", flush=True)
     model = harness.Model(shape, seed, max_tokens=T, keep_host=False, workers=16)
     lora, facs = harness.new_lora(model, seed, b_std=0.0)
     tok = synth.uniform_tokens(seed, T, shape.vocab)
+    assert np.array_equal(tok, gold["tokens"])                          # same input bytes on both sides
     print("chunk update ...", flush=True)
     loss, n = api.tl_chunk_update(lora, tok, 0, LR)
     assert n == int(gold["n_targets"]) == T - 1                        # integer work: exact
@@ -53,13 +55,16 @@ def test_config3_full_update_matches_stored_oracle():
     check(nll, gold["nll"], BF16_TOL, "per-position nll")
     assert nll[-1] == 0.0
     rows, cols = gold["dh_rows"], gold["dh_cols"]
-    for name, boundary in [("dh_final", shape.n_layers)] + [(f"dh_{int(l)}", int(l)) for l in gold["keep"]]:
+    worst_dh = worst_db = 0.0
+    for name, boundary in [("dh_final", shape.n_layers)] + [(f"dh_{l}", l) for l in reversed(range(shape.n_layers))]:
         dh = api.tl_get_dh(lora, boundary, T, shape.d_model)
-        check(dh[np.ix_(rows, cols)], gold[name], BF16_TOL if boundary == shape.n_layers else DEEP_TOL, name)
-        assert _cos(dh[np.ix_(rows, cols)], gold[name]) > 0.99, name
+        s = dh[np.ix_(rows, cols)]
+        floor = gold["floor_" + name]
+        check(s, gold[name], BF16_TOL if boundary == shape.n_layers else floor_tol(floor), name)
+        worst_dh = max(worst_dh, np.linalg.norm(s - gold[name]) / np.linalg.norm(gold[name]) / float(floor[0]))
         norm_key = "dh_final_norm" if name == "dh_final" else f"dh_norm_{boundary}"
         assert abs(np.linalg.norm(dh.astype(np.float64)) - float(gold[norm_key])) <= BF16_TOL * float(gold[norm_key])
-    for l in [int(x) for x in gold["keep"]]:
+    for l in range(shape.n_layers):
         for i, p in enumerate(synth.PROJ):
             dout, din = shape.proj_dims(p)
             dA = api.tl_get_factor(lora, l, i, api.GRAD_A, (shape.rank, din))
@@ -67,8 +72,9 @@ def test_config3_full_update_matches_stored_oracle():
             assert np.array_equal(api.tl_get_factor(lora, l, i, api.FACTOR_A, (shape.rank, din)), facs[l][p][0])
             dB = api.tl_get_factor(lora, l, i, api.GRAD_B, (dout, shape.rank))
             r = gold[f"dB_rows_{l}_{i}"]
-            check(dB[r], gold[f"dB_{l}_{i}"], DEEP_TOL, f"dB l{l} {p} (sampled rows)")
-            assert _cos(dB[r], gold[f"dB_{l}_{i}"]) > 0.99, f"dB l{l} {p}"
+            floor = gold[f"floor_dB_{l}_{i}"]
+            check(dB[r], gold[f"dB_{l}_{i}"], floor_tol(floor), f"dB l{l} {p} (sampled rows)")
+            worst_db = max(worst_db, np.linalg.norm(dB[r] - gold[f"dB_{l}_{i}"]) / np.linalg.norm(gold[f"dB_{l}_{i}"]) / float(floor[0]))
             gn = float(gold[f"dB_norm_{l}_{i}"])
             assert abs(np.linalg.norm(dB.astype(np.float64)) - gn) <= BF16_TOL * gn, f"|dB| l{l} {p}"
             # AdamW step 1 from B = 0: every entry lands on -lr * sign(g) (closed form)
@@ -79,6 +85,7 @@ def test_config3_full_update_matches_stored_oracle():
             ga = np.abs(dB.astype(np.float64))
             assert np.allclose(np.abs(B1), LR * ga / (ga + 1e-8), rtol=1e-3, atol=1e-12)
             assert np.median(np.abs(B1)) > 0.9 * LR
+    print(f"largest GPU error / storage floor on the samples: dX {worst_dh:.3f}, dB {worst_db:.3f}", flush=True)
     assert api.tl_get_step(lora) == 1
     # second epoch on the same chunk: the loss must go down (B is no longer 0, dA becomes non-zero)
     loss2, _ = api.tl_chunk_update(lora, tok, 0, LR)

@@ -21,7 +21,8 @@ pytestmark = pytest.mark.gpu
 
 from paper_2401_11504_amd import synth  # noqa: E402
 from test_gpu_kernels import BF16_TOL, check  # noqa: E402
-from test_gpu_config3 import DEEP_TOL, _cos  # noqa: E402
+from test_gpu_config3 import _cos  # noqa: E402
+DEEP_TOL = 0.15   # replaced by stored floors once they are generated
 
 GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config5_7b_seed5000.npz")
 
