@@ -28,8 +28,13 @@ def H():
     return harness
 
 
-def check(gpu, ref, tol, name="", zero_atol=0.0):
-    """zero_atol: what |gpu| may reach where the oracle is identically zero.  0 (the default) for zeros that follow from
+def check(gpu, ref, tol, name="", zero_atol=0.0, per_row=False):
+    """per_row: the max-abs criterion is applied row by row, each row (token) against 10 * tol * its own RMS, instead of
+    against the RMS of the whole tensor.  For tensors whose rows differ in scale by orders of magnitude (dK and dV of a
+    5120-token causal attention: the first key is seen by 5120 queries, the last by one; row RMS 0.7 against 3e-4) the
+    whole-tensor RMS is set by the many small rows and 10 * tol * RMS falls below two bf16 roundings of the large
+    entries, which no bf16 output can meet; per row the criterion keeps its meaning on large and small rows alike.
+    zero_atol: what |gpu| may reach where the oracle is identically zero.  0 (the default) for zeros that follow from
     a zero operand (B = 0 gives dH = s dY 0, hence dA = 0 in any arithmetic); a caller passes a small absolute bound
     only where the oracle's zero is a cancellation x - x that fp32 sums taken in two orders reproduce to rounding."""
     gpu, ref = np.asarray(gpu, np.float64), np.asarray(ref, np.float64)
@@ -43,6 +48,16 @@ def check(gpu, ref, tol, name="", zero_atol=0.0):
     rms = nr / np.sqrt(ref.size)
     mx = np.abs(gpu - ref).max()
     assert rel <= tol, f"{name}: rel L2 {rel:.3e} > {tol}"
+    if per_row and ref.ndim == 2:
+        row_rms = np.sqrt(np.mean(ref * ref, axis=1))
+        row_mx = np.abs(gpu - ref).max(axis=1)
+        live = row_rms > 0
+        worst = np.max(row_mx[live] / (10 * tol * row_rms[live]))
+        assert worst <= 1.0, f"{name}: a row's max abs error is {worst:.3f} x (10 tol x that row's RMS)"
+        # a row that is identically zero in the oracle (dq of position 0: one key, dS = x - x) is a cancellation in
+        # fp32: rounding noise relative to the tensor's scale
+        assert np.all(np.abs(gpu[~live]) <= 1e-5 * np.abs(ref).max()), name
+        return
     assert mx <= 10 * tol * rms, f"{name}: max abs {mx:.3e} > {10 * tol * rms:.3e}"
 
 
@@ -242,8 +257,9 @@ def test_swiglu(api, H, T, f):
 # ------------------------------------------------------------------ attention
 # the last case has more workgroups than the chip has CUs (9 query blocks x 30 heads, ragged): the forward kernel then
 # hands its blocks out heaviest first, a different block-to-workgroup mapping from the one-round cases
+# (4096 and 5120 tokens: the longest training samples of the paper's Table 5, Delta = 4096 behind L_T = 1024)
 @pytest.mark.parametrize("T,nh,dh", [(64, 1, 64), (200, 2, 64), (333, 2, 128), (1024, 2, 128), (1, 1, 64), (129, 1, 128),
-                                     (1100, 30, 64)])
+                                     (1100, 30, 64), (4096, 2, 128), (5120, 2, 128), (5120, 1, 64)])
 def test_attention_fwd_bwd(api, H, T, nh, dh):
     qkv = rnd(1, (T, 3 * nh * dh), 1.0)
     do = rnd(2, (T, nh * dh))
@@ -269,9 +285,9 @@ def test_attention_fwd_bwd(api, H, T, nh, dh):
     torch.cuda.synchronize()
     dq, dk, dv = O.attention_bwd(do.reshape(T, nh, dh), q, k, v, P)
     g = H.bf16_to_np(dqkv)
-    check(g[:, :d], dq.reshape(T, d), BF16_TOL, "dq")
-    check(g[:, d:2 * d], dk.reshape(T, d), BF16_TOL, "dk")
-    check(g[:, 2 * d:], dv.reshape(T, d), BF16_TOL, "dv")
+    check(g[:, :d], dq.reshape(T, d), BF16_TOL, "dq", per_row=True)
+    check(g[:, d:2 * d], dk.reshape(T, d), BF16_TOL, "dk", per_row=True)
+    check(g[:, 2 * d:], dv.reshape(T, d), BF16_TOL, "dv", per_row=True)
 
 
 # ------------------------------------------------------------------ cross entropy
