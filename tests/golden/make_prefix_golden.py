@@ -87,6 +87,8 @@ def main():
     def sample_err(x, ref):
         x, ref = np.asarray(x, np.float64), np.asarray(ref, np.float64)
         rms = np.sqrt(np.mean(ref * ref))
+        if rms == 0.0:      # rows without any gradient (conditioning rows above the last layer): the replay gives zeros too
+            return np.array([np.linalg.norm(x), np.max(np.abs(x))])
         return np.array([np.linalg.norm(x - ref) / np.linalg.norm(ref), np.max(np.abs(x - ref)) / (10.0 * rms)])
 
     t0 = time.time()

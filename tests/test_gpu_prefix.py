@@ -7,13 +7,14 @@ tests/golden/make_prefix_golden.py (oracle only).
 The full 32-layer model is then run in the same layout and checked through what holds at any size (mask, count,
 normalisation, conditioning, descent).
 
-Tolerances.  Loss, per-position nll and the hidden-state gradient at every layer boundary meet the bf16 bar (2e-2;
-measured 1.7e-3 .. 1.7e-2).  The LoRA gradients are held to GRAD_TOL = 5e-2 with cosine > 0.995: behind even a few
+Tolerances.  Loss and per-position nll meet the bf16 bar (2e-2).  Every sampled gradient is held to
+max(2e-2, 1.5 x its own storage floor): the stored files carry, next to each sample, the error that the bf16-boundary
+replay of the ORACLE (tests/bf16_floor.py: fp64 arithmetic, rounded only where Section 3 "Setup"'s bfloat16 training
+stores a tensor; no kernel involved) has against the fp64 oracle on that sample.  On four layers those floors are
+0.9-1.6 % for the hidden-state gradients and up to 3.3 % (dA) / 4.3 % (dB) for the LoRA gradients -- behind even a few
 layers of bf16 activations the attention logits carry an absolute error of (relative input noise) x |logit|, which is
-the RELATIVE error of the rebuilt probabilities and therefore of dQ and dK (measured 3-4 % on the q and k projections,
-0.4-1.4 % on v, o and down here; the attention kernels alone, from exact inputs at the same length, are within 0.25 %
-of the oracle -- test_gpu_kernels.py).  A single layer from exact inputs meets 2e-2 on every gradient
-(test_gpu_config3.py::test_config3_single_layer_full_shape)."""
+the RELATIVE error of the rebuilt probabilities and therefore of dQ and dK.  A single layer from exact inputs meets
+2e-2 on every gradient (test_gpu_config3.py::test_config3_single_layer_full_shape)."""
 import os
 
 import numpy as np
@@ -25,13 +26,13 @@ pytestmark = pytest.mark.gpu
 from paper_2401_11504_amd import synth  # noqa: E402
 from test_gpu_kernels import BF16_TOL, check  # noqa: E402
 from test_gpu_config3 import _cos  # noqa: E402
+from test_gpu_depth import floor_tol  # noqa: E402
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 # the full sample (1024 + 1024 tokens, four layers) and one of Table 5's smaller batches: the same conditioning
 # followed by a ragged piece of 333 tokens (1357 in all: no multiple of any tile), two layers
 GOLD_FILES = ["prefix_7bwidth_L4_seed2048.npz", "prefix_7bwidth_L2_seed1357.npz"]
 LR = 5e-5
-GRAD_TOL = 5e-2   # see the module docstring
 
 
 @pytest.mark.parametrize("gold_file", GOLD_FILES)
@@ -56,12 +57,16 @@ def test_prefix_sample_7b_width_matches_stored_oracle(gold_file):
     for name, boundary in [("dh_final", shape.n_layers)] + [(f"dh_{l}", l) for l in range(shape.n_layers)]:
         dh = api.tl_get_dh(lora, boundary, T, shape.d_model)
         if n_split_rows:
-            # conditioning rows receive their gradient through dK and dV alone: the attention-gradient bar
+            # conditioning rows receive their gradient through dK and dV alone (10-20x smaller than a piece row's): the
+            # two kinds of row are compared separately, each against its own floor
             pre, post = rows < n_ctx - 1, rows >= n_ctx - 1
-            check(dh[np.ix_(rows[pre], cols)], gold[name][pre], GRAD_TOL, name + " (conditioning rows)")
-            check(dh[np.ix_(rows[post], cols)], gold[name][post], BF16_TOL, name + " (piece rows)")
+            tag = "final" if name == "dh_final" else str(boundary)
+            check(dh[np.ix_(rows[pre], cols)], gold[name][pre], floor_tol(gold[f"floor_dh_cond_{tag}"]),
+                  name + " (conditioning rows)")
+            check(dh[np.ix_(rows[post], cols)], gold[name][post], floor_tol(gold[f"floor_dh_piece_{tag}"]),
+                  name + " (piece rows)")
         else:
-            check(dh[np.ix_(rows, cols)], gold[name], BF16_TOL, name)
+            check(dh[np.ix_(rows, cols)], gold[name], floor_tol(gold["floor_" + name]), name)
         key = "dh_final_norm" if name == "dh_final" else f"dh_norm_{boundary}"
         assert abs(np.linalg.norm(dh.astype(np.float64)) - float(gold[key])) <= BF16_TOL * float(gold[key]), name
     for l in range(shape.n_layers):
@@ -70,8 +75,8 @@ def test_prefix_sample_7b_width_matches_stored_oracle(gold_file):
             dA = api.tl_get_factor(lora, l, i, api.GRAD_A, (shape.rank, din))
             dB = api.tl_get_factor(lora, l, i, api.GRAD_B, (dout, shape.rank))
             sa, sb = dA[np.ix_(gold[f"rowsA_{l}_{i}"], gold[f"colsA_{l}_{i}"])], dB[gold[f"rowsB_{l}_{i}"]]
-            check(sa, gold[f"dA_{l}_{i}"], GRAD_TOL, f"dA l{l} {p}")
-            check(sb, gold[f"dB_{l}_{i}"], GRAD_TOL, f"dB l{l} {p}")
+            check(sa, gold[f"dA_{l}_{i}"], floor_tol(gold[f"floor_dA_{l}_{i}"]), f"dA l{l} {p}")
+            check(sb, gold[f"dB_{l}_{i}"], floor_tol(gold[f"floor_dB_{l}_{i}"]), f"dB l{l} {p}")
             assert _cos(sa, gold[f"dA_{l}_{i}"]) > 0.995 and _cos(sb, gold[f"dB_{l}_{i}"]) > 0.995, (l, p)
             for g, key in ((dA, f"dA_norm_{l}_{i}"), (dB, f"dB_norm_{l}_{i}")):
                 assert abs(np.linalg.norm(g.astype(np.float64)) - float(gold[key])) <= BF16_TOL * float(gold[key]), key
