@@ -4,7 +4,10 @@
 //   forward / dQ :  S^T[u][t] = K[u] . Q[t]   -> a lane owns one query t (and its partner lane t too),
 //                   so the running max, the row sum, lse[t] and delta[t] are per-lane scalars;
 //                   O^T[d][t] += V^T[d][u] P^T[u][t]   and   dQ^T[d][t] += K^T[d][u] dS^T[u][t]
-//                   reuse the score fragment directly as the B operand (see tiles.h).
+//                   reuse the score fragment directly as the B operand (see tiles.h); their A operands V^T, K^T (and
+//                   dO^T, Q^T below) are never built: the tiles stay as they lie in memory and are read through the
+//                   LDS transpose read of gfx950 (load_a_tr in tiles.h), which costs no bank conflicts and no
+//                   transposing stores.
 //   dK / dV      :  S[t][u] = Q[t] . K[u]     -> a lane owns one key u;
 //                   dV^T[d][u] += dO^T[d][t] P[t][u],  dK^T[d][u] += Q^T[d][t] dS[t][u].
 // P is never stored: the backward kernels rebuild it from the saved log-sum-exp.
@@ -44,37 +47,14 @@ __device__ __forceinline__ void store_tile_normal(bf16_t* tile, const uint4* reg
         *(uint4*)(tile + row * AttnCfg<DH>::LSK + ch * 8) = regs[i];
     }
 }
-// the same tile as row pairs for the transposing store: unit = (row pair, 8-column chunk)
-template <int DH, int NT>
-__device__ __forceinline__ void load_tile_pairs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs,
-                                                int tid = threadIdx.x) {
+// the same with row stride LD (tiles that are read with the LDS transpose read, see load_a_tr)
+template <int DH, int NT, int LD>
+__device__ __forceinline__ void store_tile_ld(bf16_t* tile, const uint4* regs, int tid = threadIdx.x) {
     constexpr int CH = DH / 8;
 #pragma unroll
-    for (int i = 0; i < 4 * DH / NT; ++i) {
-        const int c = tid + NT * i, rp = c / CH, ch = c % CH;
-        const int r = r0 + 2 * rp;
-        regs[2 * i] = (r < T) ? *(const uint4*)(base + (long)r * ld + ch * 8) : make_uint4(0, 0, 0, 0);
-        regs[2 * i + 1] = (r + 1 < T) ? *(const uint4*)(base + (long)(r + 1) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
-    }
-}
-template <int DH, int NT>
-__device__ __forceinline__ void store_tile_transposed(bf16_t* tile, const uint4* regs, int tid = threadIdx.x) {
-    constexpr int CH = DH / 8;
-#pragma unroll
-    for (int i = 0; i < 4 * DH / NT; ++i) {
-        const int c = tid + NT * i, rp = c / CH, ch = c % CH;
-        store_transposed_pair(tile, ch * 8, 2 * rp, regs[2 * i], regs[2 * i + 1]);
-    }
-}
-// registers loaded by load_tile_pairs stored as an ordinary [row][d] tile
-template <int DH, int NT>
-__device__ __forceinline__ void store_pairs_normal(bf16_t* tile, const uint4* regs, int tid = threadIdx.x) {
-    constexpr int CH = DH / 8;
-#pragma unroll
-    for (int i = 0; i < 4 * DH / NT; ++i) {
-        const int c = tid + NT * i, rp = c / CH, ch = c % CH;
-        *(uint4*)(tile + (2 * rp) * AttnCfg<DH>::LSK + ch * 8) = regs[2 * i];
-        *(uint4*)(tile + (2 * rp + 1) * AttnCfg<DH>::LSK + ch * 8) = regs[2 * i + 1];
+    for (int i = 0; i < 8 * DH / NT; ++i) {
+        const int c = tid + NT * i, row = c / CH, ch = c % CH;
+        *(uint4*)(tile + row * LD + ch * 8) = regs[i];
     }
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -108,12 +88,14 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
                                                                 float scale_log2e) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
-    constexpr int GROUP_ELEMS = 64 * C::LSK + DH * LST;          // bf16 elements of one group's K and V^T tiles
+    constexpr int LDV = LTR(DH);
+    constexpr int GROUP_ELEMS = 64 * C::LSK + 64 * LDV;          // bf16 elements of one group's K and V tiles
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / NT);
     const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
-    bf16_t* sVt = sK + 64 * C::LSK;
+    bf16_t* sV = sK + 64 * C::LSK;
+    const int tr_off = tr_lane_offset(lane, LDV);
     // Heaviest (latest) query blocks first; the second half of the heads takes the mirrored block, so that two
     // workgroups placed on one CU by round-robin dispatch (ids i and i + n/2 in dispatch order, x fastest) carry the
     // same total number of key tiles whichever CU they land on.
@@ -148,16 +130,16 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
     const int n_iter = (n_tiles + KG - 1) / KG;   // a group's surplus tile lies wholly in the future and is skipped
     uint4 rk[8 * DH / NT], rv[8 * DH / NT];
     load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
-    load_tile_pairs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
+    load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
     for (int it = 0; it < n_iter; ++it) {
         const int u0 = (it * KG + kg) * 64;
         __syncthreads();
         store_tile_normal<DH, NT>(sK, rk, tid);
-        store_tile_transposed<DH, NT>(sVt, rv, tid);
+        store_tile_ld<DH, NT, LDV>(sV, rv, tid);                 // V as it lies in memory: P V reads it transposed
         __syncthreads();
         if (it + 1 < n_iter) {
             load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
-            load_tile_pairs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
+            load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
         }
         if (u0 > tq0 + 31) continue;  // wave-uniform: every key of this tile is in the future
         // both 32-key halves of the tile at once: two independent MFMA chains, one softmax update
@@ -211,7 +193,7 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
                 const bf16x8_t b = pack_b_from_d(x + 16 * us, h);
 #pragma unroll
                 for (int dt = 0; dt < C::ND; ++dt) {
-                    const bf16x8_t a = load_a_permuted(sVt, dt * 32 + l32, us * 32 + 16 * h, g);
+                    const bf16x8_t a = load_a_tr(sV, LDV, tr_off, dt * 32, us * 32 + 16 * h);
                     oacc[dt] = mfma32(a, b, oacc[dt]);
                 }
             }
@@ -279,12 +261,14 @@ __device__ __forceinline__ void attn_dq_block(
     bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope, int qb, int head, unsigned char* smem_raw) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
-    constexpr int GROUP_ELEMS = 2 * 64 * C::LSK + DH * LST;
+    constexpr int LDT = LTR(DH);
+    constexpr int GROUP_ELEMS = 2 * 64 * C::LSK + 64 * LDT;
     const int kg = __builtin_amdgcn_readfirstlane(threadIdx.x / NT);
     const int tid = threadIdx.x % NT, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
     bf16_t* sK = (bf16_t*)smem_raw + kg * GROUP_ELEMS;
     bf16_t* sV = sK + 64 * C::LSK;
-    bf16_t* sKt = sV + 64 * C::LSK;
+    bf16_t* sK2 = sV + 64 * C::LSK;         // K once more, with the row stride of the LDS transpose read (dS K)
+    const int tr_off = tr_lane_offset(lane, LDT);
     const int q0 = qb * QB, tq0 = q0 + 32 * wave, t_abs = tq0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
     const bf16_t* qh = q + (long)head * DH;
@@ -318,17 +302,17 @@ __device__ __forceinline__ void attn_dq_block(
     const int n_tiles = (kend + 63) / 64;
     const int n_iter = (n_tiles + KG - 1) / KG;
     uint4 rk[8 * DH / NT], rv[8 * DH / NT];
-    load_tile_pairs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
+    load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
     load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
     for (int it = 0; it < n_iter; ++it) {
         const int u0 = (it * KG + kg) * 64;
         __syncthreads();
-        store_pairs_normal<DH, NT>(sK, rk, tid);
-        store_tile_transposed<DH, NT>(sKt, rk, tid);
+        store_tile_normal<DH, NT>(sK, rk, tid);
+        store_tile_ld<DH, NT, LDT>(sK2, rk, tid);
         store_tile_normal<DH, NT>(sV, rv, tid);
         __syncthreads();
         if (it + 1 < n_iter) {
-            load_tile_pairs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
+            load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
             load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
         }
         if (u0 > tq0 + 31) continue;
@@ -363,7 +347,7 @@ __device__ __forceinline__ void attn_dq_block(
                 const bf16x8_t b = pack_b_from_d(ds + 16 * us, h);
 #pragma unroll
                 for (int dt = 0; dt < C::ND; ++dt) {
-                    const bf16x8_t a = load_a_permuted(sKt, dt * 32 + l32, us * 32 + 16 * h, g);
+                    const bf16x8_t a = load_a_tr(sK2, LDT, tr_off, dt * 32, us * 32 + 16 * h);
                     acc[dt] = mfma32(a, b, acc[dt]);
                 }
             }
@@ -401,13 +385,15 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
                                                unsigned char* smem) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, KB = NW * 32;
+    constexpr int LDT = LTR(DH);
     bf16_t* sQ = (bf16_t*)smem;             // [64][LSK]
     bf16_t* sdO = sQ + 64 * C::LSK;         // [64][LSK]
-    bf16_t* sQt = sdO + 64 * C::LSK;        // [DH][LST]
-    bf16_t* sdOt = sQt + DH * LST;           // [DH][LST]
-    float* sLse = (float*)(sdOt + DH * LST); // [64]
+    bf16_t* sQ2 = sdO + 64 * C::LSK;        // [64][LDT]: Q and dO once more, with the row stride of the LDS transpose
+    bf16_t* sdO2 = sQ2 + 64 * LDT;          // [64][LDT]  read (dS^T Q and P^T dO take them with the token index as contraction)
+    float* sLse = (float*)(sdO2 + 64 * LDT); // [64]
     float* sDelta = sLse + 64;              // [64]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, g = lane >> 5;
+    const int tr_off = tr_lane_offset(lane, LDT);
     const int u0 = kb * KB, uw0 = u0 + 32 * wave, u_abs = uw0 + l32;
     const float scale_log2e = scale * 1.4426950408889634f;
     const bf16_t* qh = q + (long)head * DH;
@@ -433,8 +419,8 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
     float lse_v = 0.f, dl_v = 0.f;
     auto fetch = [&](int tile) {
         const int t0 = tile * 64;
-        load_tile_pairs<DH, NT>(qh, ldq, t0, T, rq);
-        load_tile_pairs<DH, NT>(doh, ldo, t0, T, rdo);
+        load_tile_regs<DH, NT>(qh, ldq, t0, T, rq);
+        load_tile_regs<DH, NT>(doh, ldo, t0, T, rdo);
         if (tid < 64) {
             const int t = t0 + tid;
             lse_v = (t < T) ? lse[(long)head * T + t] * 1.4426950408889634f : 1.0e30f;
@@ -445,10 +431,10 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
     for (int tile = tile0; tile < n_tiles; ++tile) {
         const int t0 = tile * 64;
         __syncthreads();
-        store_pairs_normal<DH, NT>(sQ, rq);
-        store_pairs_normal<DH, NT>(sdO, rdo);
-        store_tile_transposed<DH, NT>(sQt, rq);
-        store_tile_transposed<DH, NT>(sdOt, rdo);
+        store_tile_normal<DH, NT>(sQ, rq);
+        store_tile_normal<DH, NT>(sdO, rdo);
+        store_tile_ld<DH, NT, LDT>(sQ2, rq);
+        store_tile_ld<DH, NT, LDT>(sdO2, rdo);
         if (tid < 64) { sLse[tid] = lse_v; sDelta[tid] = dl_v; }
         __syncthreads();
         if (tile + 1 < n_tiles) fetch(tile + 1);
@@ -491,9 +477,9 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
                 const bf16x8_t bs = pack_b_from_d(ds, h);
 #pragma unroll
                 for (int dt = 0; dt < C::ND; ++dt) {
-                    const bf16x8_t a1 = load_a_permuted(sdOt, dt * 32 + l32, ts * 32 + 16 * h, g);
+                    const bf16x8_t a1 = load_a_tr(sdO2, LDT, tr_off, dt * 32, ts * 32 + 16 * h);
                     dvacc[dt] = mfma32(a1, bp, dvacc[dt]);
-                    const bf16x8_t a2 = load_a_permuted(sQt, dt * 32 + l32, ts * 32 + 16 * h, g);
+                    const bf16x8_t a2 = load_a_tr(sQ2, LDT, tr_off, dt * 32, ts * 32 + 16 * h);
                     dkacc[dt] = mfma32(a2, bs, dkacc[dt]);
                 }
             }
@@ -544,7 +530,7 @@ template <int DH, int NW, int KG>
 static hipError_t run_fwd(dim3 grid, const bf16_t* q, const bf16_t* k, const bf16_t* v, long ldq, int T, bf16_t* o,
                           long ldo, float* lse, float sl2, hipStream_t s) {
     using C = AttnCfg<DH>;
-    size_t lds = (size_t)KG * (64 * C::LSK + DH * LST) * sizeof(bf16_t);
+    size_t lds = (size_t)KG * (64 * C::LSK + 64 * LTR(DH)) * sizeof(bf16_t);
     const size_t merge = KG > 1 ? (size_t)NW * 64 * (C::ND * 16 + 2) * sizeof(float) : 0;
     if (merge > lds) lds = merge;
     auto kern = attn_fwd_kernel<DH, NW, KG>;
@@ -594,12 +580,12 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
     constexpr int NW = ATTN_NW;
     const float scale = 1.f / sqrtf((float)DH);
     dim3 grid(cdiv(T, NW * 32), n_heads, 2);
-    const size_t lds_kv = (size_t)(2 * 64 * C::LSK + 2 * DH * LST) * sizeof(bf16_t) + 128 * sizeof(float);
+    const size_t lds_kv = (size_t)(2 * 64 * C::LSK + 2 * 64 * LTR(DH)) * sizeof(bf16_t) + 128 * sizeof(float);
     const long items = (long)T * n_heads * (DH / 8);
     attn_delta_kernel<DH><<<cdiv(items, 256), 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t lds_q = (size_t)(2 * 64 * C::LSK + DH * LST) * sizeof(bf16_t);
+    const size_t lds_q = (size_t)(2 * 64 * C::LSK + 64 * LTR(DH)) * sizeof(bf16_t);
     const size_t lds = lds_q > lds_kv ? lds_q : lds_kv;
     auto kern = attn_bwd_fused_kernel<DH, NW>;
     e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
