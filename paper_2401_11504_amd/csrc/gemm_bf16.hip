@@ -782,18 +782,21 @@ hipError_t launch_gemm_nt(const GemmNT& g, hipStream_t s) {
 }
 
 // ======================================================================== TN
-// Transposing store of a [64 t][64 i] operand tile: thread (tp, ic) holds rows t = 2tp, 2tp+1 and the
-// 8 columns i = 8ic..8ic+7, and writes 8 dwords (t, t+1) pairs into the [i][t] LDS tile.  The 8-element
-// t-chunk index is XORed with (i / 8) % 8 so that the 8 column groups of one row land in distinct banks.
-// One 64x64 output tile of P^T Q over the 64-token tiles [it0, it1): two LDS buffers per operand (one barrier per
-// token tile), the next tile's global loads issued a full tile ahead.  Returns this wave's 32x32 accumulator.
+// One 64x64 output tile of P^T Q over the 64-token tiles [it0, it1).  The operand tiles stay in LDS as they lie in
+// memory, [t][i] with the token index t as rows, and the matrix unit's operands (contraction over t) come out of the
+// LDS transpose read of gfx950 (load_a_tr in tiles.h): no transposing stores, no bank conflicts.  Both operands use the
+// same slot order, so the permutation that load_a_tr applies to the 16 contraction slots of a step cancels.  Two LDS
+// buffers per operand (one barrier per token tile), the next tile's global loads issued a full tile ahead.  Thread
+// (tp, ic) moves rows t = 2tp, 2tp+1 and the 8 columns i = 8ic..8ic+7.  Returns this wave's 32x32 accumulator.
 __device__ __forceinline__ f32x16_t tn_tile(const bf16_t* P, long ldp, int Mo, const bf16_t* Q, long ldq, int No, int T,
                                             int i0, int j0, int it0, int it1) {
-    __shared__ __align__(16) bf16_t sP[2][64 * LST];
-    __shared__ __align__(16) bf16_t sQ[2][64 * LST];
+    constexpr int LD = LTR(64);
+    __shared__ __align__(16) bf16_t sP[2][64 * LD];
+    __shared__ __align__(16) bf16_t sQ[2][64 * LD];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wi = wave >> 1, wj = wave & 1, l32 = lane & 31, g = lane >> 5;
+    const int wi = wave >> 1, wj = wave & 1;
     const int tp = tid >> 3, ic = tid & 7;
+    const int tr_off = tr_lane_offset(lane, LD);
     f32x16_t acc = zero16();
     auto ld = [&](const bf16_t* base, long ldx, int c0, int cmax, int t) -> uint4 {
         const int c = c0 + ic * 8;
@@ -805,26 +808,29 @@ __device__ __forceinline__ f32x16_t tn_tile(const bf16_t* P, long ldp, int Mo, c
         p0 = ld(P, ldp, i0, Mo, t); p1 = ld(P, ldp, i0, Mo, t + 1);
         q0 = ld(Q, ldq, j0, No, t); q1 = ld(Q, ldq, j0, No, t + 1);
     };
+    auto park = [&](int buf) {
+        *(uint4*)(sP[buf] + (2 * tp) * LD + ic * 8) = p0;
+        *(uint4*)(sP[buf] + (2 * tp + 1) * LD + ic * 8) = p1;
+        *(uint4*)(sQ[buf] + (2 * tp) * LD + ic * 8) = q0;
+        *(uint4*)(sQ[buf] + (2 * tp + 1) * LD + ic * 8) = q1;
+    };
     if (it0 < it1) {
         gload(it0);
-        store_transposed_pair(sP[0], ic * 8, 2 * tp, p0, p1);
-        store_transposed_pair(sQ[0], ic * 8, 2 * tp, q0, q1);
+        park(0);
         if (it0 + 1 < it1) gload(it0 + 1);
     }
     __syncthreads();
-    const int ri = wi * 32 + l32, rj = wj * 32 + l32;
     for (int it = it0; it < it1; ++it) {
         const int buf = (it - it0) & 1;
         // registers hold tile it+1: park it in the other buffer, then fetch tile it+2
         if (it + 1 < it1) {
-            store_transposed_pair(sP[buf ^ 1], ic * 8, 2 * tp, p0, p1);
-            store_transposed_pair(sQ[buf ^ 1], ic * 8, 2 * tp, q0, q1);
+            park(buf ^ 1);
             if (it + 2 < it1) gload(it + 2);
         }
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8_t a = load_a_linear(sP[buf], ri, ks * 16 + g * 8);
-            const bf16x8_t b = load_a_linear(sQ[buf], rj, ks * 16 + g * 8);
+            const bf16x8_t a = load_a_tr(sP[buf], LD, tr_off, wi * 32, ks * 16);
+            const bf16x8_t b = load_a_tr(sQ[buf], LD, tr_off, wj * 32, ks * 16);
             acc = mfma32(a, b, acc);
         }
         __syncthreads();

@@ -25,32 +25,14 @@ __device__ __forceinline__ f32x16_t zero16() {
     return z;
 }
 
-// Offset of element (i, t) in a transposed [i][t] tile, t < 64 (LDS has 64 banks: 256 bytes per clock).
-// Rows are 68 elements = 17 x 8 bytes, so 32 lanes reading 8 bytes of 32 consecutive rows at the same t hit 32
-// distinct 8-byte slots; the 8-byte slot index inside a row is XORed with 2 * ((i / 32) % 4), which is constant
-// over such a read and spreads the dword stores of one source row (whose columns i are 8 apart per lane) over
-// all banks.
-#define LST 68
-__device__ __forceinline__ int tn_off(int i, int t) { return i * LST + ((((t >> 2) ^ (((i >> 5) & 3) << 1))) << 2) + (t & 3); }
-
-// Thread holds source rows t, t+1 (t even) and 8 columns i0..i0+7; writes 8 dwords into the [i][t] tile.
-__device__ __forceinline__ void store_transposed_pair(bf16_t* tile, int i0, int t, uint4 r0, uint4 r1) {
-    const uint32_t a[4] = {r0.x, r0.y, r0.z, r0.w}, b[4] = {r1.x, r1.y, r1.z, r1.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const uint32_t lo = (a[e] & 0xffffu) | (b[e] << 16);
-        const uint32_t hi = (a[e] >> 16) | (b[e] & 0xffff0000u);
-        *(uint32_t*)(tile + tn_off(i0 + 2 * e, t)) = lo;
-        *(uint32_t*)(tile + tn_off(i0 + 2 * e + 1, t)) = hi;
-    }
-}
-
-// A operand for a D-fragment-as-B product (contraction slots 16h + {4g..4g+3, 8+4g..8+4g+3}, see the top of this file)
-// taken from the tile as it lies in memory, [k][n] row-major with n contiguous, by the LDS transpose read of gfx950 (ds_read_b64_tr_b16): within each group of 16 lanes, lane 4q + c receives element
-// c of the four 8-byte rows that lanes q, q + 4, q + 8, q + 12 of the group point at.  Lane q + 4e therefore points at
-// row k0 + e, columns n0 + 4q .. 4q + 3, and lane 4q + c ends up with column n0 + 4q + c of rows k0 .. k0 + 3: four
-// consecutive contraction slots of one operand row, which is what the matrix unit wants.  Lane groups 0 / 1 cover
-// columns n0 .. 15 / n0 + 16 .. 31 (l32), groups 2 / 3 the same columns for g = 1.
+// A operand for a D-fragment-as-B product (contraction slots 16h + {4g..4g+3, 8+4g..8+4g+3}, see the top of this
+// file) taken from the tile as it lies in memory, [k][n] row-major with n contiguous, by the LDS transpose read of
+// gfx950 (ds_read_b64_tr_b16): within each group of 16 lanes, lane 4q + c receives element c of the four 8-byte rows
+// that lanes q, q + 4, q + 8, q + 12 of the group point at.  Lane q + 4e therefore points at row k0 + e, columns
+// n0 + 4q .. 4q + 3, and lane 4q + c ends up with column n0 + 4q + c of rows k0 .. k0 + 3: four consecutive contraction
+// slots of one operand row, which is what the matrix unit wants.  Lane groups 0 / 1 cover columns n0 .. 15 /
+// n0 + 16 .. 31 (l32), groups 2 / 3 the same columns for g = 1.  Used for both operands of a product, the slot
+// permutation cancels, so the same read serves ordinary P^T Q products (gemm_tn).
 // tr_lane_offset: the lane's share of the address, (4 g + e) * ld + 16 (G & 1) + 4 q, in elements.
 #define LTR(DH) ((DH) + 32)  // row stride of a tile read this way: 4 consecutive rows x 64 bytes fall into 4 distinct bank ranges
 __device__ __forceinline__ int tr_lane_offset(int lane, int ld) {
@@ -63,16 +45,6 @@ __device__ __forceinline__ bf16x8_t load_a_tr(const bf16_t* tile, int ld, int la
     const bf16_t* p = tile + lane_off + k16 * ld + n0;
     const bf16x4v_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(p));
     const bf16x4v_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_ptr_t)(p + 8 * ld));
-    bf16x8_t a;
-    a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
-    a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
-    return a;
-}
-
-// ordinary operand fragment (8 consecutive t) of a transposed tile, as two 8-byte pieces
-__device__ __forceinline__ bf16x8_t load_a_linear(const bf16_t* tile, int row, int t8) {
-    const bf16x4_t lo = *(const bf16x4_t*)(tile + tn_off(row, t8));
-    const bf16x4_t hi = *(const bf16x4_t*)(tile + tn_off(row, t8 + 4));
     bf16x8_t a;
     a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
     a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
