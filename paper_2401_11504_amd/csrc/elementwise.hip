@@ -14,20 +14,18 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const 
                                                           const float* resid, float* h_write) {
     __shared__ float red[16];
     const long row = blockIdx.x;
-    if (part) {
-        // assemble the row first: sum of the partial tiles a split GEMM left behind, plus the residual; it becomes
-        // the residual stream (h_write) and the input of the norm.  Each thread re-reads only what it wrote itself.
-        for (int i = threadIdx.x; i < (d >> 2); i += blockDim.x) {
-            float4 t = resid ? *(const float4*)(resid + row * d + 4 * (long)i) : make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int k = 0; k < n_part; ++k) {
-                const float4 q = *(const float4*)(part + (long)k * part_stride + row * d + 4 * (long)i);
-                t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-            }
-            *(float4*)(h_write + row * d + 4 * (long)i) = t;
+    // chunk i (four elements) of the row: read from h, or (part != null) assembled as the sum of the partial tiles a
+    // split GEMM left behind plus the residual, which becomes the residual stream (h_write) on the way
+    auto fetch = [&](int i) {
+        if (!part) return ((const float4*)(h + row * d))[i];
+        float4 t = resid ? *(const float4*)(resid + row * d + 4 * (long)i) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < n_part; ++k) {
+            const float4 q = *(const float4*)(part + (long)k * part_stride + row * d + 4 * (long)i);
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
         }
-        h = h_write;
-    }
-    const float4* hp = (const float4*)(h + row * d);
+        *(float4*)(h_write + row * d + 4 * (long)i) = t;
+        return t;
+    };
     const float4* gp = (const float4*)g;
     uint2* yp = (uint2*)(y + row * d);
     const int n4 = d >> 2;
@@ -38,12 +36,12 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const 
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + 256 * j;
-            xs[j] = i < n4 ? hp[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            xs[j] = i < n4 ? fetch(i) : make_float4(0.f, 0.f, 0.f, 0.f);
             ss += xs[j].x * xs[j].x + xs[j].y * xs[j].y + xs[j].z * xs[j].z + xs[j].w * xs[j].w;
         }
     } else {
         for (int i = threadIdx.x; i < n4; i += blockDim.x) {
-            const float4 x = hp[i];
+            const float4 x = fetch(i);
             ss += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
         }
     }
@@ -63,6 +61,7 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const 
             if (i < n4) emit(i, xs[j]);
         }
     } else {
+        const float4* hp = (const float4*)((part ? h_write : h) + row * d);   // each thread re-reads only what it wrote itself
         for (int i = threadIdx.x; i < n4; i += blockDim.x) emit(i, hp[i]);
     }
 }

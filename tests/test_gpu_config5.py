@@ -4,13 +4,17 @@ same seeded inputs (tests/golden/config5_7b_seed5000.npz, written by tests/golde
 only the oracle).  Token ids follow a Zipf law (exponent 1.1) as a stand-in for the paper's long-text streams.
 
 What can be compared, and how tightly.  Loss and per-position nll of every step meet the bf16 bar (2e-2; in practice
-2e-3).  dB depends on B only weakly (B stays within a few lr of zero), so it is held to the same depth-dependent bound
-as in the single-step test.  dA is proportional to B, and B after the first step from B = 0 is -lr * sign(dB) entry by
-entry: where |dB| is inside the bf16 noise the two sides may pick opposite signs, which changes a few per cent of the
-entries of B by 2 lr each and therefore dA by tens of per cent in L2 although both are valid continuations.  dA is
-therefore checked for what is unique: exactly zero at step 0, and from step 1 on the direction (cosine) and the norm.
-The step the GPU took from ITS OWN gradients is checked exactly against the oracle's AdamW on small shapes in
-test_gpu_update.py; here the factors are checked through bounds that hold for every valid trajectory."""
+2e-3).  Every sampled gradient is held to max(2e-2, 1.5 x its own storage floor): `make_config5_golden.py floor` replays
+the same four steps with the oracle's arithmetic in fp64 rounded to bf16 / fp32 exactly where Section 3 "Setup"'s
+bfloat16 training stores a tensor (tests/bf16_floor.py; AdamW state carried in fp32; no kernel involved) and stores that
+replay's error against the fp64 oracle next to each sample.  dB depends on B only weakly (B stays within a few lr of
+zero), so its floor is the depth floor of the single-step test (7-14 %).  dA is proportional to B, and B after the first
+step from B = 0 is -lr * sign(dB) entry by entry: where |dB| is inside the storage noise two valid implementations pick
+opposite signs, which changes a few per cent of the entries of B by 2 lr each -- the replay shows what that does to dA
+from step 1 on (its floors are tens of per cent), and the GPU is held to 1.5 x those, plus the norm of dA to
+2e-2 + 1.5 x the replay's own norm deviation.  The step the GPU took from ITS OWN gradients is checked exactly against the
+oracle's AdamW on small shapes in test_gpu_update.py; the factors after four steps are held to bounds that hold for
+every valid trajectory and to the replay's own agreement with the oracle."""
 import os
 
 import numpy as np
@@ -22,7 +26,7 @@ pytestmark = pytest.mark.gpu
 from paper_2401_11504_amd import synth  # noqa: E402
 from test_gpu_kernels import BF16_TOL, check  # noqa: E402
 from test_gpu_config3 import _cos  # noqa: E402
-DEEP_TOL = 0.15   # replaced by stored floors once they are generated
+from test_gpu_depth import floor_tol  # noqa: E402
 
 GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config5_7b_seed5000.npz")
 
@@ -56,8 +60,8 @@ def test_config5_stream_of_updates_matches_stored_oracle():
                 dout, din = shape.proj_dims(p)
                 dB = api.tl_get_factor(lora, l, i, api.GRAD_B, (dout, shape.rank))
                 rb = gold[f"rowsB_{l}_{i}"]
-                check(dB[rb], gold[f"dB_{step}_{l}_{i}"], DEEP_TOL, f"dB step {step} l{l} {p}")
-                assert _cos(dB[rb], gold[f"dB_{step}_{l}_{i}"]) > 0.99
+                check(dB[rb], gold[f"dB_{step}_{l}_{i}"], floor_tol(gold[f"floor_dB_{step}_{l}_{i}"]),
+                      f"dB step {step} l{l} {p}")
                 gn = float(gold[f"dB_norm_{step}_{l}_{i}"])
                 assert abs(np.linalg.norm(dB.astype(np.float64)) - gn) <= BF16_TOL * gn, f"|dB| step {step} l{l} {p}"
                 dA = api.tl_get_factor(lora, l, i, api.GRAD_A, (shape.rank, din))
@@ -66,8 +70,10 @@ def test_config5_stream_of_updates_matches_stored_oracle():
                     assert not dA.any(), f"dA l{l} {p} must be exactly zero while B = 0"
                 else:
                     an = float(gold[f"dA_norm_{step}_{l}_{i}"])
-                    assert abs(np.linalg.norm(dA.astype(np.float64)) - an) <= 0.25 * an, f"|dA| step {step} l{l} {p}"
-                    assert _cos(dA[np.ix_(ra, ca)], gold[f"dA_{step}_{l}_{i}"]) > 0.8, f"dA step {step} l{l} {p}"
+                    norm_tol = BF16_TOL + 1.5 * float(gold[f"floor_dA_norm_{step}_{l}_{i}"])
+                    assert abs(np.linalg.norm(dA.astype(np.float64)) - an) <= norm_tol * an, f"|dA| step {step} l{l} {p}"
+                    check(dA[np.ix_(ra, ca)], gold[f"dA_{step}_{l}_{i}"], floor_tol(gold[f"floor_dA_{step}_{l}_{i}"]),
+                          f"dA step {step} l{l} {p}")
     # descent within a chunk (second epoch on the same tokens), as in the oracle's trajectory
     assert losses[1] < losses[0] and losses[3] < losses[2]
     assert (gold["loss_1"] < gold["loss_0"]) and (gold["loss_3"] < gold["loss_2"])
@@ -81,8 +87,12 @@ def test_config5_stream_of_updates_matches_stored_oracle():
             # every AdamW step moves an entry by at most ~lr (|m_hat| / sqrt(v_hat) <= 1 up to the bias-correction ratio)
             assert np.max(np.abs(A - facs[l][p][0])) <= 1.5 * n_steps * lr
             assert np.max(np.abs(B)) <= 1.5 * n_steps * lr
-            assert np.max(np.abs(A[np.ix_(ra, ca)] - gold[f"A_final_{l}_{i}"])) <= 3.0 * n_steps * lr
-            assert _cos(B[rb], gold[f"B_final_{l}_{i}"]) > 0.9, f"B after {n_steps} steps l{l} {p}"
+            assert np.max(np.abs(A[np.ix_(ra, ca)] - gold[f"A_final_{l}_{i}"])) <= max(
+                1.5 * float(gold[f"floor_A_final_{l}_{i}"]), 2.0 * lr), f"A after {n_steps} steps l{l} {p}"
+            # the replay's own B agrees with the oracle's to this cosine; the GPU's may fall short of it by a third of
+            # the replay's own shortfall
+            c_floor = float(gold[f"floor_B_final_cos_{l}_{i}"])
+            assert _cos(B[rb], gold[f"B_final_{l}_{i}"]) >= 1.0 - 1.5 * (1.0 - c_floor), f"B after {n_steps} steps l{l} {p}"
     # Algorithm 1's last line: discard, and a fresh module on the same model reproduces the very first loss exactly
     api.tl_discard(lora)
     api.tl_lora_free(lora)
