@@ -11,10 +11,20 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from oracle import templora_oracle as O  # noqa: E402
 from paper_2401_11504_amd import synth  # noqa: E402
 from test_gpu_kernels import BF16_TOL, H, api, check  # noqa: E402,F401
+from test_gpu_depth import floor_tol  # noqa: E402
+import bf16_floor  # noqa: E402
+from bf16_floor import rel_err  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 PROJ = synth.PROJ
 ERR_ARG, ERR_TOKEN_RANGE, ERR_WINDOW = -1, -3, -4
+
+
+def _floor(x, ref):
+    """The storage floor of a tensor: the replay's relative L2 error and max-abs error / (10 RMS) against the oracle."""
+    x, ref = np.asarray(x, np.float64), np.asarray(ref, np.float64)
+    rms = np.sqrt(np.mean(ref * ref))
+    return [rel_err(x, ref), float(np.max(np.abs(x - ref)) / (10 * rms)) if rms > 0 else 0.0]
 
 
 def _oracle_train(model, facs, opt, tok, n_chunk, L_T, batch, epochs, lr, wu):
@@ -39,18 +49,28 @@ def test_chunk_train_matches_oracle(api, H, n_before, n_chunk, L_T, batch, epoch
     tok = synth.zipf_tokens(seed, n_before + n_chunk, shape.vocab)
     losses = api.tl_chunk_train(lora, tok, n_chunk, L_T, batch, epochs, lr, wu)
     ref, new, opt = _oracle_train(model, facs, O.new_opt_state(facs), tok, n_chunk, L_T, batch, epochs, lr, wu)
+    _, rep_new, rep_opt = bf16_floor.chunk_train(tok, n_chunk, L_T, batch, epochs, lr, wu, shape, model.emb, model.head,
+                                                 np.ones(shape.d_model), lambda l: model.host_layers[l], facs,
+                                                 O.new_opt_state(facs))
     assert len(losses) == len(ref) == opt["tau"] == api.tl_get_step(lora)      # step counts: exact
     assert np.allclose(losses, ref, rtol=BF16_TOL, atol=0), (losses, ref)
+    # AdamW's early steps are sign-like: an entry whose tiny gradient is inside the bf16 storage noise takes either sign
+    # and ends a few lr apart.  What that allows is measured, not guessed: the bf16-boundary replay of the oracle makes
+    # the same steps.  Which tensor the handful of flipped entries falls into differs between two valid implementations
+    # (in the replay itself the max-abs figure scatters by 5x between projections), so the floor of a KIND of tensor is
+    # the largest the replay shows for that kind anywhere in the model, and the bound max(2e-2, 1.5 x that floor).
+    every = [(l, p) for l in range(shape.n_layers) for p in PROJ]
+    floor_B = [max(rel_err(rep_new[l][p][1], new[l][p][1]) for l, p in every)]
+    floor_m = [np.max([_floor(rep_opt["m"][l][p][j], opt["m"][l][p][j]) for l, p in every], axis=0) for j in range(2)]
     for l in range(shape.n_layers):
         for i, p in enumerate(PROJ):
             dout, din = shape.proj_dims(p)
-            # AdamW's early steps are sign-like: an entry whose tiny gradient flips sign between the two sides ends a
-            # few lr apart, so the factors are compared in the L2 sense, the first moments two-sided.
             Bg = api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank))
             Bo = np.asarray(new[l][p][1], np.float64)
-            assert np.linalg.norm(Bg - Bo) / np.linalg.norm(Bo) <= 5e-2, f"B l{l} {p}"
-            check(api.tl_get_factor(lora, l, i, api.M_B, (dout, shape.rank)), opt["m"][l][p][1], 5e-2, f"mB l{l} {p}")
-            check(api.tl_get_factor(lora, l, i, api.M_A, (shape.rank, din)), opt["m"][l][p][0], 5e-2, f"mA l{l} {p}")
+            assert np.linalg.norm(Bg - Bo) / np.linalg.norm(Bo) <= floor_tol(floor_B), f"B l{l} {p}"
+            for which, j, dims in ((api.M_B, 1, (dout, shape.rank)), (api.M_A, 0, (shape.rank, din))):
+                check(api.tl_get_factor(lora, l, i, which, dims), opt["m"][l][p][j], floor_tol(floor_m[j]),
+                      f"m{'AB'[j]} l{l} {p}")
     api.tl_lora_free(lora)
     model.close()
 

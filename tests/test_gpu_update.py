@@ -9,6 +9,8 @@ pytestmark = pytest.mark.gpu
 from oracle import templora_oracle as O  # noqa: E402
 from paper_2401_11504_amd import synth  # noqa: E402
 from test_gpu_kernels import BF16_TOL, F32_TOL, check  # noqa: E402
+from test_gpu_depth import floor_tol  # noqa: E402
+import bf16_floor  # noqa: E402
 
 PROJ = synth.PROJ
 LR = 5e-5
@@ -170,6 +172,7 @@ def test_state_carry_two_chunks_two_epochs(api, H):
     lora, facs = H.new_lora(model, 4004, b_std=0.01)
     stream = synth.zipf_tokens(4004, 2 * T, shape.vocab)
     opt = O.new_opt_state(facs)
+    rep_facs, rep_opt = facs, O.new_opt_state(facs)     # the bf16-boundary replay of the oracle makes the same four steps
     # a larger rate than the paper's makes four steps visibly change the loss at this tiny size
     lr = 2e-3
     losses_g, losses_o = [], []
@@ -178,21 +181,35 @@ def test_state_carry_two_chunks_two_epochs(api, H):
         for _ in range(2):
             loss, _ = api.tl_chunk_update(lora, tok, 0, lr)
             res, facs, opt = _oracle_update(model, facs, opt, tok, 0, lr)
+            _, rep_facs, rep_opt = bf16_floor.chunk_update(tok, 0, shape, model.emb, model.head, np.ones(shape.d_model),
+                                                           lambda l: model.host_layers[l], rep_facs, rep_opt, lr)
             losses_g.append(loss), losses_o.append(res["loss"])
     assert np.allclose(losses_g, losses_o, rtol=BF16_TOL, atol=0)
     assert losses_g[1] < losses_g[0] and losses_g[3] < losses_g[2]     # second epoch on a chunk descends
     assert api.tl_get_step(lora) == 4
+    # AdamW's early steps are sign-like (|step| ~ lr whatever |g|): an entry whose tiny gradient is inside the bf16
+    # storage noise in one of the four steps takes either sign and ends 2*lr away.  How much of that a valid
+    # implementation shows is measured by the replay.  Which tensor the flipped entries fall into differs between two
+    # valid implementations, so the floor of a KIND of tensor (B, share of flipped entries, first moment of B) is the
+    # largest the replay shows for that kind anywhere in the model, and the bound max(2e-2, 1.5 x that floor).
+    every = [(l, p) for l in range(shape.n_layers) for p in PROJ]
+
+    def moment_floor(l, p):
+        ref_m, rep_m = np.asarray(opt["m"][l][p][1], np.float64), np.asarray(rep_opt["m"][l][p][1], np.float64)
+        return [bf16_floor.rel_err(rep_m, ref_m), float(np.max(np.abs(rep_m - ref_m)) / (10 * np.sqrt(np.mean(ref_m * ref_m))))]
+
+    floor_B = [max(bf16_floor.rel_err(rep_facs[l][p][1], facs[l][p][1]) for l, p in every)]
+    floor_m = np.max([moment_floor(l, p) for l, p in every], axis=0)
+    flipped = max(float(np.mean(np.abs(np.asarray(rep_facs[l][p][1], np.float64) - facs[l][p][1]) > 1.5 * lr)) for l, p in every)
     for l in range(shape.n_layers):
         for i, p in enumerate(PROJ):
             dout, din = shape.proj_dims(p)
-            # AdamW's early steps are sign-like (|step| ~ lr whatever |g|): an entry whose tiny gradient has the other
-            # sign in one of the four steps ends 2*lr away, so B is compared in the L2 sense and by the share of such
-            # entries; the first moment (linear in the gradients) takes the usual two-sided check.
             Bg = api.tl_get_factor(lora, l, i, api.FACTOR_B, (dout, shape.rank))
             Bo = np.asarray(facs[l][p][1], np.float64)
-            assert np.linalg.norm(Bg - Bo) / np.linalg.norm(Bo) <= 5e-2, f"B l{l} {p}"
-            assert np.mean(np.abs(Bg - Bo) > 1.5 * lr) < 0.02, f"B l{l} {p}"
-            check(api.tl_get_factor(lora, l, i, api.M_B, (dout, shape.rank)), opt["m"][l][p][1], 5e-2, f"mB l{l} {p}")
+            assert np.linalg.norm(Bg - Bo) / np.linalg.norm(Bo) <= floor_tol(floor_B), f"B l{l} {p}"
+            assert np.mean(np.abs(Bg - Bo) > 1.5 * lr) <= 1.5 * flipped + 2.0 / Bo.size, f"B l{l} {p}"
+            check(api.tl_get_factor(lora, l, i, api.M_B, (dout, shape.rank)), opt["m"][l][p][1], floor_tol(floor_m),
+                  f"mB l{l} {p}")
     api.tl_lora_free(lora)
     model.close()
 
