@@ -9,10 +9,10 @@ exponent 1.1 over the 32000-entry vocabulary, chunks of 1024, A ~ N(0, 0.02^2), 
 step 2 on B != 0, so dA != 0 and the low-rank path carries signal in both directions.
 
 Stored: loss and per-position nll of every step; for layers 0, 16, 31 and every projection, samples of dA and dB at
-every step and of A and B after the last step (two rows each, 256 columns of the wide ones), with full-tensor norms.
+every step and of A and B after the last step (eight rows each, 256 columns of the wide ones), with full-tensor norms.
 
-    python tests/golden/make_config5_golden.py [n_layers]      (about an hour on 8 cores, ~35 GB peak)
-    python tests/golden/make_config5_golden.py floor            (another hour; adds the floor_* entries to the file)
+    python tests/golden/make_config5_golden.py [n_layers]      (about two hours on 8 cores, ~35 GB peak: oracle, then floors)
+    python tests/golden/make_config5_golden.py floor            (the second hour alone: adds the floor_* entries to the file)
 
 `floor` replays the same four steps with tests/bf16_floor.py (the oracle's arithmetic in fp64, rounded to bf16 / fp32
 exactly where the storage format of Section 3 "Setup" stores a tensor; AdamW state in fp32; no kernel involved) and
@@ -36,7 +36,7 @@ from paper_2401_11504_amd import synth  # noqa: E402
 
 SEED, T, N_CHUNKS, N_EPOCHS, LR = 5000, 1024, 2, 2, 5e-5
 OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "config5_7b_seed5000.npz")
-SAMPLE_ROWS = 2
+SAMPLE_ROWS = 8     # rows per sample: a row of dB is one output channel, whose error is correlated along the row
 SAMPLE_COLS = 256   # columns of the sampled dA / A rows
 
 
@@ -156,3 +156,5 @@ if __name__ == "__main__":
         floor()
     else:
         main(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
+        if len(sys.argv) == 1:
+            floor()

@@ -35,8 +35,8 @@ GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "confi
 def test_config5_stream_of_updates_matches_stored_oracle():
     from paper_2401_11504_amd import api, harness
     gold = np.load(GOLD)
-    if "floor_dB_0_0_0" not in gold.files:
-        pytest.skip("the stored file has no storage floors yet: run tests/golden/make_config5_golden.py floor")
+    if "floor_dB_0_0_0" not in gold.files or gold["rowsB_0_0"].size < 8:
+        pytest.skip("the stored file predates the eight-row samples with storage floors: run tests/golden/make_config5_golden.py")
     seed, T, lr = int(gold["seed"]), 1024, float(gold["lr"])
     shape = synth.SHAPES["7b"]
     assert int(gold["n_layers"]) == shape.n_layers
