@@ -30,11 +30,14 @@ GEMM_NT_HBM_BYTES_PER_LAUNCH = 204e6
 GEMV_HBM_BYTES_PER_LAUNCH = 104.1e6
 
 
+CPU_SAMPLE_LAYERS = 6
+
+
 def cpu_baseline(shape, T, seed):
-    """The fp64 oracle as it stands, timed on this host on a bounded sample of the same update: the embedding gather,
-    layer 0 of the 7B shape (forward + backward + the AdamW step of its 14 factors; all 32 layers cost the same), and
-    the final norm / lm_head / cross-entropy part, each once.  Reported as trained tokens/s of the whole update
-    = T / (t_gather + n_layers * (t_layer + t_adamw) + t_head)."""
+    """The fp64 oracle as it stands, timed on this host on a bounded sample of the same update (about ten seconds of CPU
+    work): the embedding gather, the first CPU_SAMPLE_LAYERS layers of the 7B shape (forward + backward + the AdamW step
+    of their 14 factors each; all 32 layers cost the same), and the final norm / lm_head / cross-entropy part once.
+    Reported as trained tokens/s of the whole update = T / (t_gather + n_layers * mean(t_layer + t_adamw) + t_head)."""
     import numpy as np
     from oracle import templora_oracle as O
     from paper_2401_11504_amd import synth
@@ -43,8 +46,6 @@ def cpu_baseline(shape, T, seed):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
     except Exception:
         cores = os.cpu_count() or 1
-    W = synth.layer_weights(seed, shape, 0)
-    facs = synth.lora_factors(seed, shape, 0)
     emb = synth.embedding(seed, shape)
     tok = synth.uniform_tokens(seed, T, shape.vocab)
     t0 = time.perf_counter()
@@ -52,18 +53,26 @@ def cpu_baseline(shape, T, seed):
     t_gather = time.perf_counter() - t0
     del emb
     dy = synth.upstream_grad(seed, T, shape.d_model)
-    t0 = time.perf_counter()
-    _, cache = O.layer_fwd(h, W, facs, shape)
-    _, G = O.layer_bwd(dy, cache, W, facs, shape)
-    t_layer = time.perf_counter() - t0
-    del cache, W
-    t0 = time.perf_counter()
-    for p in O.PROJ:
-        for i in range(2):
-            z = np.zeros_like(np.asarray(facs[p][i], dtype=np.float64))
-            O.adamw_step(facs[p][i], G[p][i], z, z, 1, 5e-5)
-    t_adamw = time.perf_counter() - t0
-    del G
+    n_sample = min(CPU_SAMPLE_LAYERS, shape.n_layers)
+    t_layer = t_adamw = 0.0
+    for l in range(n_sample):
+        W = synth.layer_weights(seed, shape, l)
+        facs = synth.lora_factors(seed, shape, l)
+        t0 = time.perf_counter()
+        h_next, cache = O.layer_fwd(h, W, facs, shape)
+        _, G = O.layer_bwd(dy, cache, W, facs, shape)
+        t_layer += time.perf_counter() - t0
+        del cache, W
+        t0 = time.perf_counter()
+        for p in O.PROJ:
+            for i in range(2):
+                z = np.zeros_like(np.asarray(facs[p][i], dtype=np.float64))
+                O.adamw_step(facs[p][i], G[p][i], z, z, 1, 5e-5)
+        t_adamw += time.perf_counter() - t0
+        del G
+        h = h_next
+    t_layer /= n_sample
+    t_adamw /= n_sample
     head = synth.lm_head(seed, shape)
     t0 = time.perf_counter()
     labels, mask, _ = O.labels_and_mask(tok, 0)
@@ -75,8 +84,8 @@ def cpu_baseline(shape, T, seed):
     t_head = time.perf_counter() - t0
     total = t_gather + shape.n_layers * (t_layer + t_adamw) + t_head
     return {"value": T / total, "unit": "trained tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 oracle: embedding gather ({t_gather:.3f} s) + layer 0 fwd+bwd ({t_layer:.2f} s) and its AdamW "
-                      f"step ({t_adamw:.2f} s), each timed once and counted x{shape.n_layers} layers + final "
+            "sample": f"fp64 oracle: embedding gather ({t_gather:.3f} s) + layers 0..{n_sample - 1} fwd+bwd (mean {t_layer:.2f} s) "
+                      f"and their AdamW steps (mean {t_adamw:.2f} s), the means counted x{shape.n_layers} layers + final "
                       f"norm/lm_head/CE fwd+bwd timed once ({t_head:.2f} s)"}
 
 
