@@ -27,15 +27,34 @@ struct AttnCfg {
     static constexpr int ND = DH / 32;  // 32-wide d tiles
 };
 
-// load a [64 rows][DH] tile (rows r0.., zero beyond T) into registers; NT = threads of the workgroup
+// Byte offsets, within a [64 rows][DH] tile of a matrix with row stride ld, of the 16-byte chunks this thread fetches
+// (NT = threads that share the tile).  Computed once per kernel: the loop then adds them to a wave-uniform tile
+// address, which costs no vector arithmetic per load.
 template <int DH, int NT>
-__device__ __forceinline__ void load_tile_regs(const bf16_t* __restrict__ base, long ld, int r0, int T, uint4* regs,
-                                               int tid = threadIdx.x) {
+__device__ __forceinline__ void tile_chunk_offsets(long ld, unsigned* off, int tid = threadIdx.x) {
     constexpr int CH = DH / 8;  // chunks per row
 #pragma unroll
     for (int i = 0; i < 8 * DH / NT; ++i) {
         const int c = tid + NT * i, row = c / CH, ch = c % CH;
-        regs[i] = (r0 + row < T) ? *(const uint4*)(base + (long)(r0 + row) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
+        off[i] = (unsigned)((row * ld + ch * 8) * 2);
+    }
+}
+// load the tile of rows r0 .. r0 + 63 (zero beyond T) into registers; r0 is wave-uniform, so only a ragged last tile
+// pays for per-row checks
+template <int DH, int NT>
+__device__ __forceinline__ void load_tile_regs(const bf16_t* __restrict__ base, long ld, int r0, int T, const unsigned* off,
+                                               uint4* regs, int tid = threadIdx.x) {
+    constexpr int CH = DH / 8;
+    const char* p = (const char*)(base + (long)r0 * ld);
+    if (r0 + 64 <= T) {
+#pragma unroll
+        for (int i = 0; i < 8 * DH / NT; ++i) regs[i] = *(const uint4*)(p + off[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8 * DH / NT; ++i) {
+            const int row = (tid + NT * i) / CH;
+            regs[i] = (r0 + row < T) ? *(const uint4*)(p + off[i]) : make_uint4(0, 0, 0, 0);
+        }
     }
 }
 template <int DH, int NT>
@@ -129,8 +148,10 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
     const int n_tiles = (kend + 63) / 64;
     const int n_iter = (n_tiles + KG - 1) / KG;   // a group's surplus tile lies wholly in the future and is skipped
     uint4 rk[8 * DH / NT], rv[8 * DH / NT];
-    load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
-    load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
+    unsigned toff[8 * DH / NT];
+    tile_chunk_offsets<DH, NT>(ldq, toff, tid);
+    load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, toff, rk, tid);
+    load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, toff, rv, tid);
     for (int it = 0; it < n_iter; ++it) {
         const int u0 = (it * KG + kg) * 64;
         __syncthreads();
@@ -138,8 +159,8 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
         store_tile_ld<DH, NT, LDV>(sV, rv, tid);                 // V as it lies in memory: P V reads it transposed
         __syncthreads();
         if (it + 1 < n_iter) {
-            load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
-            load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
+            load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, toff, rk, tid);
+            load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, toff, rv, tid);
         }
         if (u0 > tq0 + 31) continue;  // wave-uniform: every key of this tile is in the future
         // both 32-key halves of the tile at once: two independent MFMA chains, one softmax update
@@ -251,13 +272,13 @@ __device__ __forceinline__ void rope_rotate_dT(f32x16_t* acc, const float2* __re
 
 // ======================================================================== backward: dQ
 // Same shape as the forward kernel: KG key groups share the causal range tile by tile and their dQ partial sums are
-// added through LDS at the end.  delta[t] = dO[t] . O[t] is formed here from the rows the wave already holds (and
-// written out, if delta != null, for a dK/dV kernel that runs afterwards); with a RoPE table the gradient is rotated
-// back before it is stored, so no separate pass over dq is needed.
+// added through LDS at the end.  delta[t] = dO[t] . O[t] is read from memory (attn_delta_kernel wrote it for the dK/dV
+// parts of the same launch); with a RoPE table the gradient is rotated back before it is stored, so no separate pass
+// over dq is needed.
 template <int DH, int NW, int KG>
 __device__ __forceinline__ void attn_dq_block(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
-    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, float* __restrict__ delta, long ldq, long ldo, int T,
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta, long ldq, long ldo, int T,
     bf16_t* __restrict__ dq, float scale, const float2* __restrict__ rope, int qb, int head, unsigned char* smem_raw) {
     using C = AttnCfg<DH>;
     constexpr int NT = NW * 64, QB = NW * 32;
@@ -275,24 +296,16 @@ __device__ __forceinline__ void attn_dq_block(
     const bf16_t* kh = k + (long)head * DH;
     const bf16_t* vh = v + (long)head * DH;
     const bf16_t* doh = d_o + (long)head * DH;
-    const bf16_t* oh = o + (long)head * DH;
 
     bf16x8_t qf[C::NKS], dof[C::NKS];
-    float dlt = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::NKS; ++ks) {
         uint4 r = (t_abs < T) ? *(const uint4*)(qh + (long)t_abs * ldq + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
         qf[ks] = *(bf16x8_t*)&r;
         uint4 r2 = (t_abs < T) ? *(const uint4*)(doh + (long)t_abs * ldo + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
         dof[ks] = *(bf16x8_t*)&r2;
-        const uint4 r3 = (t_abs < T) ? *(const uint4*)(oh + (long)t_abs * ldo + ks * 16 + g * 8) : make_uint4(0, 0, 0, 0);
-        const uint32_t aw[4] = {r2.x, r2.y, r2.z, r2.w}, bw[4] = {r3.x, r3.y, r3.z, r3.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            dlt += bf16_to_f32(aw[e] & 0xffff) * bf16_to_f32(bw[e] & 0xffff) + bf16_to_f32(aw[e] >> 16) * bf16_to_f32(bw[e] >> 16);
     }
-    dlt += __shfl_xor(dlt, 32, 64);   // the partner lane holds the other eight of every sixteen columns
-    if (delta && kg == 0 && g == 0 && t_abs < T) delta[(long)head * T + t_abs] = dlt;
+    const float dlt = (t_abs < T) ? delta[(long)head * T + t_abs] : 0.f;
     const float lse2 = (t_abs < T) ? lse[(long)head * T + t_abs] * 1.4426950408889634f : 1.0e30f;
     f32x16_t acc[C::ND];
 #pragma unroll
@@ -302,8 +315,10 @@ __device__ __forceinline__ void attn_dq_block(
     const int n_tiles = (kend + 63) / 64;
     const int n_iter = (n_tiles + KG - 1) / KG;
     uint4 rk[8 * DH / NT], rv[8 * DH / NT];
-    load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, rk, tid);
-    load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, rv, tid);
+    unsigned toff[8 * DH / NT];
+    tile_chunk_offsets<DH, NT>(ldq, toff, tid);
+    load_tile_regs<DH, NT>(kh, ldq, kg * 64, T, toff, rk, tid);
+    load_tile_regs<DH, NT>(vh, ldq, kg * 64, T, toff, rv, tid);
     for (int it = 0; it < n_iter; ++it) {
         const int u0 = (it * KG + kg) * 64;
         __syncthreads();
@@ -312,8 +327,8 @@ __device__ __forceinline__ void attn_dq_block(
         store_tile_normal<DH, NT>(sV, rv, tid);
         __syncthreads();
         if (it + 1 < n_iter) {
-            load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, rk, tid);
-            load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, rv, tid);
+            load_tile_regs<DH, NT>(kh, ldq, u0 + 64 * KG, T, toff, rk, tid);
+            load_tile_regs<DH, NT>(vh, ldq, u0 + 64 * KG, T, toff, rv, tid);
         }
         if (u0 > tq0 + 31) continue;
         f32x16_t s0 = zero16(), s1 = zero16(), dp0 = zero16(), dp1 = zero16();
@@ -416,11 +431,14 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
     const int n_tiles = (T + 63) / 64;
     const int tile0 = u0 / 64;
     uint4 rq[8 * DH / NT], rdo[8 * DH / NT];
+    unsigned qoff[8 * DH / NT], dooff[8 * DH / NT];
+    tile_chunk_offsets<DH, NT>(ldq, qoff);
+    tile_chunk_offsets<DH, NT>(ldo, dooff);
     float lse_v = 0.f, dl_v = 0.f;
     auto fetch = [&](int tile) {
         const int t0 = tile * 64;
-        load_tile_regs<DH, NT>(qh, ldq, t0, T, rq);
-        load_tile_regs<DH, NT>(doh, ldo, t0, T, rdo);
+        load_tile_regs<DH, NT>(qh, ldq, t0, T, qoff, rq);
+        load_tile_regs<DH, NT>(doh, ldo, t0, T, dooff, rdo);
         if (tid < 64) {
             const int t = t0 + tid;
             lse_v = (t < T) ? lse[(long)head * T + t] * 1.4426950408889634f : 1.0e30f;
@@ -502,7 +520,7 @@ __device__ __forceinline__ void attn_dkv_block(const bf16_t* __restrict__ q, con
 // workgroups' dQ parts own).  grid = (n blocks, heads, 2).
 template <int DH, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_fused_kernel(
-    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, const bf16_t* __restrict__ o,
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ d_o, const float* __restrict__ lse, const float* __restrict__ delta, long ldq, long ldo,
     int T, bf16_t* __restrict__ dq, bf16_t* __restrict__ dk, bf16_t* __restrict__ dv, float scale,
     const float2* __restrict__ rope) {
@@ -511,7 +529,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_fused_kernel(
     const int idx = (blockIdx.z * heads + blockIdx.y) * n + blockIdx.x;   // position in dispatch order (x fastest)
     const int level = idx / (2 * heads), r = idx % (2 * heads), head = r % heads;
     if (r < heads) attn_dkv_block<DH, NW>(q, k, v, d_o, lse, delta, ldq, ldo, T, dk, dv, scale, rope, level, head, smem);
-    else attn_dq_block<DH, NW, 1>(q, k, v, o, d_o, lse, nullptr, ldq, ldo, T, dq, scale, rope, n - 1 - level, head, smem);
+    else attn_dq_block<DH, NW, 1>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, scale, rope, n - 1 - level, head, smem);
 }
 
 // ======================================================================== launchers
@@ -590,7 +608,7 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
     auto kern = attn_bwd_fused_kernel<DH, NW>;
     e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, NW * 64, lds, s>>>(q, k, v, o, d_o, lse, delta, ldq, ldo, T, dq, dk, dv, scale, rope);
+    kern<<<grid, NW * 64, lds, s>>>(q, k, v, d_o, lse, delta, ldq, ldo, T, dq, dk, dv, scale, rope);
     return hipGetLastError();
 }
 
