@@ -172,8 +172,33 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// How a launch maps workgroup ids to tiles and contraction ranges, worked out on the host: the kernel's prologue is
+// exposed time on every launch, and integer divisions by run-time values cost it dozens of scalar instructions each.
+// q = n / d for the small n that occur here is umulhi(n, ceil(2^32 / d)) (exact while n * d < 2^32).
+struct NtMap {
+    int tiles_m, tiles_n;
+    unsigned inv_tiles_m;    // ceil(2^32 / tiles_m)
+    unsigned inv_n_split;    // ceil(2^32 / n_split)
+    int xcd_split;           // 1: the XCD a workgroup runs on also fixes its split (n_split 2, 4 or 8 and tiles divide evenly)
+    int xs_log2;             // log2 of the XCDs per split in that case
+    int tiles_per_xs;        // tiles / XCDs per split
+};
+static NtMap make_nt_map(int tiles_m, int tiles_n, int n_split, int batch, bool splitk) {
+    NtMap m;
+    m.tiles_m = tiles_m;
+    m.tiles_n = tiles_n;
+    m.inv_tiles_m = (unsigned)((0x100000000ull + (unsigned)tiles_m - 1) / (unsigned)tiles_m);
+    m.inv_n_split = (unsigned)((0x100000000ull + (unsigned)n_split - 1) / (unsigned)n_split);
+    const int ntiles = tiles_m * tiles_n, xs = 8 / (n_split > 0 ? n_split : 1);
+    m.xcd_split = splitk && batch == 1 && (n_split == 2 || n_split == 4 || n_split == 8) && ntiles % xs == 0;
+    m.xs_log2 = xs == 4 ? 2 : xs == 2 ? 1 : 0;
+    m.tiles_per_xs = m.xcd_split ? ntiles / xs : 0;
+    return m;
+}
+__device__ __forceinline__ unsigned div_by(unsigned n, unsigned inv) { return inv == 0 ? n : __umulhi(n, inv); }   // inv == 0 encodes d = 1
+
 template <int BM, int BN, int WM, int WN, int STAGES, int BKT = 64, bool SPLITK = false, int PIPE = 0>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, NtMap map) {
     constexpr int NT = WM * WN * 64;
     constexpr int ROWS = BM + BN;
     constexpr int CPRW = BKT / 8;             // 16-byte chunks per tile row
@@ -198,18 +223,18 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     // range of tiles (m fastest), so that its CUs share weight rows.  With the contraction split 2, 4 or 8 ways the
     // XCD also fixes the split: XCD c works on split c / (8 / n_split) only, so an XCD fetches just its share of the
     // contraction range of the activations instead of all of it.
+    const int tiles_m = map.tiles_m, tiles_n = map.tiles_n;
     const int ntiles = tiles_m * tiles_n;
     const int n_split = SPLITK ? (int)gridDim.y : 1;
     int pid = blockIdx.x, split = SPLITK ? (int)blockIdx.y : 0;
-    const int xs = 8 / max(n_split, 1);   // XCDs per split
-    if (SPLITK && gridDim.z == 1 && (n_split == 2 || n_split == 4 || n_split == 8) && ntiles % xs == 0) {
+    if (SPLITK && map.xcd_split) {
         const int id = blockIdx.y * gridDim.x + blockIdx.x, c = id & 7, j = id >> 3;
-        split = c / xs;
-        pid = (c % xs) * (ntiles / xs) + j;
+        split = c >> map.xs_log2;
+        pid = (c & ((1 << map.xs_log2) - 1)) * map.tiles_per_xs + j;
     } else {
         pid = xcd_contiguous(pid, ntiles);
     }
-    const int tile_m = pid % tiles_m, tile_n = pid / tiles_m;
+    const int tile_n = (int)div_by((unsigned)pid, map.inv_tiles_m), tile_m = pid - tile_n * tiles_m;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int z = blockIdx.z;
 
@@ -219,22 +244,23 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, int t
     const bf16_t* B2 = p.B2 ? p.B2 + (long)z * p.bB2 : nullptr;
     const int nk1 = p.K / BKT, nk2 = p.K2 / BKT;
     // with SPLITK, n_split workgroups share one output tile: this one takes k-tiles [kt0, kt0 + nk)
-    const int kt0 = (int)((long)(nk1 + nk2) * split / n_split);
-    const int nk = (int)((long)(nk1 + nk2) * (split + 1) / n_split) - kt0;
+    const int kt0 = SPLITK ? (int)div_by((unsigned)((nk1 + nk2) * split), map.inv_n_split) : 0;
+    const int nk = (SPLITK ? (int)div_by((unsigned)((nk1 + nk2) * (split + 1)), map.inv_n_split) : nk1 + nk2) - kt0;
 
     // per-thread byte offsets of its L chunks, for the main and the low-rank operand pair
     unsigned vo1[L], vo2[L];
 #pragma unroll
     for (int j = 0; j < L; ++j) {
         const int q = j * NT + tid, r = q / CPRW, c = (q % CPRW) ^ ((r / RP) % CPRW);
+        // 32-bit arithmetic: the launcher only takes this path for operands below 2^30 elements
         if (j < LA) {
-            const long row = min(m0 + r, p.M - 1);
-            vo1[j] = (unsigned)((row * p.lda + c * 8) * 2);
-            vo2[j] = (unsigned)((row * p.lda2 + c * 8) * 2);
+            const unsigned row = (unsigned)min(m0 + r, p.M - 1);
+            vo1[j] = (row * (unsigned)p.lda + c * 8) * 2;
+            vo2[j] = (row * (unsigned)p.lda2 + c * 8) * 2;
         } else {
-            const long row = min(n0 + r - BM, p.N - 1);
-            vo1[j] = (unsigned)((row * p.ldb + c * 8) * 2);
-            vo2[j] = (unsigned)((row * p.ldb2 + c * 8) * 2);
+            const unsigned row = (unsigned)min(n0 + r - BM, p.N - 1);
+            vo1[j] = (row * (unsigned)p.ldb + c * 8) * 2;
+            vo2[j] = (row * (unsigned)p.ldb2 + c * 8) * 2;
         }
     }
     auto issue = [&](int ktl) {
@@ -539,7 +565,7 @@ static hipError_t run_nt_dl(const GemmNT& g, hipStream_t s, int n_split = 1) {
     if (e != hipSuccess) return e;
     GemmNT gk = g;
     if (!(SPLITK && g.deferred && BM >= 256)) gk.partial_bf16 = 0;   // bf16 partial tiles only where the reduce is left to the consumer
-    kern<<<grid, WM * WN * 64, lds, s>>>(gk, tiles_m, tiles_n);
+    kern<<<grid, WM * WN * 64, lds, s>>>(gk, make_nt_map(tiles_m, tiles_n, SPLITK ? n_split : 1, g.batch, SPLITK));
     if (SPLITK) {
         if (g.deferred && BM >= 256) {    // wide-output instance: the consumer adds the partial tiles up
             *g.deferred = n_split;
