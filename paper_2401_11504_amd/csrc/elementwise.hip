@@ -231,6 +231,35 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ x, long 
     *(uint32_t*)(p + half) = pack_bf16x2(b0 * c[0] + a0 * sn[0], b1 * c[1] + a1 * sn[1]);
 }
 
+// The same with a table and 16-byte accesses: a thread rotates eight neighbouring pairs (columns i .. i+7 of a head
+// with columns i + half .. i + half + 7).
+__global__ __launch_bounds__(256) void rope_table_vec_kernel(bf16_t* __restrict__ x, long ld, int T, int n_heads,
+                                                             int d_head, int pos0, float sign,
+                                                             const float2* __restrict__ table) {
+    const int half = d_head >> 1, per_head = half >> 3;
+    const int per_row = n_heads * per_head;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)T * per_row) return;
+    const int t = (int)(idx / per_row), rem = (int)(idx % per_row);
+    const int hd = rem / per_head, i = (rem % per_head) * 8;
+    bf16_t* p = x + (long)t * ld + (long)hd * d_head + i;
+    float a[8], b[8], lo[8], hi[8];
+    unpack8(*(const uint4*)p, a);
+    unpack8(*(const uint4*)(p + half), b);
+    const float4* cs4 = (const float4*)(table + (long)(pos0 + t) * half + i);   // (cos, sin) pairs, two per float4
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float4 w = cs4[e];
+        const float s0 = w.y * sign, s1 = w.w * sign;
+        lo[2 * e] = a[2 * e] * w.x - b[2 * e] * s0;
+        hi[2 * e] = b[2 * e] * w.x + a[2 * e] * s0;
+        lo[2 * e + 1] = a[2 * e + 1] * w.z - b[2 * e + 1] * s1;
+        hi[2 * e + 1] = b[2 * e + 1] * w.z + a[2 * e + 1] * s1;
+    }
+    *(uint4*)p = pack8(lo);
+    *(uint4*)(p + half) = pack8(hi);
+}
+
 hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, hipStream_t s) {
     const long n = (long)n_pos * (d_head / 2);
     if (n <= 0) return hipSuccess;
@@ -241,6 +270,11 @@ hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float
                        const float2* table, hipStream_t s) {
     const long n = (long)T * n_heads * (d_head / 4);
     if (n <= 0) return hipSuccess;
+    if (table && (d_head & 15) == 0 && (ld & 7) == 0 && ((size_t)x & 15) == 0) {
+        const long nv = (long)T * n_heads * (d_head / 16);
+        rope_table_vec_kernel<<<cdiv(nv, 256), 256, 0, s>>>(x, ld, T, n_heads, d_head, pos0, sign >= 0 ? 1.f : -1.f, table);
+        return hipGetLastError();
+    }
     rope_kernel<<<cdiv(n, 256), 256, 0, s>>>(x, ld, T, n_heads, d_head, (double)base, pos0, sign >= 0 ? 1.f : -1.f,
                                              table);
     return hipGetLastError();
