@@ -824,15 +824,27 @@ __device__ __forceinline__ f32x16_t tn_tile(const bf16_t* P, long ldp, int Mo, c
     const int tp = tid >> 3, ic = tid & 7;
     const int tr_off = tr_lane_offset(lane, LD);
     f32x16_t acc = zero16();
-    auto ld = [&](const bf16_t* base, long ldx, int c0, int cmax, int t) -> uint4 {
-        const int c = c0 + ic * 8;
-        return (t < T && c < cmax) ? *(const uint4*)(base + (long)t * ldx + c) : make_uint4(0, 0, 0, 0);
-    };
+    // byte offsets of this thread's two rows within a 64-token tile, computed once; a tile's address is wave-uniform,
+    // and only a ragged last tile (or a ragged last column block) pays for per-element bounds checks
+    const unsigned po = (unsigned)((2 * tp * ldp + i0 + ic * 8) * 2), qo = (unsigned)((2 * tp * ldq + j0 + ic * 8) * 2);
+    const unsigned pstep = (unsigned)(ldp * 2), qstep = (unsigned)(ldq * 2);
+    const bool pc = i0 + ic * 8 < Mo, qc = j0 + ic * 8 < No;
+    const bool cols_full = i0 + 64 <= Mo && j0 + 64 <= No;
     uint4 p0, p1, q0, q1;
     auto gload = [&](int it) {
-        const int t = it * 64 + 2 * tp;
-        p0 = ld(P, ldp, i0, Mo, t); p1 = ld(P, ldp, i0, Mo, t + 1);
-        q0 = ld(Q, ldq, j0, No, t); q1 = ld(Q, ldq, j0, No, t + 1);
+        const char* pb = (const char*)(P + (long)it * 64 * ldp);
+        const char* qb = (const char*)(Q + (long)it * 64 * ldq);
+        if (cols_full && it * 64 + 64 <= T) {
+            p0 = *(const uint4*)(pb + po); p1 = *(const uint4*)(pb + po + pstep);
+            q0 = *(const uint4*)(qb + qo); q1 = *(const uint4*)(qb + qo + qstep);
+        } else {
+            const int t = it * 64 + 2 * tp;
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            p0 = (t < T && pc) ? *(const uint4*)(pb + po) : z;
+            p1 = (t + 1 < T && pc) ? *(const uint4*)(pb + po + pstep) : z;
+            q0 = (t < T && qc) ? *(const uint4*)(qb + qo) : z;
+            q1 = (t + 1 < T && qc) ? *(const uint4*)(qb + qo + qstep) : z;
+        }
     };
     auto park = [&](int buf) {
         *(uint4*)(sP[buf] + (2 * tp) * LD + ic * 8) = p0;
