@@ -541,8 +541,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, NtMap
                 if (vec_ok && col + 8 <= p.N) {
                     *(uint4*)dst = val;
                 } else {
-                    const bf16_t* e = (const bf16_t*)&val;
-                    for (int x = 0; x < 8 && col + x < p.N; ++x) dst[x] = e[x];
+                    // (taken apart by shifts: a pointer into `val` would put it, and a scratch allocation, into memory)
+                    const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+                    for (int x = 0; x < 8; ++x)
+                        if (col + x < p.N) dst[x] = (bf16_t)(w[x >> 1] >> (16 * (x & 1)));
                 }
             }
             __builtin_amdgcn_wave_barrier();
@@ -830,27 +833,29 @@ __device__ __forceinline__ f32x16_t tn_tile(const bf16_t* P, long ldp, int Mo, c
     const unsigned pstep = (unsigned)(ldp * 2), qstep = (unsigned)(ldq * 2);
     const bool pc = i0 + ic * 8 < Mo, qc = j0 + ic * 8 < No;
     const bool cols_full = i0 + 64 <= Mo && j0 + 64 <= No;
-    uint4 p0, p1, q0, q1;
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // a plain vector value: stays in registers on every path
+    u32x4 p0, p1, q0, q1;
     auto gload = [&](int it) {
         const char* pb = (const char*)(P + (long)it * 64 * ldp);
         const char* qb = (const char*)(Q + (long)it * 64 * ldq);
         if (cols_full && it * 64 + 64 <= T) {
-            p0 = *(const uint4*)(pb + po); p1 = *(const uint4*)(pb + po + pstep);
-            q0 = *(const uint4*)(qb + qo); q1 = *(const uint4*)(qb + qo + qstep);
+            p0 = *(const u32x4*)(pb + po); p1 = *(const u32x4*)(pb + po + pstep);
+            q0 = *(const u32x4*)(qb + qo); q1 = *(const u32x4*)(qb + qo + qstep);
         } else {
             const int t = it * 64 + 2 * tp;
-            const uint4 z = make_uint4(0, 0, 0, 0);
-            p0 = (t < T && pc) ? *(const uint4*)(pb + po) : z;
-            p1 = (t + 1 < T && pc) ? *(const uint4*)(pb + po + pstep) : z;
-            q0 = (t < T && qc) ? *(const uint4*)(qb + qo) : z;
-            q1 = (t + 1 < T && qc) ? *(const uint4*)(qb + qo + qstep) : z;
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            p0 = z; p1 = z; q0 = z; q1 = z;
+            if (t < T && pc) p0 = *(const u32x4*)(pb + po);
+            if (t + 1 < T && pc) p1 = *(const u32x4*)(pb + po + pstep);
+            if (t < T && qc) q0 = *(const u32x4*)(qb + qo);
+            if (t + 1 < T && qc) q1 = *(const u32x4*)(qb + qo + qstep);
         }
     };
     auto park = [&](int buf) {
-        *(uint4*)(sP[buf] + (2 * tp) * LD + ic * 8) = p0;
-        *(uint4*)(sP[buf] + (2 * tp + 1) * LD + ic * 8) = p1;
-        *(uint4*)(sQ[buf] + (2 * tp) * LD + ic * 8) = q0;
-        *(uint4*)(sQ[buf] + (2 * tp + 1) * LD + ic * 8) = q1;
+        *(u32x4*)(sP[buf] + (2 * tp) * LD + ic * 8) = p0;
+        *(u32x4*)(sP[buf] + (2 * tp + 1) * LD + ic * 8) = p1;
+        *(u32x4*)(sQ[buf] + (2 * tp) * LD + ic * 8) = q0;
+        *(u32x4*)(sQ[buf] + (2 * tp + 1) * LD + ic * 8) = q1;
     };
     if (it0 < it1) {
         gload(it0);
