@@ -359,6 +359,11 @@ tl_status tl_k_rmsnorm_bwd(const uint16_t* dy, const float* h, const float* g, c
 /* In-place RoPE on x bf16 [T, n_heads, d_head] with row stride ld elements; sign = +1 forward, -1 backward. */
 tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_heads, int32_t d_head, float base, int32_t pos0,
                     int32_t sign, void* hip_stream);
+/* The same through the (cos, sin) table the chunk path uses: `table` (device, 16-byte aligned, table_elems >=
+ * (pos0 + T) * d_head floats, caller-owned scratch) is filled with the angles of positions 0 .. pos0 + T - 1 and the
+ * rotation then reads it.  TL_ERR_SHAPE if the table is too small or misaligned. */
+tl_status tl_k_rope_table(uint16_t* x, int32_t ld, int32_t T, int32_t n_heads, int32_t d_head, float base,
+                          int32_t pos0, int32_t sign, float* table, size_t table_elems, void* hip_stream);
 /* a = silu(g) * u, gu bf16 [T, 2f] = [gate | up], a bf16 [T, f]. */
 /* y = D o x for one projection group input (bf16 [T, d_in]), D as defined with tl_lora_cfg.dropout. */
 tl_status tl_k_dropout(const uint16_t* x, int32_t T, int32_t d_in, float p, uint64_t seed, int64_t step,

@@ -90,6 +90,7 @@ _SIGS = {
     "tl_k_rmsnorm_fwd": [_vp, _vp, _i32, _i32, _f32, _vp, _vp],
     "tl_k_rmsnorm_bwd": [_vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp],
     "tl_k_rope": [_vp, _i32, _i32, _i32, _i32, _f32, _i32, _i32, _vp],
+    "tl_k_rope_table": [_vp, _i32, _i32, _i32, _i32, _f32, _i32, _i32, _vp, _sz, _vp],
     "tl_k_dropout": [_vp, _i32, _i32, _f32, C.c_uint64, _i64, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_fwd": [_vp, _i32, _i32, _vp, _vp],
     "tl_k_swiglu_bwd": [_vp, _vp, _i32, _i32, _vp, _vp],
@@ -358,6 +359,11 @@ def tl_k_rmsnorm_bwd(dy, h, g, dres, eps, dh_out, dh_out_bf16=None, stream=None)
 
 def tl_k_rope(x, n_heads, d_head, base=10000.0, pos0=0, sign=1, stream=None):
     _chk(_lib.tl_k_rope(_dp(x), x.stride(0), x.shape[0], n_heads, d_head, base, pos0, sign, _s(stream)))
+
+
+def tl_k_rope_table(x, n_heads, d_head, table, base=10000.0, pos0=0, sign=1, stream=None):
+    _chk(_lib.tl_k_rope_table(_dp(x), x.stride(0), x.shape[0], n_heads, d_head, base, pos0, sign, _dp(table),
+                              table.numel(), _s(stream)))
 
 
 def tl_k_dropout(x, y, p, seed, step, layer, group, stream=None):

@@ -1386,6 +1386,16 @@ extern "C" tl_status tl_k_rope(uint16_t* x, int32_t ld, int32_t T, int32_t n_hea
     HIPCHK(launch_rope(x, ld, T, n_heads, d_head, base, pos0, sign, nullptr, (hipStream_t)hip_stream));
     return TL_OK;
 }
+extern "C" tl_status tl_k_rope_table(uint16_t* x, int32_t ld, int32_t T, int32_t n_heads, int32_t d_head, float base,
+                                     int32_t pos0, int32_t sign, float* table, size_t table_elems, void* hip_stream) {
+    KARGS_OK(x && table && T >= 0 && n_heads > 0 && d_head >= 4 && (d_head & 3) == 0 && (ld & 1) == 0 && pos0 >= 0,
+             "tl_k_rope_table");
+    if (((size_t)table & 15) || table_elems < (size_t)(pos0 + T) * d_head)
+        return fail(TL_ERR_SHAPE, "tl_k_rope_table: the table needs (pos0 + T) * d_head floats, 16-byte aligned");
+    HIPCHK(launch_rope_table((float2*)table, pos0 + T, d_head, base, (hipStream_t)hip_stream));
+    HIPCHK(launch_rope(x, ld, T, n_heads, d_head, base, pos0, sign, (const float2*)table, (hipStream_t)hip_stream));
+    return TL_OK;
+}
 extern "C" tl_status tl_k_dropout(const uint16_t* x, int32_t T, int32_t d_in, float p, uint64_t seed, int64_t step,
                                   int32_t layer, int32_t group, uint16_t* y, void* hip_stream) {
     if (!x || !y) return fail(TL_ERR_ARG, "tl_k_dropout: null pointer");

@@ -240,6 +240,25 @@ def test_rope(api, H, T, nh, dh, pos0):
     check(H.bf16_to_np(xb), O.rope_bwd(x.reshape(T, nh, dh), 10000.0, pos0).reshape(T, nh * dh), BF16_TOL, "bwd")
 
 
+@pytest.mark.parametrize("T,nh,dh,pos0,ld_extra", [(70, 3, 64, 0, 0), (1024, 2, 128, 0, 0), (9, 1, 64, 1000, 0),
+                                                   (130, 2, 128, 7, 256),      # a slice of a wider buffer (q | k of q|k|v)
+                                                   (33, 2, 24, 0, 0)])         # head width no multiple of 16: scalar kernel
+def test_rope_through_the_angle_table(api, H, T, nh, dh, pos0, ld_extra):
+    """The chunk path rotates q and k with a (cos, sin) table built in fp64 and 16-byte accesses; same bar as above."""
+    x = rnd(2, (T, nh * dh + ld_extra))
+    table = torch.empty((pos0 + T) * dh, dtype=torch.float32, device="cuda")
+    for sign, ref_fn in ((+1, O.rope_fwd), (-1, O.rope_bwd)):
+        xd = H.to_dev_bf16(x)
+        api.tl_k_rope_table(xd[:, :nh * dh], nh, dh, table, 10000.0, pos0, sign)
+        torch.cuda.synchronize()
+        got = H.bf16_to_np(xd)
+        ref = ref_fn(x[:, :nh * dh].reshape(T, nh, dh), 10000.0, pos0).reshape(T, nh * dh)
+        check(got[:, :nh * dh], ref, BF16_TOL, f"sign {sign}")
+        assert np.array_equal(got[:, nh * dh:], H.bf16_to_np(H.to_dev_bf16(x))[:, nh * dh:])   # columns beyond the heads untouched
+    with pytest.raises(api.TlError):
+        api.tl_k_rope_table(H.to_dev_bf16(x)[:, :nh * dh], nh, dh, table[:8], 10000.0, pos0, +1)
+
+
 # ------------------------------------------------------------------ SwiGLU
 @pytest.mark.parametrize("T,f", [(3, 8), (257, 704), (64, 11008)])
 def test_swiglu(api, H, T, f):
