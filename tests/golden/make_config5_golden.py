@@ -14,6 +14,11 @@ every step and of A and B after the last step (eight rows each, 256 columns of t
     python tests/golden/make_config5_golden.py [n_layers]      (about two hours on 8 cores, ~35 GB peak: oracle, then floors)
     python tests/golden/make_config5_golden.py floor            (the second hour alone: adds the floor_* entries to the file)
 
+Run without arguments, the script also keeps the oracle's FULL dA / dB of the sampled layers in memory and stores
+`floormax_*`: the largest error the replay shows on any of 16 samples of the stored size drawn from the same tensor (the
+stored sample is one of them).  A row of dB is one output channel whose error is correlated along the row, so an eight-row
+sample estimates the floor of its tensor only to a few tens of per cent; the tests bound the GPU by 1.5 x floormax.
+
 `floor` replays the same four steps with tests/bf16_floor.py (the oracle's arithmetic in fp64, rounded to bf16 / fp32
 exactly where the storage format of Section 3 "Setup" stores a tensor; AdamW state in fp32; no kernel involved) and
 stores, next to every sample already in the file, that replay's error against it as (relative L2, max-abs / 10 RMS):
@@ -38,9 +43,11 @@ SEED, T, N_CHUNKS, N_EPOCHS, LR = 5000, 1024, 2, 2, 5e-5
 OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "config5_7b_seed5000.npz")
 SAMPLE_ROWS = 8     # rows per sample: a row of dB is one output channel, whose error is correlated along the row
 SAMPLE_COLS = 256   # columns of the sampled dA / A rows
+N_GROUPS = 16       # samples of the stored size per tensor over which floormax_* is taken
+FULL = {}           # (step, layer, projection) -> the oracle's full (dA, dB), kept only inside a run without arguments
 
 
-def main(n_layers=32):
+def main(n_layers=32, keep_full=False):
     shape = synth.SHAPES["7b"].with_layers(n_layers)
     stream = synth.zipf_tokens(SEED, N_CHUNKS * T, shape.vocab)
     emb, head = synth.embedding(SEED, shape), synth.lm_head(SEED, shape)
@@ -84,6 +91,8 @@ def main(n_layers=32):
                     out[f"dB_{step}_{l}_{i}"] = f32(dB[rows[(l, i, 1)]])
                     out[f"dA_norm_{step}_{l}_{i}"] = np.float64(np.linalg.norm(dA))
                     out[f"dB_norm_{step}_{l}_{i}"] = np.float64(np.linalg.norm(dB))
+                    if keep_full:
+                        FULL[(step, l, i)] = (np.array(dA, dtype=np.float64), np.array(dB, dtype=np.float64))
             del res
             step += 1
     for l in keep:
@@ -92,12 +101,14 @@ def main(n_layers=32):
             out[f"A_final_{l}_{i}"] = f32(np.asarray(A)[np.ix_(rows[(l, i, 0)], rows[(l, i, 2)])])
             out[f"B_final_{l}_{i}"] = f32(np.asarray(B)[rows[(l, i, 1)]])
     out["n_steps"] = np.int64(step)
-    np.savez_compressed(OUT if n_layers == 32 else OUT.replace(".npz", f"_L{n_layers}.npz"), **out)
-    print("wrote", OUT, flush=True)
+    path = OUT if n_layers == 32 else OUT.replace(".npz", f"_L{n_layers}.npz")
+    np.savez_compressed(path, **out)
+    print("wrote", path, flush=True)
+    return path
 
 
-def floor():
-    gold = dict(np.load(OUT))
+def floor(path=OUT):
+    gold = dict(np.load(path))
     shape = synth.SHAPES["7b"].with_layers(int(gold["n_layers"]))
     stream = synth.zipf_tokens(SEED, N_CHUNKS * T, shape.vocab)
     assert np.array_equal(stream, gold["tokens"])
@@ -136,6 +147,18 @@ def floor():
                 gold[f"floor_dB_{step}_{l}_{i}"] = sample_err(dB[rb], gold[f"dB_{step}_{l}_{i}"])
                 gold[f"floor_dA_norm_{step}_{l}_{i}"] = np.float64(
                     abs(np.linalg.norm(dA) - float(gold[f"dA_norm_{step}_{l}_{i}"])) / max(float(gold[f"dA_norm_{step}_{l}_{i}"]), 1e-300))
+                if (step, l, i) in FULL:
+                    oA, oB = FULL.pop((step, l, i))
+                    rg = np.random.default_rng(SEED + 1000 * step + 10 * l + i)
+                    fa, fb = [gold[f"floor_dA_{step}_{l}_{i}"]], [gold[f"floor_dB_{step}_{l}_{i}"]]
+                    for _ in range(N_GROUPS - 1):
+                        r1 = np.sort(rg.choice(oA.shape[0], ra.size, replace=False))
+                        c1 = np.sort(rg.choice(oA.shape[1], ca.size, replace=False))
+                        r2 = np.sort(rg.choice(oB.shape[0], rb.size, replace=False))
+                        fa.append(sample_err(np.asarray(dA)[np.ix_(r1, c1)], oA[np.ix_(r1, c1)]))
+                        fb.append(sample_err(np.asarray(dB)[r2], oB[r2]))
+                    gold[f"floormax_dA_{step}_{l}_{i}"] = np.max(fa, axis=0)
+                    gold[f"floormax_dB_{step}_{l}_{i}"] = np.max(fb, axis=0)
         print(f"replay step {step}: {time.time() - t0:.1f} s, loss floor {gold[f'floor_loss_{step}']:.2e}, largest dA / dB floor "
               f"{max(gold[f'floor_dA_{step}_{l}_{i}'][0] for l in keep for i in range(7)):.3f} / "
               f"{max(gold[f'floor_dB_{step}_{l}_{i}'][0] for l in keep for i in range(7)):.3f}", flush=True)
@@ -147,14 +170,13 @@ def floor():
             gold[f"floor_A_final_{l}_{i}"] = np.float64(np.max(np.abs(np.asarray(A)[np.ix_(ra, ca)] - gold[f"A_final_{l}_{i}"])))
             b, rb_ = np.asarray(B)[rb].ravel(), np.asarray(gold[f"B_final_{l}_{i}"], np.float64).ravel()
             gold[f"floor_B_final_cos_{l}_{i}"] = np.float64(b @ rb_ / (np.linalg.norm(b) * np.linalg.norm(rb_)))
-    np.savez_compressed(OUT, **gold)
-    print("wrote", OUT, flush=True)
+    np.savez_compressed(path, **gold)
+    print("wrote", path, flush=True)
 
 
 if __name__ == "__main__":
     if sys.argv[1:] == ["floor"]:
         floor()
     else:
-        main(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
-        if len(sys.argv) == 1:
-            floor()
+        # a layer count (debugging) writes config5_7b_seed5000_L<n>.npz, which no test reads
+        floor(main(int(sys.argv[1]) if len(sys.argv) > 1 else 32, keep_full=True))

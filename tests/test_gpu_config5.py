@@ -4,10 +4,13 @@ same seeded inputs (tests/golden/config5_7b_seed5000.npz, written by tests/golde
 only the oracle).  Token ids follow a Zipf law (exponent 1.1) as a stand-in for the paper's long-text streams.
 
 What can be compared, and how tightly.  Loss and per-position nll of every step meet the bf16 bar (2e-2; in practice
-2e-3).  Every sampled gradient is held to max(2e-2, 1.5 x its own storage floor): `make_config5_golden.py floor` replays
+2e-3).  Every sampled gradient is held to max(2e-2, 1.5 x the storage floor of a sample of its size): the script replays
 the same four steps with the oracle's arithmetic in fp64 rounded to bf16 / fp32 exactly where Section 3 "Setup"'s
 bfloat16 training stores a tensor (tests/bf16_floor.py; AdamW state carried in fp32; no kernel involved) and stores that
-replay's error against the fp64 oracle next to each sample.  dB depends on B only weakly (B stays within a few lr of
+replay's error against the fp64 oracle next to each sample -- on the stored sample (floor_*) and, because an eight-row
+sample estimates the floor of its tensor only to a few tens of per cent (a row of dB is one output channel, its error
+correlated along the row; the same tensor's floor_* ranges from 0.028 to 0.072 over the four steps), the largest over 16
+samples of the same size drawn from the same tensor (floormax_*), which is what bounds the GPU.  dB depends on B only weakly (B stays within a few lr of
 zero), so its floor is the depth floor of the single-step test (7-14 %).  dA is proportional to B, and B after the first
 step from B = 0 is -lr * sign(dB) entry by entry: where |dB| is inside the storage noise two valid implementations pick
 opposite signs, which changes a few per cent of the entries of B by 2 lr each -- the replay shows what that does to dA
@@ -35,8 +38,8 @@ GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "confi
 def test_config5_stream_of_updates_matches_stored_oracle():
     from paper_2401_11504_amd import api, harness
     gold = np.load(GOLD)
-    if "floor_dB_0_0_0" not in gold.files or gold["rowsB_0_0"].size < 8:
-        pytest.skip("the stored file predates the eight-row samples with storage floors: run tests/golden/make_config5_golden.py")
+    if "floormax_dB_0_0_0" not in gold.files:
+        pytest.skip("the stored file predates the storage floors over 16 samples per tensor: run tests/golden/make_config5_golden.py")
     seed, T, lr = int(gold["seed"]), 1024, float(gold["lr"])
     shape = synth.SHAPES["7b"]
     assert int(gold["n_layers"]) == shape.n_layers
@@ -62,7 +65,7 @@ def test_config5_stream_of_updates_matches_stored_oracle():
                 dout, din = shape.proj_dims(p)
                 dB = api.tl_get_factor(lora, l, i, api.GRAD_B, (dout, shape.rank))
                 rb = gold[f"rowsB_{l}_{i}"]
-                check(dB[rb], gold[f"dB_{step}_{l}_{i}"], floor_tol(gold[f"floor_dB_{step}_{l}_{i}"]),
+                check(dB[rb], gold[f"dB_{step}_{l}_{i}"], floor_tol(gold[f"floormax_dB_{step}_{l}_{i}"]),
                       f"dB step {step} l{l} {p}")
                 gn = float(gold[f"dB_norm_{step}_{l}_{i}"])
                 assert abs(np.linalg.norm(dB.astype(np.float64)) - gn) <= BF16_TOL * gn, f"|dB| step {step} l{l} {p}"
@@ -72,14 +75,19 @@ def test_config5_stream_of_updates_matches_stored_oracle():
                     assert not dA.any(), f"dA l{l} {p} must be exactly zero while B = 0"
                 else:
                     an = float(gold[f"dA_norm_{step}_{l}_{i}"])
-                    norm_tol = BF16_TOL + 1.5 * float(gold[f"floor_dA_norm_{step}_{l}_{i}"])
+                    # the deviation of a norm is one signed number per tensor: what the replay drew for THIS tensor says
+                    # nothing about another implementation's draw, so the floor is the largest over the step's tensors
+                    norm_tol = BF16_TOL + 1.5 * max(float(gold[f"floor_dA_norm_{step}_{ll}_{ii}"]) for ll in keep for ii in range(7))
                     assert abs(np.linalg.norm(dA.astype(np.float64)) - an) <= norm_tol * an, f"|dA| step {step} l{l} {p}"
-                    check(dA[np.ix_(ra, ca)], gold[f"dA_{step}_{l}_{i}"], floor_tol(gold[f"floor_dA_{step}_{l}_{i}"]),
+                    check(dA[np.ix_(ra, ca)], gold[f"dA_{step}_{l}_{i}"], floor_tol(gold[f"floormax_dA_{step}_{l}_{i}"]),
                           f"dA step {step} l{l} {p}")
     # descent within a chunk (second epoch on the same tokens), as in the oracle's trajectory
     assert losses[1] < losses[0] and losses[3] < losses[2]
     assert (gold["loss_1"] < gold["loss_0"]) and (gold["loss_3"] < gold["loss_2"])
     n_steps = int(gold["n_steps"])
+    # scalars per tensor again (a largest deviation, a cosine): pooled over the sampled tensors like the norms above
+    a_floor = max(float(gold[f"floor_A_final_{l}_{i}"]) for l in keep for i in range(7))
+    c_floor = min(float(gold[f"floor_B_final_cos_{l}_{i}"]) for l in keep for i in range(7))
     for l in keep:
         for i, p in enumerate(synth.PROJ):
             dout, din = shape.proj_dims(p)
@@ -89,11 +97,9 @@ def test_config5_stream_of_updates_matches_stored_oracle():
             # every AdamW step moves an entry by at most ~lr (|m_hat| / sqrt(v_hat) <= 1 up to the bias-correction ratio)
             assert np.max(np.abs(A - facs[l][p][0])) <= 1.5 * n_steps * lr
             assert np.max(np.abs(B)) <= 1.5 * n_steps * lr
-            assert np.max(np.abs(A[np.ix_(ra, ca)] - gold[f"A_final_{l}_{i}"])) <= max(
-                1.5 * float(gold[f"floor_A_final_{l}_{i}"]), 2.0 * lr), f"A after {n_steps} steps l{l} {p}"
-            # the replay's own B agrees with the oracle's to this cosine; the GPU's may fall short of it by a third of
-            # the replay's own shortfall
-            c_floor = float(gold[f"floor_B_final_cos_{l}_{i}"])
+            assert np.max(np.abs(A[np.ix_(ra, ca)] - gold[f"A_final_{l}_{i}"])) <= max(1.5 * a_floor, 2.0 * lr), \
+                f"A after {n_steps} steps l{l} {p}"
+            # the replay's own B agrees with the oracle's to the cosine c_floor; the GPU's shortfall from 1 may be 1.5 x that
             assert _cos(B[rb], gold[f"B_final_{l}_{i}"]) >= 1.0 - 1.5 * (1.0 - c_floor), f"B after {n_steps} steps l{l} {p}"
     # Algorithm 1's last line: discard, and a fresh module on the same model reproduces the very first loss exactly
     api.tl_discard(lora)
