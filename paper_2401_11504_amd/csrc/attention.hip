@@ -172,31 +172,34 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
             s0 = mfma32(a0, qf[ks], s0);
             s1 = mfma32(a1, qf[ks], s1);
         }
+        // the running max m is kept in units of the raw scores (the scale is positive, so it commutes with max) and
+        // the scale is folded into the exponent's multiply-add: one instruction per score less
         float x[32];
         float mloc = NEG_BIG;
         if (u0 + 63 > tq0) {  // the tile touches the diagonal: causal mask
 #pragma unroll
             for (int vv = 0; vv < 16; ++vv) {
                 const int u = u0 + 8 * (vv >> 2) + 4 * g + (vv & 3);
-                x[vv] = (u > t_abs) ? NEG_BIG : s0[vv] * scale_log2e;
-                x[16 + vv] = (u + 32 > t_abs) ? NEG_BIG : s1[vv] * scale_log2e;
+                x[vv] = (u > t_abs) ? NEG_BIG : s0[vv];
+                x[16 + vv] = (u + 32 > t_abs) ? NEG_BIG : s1[vv];
             }
         } else {
 #pragma unroll
             for (int vv = 0; vv < 16; ++vv) {
-                x[vv] = s0[vv] * scale_log2e;
-                x[16 + vv] = s1[vv] * scale_log2e;
+                x[vv] = s0[vv];
+                x[16 + vv] = s1[vv];
             }
         }
 #pragma unroll
         for (int vv = 0; vv < 32; ++vv) mloc = fmaxf(mloc, x[vv]);
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
         const float m_new = fmaxf(m, mloc);
-        const float alpha = fast_exp2(m - m_new);
+        const float alpha = fast_exp2((m - m_new) * scale_log2e);
+        const float mb = m_new * scale_log2e;
         float psum = 0.f;
 #pragma unroll
         for (int vv = 0; vv < 32; ++vv) {
-            x[vv] = fast_exp2(x[vv] - m_new);
+            x[vv] = fast_exp2(fmaf(x[vv], scale_log2e, -mb));
             psum += x[vv];
         }
         lpart = lpart * alpha + psum;
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
         if (kg == 1) return;
         const float m1 = mg[(C::ND * 16) * NT + tid], l1 = mg[(C::ND * 16 + 1) * NT + tid];
         const float mt = fmaxf(m, m1);
-        const float a0 = fast_exp2(m - mt), a1 = fast_exp2(m1 - mt);
+        const float a0 = fast_exp2((m - mt) * scale_log2e), a1 = fast_exp2((m1 - mt) * scale_log2e);
 #pragma unroll
         for (int dt = 0; dt < C::ND; ++dt)
 #pragma unroll
@@ -247,7 +250,7 @@ __global__ __launch_bounds__(NW * 64 * KG) void attn_fwd_kernel(const bf16_t* __
     const float ltot = lpart + __shfl_xor(lpart, 32, 64);
     if (t_abs < T) {
         write_rows_from_dT<DH>(o + (long)t_abs * ldo + (long)head * DH, oacc, 1.f / ltot, g);
-        if (g == 0) lse[(long)head * T + t_abs] = (m + log2f(ltot)) * 0.6931471805599453f;
+        if (g == 0) lse[(long)head * T + t_abs] = (m * scale_log2e + log2f(ltot)) * 0.6931471805599453f;
     }
 }
 
