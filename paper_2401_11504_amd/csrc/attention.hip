@@ -578,18 +578,20 @@ hipError_t launch_attention_fwd(const bf16_t* q, const bf16_t* k, const bf16_t* 
 template <int DH>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ d_o,
                                                          long ldo, int T, int n_heads, float* __restrict__ delta) {
+    // grid: x over the heads of a token (256 / LPR heads per workgroup), y over tokens
     constexpr int LPR = DH / 8;
-    const long item = ((long)blockIdx.x * 256 + threadIdx.x) / LPR;
-    const int sub = threadIdx.x % LPR;
-    const bool live = item < (long)T * n_heads;
-    const int t = live ? (int)(item / n_heads) : 0, head = live ? (int)(item % n_heads) : 0;
-    float a[8], b[8], dot = 0.f;
-    unpack8(*(const uint4*)(o + (long)t * ldo + (long)head * DH + sub * 8), a);
-    unpack8(*(const uint4*)(d_o + (long)t * ldo + (long)head * DH + sub * 8), b);
+    const int head_raw = (int)(blockIdx.x * 256 + threadIdx.x) / LPR, sub = threadIdx.x % LPR;
+    const bool live = head_raw < n_heads;
+    const int head = live ? head_raw : 0;
+    for (long t = blockIdx.y; t < T; t += gridDim.y) {
+        float a[8], b[8], dot = 0.f;
+        unpack8(*(const uint4*)(o + t * ldo + (long)head * DH + sub * 8), a);
+        unpack8(*(const uint4*)(d_o + t * ldo + (long)head * DH + sub * 8), b);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) dot += a[e] * b[e];
-    for (int off = LPR >> 1; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
-    if (live && sub == 0) delta[(long)head * T + t] = dot;
+        for (int e = 0; e < 8; ++e) dot += a[e] * b[e];
+        for (int off = LPR >> 1; off > 0; off >>= 1) dot += __shfl_xor(dot, off, 64);
+        if (live && sub == 0) delta[(long)head * T + t] = dot;
+    }
 }
 
 // delta from its own small kernel, then one launch that holds every dK/dV and every dQ part, longest first.
@@ -602,8 +604,8 @@ static hipError_t run_bwd(const bf16_t* q, const bf16_t* k, const bf16_t* v, con
     const float scale = 1.f / sqrtf((float)DH);
     dim3 grid(cdiv(T, NW * 32), n_heads, 2);
     const size_t lds_kv = (size_t)(2 * 64 * C::LSK + 2 * 64 * LTR(DH)) * sizeof(bf16_t) + 128 * sizeof(float);
-    const long items = (long)T * n_heads * (DH / 8);
-    attn_delta_kernel<DH><<<cdiv(items, 256), 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
+    const dim3 dgrid(cdiv((long)n_heads * (DH / 8), 256), T < 65535 ? T : 65535);
+    attn_delta_kernel<DH><<<dgrid, 256, 0, s>>>(o, d_o, ldo, T, n_heads, delta);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t lds_q = (size_t)(2 * 64 * C::LSK + 64 * LTR(DH)) * sizeof(bf16_t);

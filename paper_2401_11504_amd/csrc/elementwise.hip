@@ -236,28 +236,29 @@ __global__ __launch_bounds__(256) void rope_kernel(bf16_t* __restrict__ x, long 
 __global__ __launch_bounds__(256) void rope_table_vec_kernel(bf16_t* __restrict__ x, long ld, int T, int n_heads,
                                                              int d_head, int pos0, float sign,
                                                              const float2* __restrict__ table) {
+    // grid: x over the (head, eight-pair chunk) items of a row, y over rows
     const int half = d_head >> 1, per_head = half >> 3;
-    const int per_row = n_heads * per_head;
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long)T * per_row) return;
-    const int t = (int)(idx / per_row), rem = (int)(idx % per_row);
-    const int hd = rem / per_head, i = (rem % per_head) * 8;
-    bf16_t* p = x + (long)t * ld + (long)hd * d_head + i;
-    float a[8], b[8], lo[8], hi[8];
-    unpack8(*(const uint4*)p, a);
-    unpack8(*(const uint4*)(p + half), b);
-    const float4* cs4 = (const float4*)(table + (long)(pos0 + t) * half + i);   // (cos, sin) pairs, two per float4
+    const unsigned rem = blockIdx.x * blockDim.x + threadIdx.x;
+    if (rem >= (unsigned)(n_heads * per_head)) return;
+    const unsigned hd = rem / (unsigned)per_head, i = (rem - hd * per_head) * 8;
+    for (long t = blockIdx.y; t < T; t += gridDim.y) {
+        bf16_t* p = x + t * ld + (long)hd * d_head + i;
+        float a[8], b[8], lo[8], hi[8];
+        unpack8(*(const uint4*)p, a);
+        unpack8(*(const uint4*)(p + half), b);
+        const float4* cs4 = (const float4*)(table + (pos0 + t) * half + i);   // (cos, sin) pairs, two per float4
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const float4 w = cs4[e];
-        const float s0 = w.y * sign, s1 = w.w * sign;
-        lo[2 * e] = a[2 * e] * w.x - b[2 * e] * s0;
-        hi[2 * e] = b[2 * e] * w.x + a[2 * e] * s0;
-        lo[2 * e + 1] = a[2 * e + 1] * w.z - b[2 * e + 1] * s1;
-        hi[2 * e + 1] = b[2 * e + 1] * w.z + a[2 * e + 1] * s1;
+        for (int e = 0; e < 4; ++e) {
+            const float4 w = cs4[e];
+            const float s0 = w.y * sign, s1 = w.w * sign;
+            lo[2 * e] = a[2 * e] * w.x - b[2 * e] * s0;
+            hi[2 * e] = b[2 * e] * w.x + a[2 * e] * s0;
+            lo[2 * e + 1] = a[2 * e + 1] * w.z - b[2 * e + 1] * s1;
+            hi[2 * e + 1] = b[2 * e + 1] * w.z + a[2 * e + 1] * s1;
+        }
+        *(uint4*)p = pack8(lo);
+        *(uint4*)(p + half) = pack8(hi);
     }
-    *(uint4*)p = pack8(lo);
-    *(uint4*)(p + half) = pack8(hi);
 }
 
 hipError_t launch_rope_table(float2* table, int n_pos, int d_head, float base, hipStream_t s) {
@@ -271,8 +272,8 @@ hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float
     const long n = (long)T * n_heads * (d_head / 4);
     if (n <= 0) return hipSuccess;
     if (table && (d_head & 15) == 0 && (ld & 7) == 0 && ((size_t)x & 15) == 0) {
-        const long nv = (long)T * n_heads * (d_head / 16);
-        rope_table_vec_kernel<<<cdiv(nv, 256), 256, 0, s>>>(x, ld, T, n_heads, d_head, pos0, sign >= 0 ? 1.f : -1.f, table);
+        const dim3 grid(cdiv((long)n_heads * (d_head / 16), 256), T < 65535 ? T : 65535);
+        rope_table_vec_kernel<<<grid, 256, 0, s>>>(x, ld, T, n_heads, d_head, pos0, sign >= 0 ? 1.f : -1.f, table);
         return hipGetLastError();
     }
     rope_kernel<<<cdiv(n, 256), 256, 0, s>>>(x, ld, T, n_heads, d_head, (double)base, pos0, sign >= 0 ? 1.f : -1.f,
@@ -284,51 +285,50 @@ hipError_t launch_rope(bf16_t* x, long ld, int T, int n_heads, int d_head, float
 // gu [T, 2f] = [gate | up];  a = gate * sigmoid(gate) * up
 __global__ __launch_bounds__(256) void swiglu_fwd_kernel(const bf16_t* __restrict__ gu, int T, int f,
                                                          bf16_t* __restrict__ a) {
-    const int f8 = f >> 3;
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long)T * f8) return;
-    const long t = idx / f8;
-    const int c = (int)(idx % f8) * 8;
-    float g[8], u[8], o[8];
-    unpack8(*(const uint4*)(gu + t * 2 * f + c), g);
-    unpack8(*(const uint4*)(gu + t * 2 * f + f + c), u);
+    // grid: x over the eight-column chunks of a row, y over rows (no index division per thread)
+    const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (c >= f) return;
+    for (long t = blockIdx.y; t < T; t += gridDim.y) {
+        float g[8], u[8], o[8];
+        unpack8(*(const uint4*)(gu + t * 2 * f + c), g);
+        unpack8(*(const uint4*)(gu + t * 2 * f + f + c), u);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.f + __expf(-g[e])) * u[e];
-    *(uint4*)(a + t * f + c) = pack8(o);
+        for (int e = 0; e < 8; ++e) o[e] = g[e] * __builtin_amdgcn_rcpf(1.f + __expf(-g[e])) * u[e];   // 1 ulp reciprocal: the result is rounded to bf16
+        *(uint4*)(a + t * f + c) = pack8(o);
+    }
 }
 
 // dgate = da * up * sig * (1 + gate (1 - sig));  dup = da * gate * sig
 __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t* __restrict__ da, const bf16_t* __restrict__ gu,
                                                          int T, int f, bf16_t* __restrict__ dgu) {
-    const int f8 = f >> 3;
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (long)T * f8) return;
-    const long t = idx / f8;
-    const int c = (int)(idx % f8) * 8;
-    float g[8], u[8], d[8], dg[8], du[8];
-    unpack8(*(const uint4*)(gu + t * 2 * f + c), g);
-    unpack8(*(const uint4*)(gu + t * 2 * f + f + c), u);
-    unpack8(*(const uint4*)(da + t * f + c), d);
+    const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (c >= f) return;
+    for (long t = blockIdx.y; t < T; t += gridDim.y) {
+        float g[8], u[8], d[8], dg[8], du[8];
+        unpack8(*(const uint4*)(gu + t * 2 * f + c), g);
+        unpack8(*(const uint4*)(gu + t * 2 * f + f + c), u);
+        unpack8(*(const uint4*)(da + t * f + c), d);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float sg = 1.f / (1.f + __expf(-g[e]));
-        dg[e] = d[e] * u[e] * sg * (1.f + g[e] * (1.f - sg));
-        du[e] = d[e] * g[e] * sg;
+        for (int e = 0; e < 8; ++e) {
+            float sg = __builtin_amdgcn_rcpf(1.f + __expf(-g[e]));
+            dg[e] = d[e] * u[e] * sg * (1.f + g[e] * (1.f - sg));
+            du[e] = d[e] * g[e] * sg;
+        }
+        *(uint4*)(dgu + t * 2 * f + c) = pack8(dg);
+        *(uint4*)(dgu + t * 2 * f + f + c) = pack8(du);
     }
-    *(uint4*)(dgu + t * 2 * f + c) = pack8(dg);
-    *(uint4*)(dgu + t * 2 * f + f + c) = pack8(du);
 }
 
 hipError_t launch_swiglu_fwd(const bf16_t* gu, int T, int f, bf16_t* a, hipStream_t s) {
     const long n = (long)T * (f / 8);
     if (n <= 0) return hipSuccess;
-    swiglu_fwd_kernel<<<cdiv(n, 256), 256, 0, s>>>(gu, T, f, a);
+    swiglu_fwd_kernel<<<dim3(cdiv(f / 8, 256), T < 65535 ? T : 65535), 256, 0, s>>>(gu, T, f, a);
     return hipGetLastError();
 }
 hipError_t launch_swiglu_bwd(const bf16_t* da, const bf16_t* gu, int T, int f, bf16_t* dgu, hipStream_t s) {
     const long n = (long)T * (f / 8);
     if (n <= 0) return hipSuccess;
-    swiglu_bwd_kernel<<<cdiv(n, 256), 256, 0, s>>>(da, gu, T, f, dgu);
+    swiglu_bwd_kernel<<<dim3(cdiv(f / 8, 256), T < 65535 ? T : 65535), 256, 0, s>>>(da, gu, T, f, dgu);
     return hipGetLastError();
 }
 
