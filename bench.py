@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak (vendor figure, 
 # (FETCH_SIZE, then WRITE_SIZE; summed over the kernel's launches of one update, divided by their number,
 # each counter scaled by what it reads for --copy-calibration's 1 GiB copy).  The passes and the scaling
 # factors are in profiles/chunk_update_7b_r64_T1024.md; counters cannot be read from inside this process.
-GEMM_NT_HBM_BYTES_PER_LAUNCH = 204e6
+GEMM_NT_HBM_BYTES_PER_LAUNCH = 202e6
 # the same for the weight-streaming matrix-vector launches of the generation side (profiles/decode_7b_r64_window1024.md):
 # 50 839 KiB of FETCH_SIZE per launch x 2.000 = 104.1 MB against 103.8 MB of algorithmic bytes; writes are negligible
 GEMV_HBM_BYTES_PER_LAUNCH = 104.1e6
