@@ -161,6 +161,62 @@ def generate_bench(args, torch, api, harness, synth):
         "generated_tokens_per_s": round(1024 * chunks / dt, 1)}))
 
 
+def cycle_bench(args, torch, api, harness, synth):
+    """configs[3]: the streaming cycle with its two halves timed separately.  Each cycle decodes 1024 greedy tokens over
+    a key/value window that starts at the last 1024 tokens (and grows to 2048), then runs ONE chunk update on the 1024
+    tokens just decoded, then recomputes the cache from them with the updated module (the paper's default).  Reports
+    decode tokens/s, update trained tokens/s and the cache recomputation apart."""
+    import numpy as np
+    shape = synth.SHAPES["7b"].with_layers(args.layers)
+    seed, cycles, W, D = 3000, args.cycle, 1024, 1024
+    model = harness.Model(shape, seed, max_tokens=W + D + 1, keep_host=False, device_random=True)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    window = synth.uniform_tokens(seed, W, shape.vocab)          # the stream so far (seeded stand-in for a prompt)
+    nxt, _ = api.tl_prefill(lora, window)
+    for _ in range(8):                                           # warm-up: a few tokens, one update, the prefill again
+        nxt, _ = api.tl_decode_step(lora, nxt)
+    api.tl_chunk_update(lora, window, 0, 5e-5)
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    lora = api.tl_lora_init(model.handle, shape.rank, shape.alpha, a_init_std=0.02, seed=seed)
+    nxt, _ = api.tl_prefill(lora, window)
+    torch.cuda.synchronize()
+    t_dec = t_upd = t_pre = 0.0
+    losses = []
+    for _ in range(cycles):
+        chunk = np.empty(D, dtype=np.int32)
+        t0 = time.perf_counter()
+        for i in range(D):
+            chunk[i] = nxt
+            nxt, _ = api.tl_decode_step(lora, nxt)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        loss, _ = api.tl_chunk_update(lora, chunk, 0, 5e-5)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        nxt, _ = api.tl_prefill(lora, chunk[-W:])
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        t_dec += t1 - t0; t_upd += t2 - t1; t_pre += t3 - t2
+        losses.append(round(loss, 5))
+    api.tl_discard(lora)
+    api.tl_lora_free(lora)
+    model.close()
+    total = t_dec + t_upd + t_pre
+    print(json.dumps({
+        "metric": "streaming Temp-Lora cycle (7B-shape, r=64): decode and update timed separately",
+        "value": round(D * cycles / t_upd, 1), "unit": "trained tokens/s (update half)", "n_gpus": 1, "steps": cycles,
+        "warmup": 1, "ms_per_step": round(1e3 * total / cycles, 1), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"DEBUG (not the headline metric): configs[3], {cycles} cycles of (decode 1024 greedy tokens over "
+                               "a 1024..2048-token key/value window, one chunk update on them, cache recomputed from them)",
+                   "n_layers": args.layers, "stream_tokens": D * cycles},
+        "update_trained_tokens_per_s": round(D * cycles / t_upd, 1), "decode_tokens_per_s": round(D * cycles / t_dec, 1),
+        "ms_per_update": round(1e3 * t_upd / cycles, 2), "ms_per_decoded_token": round(1e3 * t_dec / (D * cycles), 3),
+        "ms_per_cache_recompute": round(1e3 * t_pre / cycles, 2), "s_per_1024_stream_tokens": round(total / cycles, 3),
+        "first_update_loss": losses[0], "last_update_loss": losses[-1]}))
+
+
 def decode_bench(args, torch, api, harness, synth):
     """Greedy decoding with the module over the key/value cache (Algorithm 1's token loop): tokens/s, and the
     matrix-vector kernel that streams the frozen weights against the HBM roofline."""
@@ -235,6 +291,8 @@ def main():
                          "Zipf(1.1) token stream, two epochs each, module state carried, discarded at the end")
     ap.add_argument("--generate", type=int, default=0, metavar="CHUNKS",
                     help="measure Algorithm 1 end to end instead: generate CHUNKS chunks of 1024 tokens with tl_generate")
+    ap.add_argument("--cycle", type=int, default=0, metavar="CYCLES",
+                    help="debug line: configs[3], CYCLES x (decode 1024 tokens, one update on them), halves timed separately")
     ap.add_argument("--decode", action="store_true",
                     help="measure the generation side instead (the step either side of the update): one step = one "
                          "greedily decoded token with the module applied, after a prefill of --prompt tokens")
@@ -270,6 +328,9 @@ def main():
         return
     if args.generate > 0:
         generate_bench(args, torch, api, harness, synth)
+        return
+    if args.cycle > 0:
+        cycle_bench(args, torch, api, harness, synth)
         return
     if args.decode:
         decode_bench(args, torch, api, harness, synth)
