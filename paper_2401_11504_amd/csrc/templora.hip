@@ -190,11 +190,18 @@ struct tl_lora {
     double prof_flop = 0.0;
 };
 
+// Events that order the two streams of one GPU against each other: no timing, and no system-scope fence when they are
+// recorded (that fence writes the caches back and invalidates them for the host's and other devices' sake; kernels of
+// one device see each other's results through the release at the end of every kernel).
+static constexpr unsigned kSyncEvent = hipEventDisableTiming | hipEventDisableSystemFence;
+// Events that only bracket launches for timing: no system-scope fence either, which would lengthen what they measure.
+static constexpr unsigned kTimingEvent = hipEventDisableSystemFence;
+
 static void prof_mark(tl_lora* L) {
     if (!L->prof_on) return;
     if (L->prof_used == L->prof_ev.size()) {
         hipEvent_t e;
-        if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); L->prof_on = false; return; }
+        if (hipEventCreateWithFlags(&e, kTimingEvent) != hipSuccess) { (void)hipGetLastError(); L->prof_on = false; return; }
         L->prof_ev.push_back(e);
     }
     (void)hipEventRecord(L->prof_ev[L->prof_used++], L->model->stream);
@@ -437,11 +444,11 @@ extern "C" tl_status tl_lora_init(tl_model* m, const tl_lora_cfg* cfg, tl_lora**
         TLCHK(L->pool.alloc(&L->dH, (size_t)Tm * 3 * r));
         for (int k = 0; k < 2; ++k) {
             for (int g = 0; g < N_GROUPS; ++g) TLCHK(L->pool.alloc(&L->dHg[k][g], (size_t)Tm * kGroupCount[g] * r));
-            HIPCHK(hipEventCreateWithFlags(&L->ev_ready[k], hipEventDisableTiming));
-            HIPCHK(hipEventCreateWithFlags(&L->ev_done[k], hipEventDisableTiming));
+            HIPCHK(hipEventCreateWithFlags(&L->ev_ready[k], kSyncEvent));
+            HIPCHK(hipEventCreateWithFlags(&L->ev_done[k], kSyncEvent));
         }
         HIPCHK(hipStreamCreateWithFlags(&L->side, hipStreamNonBlocking));
-        HIPCHK(hipEventCreateWithFlags(&L->ev_opt, hipEventDisableTiming));
+        HIPCHK(hipEventCreateWithFlags(&L->ev_opt, hipEventDisableTiming));   // gates the copy of loss and status word to the host: keeps its system-scope fence
         TLCHK(L->pool.alloc(&L->delta, (size_t)mc.n_heads * Tm));
         // split-contraction scratch: up to 16 partial copies of the largest skinny output (Hs: [T, 3r]) or four of a
         // [T, d_model] output (long-K GEMMs with few output tiles)
