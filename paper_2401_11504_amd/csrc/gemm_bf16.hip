@@ -473,6 +473,18 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, NtMap
         // each split stores its fp32 tile; splitk_reduce_kernel adds the splits in index order afterwards
         // (a second launch: device-wide fences inside a kernel cost a full L2 write-back on this chip)
         float* part = p.partial + ((long)z * n_split + split) * (long)p.M * p.N;
+        if (m0 + BM <= p.M && n0 + BN <= p.N) {
+            // a whole tile (workgroup-uniform): no bounds checks, one base address per lane
+            float* base = part + (long)(m0 + wm * TM + 4 * g) * p.N + n0 + wn * TN + l32;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        base[(long)(i * 32 + 8 * (v >> 2) + (v & 3)) * p.N + j * 32] = acc[i][j][v];
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
