@@ -543,6 +543,18 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_nt_dl_kernel(GemmNT p, NtMap
             __builtin_amdgcn_wave_barrier();
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             constexpr int CPR = TN / 8;  // 16-byte chunks per slab row
+            if (vec_ok && m0 + BM <= p.M && n0 + BN <= p.N) {
+                // a whole tile with aligned rows (workgroup-uniform): no bounds checks
+                bf16_t* tile = Cb + (long)(m0 + wm * TM + i * 32) * ldc + n0 + wn * TN;
+#pragma unroll
+                for (int c = lane; c < 32 * CPR; c += 64) {
+                    const int r = c / CPR, cc = (c % CPR) * 8;
+                    *(uint4*)(tile + (long)r * ldc + cc) = *(const uint4*)(slab + r * SLD + cc);
+                }
+                __builtin_amdgcn_wave_barrier();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                continue;
+            }
 #pragma unroll
             for (int c = lane; c < 32 * CPR; c += 64) {
                 const int r = c / CPR, cc = (c % CPR) * 8;
