@@ -31,12 +31,13 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const 
     const int n4 = d >> 2;
     float ss = 0.f;
     constexpr int NR = NV > 0 ? NV : 1;
-    float4 xs[NR];
+    float4 xs[NR], ws[NR];
     if constexpr (NV > 0) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + 256 * j;
             xs[j] = i < n4 ? fetch(i) : make_float4(0.f, 0.f, 0.f, 0.f);
+            ws[j] = i < n4 ? gp[i] : make_float4(0.f, 0.f, 0.f, 0.f);   // the gain too: the output pass then only stores
             ss += xs[j].x * xs[j].x + xs[j].y * xs[j].y + xs[j].z * xs[j].z + xs[j].w * xs[j].w;
         }
     } else {
@@ -47,8 +48,7 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const 
     }
     ss = block_sum(ss, red);
     const float rho = rsqrtf(ss / (float)d + eps);
-    auto emit = [&](int i, const float4& x) {
-        const float4 w = gp[i];
+    auto emit = [&](int i, const float4& x, const float4& w) {
         uint2 o;
         o.x = pack_bf16x2(x.x * rho * w.x, x.y * rho * w.y);
         o.y = pack_bf16x2(x.z * rho * w.z, x.w * rho * w.w);
@@ -58,11 +58,11 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* h, const 
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + 256 * j;
-            if (i < n4) emit(i, xs[j]);
+            if (i < n4) emit(i, xs[j], ws[j]);
         }
     } else {
         const float4* hp = (const float4*)((part ? h_write : h) + row * d);   // each thread re-reads only what it wrote itself
-        for (int i = threadIdx.x; i < n4; i += blockDim.x) emit(i, hp[i]);
+        for (int i = threadIdx.x; i < n4; i += blockDim.x) emit(i, hp[i], gp[i]);
     }
 }
 
@@ -105,14 +105,17 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
     const int n4 = d >> 2;
     float ss = 0.f, dot = 0.f;
     constexpr int NR = NV > 0 ? NV : 1;
-    float4 xs[NR], gd[NR];   // h and g * dy of this thread's chunks
+    float4 xs[NR], gd[NR], rs[NR];   // h, g * dy and the upstream residual gradient of this thread's chunks: everything the
+                                     // output pass needs is fetched before the reduction, so that pass only stores
     if constexpr (NV > 0) {
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + 256 * j;
             xs[j] = make_float4(0.f, 0.f, 0.f, 0.f);
             gd[j] = xs[j];
+            rs[j] = xs[j];
             if (i < n4) {
+                if (rp) rs[j] = rp[i];
                 const float4 x = hp[i], w = gp[i], dv = dy4(i);
                 xs[j] = x;
                 gd[j] = make_float4(w.x * dv.x, w.y * dv.y, w.z * dv.z, w.w * dv.w);
@@ -137,12 +140,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
     dot = (red[4] + red[5]) + (red[6] + red[7]);
     const float rho = rsqrtf(ss / (float)d + eps);
     const float c = rho * rho * rho * (dot / (float)d);
-    auto emit = [&](int i, const float4& x, const float4& wd) {
+    auto emit = [&](int i, const float4& x, const float4& wd, const float4& q) {
         float4 o = make_float4(rho * wd.x - x.x * c, rho * wd.y - x.y * c, rho * wd.z - x.z * c, rho * wd.w - x.w * c);
-        if (rp) {
-            const float4 q = rp[i];
-            o.x += q.x; o.y += q.y; o.z += q.z; o.w += q.w;
-        }
+        o.x += q.x; o.y += q.y; o.z += q.z; o.w += q.w;
         op[i] = o;
         if (bp) {
             uint2 b;
@@ -155,12 +155,13 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const bf16_t* __restri
 #pragma unroll
         for (int j = 0; j < NV; ++j) {
             const int i = threadIdx.x + 256 * j;
-            if (i < n4) emit(i, xs[j], gd[j]);
+            if (i < n4) emit(i, xs[j], gd[j], rs[j]);
         }
     } else {
         for (int i = threadIdx.x; i < n4; i += blockDim.x) {
             const float4 x = hp[i], w = gp[i], dv = dy4(i);
-            emit(i, x, make_float4(w.x * dv.x, w.y * dv.y, w.z * dv.z, w.w * dv.w));
+            emit(i, x, make_float4(w.x * dv.x, w.y * dv.y, w.z * dv.z, w.w * dv.w),
+                 rp ? rp[i] : make_float4(0.f, 0.f, 0.f, 0.f));
         }
     }
 }
